@@ -1,0 +1,2 @@
+"""CPU oracle of the strided tensor engine.  TEST INFRASTRUCTURE ONLY: imported by the tests,
+the smoke check and the benchmark's CPU-baseline leg, never by the product package."""
