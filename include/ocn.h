@@ -1,0 +1,225 @@
+/*
+ * ocn - a strided n-dimensional tensor engine for AMD MI355X (gfx950).
+ *
+ * C ABI of the data-parallel core of the Ocean Tensor Package (van den Berg, arXiv
+ * 1810.08723): elementwise unary and binary operations, type-casting copies and reductions
+ * along one or more axes, over tensors described the way the paper describes them
+ * (section 3.1.3 "Tensors": a data type, at most eight dimensions, sizes, general strides
+ * given in bytes; section 3.1.2 "Storage": memory that may be provided by an external
+ * source and carry several superimposed tensors of different types).
+ *
+ * Conventions common to every call
+ *  - Every ocn_tensor::base is DEVICE memory owned by the caller.  The library never
+ *    allocates, frees or keeps a pointer after a call returns.  Descriptor structs
+ *    themselves are HOST memory and are only read during the call.
+ *  - Element (i0,...,i{n-1}) of a view lives at base + offset + sum_d i_d * stride[d].
+ *    Strides and offset are BYTES; a stride may be zero (broadcast) or negative (reversed
+ *    axis).  offset and every stride must be a multiple of the scalar size of the dtype
+ *    (for complex types, of its real component), and base + offset must be so aligned.
+ *  - Work is enqueued on `stream` (a hipStream_t, or NULL for the default stream) and the
+ *    call returns without waiting for it (section 3.1: operations are scheduled
+ *    asynchronously on a stream).
+ *  - Return value: OCN_OK (0) or a negative OCN_ERR_* code.  On error nothing is launched
+ *    and no memory is written.  No exception crosses this boundary.
+ *  - An output with zero elements makes the call a successful no-op.
+ */
+#ifndef OCN_H
+#define OCN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define OCN_MAX_DIMS 8 /* section 3.1.3: the maximum number of tensor dimensions is eight */
+
+/* Element types (footnote in section 4): booleans; 8, 16, 32 and 64-bit signed and unsigned
+ * integers; real and complex half, single and double precision floating point.  A complex
+ * element is the pair (re, im) of its real component type. */
+typedef enum {
+  OCN_BOOL = 0, OCN_INT8, OCN_INT16, OCN_INT32, OCN_INT64,
+  OCN_UINT8, OCN_UINT16, OCN_UINT32, OCN_UINT64,
+  OCN_HALF, OCN_FLOAT, OCN_DOUBLE,
+  OCN_CHALF, OCN_CFLOAT, OCN_CDOUBLE,
+  OCN_NUM_DTYPES
+} ocn_dtype;
+
+/* The paper's unified tensor type (sections 2.2 and 3.1.3) reduced to a plain descriptor. */
+typedef struct {
+  void *base;                    /* device pointer to the start of the storage; borrowed  */
+  int64_t offset;                /* bytes from base to element (0,...,0) of this view     */
+  int32_t dtype;                 /* ocn_dtype                                             */
+  int32_t ndim;                  /* 0 (a scalar) .. OCN_MAX_DIMS                          */
+  int64_t size[OCN_MAX_DIMS];    /* extents, >= 0                                         */
+  int64_t stride[OCN_MAX_DIMS];  /* bytes; may be 0 or negative                           */
+  int32_t device;                /* HIP device ordinal; all operands of a call must agree */
+} ocn_tensor;
+
+typedef enum { /* section 3.2: basic arithmetic; complex types add conjugation (section 4) */
+  OCN_U_IDENT = 0, /* out = a (a cast when the types differ)                   */
+  OCN_U_NEG,       /* -a; integers wrap                                        */
+  OCN_U_ABS,       /* |a| for real types; integers wrap; not defined for complex */
+  OCN_U_CONJ,      /* complex conjugate; identity on real types                */
+  OCN_U_LNOT,      /* !(a != 0)                                                */
+  OCN_U_BNOT,      /* ~a for integers, ! for bool                              */
+  OCN_U_SQRT,      /* correctly rounded square root, real floating types       */
+  OCN_NUM_UNARY
+} ocn_unary_op;
+
+typedef enum {
+  OCN_B_ADD = 0, OCN_B_SUB, OCN_B_MUL, OCN_B_DIV, OCN_B_MIN, OCN_B_MAX, /* arithmetic */
+  OCN_B_BAND, OCN_B_BOR, OCN_B_BXOR,                                    /* bitwise    */
+  OCN_B_LAND, OCN_B_LOR, OCN_B_LXOR,                                    /* logical    */
+  OCN_B_EQ, OCN_B_NE, OCN_B_LT, OCN_B_LE, OCN_B_GT, OCN_B_GE,           /* comparison */
+  OCN_B_ABSGT,                                                          /* |a| > |b|  */
+  OCN_NUM_BINARY
+} ocn_binary_op;
+
+typedef enum { /* section 3.2: tensor reductions along one or more axes */
+  OCN_R_SUM = 0, OCN_R_PROD, OCN_R_MIN, OCN_R_MAX, OCN_R_ANY, OCN_R_ALL,
+  OCN_NUM_REDUCE
+} ocn_reduce_op;
+
+typedef enum {
+  OCN_OK = 0,
+  OCN_ERR_NULLPTR = -1,     /* a required pointer is NULL                                        */
+  OCN_ERR_DTYPE = -2,       /* bad dtype, operation not defined for the type, or a type mismatch
+                               with OCN_STRICT_TYPES set                                         */
+  OCN_ERR_NDIM = -3,        /* ndim outside 0..OCN_MAX_DIMS                                      */
+  OCN_ERR_SHAPE = -4,       /* negative size, input not broadcastable to out, bad axes           */
+  OCN_ERR_DEVICE = -5,      /* operands name different devices                                   */
+  OCN_ERR_ALIGN = -6,       /* offset/stride/base not a multiple of the scalar size              */
+  OCN_ERR_OVERLAP_OUT = -7, /* the output view addresses some byte more than once                */
+  OCN_ERR_ALIAS = -8,       /* an input shares bytes with the output without being the same view */
+  OCN_ERR_WORKSPACE = -9,   /* reduction workspace missing or too small                          */
+  OCN_ERR_EMPTY = -10,      /* min/max over zero elements                                        */
+  OCN_ERR_LAUNCH = -11,     /* the HIP runtime reported an error; see ocn_last_hip_error         */
+  OCN_ERR_OP = -12          /* unknown operation code                                            */
+} ocn_status;
+
+/* flags */
+#define OCN_STRICT_TYPES 1u /* section 3.2.1: automatic type casting switched off; operand
+                               types that differ are an error instead of being converted */
+
+/*
+ * Elementwise unary operation (sections 3.2 and 3.2.1): for every index i of out,
+ *     out[i] = convert_out( f( convert_T( a[i] ) ) ).
+ * T is out's dtype (bool for OCN_U_LNOT).  `a` broadcasts against out as in ocn_binary.
+ * a may be the identical view as out (in place); any other sharing of bytes between a and
+ * out is OCN_ERR_ALIAS (section 4: overlap between tensors must not corrupt results; the
+ * paper resolves it with an intermediate tensor, which is the caller's to provide here).
+ */
+int ocn_unary(int op, const ocn_tensor *a, const ocn_tensor *out, uint32_t flags, void *stream);
+
+/*
+ * Elementwise binary operation with implicit type casting and broadcasting (section 3.2.1;
+ * section 2.1: type conversions and broadcasting happen before the device function runs -
+ * here they are fused into the kernel, no intermediate tensor exists):
+ *     out[i] = convert_out( g( convert_T(a[i]), convert_T(b[i]) ) ).
+ * Shapes: out fixes the result shape.  Inputs are right-aligned against it; an input
+ * dimension must equal out's or be 1, and a size-1 dimension is read at index 0 whatever
+ * its stride says (section 4: broadcasting along dimensions).
+ * Compute type T: out's dtype for arithmetic and bitwise operations (as in "A += B", where
+ * B is coerced to A); ocn_promote(a.dtype, b.dtype) for comparisons and OCN_B_ABSGT; bool
+ * for the logical operations.  Half-precision types are evaluated in single precision and
+ * rounded once when stored.  With OCN_STRICT_TYPES, a.dtype != b.dtype (and, for arithmetic
+ * and bitwise operations, a.dtype != out.dtype) is OCN_ERR_DTYPE.
+ * Either input may be the identical view as out.
+ */
+int ocn_binary(int op, const ocn_tensor *a, const ocn_tensor *b, const ocn_tensor *out,
+               uint32_t flags, void *stream);
+
+/*
+ * Type-casting copy on one device (section 3.2.1, ocean.cast / ocean.ensure): dst[i] =
+ * convert(src[i]).  Float to integer truncates toward zero, saturates, NaN gives 0; integer
+ * to integer saturates; anything to bool is "!= 0"; to floating types rounds to nearest even
+ * in one step; complex to real keeps the real part.  Same as ocn_unary(OCN_U_IDENT, ...).
+ */
+int ocn_cast_copy(const ocn_tensor *src, const ocn_tensor *dst, void *stream);
+
+/*
+ * Reduction along `naxes` distinct axes of a (section 3.2).  out must have
+ * a.ndim - naxes dimensions: the kept dimensions of a in their original order.  naxes ==
+ * a.ndim is a full reduction to a 0-dimensional out; naxes == 0 is a cast copy.
+ * Accumulation: integer and bool sums/products in wrapping 64-bit; half in single, single
+ * and double in double precision; min/max exactly in the input type, NaN-propagating, +0
+ * above -0; any/all on "!= 0".  The accumulated value is converted once to out's dtype by
+ * the ocn_cast_copy rules.  Results of floating sums do not depend on timing (no floating
+ * atomics): the same call gives the same bits every time.
+ * workspace: DEVICE scratch of at least ocn_reduce_workspace_bytes(...) bytes, 256-byte
+ * aligned, caller-owned, used only during the enqueued work (may be NULL when that size is
+ * 0).  out must not share bytes with a.  min/max over zero elements: OCN_ERR_EMPTY.
+ */
+int ocn_reduce(int op, const ocn_tensor *a, const int32_t *axes, int32_t naxes,
+               const ocn_tensor *out, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Bytes of workspace ocn_reduce needs for these arguments (0 when it runs in one pass).
+ * Returns 0 as well when the arguments are invalid; ocn_reduce then reports the error. */
+size_t ocn_reduce_workspace_bytes(int op, const ocn_tensor *a, const int32_t *axes,
+                                  int32_t naxes, const ocn_tensor *out);
+
+/* Result type of implicit casting (section 3.2.1): the smallest type that can keep both;
+ * signed with unsigned 8-bit gives int16; a 64-bit integer with a floating type gives
+ * double; a complex operand makes the result complex.  Negative on a bad dtype. */
+int ocn_promote(int dtype_a, int dtype_b);
+
+/* Element size in bytes of a dtype, 0 if invalid. */
+int ocn_dtype_size(int dtype);
+
+/* Static description of a status code. */
+const char *ocn_error_string(int code);
+
+/* The hipError_t (as int) behind the most recent OCN_ERR_LAUNCH on this host thread. */
+int ocn_last_hip_error(void);
+
+/* ---- plan inspection (host only; launches nothing, touches no device memory) -------- */
+
+typedef enum {
+  OCN_KERNEL_NONE = 0,     /* zero elements: nothing to launch                              */
+  OCN_KERNEL_EW_ROWS,      /* vectorised rows: every operand contiguous (or broadcast)
+                              along the innermost canonical dimension                      */
+  OCN_KERNEL_EW_TILED,     /* LDS-staged tiles: operands disagree on their fastest axis     */
+  OCN_KERNEL_EW_GENERIC,   /* one element per lane, arbitrary strides                       */
+  OCN_KERNEL_RED_ROWS,     /* reduced axis is the input's fastest                           */
+  OCN_KERNEL_RED_COLS,     /* a kept axis is the input's fastest                            */
+  OCN_KERNEL_RED_GENERIC   /* one output per lane, arbitrary strides                        */
+} ocn_kernel_kind;
+
+/* What the host planner decided for a call: the canonical dimension list after dropping
+ * size-1 dimensions, flipping, sorting by stride and merging (section 4 of the paper:
+ * "sorting of axes and merging of consecutive axes"), slowest dimension first. */
+typedef struct {
+  int32_t kernel;                     /* ocn_kernel_kind                                    */
+  int32_t compute_dtype;              /* T                                                  */
+  int32_t ndim;                       /* canonical dimensions (elementwise), or kept dims   */
+  int32_t nred;                       /* reductions: canonical reduced dimensions           */
+  int64_t size[OCN_MAX_DIMS];
+  int64_t stride_out[OCN_MAX_DIMS];   /* bytes                                              */
+  int64_t stride_a[OCN_MAX_DIMS];
+  int64_t stride_b[OCN_MAX_DIMS];
+  int64_t offset_out, offset_a, offset_b; /* bytes from each base, after flips              */
+  int64_t red_size[OCN_MAX_DIMS];     /* reductions: reduced dims, slowest first            */
+  int64_t red_stride_a[OCN_MAX_DIMS];
+  int32_t vec;                        /* elements per lane access along the fastest dim     */
+  int32_t tile_log2[OCN_MAX_DIMS];    /* tiled kernel: log2 of the tile extent per dim      */
+  int32_t stage_a, stage_b;           /* tiled kernel: operand goes through LDS             */
+  int32_t specialised;                /* 1: dtype-specialised kernel; 0: generic-dtype path */
+  int32_t passes;                     /* kernel launches the call would make                */
+  int64_t grid, block;                /* first launch                                       */
+  int64_t split;                      /* reductions: partial results per output (1 = none)  */
+  int64_t lds_bytes;
+} ocn_plan_info;
+
+int ocn_plan_unary(int op, const ocn_tensor *a, const ocn_tensor *out, uint32_t flags,
+                   ocn_plan_info *info);
+int ocn_plan_binary(int op, const ocn_tensor *a, const ocn_tensor *b, const ocn_tensor *out,
+                    uint32_t flags, ocn_plan_info *info);
+int ocn_plan_reduce(int op, const ocn_tensor *a, const int32_t *axes, int32_t naxes,
+                    const ocn_tensor *out, ocn_plan_info *info);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OCN_H */

@@ -1,0 +1,225 @@
+"""Thin ctypes binding of libocn.so - argument marshalling only.
+
+Every step of every operation runs inside the library's HIP kernels; nothing here computes.
+PyTorch appears only as the owner of device memory and streams.  If the built library is
+missing the import fails loudly: there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass, field
+from typing import Any, Optional, Sequence, Tuple
+
+MAX_DIMS = 8
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libocn.so")
+
+DTYPES = ("bool", "int8", "int16", "int32", "int64", "uint8", "uint16", "uint32", "uint64",
+          "half", "float", "double", "chalf", "cfloat", "cdouble")
+DTYPE_CODE = {n: i for i, n in enumerate(DTYPES)}
+UNARY_OPS = ("ident", "neg", "abs", "conj", "lnot", "bnot", "sqrt")
+BINARY_OPS = ("add", "sub", "mul", "div", "min", "max", "band", "bor", "bxor", "land", "lor",
+              "lxor", "eq", "ne", "lt", "le", "gt", "ge", "absgt")
+REDUCE_OPS = ("sum", "prod", "min", "max", "any", "all")
+UNARY_CODE = {n: i for i, n in enumerate(UNARY_OPS)}
+BINARY_CODE = {n: i for i, n in enumerate(BINARY_OPS)}
+REDUCE_CODE = {n: i for i, n in enumerate(REDUCE_OPS)}
+
+STRICT_TYPES = 1
+
+OK = 0
+ERR = {"NULLPTR": -1, "DTYPE": -2, "NDIM": -3, "SHAPE": -4, "DEVICE": -5, "ALIGN": -6,
+       "OVERLAP_OUT": -7, "ALIAS": -8, "WORKSPACE": -9, "EMPTY": -10, "LAUNCH": -11, "OP": -12}
+
+KERNELS = ("none", "ew_rows", "ew_tiled", "ew_generic", "red_rows", "red_cols", "red_generic")
+
+EXPORTS = ("ocn_unary", "ocn_binary", "ocn_cast_copy", "ocn_reduce", "ocn_reduce_workspace_bytes",
+           "ocn_promote", "ocn_dtype_size", "ocn_error_string", "ocn_last_hip_error",
+           "ocn_plan_unary", "ocn_plan_binary", "ocn_plan_reduce")
+
+
+class OcnTensor(C.Structure):
+    _fields_ = [("base", C.c_void_p), ("offset", C.c_int64), ("dtype", C.c_int32),
+                ("ndim", C.c_int32), ("size", C.c_int64 * MAX_DIMS),
+                ("stride", C.c_int64 * MAX_DIMS), ("device", C.c_int32)]
+
+
+class OcnPlanInfo(C.Structure):
+    _fields_ = [("kernel", C.c_int32), ("compute_dtype", C.c_int32), ("ndim", C.c_int32),
+                ("nred", C.c_int32), ("size", C.c_int64 * MAX_DIMS),
+                ("stride_out", C.c_int64 * MAX_DIMS), ("stride_a", C.c_int64 * MAX_DIMS),
+                ("stride_b", C.c_int64 * MAX_DIMS), ("offset_out", C.c_int64),
+                ("offset_a", C.c_int64), ("offset_b", C.c_int64),
+                ("red_size", C.c_int64 * MAX_DIMS), ("red_stride_a", C.c_int64 * MAX_DIMS),
+                ("vec", C.c_int32), ("tile_log2", C.c_int32 * MAX_DIMS), ("stage_a", C.c_int32),
+                ("stage_b", C.c_int32), ("specialised", C.c_int32), ("passes", C.c_int32),
+                ("grid", C.c_int64), ("block", C.c_int64), ("split", C.c_int64),
+                ("lds_bytes", C.c_int64)]
+
+
+class OcnError(RuntimeError):
+    def __init__(self, code: int):
+        msg = lib().ocn_error_string(code).decode()
+        if code == ERR["LAUNCH"]:
+            msg += f" (hipError {lib().ocn_last_hip_error()})"
+        super().__init__(f"ocn error {code}: {msg}")
+        self.code = code
+
+
+_lib: Optional[C.CDLL] = None
+
+
+def lib() -> C.CDLL:
+    """The loaded library.  Raises if it has not been built (python -m paper_1810_08723_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build it with "
+                              "`python -m paper_1810_08723_amd.build` (no fallback exists)")
+        L = C.CDLL(LIB_PATH)
+        T, I = C.POINTER(OcnTensor), C.POINTER(OcnPlanInfo)
+        L.ocn_unary.argtypes = [C.c_int, T, T, C.c_uint32, C.c_void_p]
+        L.ocn_binary.argtypes = [C.c_int, T, T, T, C.c_uint32, C.c_void_p]
+        L.ocn_cast_copy.argtypes = [T, T, C.c_void_p]
+        L.ocn_reduce.argtypes = [C.c_int, T, C.POINTER(C.c_int32), C.c_int32, T, C.c_void_p,
+                                 C.c_size_t, C.c_void_p]
+        L.ocn_reduce_workspace_bytes.argtypes = [C.c_int, T, C.POINTER(C.c_int32), C.c_int32, T]
+        L.ocn_reduce_workspace_bytes.restype = C.c_size_t
+        L.ocn_promote.argtypes = [C.c_int, C.c_int]
+        L.ocn_dtype_size.argtypes = [C.c_int]
+        L.ocn_error_string.argtypes = [C.c_int]
+        L.ocn_error_string.restype = C.c_char_p
+        L.ocn_last_hip_error.argtypes = []
+        L.ocn_plan_unary.argtypes = [C.c_int, T, T, C.c_uint32, I]
+        L.ocn_plan_binary.argtypes = [C.c_int, T, T, T, C.c_uint32, I]
+        L.ocn_plan_reduce.argtypes = [C.c_int, T, C.POINTER(C.c_int32), C.c_int32, T, I]
+        _lib = L
+    return _lib
+
+
+@dataclass
+class Tensor:
+    """A view on device storage: the descriptor the C ABI takes, plus a keep-alive reference."""
+    base: int                      # device address of the storage start
+    dtype: str
+    sizes: Tuple[int, ...]
+    strides: Tuple[int, ...]       # bytes
+    offset: int = 0                # bytes
+    device: int = 0
+    keepalive: Any = field(default=None, repr=False, compare=False)
+
+    @staticmethod
+    def on_storage(storage, dtype: str, sizes: Sequence[int], strides: Sequence[int],
+                   offset: int = 0) -> "Tensor":
+        """View over a 1-D uint8 torch tensor living on a GPU."""
+        dev = storage.device.index if storage.device.index is not None else 0
+        return Tensor(storage.data_ptr(), dtype, tuple(sizes), tuple(strides), offset, dev, storage)
+
+    def desc(self) -> OcnTensor:
+        t = OcnTensor()
+        t.base = self.base
+        t.offset = self.offset
+        t.dtype = DTYPE_CODE[self.dtype] if isinstance(self.dtype, str) else int(self.dtype)
+        t.ndim = len(self.sizes)
+        for d in range(min(len(self.sizes), MAX_DIMS)):
+            t.size[d] = self.sizes[d]
+            t.stride[d] = self.strides[d]
+        t.device = self.device
+        return t
+
+
+def _stream(stream) -> int:
+    if stream is not None:
+        return int(stream)
+    import torch
+    return int(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(rc: int) -> None:
+    if rc != OK:
+        raise OcnError(rc)
+
+
+def _axes(axes: Sequence[int]):
+    return (C.c_int32 * max(len(axes), 1))(*axes), len(axes)
+
+
+def unary(op: str, a: Tensor, out: Tensor, flags: int = 0, stream=None) -> None:
+    _check(lib().ocn_unary(UNARY_CODE[op], C.byref(a.desc()), C.byref(out.desc()), flags, _stream(stream)))
+
+
+def binary(op: str, a: Tensor, b: Tensor, out: Tensor, flags: int = 0, stream=None) -> None:
+    _check(lib().ocn_binary(BINARY_CODE[op], C.byref(a.desc()), C.byref(b.desc()),
+                            C.byref(out.desc()), flags, _stream(stream)))
+
+
+def cast_copy(src: Tensor, dst: Tensor, stream=None) -> None:
+    _check(lib().ocn_cast_copy(C.byref(src.desc()), C.byref(dst.desc()), _stream(stream)))
+
+
+def reduce_workspace_bytes(op: str, a: Tensor, axes: Sequence[int], out: Tensor) -> int:
+    ax, n = _axes(axes)
+    return int(lib().ocn_reduce_workspace_bytes(REDUCE_CODE[op], C.byref(a.desc()), ax, n,
+                                                C.byref(out.desc())))
+
+
+def reduce(op: str, a: Tensor, axes: Sequence[int], out: Tensor, workspace=None, stream=None) -> None:
+    """`workspace`: a uint8 torch tensor on the device of at least reduce_workspace_bytes(...)
+    bytes, or None to have this wrapper allocate one through torch when the call needs it
+    (the library itself never allocates)."""
+    ax, n = _axes(axes)
+    ws_ptr, ws_bytes = None, 0
+    if workspace is None:
+        need = reduce_workspace_bytes(op, a, axes, out)
+        if need:
+            import torch
+            workspace = torch.empty(need, dtype=torch.uint8, device=f"cuda:{a.device}")
+    if workspace is not None:
+        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel()
+    _check(lib().ocn_reduce(REDUCE_CODE[op], C.byref(a.desc()), ax, n, C.byref(out.desc()),
+                            ws_ptr, ws_bytes, _stream(stream)))
+
+
+def promote(a: str, b: str) -> str:
+    rc = lib().ocn_promote(DTYPE_CODE[a], DTYPE_CODE[b])
+    _check(rc if rc < 0 else OK)
+    return DTYPES[rc]
+
+
+def dtype_size(dtype: str) -> int:
+    return int(lib().ocn_dtype_size(DTYPE_CODE[dtype]))
+
+
+def _info_dict(info: OcnPlanInfo) -> dict:
+    n, r = info.ndim, info.nred
+    return {
+        "kernel": KERNELS[info.kernel], "compute_dtype": DTYPES[info.compute_dtype],
+        "ndim": n, "size": tuple(info.size[:n]), "stride_out": tuple(info.stride_out[:n]),
+        "stride_a": tuple(info.stride_a[:n]), "stride_b": tuple(info.stride_b[:n]),
+        "offset_out": info.offset_out, "offset_a": info.offset_a, "offset_b": info.offset_b,
+        "red_size": tuple(info.red_size[:r]), "red_stride_a": tuple(info.red_stride_a[:r]),
+        "vec": info.vec, "tile_log2": tuple(info.tile_log2[:n]), "stage_a": bool(info.stage_a),
+        "stage_b": bool(info.stage_b), "specialised": bool(info.specialised), "passes": info.passes,
+        "grid": info.grid, "block": info.block, "split": info.split, "lds_bytes": info.lds_bytes,
+    }
+
+
+def plan_unary(op: str, a: Tensor, out: Tensor, flags: int = 0) -> dict:
+    info = OcnPlanInfo()
+    _check(lib().ocn_plan_unary(UNARY_CODE[op], C.byref(a.desc()), C.byref(out.desc()), flags, C.byref(info)))
+    return _info_dict(info)
+
+
+def plan_binary(op: str, a: Tensor, b: Tensor, out: Tensor, flags: int = 0) -> dict:
+    info = OcnPlanInfo()
+    _check(lib().ocn_plan_binary(BINARY_CODE[op], C.byref(a.desc()), C.byref(b.desc()),
+                                 C.byref(out.desc()), flags, C.byref(info)))
+    return _info_dict(info)
+
+
+def plan_reduce(op: str, a: Tensor, axes: Sequence[int], out: Tensor) -> dict:
+    info = OcnPlanInfo()
+    ax, n = _axes(axes)
+    _check(lib().ocn_plan_reduce(REDUCE_CODE[op], C.byref(a.desc()), ax, n, C.byref(out.desc()), C.byref(info)))
+    return _info_dict(info)

@@ -1,0 +1,165 @@
+// C ABI of the tensor engine (see include/ocn.h): argument checks, planning, launch.
+#include <hip/hip_runtime.h>
+
+#include <mutex>
+
+#include "../../include/ocn.h"
+#include "ew_launch.hpp"
+#include "planner.hpp"
+#include "red_launch.hpp"
+
+namespace ocn {
+
+// the internal numbering must match the public header
+static_assert(DT_BOOL == OCN_BOOL && DT_I64 == OCN_INT64 && DT_U8 == OCN_UINT8 && DT_U64 == OCN_UINT64 &&
+              DT_F16 == OCN_HALF && DT_F64 == OCN_DOUBLE && DT_C16 == OCN_CHALF && DT_C64 == OCN_CDOUBLE &&
+              DT_COUNT == OCN_NUM_DTYPES, "dtype numbering");
+static_assert(B_ADD == OCN_B_ADD && B_MAX == OCN_B_MAX && B_BAND == OCN_B_BAND && B_LAND == OCN_B_LAND &&
+              B_EQ == OCN_B_EQ && B_GE == OCN_B_GE && B_ABSGT == OCN_B_ABSGT && B_COUNT == OCN_NUM_BINARY,
+              "binary op numbering");
+static_assert(U_IDENT == OCN_U_IDENT && U_NEG == OCN_U_NEG && U_ABS == OCN_U_ABS && U_CONJ == OCN_U_CONJ &&
+              U_LNOT == OCN_U_LNOT && U_BNOT == OCN_U_BNOT && U_SQRT == OCN_U_SQRT && U_COUNT == OCN_NUM_UNARY,
+              "unary op numbering");
+static_assert(R_SUM == OCN_R_SUM && R_PROD == OCN_R_PROD && R_MIN == OCN_R_MIN && R_MAX == OCN_R_MAX &&
+              R_ANY == OCN_R_ANY && R_ALL == OCN_R_ALL && R_COUNT == OCN_NUM_REDUCE, "reduce op numbering");
+
+void register_ew_slice_0(); void register_ew_slice_1(); void register_ew_slice_2(); void register_ew_slice_3();
+void register_ew_slice_4(); void register_ew_slice_5(); void register_ew_slice_6(); void register_ew_slice_7();
+void register_red_slice_0(); void register_red_slice_1(); void register_red_slice_2(); void register_red_slice_3();
+
+static std::once_flag g_once;
+static void ensure_registered() {
+  std::call_once(g_once, [] {
+    register_ew_slice_0(); register_ew_slice_1(); register_ew_slice_2(); register_ew_slice_3();
+    register_ew_slice_4(); register_ew_slice_5(); register_ew_slice_6(); register_ew_slice_7();
+    register_red_slice_0(); register_red_slice_1(); register_red_slice_2(); register_red_slice_3();
+  });
+}
+
+static thread_local int g_last_hip_error = 0;
+
+static int finish(hipError_t e) {
+  if (e == hipSuccess) return OCN_OK;
+  g_last_hip_error = (int)e;
+  return OCN_ERR_LAUNCH;
+}
+
+static int run_elementwise(const EwPlan &p, hipStream_t stream) {
+  if (p.kernel == OCN_KERNEL_NONE) return OCN_OK;
+  ensure_registered();
+  if (!p.specialised) return finish(launch_interp(p, stream));
+  EwLauncher f = p.nin == 2 ? g_binary_launchers[p.op][p.a.dtype][p.b.dtype][p.out.dtype]
+                            : g_unary_launchers[p.op][p.a.dtype][p.out.dtype];
+  if (!f) return finish(launch_interp(p, stream));
+  return finish(f(p, stream));
+}
+
+}  // namespace ocn
+
+using namespace ocn;
+
+extern "C" {
+
+int ocn_unary(int op, const ocn_tensor *a, const ocn_tensor *out, uint32_t flags, void *stream) {
+  EwPlan p;
+  const int rc = plan_elementwise(1, op, a, nullptr, out, flags, &p);
+  if (rc != OCN_OK) return rc;
+  return run_elementwise(p, (hipStream_t)stream);
+}
+
+int ocn_binary(int op, const ocn_tensor *a, const ocn_tensor *b, const ocn_tensor *out,
+               uint32_t flags, void *stream) {
+  EwPlan p;
+  const int rc = plan_elementwise(2, op, a, b, out, flags, &p);
+  if (rc != OCN_OK) return rc;
+  return run_elementwise(p, (hipStream_t)stream);
+}
+
+int ocn_cast_copy(const ocn_tensor *src, const ocn_tensor *dst, void *stream) {
+  return ocn_unary(OCN_U_IDENT, src, dst, 0, stream);
+}
+
+int ocn_reduce(int op, const ocn_tensor *a, const int32_t *axes, int32_t naxes,
+               const ocn_tensor *out, void *workspace, size_t workspace_bytes, void *stream) {
+  RedPlan p;
+  const int rc = plan_reduce(op, a, axes, naxes, out, &p);
+  if (rc != OCN_OK) return rc;
+  if (p.kernel == OCN_KERNEL_NONE) return OCN_OK;
+  if (p.workspace_bytes > 0) {
+    if (!workspace || workspace_bytes < p.workspace_bytes) return OCN_ERR_WORKSPACE;
+    if ((uintptr_t)workspace % 256 != 0) return OCN_ERR_ALIGN;
+  }
+  ensure_registered();
+  RedLauncher f = g_reduce_launchers[p.op][p.a_dtype];
+  if (!f) return OCN_ERR_DTYPE;
+  int st = finish(f(p, (char *)workspace, (hipStream_t)stream));
+  if (st != OCN_OK || p.split == 1) return st;
+  RedPlan q;
+  plan_second_pass(p, (char *)workspace, &q);
+  RedLauncher g = g_reduce_launchers[q.op][q.a_dtype];
+  if (!g) return OCN_ERR_DTYPE;
+  return finish(g(q, nullptr, (hipStream_t)stream));
+}
+
+size_t ocn_reduce_workspace_bytes(int op, const ocn_tensor *a, const int32_t *axes, int32_t naxes,
+                                  const ocn_tensor *out) {
+  RedPlan p;
+  if (plan_reduce(op, a, axes, naxes, out, &p) != OCN_OK) return 0;
+  return p.workspace_bytes;
+}
+
+int ocn_promote(int dtype_a, int dtype_b) { return promote(dtype_a, dtype_b); }
+
+int ocn_dtype_size(int dtype) { return dtype >= 0 && dtype < DT_COUNT ? dt_size(dtype) : 0; }
+
+const char *ocn_error_string(int code) {
+  switch (code) {
+    case OCN_OK: return "success";
+    case OCN_ERR_NULLPTR: return "a required pointer is null";
+    case OCN_ERR_DTYPE: return "invalid dtype, operation not defined for the type, or strict type mismatch";
+    case OCN_ERR_NDIM: return "number of dimensions outside 0..8";
+    case OCN_ERR_SHAPE: return "shapes are not compatible";
+    case OCN_ERR_DEVICE: return "operands are on different devices";
+    case OCN_ERR_ALIGN: return "offset, stride or pointer is not aligned to the element's scalar size";
+    case OCN_ERR_OVERLAP_OUT: return "the output view overlaps itself";
+    case OCN_ERR_ALIAS: return "an input overlaps the output without being the same view";
+    case OCN_ERR_WORKSPACE: return "reduction workspace missing or too small";
+    case OCN_ERR_EMPTY: return "min/max over zero elements";
+    case OCN_ERR_LAUNCH: return "HIP runtime error";
+    case OCN_ERR_OP: return "unknown operation";
+    default: return "unknown status code";
+  }
+}
+
+int ocn_last_hip_error(void) { return g_last_hip_error; }
+
+int ocn_plan_unary(int op, const ocn_tensor *a, const ocn_tensor *out, uint32_t flags, ocn_plan_info *info) {
+  if (!info) return OCN_ERR_NULLPTR;
+  EwPlan p;
+  const int rc = plan_elementwise(1, op, a, nullptr, out, flags, &p);
+  if (rc != OCN_OK) return rc;
+  fill_info(p, info);
+  return OCN_OK;
+}
+
+int ocn_plan_binary(int op, const ocn_tensor *a, const ocn_tensor *b, const ocn_tensor *out,
+                    uint32_t flags, ocn_plan_info *info) {
+  if (!info) return OCN_ERR_NULLPTR;
+  EwPlan p;
+  const int rc = plan_elementwise(2, op, a, b, out, flags, &p);
+  if (rc != OCN_OK) return rc;
+  fill_info(p, info);
+  return OCN_OK;
+}
+
+int ocn_plan_reduce(int op, const ocn_tensor *a, const int32_t *axes, int32_t naxes,
+                    const ocn_tensor *out, ocn_plan_info *info) {
+  if (!info) return OCN_ERR_NULLPTR;
+  RedPlan p;
+  const int rc = plan_reduce(op, a, axes, naxes, out, &p);
+  if (rc != OCN_OK) return rc;
+  fill_info(p, info);
+  return OCN_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,113 @@
+// Generic-dtype elementwise kernel: any combination of the fifteen element types, with the
+// conversions picked by (wavefront-uniform) runtime switches.  It serves the combinations for
+// which no dtype-specialised kernel is instantiated; one element per lane, 64-bit index math.
+#include "ew_launch.hpp"
+
+namespace ocn {
+
+// load an element of runtime dtype `dt` and convert it to compile-time type T
+template <int T> __device__ __noinline__ reg_t<T> load_as(const char *p, int dt) {
+  switch (dt) {
+#define OCN_CASE(D) \
+  case D: return convert<T>(from_storage<D>(*reinterpret_cast<const storage_t<D> *>(p)));
+    OCN_CASE(DT_BOOL) OCN_CASE(DT_I8) OCN_CASE(DT_I16) OCN_CASE(DT_I32) OCN_CASE(DT_I64)
+    OCN_CASE(DT_U8) OCN_CASE(DT_U16) OCN_CASE(DT_U32) OCN_CASE(DT_U64)
+    OCN_CASE(DT_F16) OCN_CASE(DT_F32) OCN_CASE(DT_F64)
+    OCN_CASE(DT_C16) OCN_CASE(DT_C32) OCN_CASE(DT_C64)
+#undef OCN_CASE
+    default: return reg_t<T>{};
+  }
+}
+
+// convert a register value to runtime dtype `dt` and store it
+template <class R> __device__ __noinline__ void store_as(char *p, int dt, R r) {
+  switch (dt) {
+#define OCN_CASE(D) \
+  case D: *reinterpret_cast<storage_t<D> *>(p) = to_storage<D>(convert<D>(r)); break;
+    OCN_CASE(DT_BOOL) OCN_CASE(DT_I8) OCN_CASE(DT_I16) OCN_CASE(DT_I32) OCN_CASE(DT_I64)
+    OCN_CASE(DT_U8) OCN_CASE(DT_U16) OCN_CASE(DT_U32) OCN_CASE(DT_U64)
+    OCN_CASE(DT_F16) OCN_CASE(DT_F32) OCN_CASE(DT_F64)
+    OCN_CASE(DT_C16) OCN_CASE(DT_C32) OCN_CASE(DT_C64)
+#undef OCN_CASE
+    default: break;
+  }
+}
+
+template <int T, int OP> OCN_DEV void binary_one(const InterpArgs &p, reg_t<T> a, reg_t<T> b, char *po) {
+  // logical operations always compute in bool
+  if constexpr (binary_supported(OP, T) && (!is_logical(OP) || T == DT_BOOL)) {
+    auto r = apply_binary<OP, T>(a, b);
+    // arithmetic and bitwise results already have the output type (T is out's dtype)
+    if constexpr (is_arith(OP) || is_bitwise(OP)) *reinterpret_cast<storage_t<T> *>(po) = to_storage<T>(r);
+    else store_as<bool>(po, p.dt_o, r);
+  }
+}
+
+template <int T, int OP> OCN_DEV void unary_one(const InterpArgs &p, reg_t<T> a, char *po) {
+  if constexpr (unary_supported(OP, T) && (OP != U_LNOT || T == DT_BOOL)) {
+    auto r = apply_unary<OP, T>(a);
+    if constexpr (OP == U_LNOT) store_as<bool>(po, p.dt_o, r);
+    else *reinterpret_cast<storage_t<T> *>(po) = to_storage<T>(r);
+  }
+}
+
+template <int T> OCN_DEV void interp_body(const InterpArgs &p, const char *pa, const char *pb, char *po) {
+  const reg_t<T> a = load_as<T>(pa, p.dt_a);
+  if (p.nin == 2) {
+    const reg_t<T> b = load_as<T>(pb, p.dt_b);
+    switch (p.op) {
+#define OCN_CASE(O) case O: binary_one<T, O>(p, a, b, po); break;
+      OCN_CASE(B_ADD) OCN_CASE(B_SUB) OCN_CASE(B_MUL) OCN_CASE(B_DIV) OCN_CASE(B_MIN) OCN_CASE(B_MAX)
+      OCN_CASE(B_BAND) OCN_CASE(B_BOR) OCN_CASE(B_BXOR) OCN_CASE(B_LAND) OCN_CASE(B_LOR) OCN_CASE(B_LXOR)
+      OCN_CASE(B_EQ) OCN_CASE(B_NE) OCN_CASE(B_LT) OCN_CASE(B_LE) OCN_CASE(B_GT) OCN_CASE(B_GE)
+      OCN_CASE(B_ABSGT)
+#undef OCN_CASE
+      default: break;
+    }
+  } else {
+    switch (p.op) {
+#define OCN_CASE(O) case O: unary_one<T, O>(p, a, po); break;
+      OCN_CASE(U_IDENT) OCN_CASE(U_NEG) OCN_CASE(U_ABS) OCN_CASE(U_CONJ) OCN_CASE(U_LNOT)
+      OCN_CASE(U_BNOT) OCN_CASE(U_SQRT)
+#undef OCN_CASE
+      default: break;
+    }
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void ew_interp_kernel(const InterpArgs p) {
+  int64_t lin = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (lin >= p.numel) return;
+  int64_t off_o = 0, off_a = 0, off_b = 0;
+#pragma unroll
+  for (int d = kMaxDims - 1; d >= 0; --d) {
+    if (d < p.ndim) {
+      const int64_t q = lin / p.size[d];
+      const int64_t i = lin - q * p.size[d];
+      lin = q;
+      off_o += i * p.so[d];
+      off_a += i * p.sa[d];
+      off_b += i * p.sb[d];
+    }
+  }
+  const char *pa = p.a + off_a;
+  const char *pb = p.nin == 2 ? p.b + off_b : nullptr;
+  char *po = p.out + off_o;
+  switch (p.T) {
+#define OCN_CASE(D) case D: interp_body<D>(p, pa, pb, po); break;
+    OCN_CASE(DT_BOOL) OCN_CASE(DT_I8) OCN_CASE(DT_I16) OCN_CASE(DT_I32) OCN_CASE(DT_I64)
+    OCN_CASE(DT_U8) OCN_CASE(DT_U16) OCN_CASE(DT_U32) OCN_CASE(DT_U64)
+    OCN_CASE(DT_F16) OCN_CASE(DT_F32) OCN_CASE(DT_F64)
+    OCN_CASE(DT_C16) OCN_CASE(DT_C32) OCN_CASE(DT_C64)
+#undef OCN_CASE
+    default: break;
+  }
+}
+
+hipError_t launch_interp(const EwPlan &p, hipStream_t stream) {
+  const InterpArgs args = make_interp_args(p);
+  hipLaunchKernelGGL(ew_interp_kernel, dim3((unsigned)p.grid), dim3(kBlock), 0, stream, args);
+  return hipGetLastError();
+}
+
+}  // namespace ocn

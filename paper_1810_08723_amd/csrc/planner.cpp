@@ -1,0 +1,765 @@
+// Host planner: see planner.hpp.  Plain C++, no HIP.
+#include "planner.hpp"
+
+#include <algorithm>
+#include <cstdlib>
+#include <cstring>
+
+#include "sigs.hpp"
+
+namespace ocn {
+
+// ---------------------------------------------------------------------------------------
+// small helpers
+// ---------------------------------------------------------------------------------------
+
+FastDiv make_fastdiv(uint32_t d) {
+  // q = (mulhi(n, m) + n) >> s with s = ceil(log2 d), m = floor(2^32 (2^s - d) / d) + 1;
+  // exact for every n < 2^31
+  FastDiv f;
+  f.d = d ? d : 1;
+  uint32_t s = 0;
+  while (((uint64_t)1 << s) < f.d) ++s;
+  f.s = s;
+  f.m = (uint32_t)(((((uint64_t)1 << s) - f.d) << 32) / f.d + 1);
+  return f;
+}
+
+static bool valid_dtype(int dt) { return dt >= 0 && dt < DT_COUNT; }
+static int scalar_size(int dt) { return dt_size(dt_real_of(dt)); }
+
+static int check_tensor(const ocn_tensor *t) {
+  if (!t) return OCN_ERR_NULLPTR;
+  if (!valid_dtype(t->dtype)) return OCN_ERR_DTYPE;
+  if (t->ndim < 0 || t->ndim > kMaxDims) return OCN_ERR_NDIM;
+  bool empty = false;
+  for (int d = 0; d < t->ndim; ++d) {
+    if (t->size[d] < 0) return OCN_ERR_SHAPE;
+    if (t->size[d] == 0) empty = true;
+  }
+  if (!empty && !t->base) return OCN_ERR_NULLPTR;
+  return OCN_OK;
+}
+
+static int check_alignment(const ocn_tensor *t) {
+  const int64_t sc = scalar_size(t->dtype);
+  if (((intptr_t)t->base + t->offset) % sc != 0) return OCN_ERR_ALIGN;
+  for (int d = 0; d < t->ndim; ++d)
+    if (t->size[d] > 1 && t->stride[d] % sc != 0) return OCN_ERR_ALIGN;
+  return OCN_OK;
+}
+
+// [lo, hi) of the bytes a view touches, relative to address zero
+static void byte_range(const ocn_tensor *t, intptr_t *lo, intptr_t *hi) {
+  intptr_t l = (intptr_t)t->base + t->offset, h = l;
+  for (int d = 0; d < t->ndim; ++d) {
+    if (t->size[d] <= 1) continue;
+    int64_t span = (t->size[d] - 1) * t->stride[d];
+    if (span < 0) l += span; else h += span;
+  }
+  *lo = l;
+  *hi = h + dt_size(t->dtype);
+}
+
+// Conservative proof that no byte of the view is addressed twice: with dimensions sorted by
+// |stride|, each stride must step over everything the faster dimensions span.
+static bool provably_non_overlapping(const ocn_tensor *t) {
+  int64_t st[kMaxDims], sz[kMaxDims];
+  int n = 0;
+  for (int d = 0; d < t->ndim; ++d) {
+    if (t->size[d] <= 1) continue;
+    st[n] = std::llabs(t->stride[d]);
+    sz[n] = t->size[d];
+    ++n;
+  }
+  for (int i = 1; i < n; ++i)  // insertion sort by stride, ascending
+    for (int j = i; j > 0 && st[j] < st[j - 1]; --j) {
+      std::swap(st[j], st[j - 1]);
+      std::swap(sz[j], sz[j - 1]);
+    }
+  int64_t extent = dt_size(t->dtype);  // bytes spanned so far
+  for (int i = 0; i < n; ++i) {
+    if (st[i] < extent) return false;
+    extent = (sz[i] - 1) * st[i] + extent;
+  }
+  return true;
+}
+
+// ---------------------------------------------------------------------------------------
+// implicit casting (section 3.2.1): the smallest type that can keep both
+// ---------------------------------------------------------------------------------------
+
+static int int_bits_of(int dt) { return dt_size(dt) * 8; }
+
+static int float_for_bits(int need_bits, int at_least) {
+  // smallest real floating type with >= need_bits of exact integer range and >= at_least
+  int r = at_least;
+  if (need_bits > 11 && r < DT_F32) r = DT_F32;
+  if (need_bits > 24 && r < DT_F64) r = DT_F64;
+  return r;
+}
+
+static int promote_real(int a, int b) {
+  const int ka = dt_kind(a), kb = dt_kind(b);
+  if (ka == K_BOOL) return b;
+  if (kb == K_BOOL) return a;
+  if (ka == K_REAL && kb == K_REAL) return std::max(a, b);
+  if (ka == K_REAL || kb == K_REAL) {
+    const int f = ka == K_REAL ? a : b, i = ka == K_REAL ? b : a;
+    // magnitude bits an integer type needs to be held exactly by a float significand
+    const int need = dt_kind(i) == K_SINT ? int_bits_of(i) - 1 : int_bits_of(i);
+    if (need > 53) return DT_F64;  // the paper's stated exception for 64-bit integers
+    return float_for_bits(need, f);
+  }
+  if (ka == kb) return int_bits_of(a) >= int_bits_of(b) ? a : b;
+  // signed with unsigned: a signed type strictly wider than the unsigned one
+  const int s = ka == K_SINT ? a : b, u = ka == K_SINT ? b : a;
+  const int ub = int_bits_of(u), sb = int_bits_of(s);
+  if (sb > ub) return s;
+  switch (ub) {
+    case 8: return DT_I16;
+    case 16: return DT_I32;
+    case 32: return DT_I64;
+    default: return DT_F64;  // nothing keeps uint64 and a signed integer
+  }
+}
+
+int promote(int a, int b) {
+  if (!valid_dtype(a) || !valid_dtype(b)) return OCN_ERR_DTYPE;
+  if (dt_kind(a) == K_CPLX || dt_kind(b) == K_CPLX) {
+    const int r = promote_real(dt_real_of(a), dt_real_of(b));
+    return r == DT_F16 ? DT_C16 : r == DT_F32 ? DT_C32 : DT_C64;
+  }
+  return promote_real(a, b);
+}
+
+// ---------------------------------------------------------------------------------------
+// elementwise planning
+// ---------------------------------------------------------------------------------------
+
+namespace {
+
+struct Dim {
+  int64_t size;
+  int64_t so, sa, sb;
+};
+
+int64_t iabs64(int64_t x) { return x < 0 ? -x : x; }
+
+int ilog2_ceil(int64_t x) {
+  int l = 0;
+  while (((int64_t)1 << l) < x) ++l;
+  return l;
+}
+
+// is the input the identical view as the output (same address, element size and strides)?
+bool same_view(const ocn_tensor *in, const ocn_tensor *out) {
+  if ((intptr_t)in->base + in->offset != (intptr_t)out->base + out->offset) return false;
+  if (dt_size(in->dtype) != dt_size(out->dtype)) return false;
+  if (in->ndim != out->ndim) return false;
+  for (int d = 0; d < out->ndim; ++d) {
+    if (in->size[d] != out->size[d]) return false;
+    if (out->size[d] > 1 && in->stride[d] != out->stride[d]) return false;
+  }
+  return true;
+}
+
+int check_alias(const ocn_tensor *in, const ocn_tensor *out) {
+  if (same_view(in, out)) return OCN_OK;
+  intptr_t ilo, ihi, olo, ohi;
+  byte_range(in, &ilo, &ihi);
+  byte_range(out, &olo, &ohi);
+  if (ilo < ohi && olo < ihi) return OCN_ERR_ALIAS;
+  return OCN_OK;
+}
+
+int check_broadcast(const ocn_tensor *in, const ocn_tensor *out) {
+  if (in->ndim > out->ndim) return OCN_ERR_SHAPE;
+  const int lead = out->ndim - in->ndim;
+  for (int d = 0; d < in->ndim; ++d)
+    if (in->size[d] != out->size[lead + d] && in->size[d] != 1) return OCN_ERR_SHAPE;
+  return OCN_OK;
+}
+
+// stride of input along out's dimension d (zero where the input is broadcast)
+int64_t bstride(const ocn_tensor *in, const ocn_tensor *out, int d) {
+  const int lead = out->ndim - in->ndim;
+  if (d < lead) return 0;
+  return in->size[d - lead] == 1 ? 0 : in->stride[d - lead];
+}
+
+// the dimension with the smallest non-zero |stride| (ties: the later one); -1 if none
+template <class Get> int fastest_dim(int n, Get stride_of) {
+  int best = -1;
+  int64_t bs = 0;
+  for (int d = 0; d < n; ++d) {
+    int64_t s = iabs64(stride_of(d));
+    if (s == 0) continue;
+    if (best < 0 || s <= bs) { best = d; bs = s; }
+  }
+  return best;
+}
+
+// order the tiled dims of one operand by that operand's |stride|, fastest first; zero
+// strides (broadcast) go last since they do not affect coalescing
+void tile_order(const EwPlan &p, const int64_t *stride, int8_t *ord) {
+  int n = 0;
+  for (int d = p.ndim - 1; d >= 0; --d)
+    if (p.tile_log2[d] > 0) ord[n++] = (int8_t)d;
+  auto key = [&](int d) {
+    int64_t s = iabs64(stride[d]);
+    return s == 0 ? INT64_MAX : s;
+  };
+  for (int i = 1; i < n; ++i)
+    for (int j = i; j > 0 && key(ord[j]) < key(ord[j - 1]); --j) std::swap(ord[j], ord[j - 1]);
+}
+
+constexpr int64_t kMaxLdsBytes = 64 * 1024;  // per workgroup: two workgroups share a CU's 160 KB
+
+void choose_tiles(EwPlan &p) {
+  // Operands that want coalescing along their own fastest axis: the output and every staged
+  // input.  Hand out tile bits round-robin, each operand growing its fastest unsaturated
+  // dimension, until the tile holds 2^budget elements.
+  const int es_o = dt_size(p.out.dtype), es_a = dt_size(p.a.dtype);
+  const int es_b = p.nin == 2 ? dt_size(p.b.dtype) : 0;
+  int staged_bytes = (p.stage_a ? es_a : 0) + (p.stage_b ? es_b : 0);
+  int budget = 12;
+  while (budget > 8 && ((int64_t)staged_bytes << budget) + ((int64_t)staged_bytes << (budget - 1)) > kMaxLdsBytes)
+    --budget;
+  (void)es_o;
+  const int64_t *strides[3] = {p.out.stride, p.a.stride, p.b.stride};
+  bool wants[3] = {true, p.stage_a, p.stage_b};
+  int used = 0;
+  auto saturated = [&](int d) { return ((int64_t)1 << p.tile_log2[d]) >= p.size[d]; };
+  bool progress = true;
+  while (used < budget && progress) {
+    progress = false;
+    for (int o = 0; o < 3 && used < budget; ++o) {
+      if (!wants[o]) continue;
+      // fastest unsaturated dim of this operand
+      int best = -1;
+      int64_t bs = 0;
+      for (int d = 0; d < p.ndim; ++d) {
+        if (saturated(d)) continue;
+        int64_t s = iabs64(strides[o][d]);
+        if (s == 0) continue;
+        if (best < 0 || s < bs || (s == bs && d > best)) { best = d; bs = s; }
+      }
+      if (best < 0) continue;
+      ++p.tile_log2[best];
+      ++used;
+      progress = true;
+    }
+  }
+  p.tile_bits = used;
+}
+
+}  // namespace
+
+int plan_elementwise(int nin, int op, const ocn_tensor *a, const ocn_tensor *b,
+                     const ocn_tensor *out, uint32_t flags, EwPlan *plan) {
+  EwPlan p;
+  p.nin = nin;
+  p.op = op;
+  int rc;
+  if ((rc = check_tensor(a)) != OCN_OK) return rc;
+  if (nin == 2 && (rc = check_tensor(b)) != OCN_OK) return rc;
+  if ((rc = check_tensor(out)) != OCN_OK) return rc;
+  if (nin == 2 ? (op < 0 || op >= B_COUNT) : (op < 0 || op >= U_COUNT)) return OCN_ERR_OP;
+  if (a->device != out->device || (nin == 2 && b->device != out->device)) return OCN_ERR_DEVICE;
+  if ((rc = check_broadcast(a, out)) != OCN_OK) return rc;
+  if (nin == 2 && (rc = check_broadcast(b, out)) != OCN_OK) return rc;
+
+  // compute type and strict-mode checks (section 3.2.1)
+  const int sa = a->dtype, sb = nin == 2 ? b->dtype : a->dtype, so = out->dtype;
+  if (nin == 2) {
+    if ((flags & OCN_STRICT_TYPES) && sa != sb) return OCN_ERR_DTYPE;
+    if ((flags & OCN_STRICT_TYPES) && !is_compare(op) && !is_logical(op) && sa != so) return OCN_ERR_DTYPE;
+    p.T = binary_compute_dtype(op, sa, sb, so, promote(sa, sb));
+    if (!binary_supported(op, p.T)) return OCN_ERR_DTYPE;
+    p.specialised = binary_specialised(op, sa, sb, so);
+  } else {
+    if ((flags & OCN_STRICT_TYPES) && op != U_LNOT && sa != so) return OCN_ERR_DTYPE;
+    p.T = unary_compute_dtype(op, so);
+    if (!unary_supported(op, p.T)) return OCN_ERR_DTYPE;
+    p.specialised = unary_specialised(op, sa, so);
+  }
+
+  int64_t numel = 1;
+  for (int d = 0; d < out->ndim; ++d) numel *= out->size[d];
+  p.numel = numel;
+  if (numel == 0) {  // nothing to do
+    *plan = p;
+    return OCN_OK;
+  }
+  if ((rc = check_alignment(a)) != OCN_OK) return rc;
+  if (nin == 2 && (rc = check_alignment(b)) != OCN_OK) return rc;
+  if ((rc = check_alignment(out)) != OCN_OK) return rc;
+  if (!provably_non_overlapping(out)) return OCN_ERR_OVERLAP_OUT;
+  if ((rc = check_alias(a, out)) != OCN_OK) return rc;
+  if (nin == 2 && (rc = check_alias(b, out)) != OCN_OK) return rc;
+
+  // ---- canonical dimension list ---------------------------------------------------------
+  Dim dims[kMaxDims];
+  int n = 0;
+  int64_t off_o = out->offset, off_a = a->offset, off_b = nin == 2 ? b->offset : 0;
+  for (int d = 0; d < out->ndim; ++d) {
+    if (out->size[d] == 1) continue;  // drop
+    Dim x{out->size[d], out->stride[d], bstride(a, out, d), nin == 2 ? bstride(b, out, d) : 0};
+    if (x.so < 0) {  // flip so that the output walks forward
+      off_o += (x.size - 1) * x.so;
+      off_a += (x.size - 1) * x.sa;
+      off_b += (x.size - 1) * x.sb;
+      x.so = -x.so; x.sa = -x.sa; x.sb = -x.sb;
+    }
+    dims[n++] = x;
+  }
+  // sort by output stride, slowest first (insertion sort: n <= 8, and stable)
+  for (int i = 1; i < n; ++i)
+    for (int j = i; j > 0 && dims[j].so > dims[j - 1].so; --j) std::swap(dims[j], dims[j - 1]);
+  // merge neighbours that every operand walks as one longer dimension
+  int m = 0;
+  for (int i = 0; i < n; ++i) {
+    if (m > 0) {
+      Dim &u = dims[m - 1];
+      const Dim &v = dims[i];
+      if (u.so == v.so * v.size && u.sa == v.sa * v.size && u.sb == v.sb * v.size) {
+        u.size *= v.size;
+        u.so = v.so; u.sa = v.sa; u.sb = v.sb;
+        continue;
+      }
+    }
+    dims[m++] = dims[i];
+  }
+  n = m;
+  if (n == 0) {  // a single element
+    dims[0] = Dim{1, (int64_t)dt_size(so), 0, 0};
+    n = 1;
+  }
+  p.ndim = n;
+  for (int d = 0; d < n; ++d) {
+    p.size[d] = dims[d].size;
+    p.out.stride[d] = dims[d].so;
+    p.a.stride[d] = dims[d].sa;
+    p.b.stride[d] = dims[d].sb;
+  }
+  p.off_out = off_o; p.off_a = off_a; p.off_b = off_b;
+  p.out.ptr = (char *)out->base + off_o; p.out.dtype = so;
+  p.a.ptr = (char *)a->base + off_a; p.a.dtype = sa;
+  p.b.ptr = nin == 2 ? (char *)b->base + off_b : nullptr; p.b.dtype = sb;
+
+  // ---- kernel selection ------------------------------------------------------------------
+  const int es_o = dt_size(so), es_a = dt_size(sa), es_b = dt_size(sb);
+  const int inner = n - 1;
+  const int es_min = std::min({es_o, es_a, nin == 2 ? es_b : es_a});
+  const int es_max = std::max({es_o, es_a, nin == 2 ? es_b : es_a});
+  const int V = rows_vec(es_min, es_max);
+  auto inner_ok = [&](int64_t stride, int es) { return stride == es || stride == 0; };
+  bool rows = p.specialised && p.out.stride[inner] == es_o && inner_ok(p.a.stride[inner], es_a) &&
+              (nin == 1 || inner_ok(p.b.stride[inner], es_b));
+  if (rows) {
+    // every row start of every non-broadcast operand must be aligned to its vector
+    auto aligned = [&](const Operand &x, int es) {
+      if (x.stride[inner] == 0) return true;
+      const int64_t vb = (int64_t)V * es;
+      if ((intptr_t)x.ptr % vb != 0) return false;
+      for (int d = 0; d < inner; ++d)
+        if (x.stride[d] % vb != 0) return false;
+      return true;
+    };
+    rows = aligned(p.out, es_o) && aligned(p.a, es_a) && (nin == 1 || aligned(p.b, es_b));
+    // 32-bit vector and row indices (a flat 1-D tensor needs no division and may be larger)
+    const int64_t vpr = (p.size[inner] + V - 1) / V;
+    const int64_t nrows = numel / p.size[inner];
+    if (n > 1 && (vpr * nrows >= ((int64_t)1 << 31))) rows = false;
+    if (rows) {
+      p.kernel = OCN_KERNEL_EW_ROWS;
+      p.vec = V;
+      p.unroll = rows_unroll(V, es_max);
+      p.a_inner_bcast = p.a.stride[inner] == 0;
+      p.b_inner_bcast = nin == 2 && p.b.stride[inner] == 0;
+      const int64_t nvec = vpr * nrows;
+      p.grid = (nvec + (int64_t)kBlock * p.unroll - 1) / ((int64_t)kBlock * p.unroll);
+      p.lds_bytes = 0;
+      *plan = p;
+      return OCN_OK;
+    }
+  }
+
+  if (!p.specialised) {
+    // generic-dtype kernel: one element per lane, conversions through runtime switches
+    p.kernel = OCN_KERNEL_EW_GENERIC;
+    p.vec = 1;
+    p.grid = (numel + kBlock - 1) / kBlock;
+    *plan = p;
+    return OCN_OK;
+  }
+
+  // tiled / generic: stage an input through LDS when its fastest axis is not the output's
+  const int fo = inner;  // the output's fastest dim after sorting
+  const int fa = fastest_dim(n, [&](int d) { return p.a.stride[d]; });
+  const int fb = nin == 2 ? fastest_dim(n, [&](int d) { return p.b.stride[d]; }) : -1;
+  p.stage_a = fa >= 0 && fa != fo;
+  p.stage_b = fb >= 0 && fb != fo;
+  choose_tiles(p);
+  tile_order(p, p.out.stride, p.ord_o);
+  tile_order(p, p.a.stride, p.ord_a);
+  tile_order(p, p.b.stride, p.ord_b);
+  p.nord = 0;
+  for (int d = 0; d < n; ++d)
+    if (p.tile_log2[d] > 0) ++p.nord;
+  // LDS slot = position in the output's enumeration order; a staged operand skews its
+  // slots by one element per step of its own fastest tiled dim to spread LDS banks
+  auto pad_shift = [&](const int8_t *ord) {
+    if (p.nord == 0) return 0;
+    int shift = 0;
+    for (int k = 0; k < p.nord; ++k) {
+      if (p.ord_o[k] == ord[0]) return shift;
+      shift += p.tile_log2[p.ord_o[k]];
+    }
+    return 0;
+  };
+  p.pad_shift_a = p.stage_a ? pad_shift(p.ord_a) : 0;
+  p.pad_shift_b = p.stage_b ? pad_shift(p.ord_b) : 0;
+  if (p.stage_a && p.pad_shift_a == 0) p.stage_a = false;  // same fastest tiled dim after all
+  if (p.stage_b && p.pad_shift_b == 0) p.stage_b = false;
+  const int64_t tile_elems = (int64_t)1 << p.tile_bits;
+  auto lds_elems = [&](int shift) { return tile_elems + (tile_elems >> shift) + 1; };
+  p.lds_bytes = 0;
+  if (p.stage_a) p.lds_bytes += (lds_elems(p.pad_shift_a) * es_a + 15) / 16 * 16;
+  if (p.stage_b) p.lds_bytes += (lds_elems(p.pad_shift_b) * es_b + 15) / 16 * 16;
+  p.total_tiles = 1;
+  for (int d = 0; d < n; ++d) {
+    p.ntiles[d] = (p.size[d] + ((int64_t)1 << p.tile_log2[d]) - 1) >> p.tile_log2[d];
+    p.total_tiles *= p.ntiles[d];
+  }
+  p.grid = p.total_tiles;
+  p.kernel = (p.stage_a || p.stage_b) ? OCN_KERNEL_EW_TILED : OCN_KERNEL_EW_GENERIC;
+  p.vec = 1;
+  *plan = p;
+  return OCN_OK;
+}
+
+// ---------------------------------------------------------------------------------------
+// reduction planning
+// ---------------------------------------------------------------------------------------
+
+bool reduce_supported(int op, int dt) {
+  if (op < 0 || op >= R_COUNT || !valid_dtype(dt)) return false;
+  const int k = dt_kind(dt);
+  switch (op) {
+    case R_SUM: case R_ANY: case R_ALL: return true;
+    default: return k != K_CPLX;
+  }
+}
+
+int reduce_acc_dtype(int op, int dt) {
+  const int k = dt_kind(dt);
+  switch (op) {
+    case R_SUM: case R_PROD:
+      if (k == K_BOOL || k == K_SINT) return DT_I64;
+      if (k == K_UINT) return DT_U64;
+      if (dt == DT_F16) return DT_F32;
+      if (dt == DT_F32 || dt == DT_F64) return DT_F64;
+      return dt == DT_C16 ? DT_C32 : DT_C64;
+    case R_MIN: case R_MAX: return dt;
+    default: return DT_BOOL;
+  }
+}
+
+namespace {
+
+struct RDim { int64_t size, sa, so; };
+
+int sort_merge(RDim *d, int n, bool by_out) {
+  auto key = [&](const RDim &x) { return by_out ? x.so : iabs64(x.sa); };
+  for (int i = 1; i < n; ++i)
+    for (int j = i; j > 0 && key(d[j]) > key(d[j - 1]); --j) std::swap(d[j], d[j - 1]);
+  int m = 0;
+  for (int i = 0; i < n; ++i) {
+    if (m > 0) {
+      RDim &u = d[m - 1];
+      const RDim &v = d[i];
+      if (u.sa == v.sa * v.size && u.so == v.so * v.size) {
+        u.size *= v.size; u.sa = v.sa; u.so = v.so;
+        continue;
+      }
+    }
+    d[m++] = d[i];
+  }
+  return m;
+}
+
+constexpr int64_t kTargetWaves = 256 * 8;  // enough wavefronts to occupy every CU
+
+void choose_reduce_launch(RedPlan &p) {
+  const int es = dt_size(p.a_dtype);
+  const int acc_es = dt_size(p.acc_dtype);
+  // fastest dims
+  const int64_t r_fast = p.nred ? iabs64(p.rstride_a[p.nred - 1]) : 0;
+  int64_t k_fast = 0;  // smallest non-zero kept stride of the input
+  int k_fast_dim = -1;
+  for (int d = 0; d < p.nkept; ++d) {
+    int64_t s = iabs64(p.kstride_a[d]);
+    if (s && (k_fast_dim < 0 || s <= k_fast)) { k_fast = s; k_fast_dim = d; }
+  }
+  const int vfull = std::max(1, 16 / es);
+  auto all_aligned = [&](int64_t vb, int skip_kept, int skip_red) {
+    if ((intptr_t)p.a_ptr % vb) return false;
+    for (int d = 0; d < p.nkept; ++d)
+      if (d != skip_kept && p.kstride_a[d] % vb) return false;
+    for (int d = 0; d < p.nred; ++d)
+      if (d != skip_red && p.rstride_a[d] % vb) return false;
+    return true;
+  };
+  bool idx32 = p.nout < ((int64_t)1 << 31) && p.nredtot < ((int64_t)1 << 31);
+  for (int d = 0; d < p.nkept; ++d) idx32 = idx32 && p.ksize[d] < ((int64_t)1 << 31);
+  for (int d = 0; d < p.nred; ++d) idx32 = idx32 && p.rsize[d] < ((int64_t)1 << 31);
+  // a flat contiguous full reduction may be longer than 2^31 elements
+  const bool flat_full = p.nkept == 0 && p.nred == 1;
+
+  if (p.nred >= 1 && r_fast == es && (k_fast_dim < 0 || k_fast > r_fast) && p.nredtot >= 32 &&
+      (idx32 || flat_full)) {
+    // ---- rows: the reduced axis is the input's fastest ---------------------------------
+    p.kernel = OCN_KERNEL_RED_ROWS;
+    p.vec = all_aligned((int64_t)vfull * es, -1, p.nred - 1) ? vfull : 1;
+    const int64_t n0 = p.rsize[p.nred - 1];
+    const int64_t vpr = (n0 + p.vec - 1) / p.vec;         // vectors per innermost run
+    const int64_t nvec = vpr * (p.nredtot / n0);          // vectors per output
+    p.group = (nvec * p.vec * es <= 32 * 1024) ? kWave : kBlock;
+    const int64_t groups_per_block = kBlock / p.group;
+    const int64_t waves = p.nout * (p.group / kWave);
+    p.split = 1;
+    if (waves < kTargetWaves) {
+      // split long reductions so the device fills; keep >= 16 vectors per lane per split
+      const int64_t want = (kTargetWaves + waves - 1) / waves;
+      const int64_t most = std::max<int64_t>(1, nvec / ((int64_t)p.group * 16));
+      p.split = std::max<int64_t>(1, std::min(want, most));
+    }
+    p.chunk = (nvec + p.split - 1) / p.split;
+    p.split = (nvec + p.chunk - 1) / p.chunk;
+    p.grid = (p.nout * p.split + groups_per_block - 1) / groups_per_block;
+  } else if (k_fast_dim >= 0 && k_fast == es && (p.nred == 0 || r_fast == 0 || r_fast > k_fast) &&
+             p.nredtot >= 1 && idx32 && k_fast_dim == p.nkept - 1 && p.nred >= 1) {
+    // ---- cols: a kept axis is the input's fastest; lanes own output columns -------------
+    // (requires that axis to be the last canonical kept dim, i.e. also the output's fastest)
+    p.kernel = OCN_KERNEL_RED_COLS;
+    p.vec = all_aligned((int64_t)vfull * es, p.nkept - 1, -1) ? vfull : 1;
+    const int64_t nc = p.ksize[p.nkept - 1];
+    const int64_t colblocks = (nc + (int64_t)kWave * p.vec - 1) / ((int64_t)kWave * p.vec);
+    const int64_t others = p.nout / nc;
+    const int64_t blocks0 = colblocks * others;
+    p.split = 1;
+    if (blocks0 * 4 < kTargetWaves) {
+      const int64_t want = (kTargetWaves + blocks0 * 4 - 1) / (blocks0 * 4);
+      const int64_t most = std::max<int64_t>(1, p.nredtot / (4 * 16));  // >= 16 rows per wave
+      p.split = std::max<int64_t>(1, std::min(want, most));
+    }
+    p.chunk = (p.nredtot + p.split - 1) / p.split;
+    p.split = (p.nredtot + p.chunk - 1) / p.chunk;
+    p.grid = blocks0 * p.split;
+  } else {
+    p.kernel = OCN_KERNEL_RED_GENERIC;
+    p.vec = 1;
+    p.split = 1;
+    p.chunk = p.nredtot;
+    p.grid = (p.nout + kBlock - 1) / kBlock;
+  }
+  p.passes = p.split > 1 ? 2 : 1;
+  p.workspace_bytes = p.split > 1 ? (size_t)(p.nout * p.split * acc_es) : 0;
+}
+
+}  // namespace
+
+int plan_reduce(int op, const ocn_tensor *a, const int32_t *axes, int32_t naxes,
+                const ocn_tensor *out, RedPlan *plan) {
+  RedPlan p;
+  p.op = op;
+  int rc;
+  if ((rc = check_tensor(a)) != OCN_OK) return rc;
+  if ((rc = check_tensor(out)) != OCN_OK) return rc;
+  if (op < 0 || op >= R_COUNT) return OCN_ERR_OP;
+  if (a->device != out->device) return OCN_ERR_DEVICE;
+  if (naxes < 0 || naxes > a->ndim) return OCN_ERR_SHAPE;
+  if (naxes > 0 && !axes) return OCN_ERR_NULLPTR;
+  bool reduced[kMaxDims] = {false};
+  for (int i = 0; i < naxes; ++i) {
+    if (axes[i] < 0 || axes[i] >= a->ndim || reduced[axes[i]]) return OCN_ERR_SHAPE;
+    reduced[axes[i]] = true;
+  }
+  if (out->ndim != a->ndim - naxes) return OCN_ERR_SHAPE;
+  RDim kd[kMaxDims], rd[kMaxDims];
+  int nk = 0, nr = 0, j = 0;
+  int64_t nout = 1, nred = 1;
+  for (int d = 0; d < a->ndim; ++d) {
+    if (reduced[d]) {
+      nred *= a->size[d];
+      rd[nr++] = RDim{a->size[d], a->stride[d], 0};
+    } else {
+      if (out->size[j] != a->size[d]) return OCN_ERR_SHAPE;
+      nout *= a->size[d];
+      kd[nk++] = RDim{a->size[d], a->stride[d], out->stride[j]};
+      ++j;
+    }
+  }
+  if (!reduce_supported(op, a->dtype)) return OCN_ERR_DTYPE;
+  p.nout = nout;
+  p.nredtot = nred;
+  p.a_dtype = a->dtype;
+  p.out_dtype = out->dtype;
+  p.acc_dtype = reduce_acc_dtype(op, a->dtype);
+  if (nout == 0) { *plan = p; return OCN_OK; }
+  if ((op == R_MIN || op == R_MAX) && nred == 0) return OCN_ERR_EMPTY;
+  if (nred > 0 && (rc = check_alignment(a)) != OCN_OK) return rc;
+  if ((rc = check_alignment(out)) != OCN_OK) return rc;
+  if (!provably_non_overlapping(out)) return OCN_ERR_OVERLAP_OUT;
+  if (nred > 0) {
+    intptr_t ilo, ihi, olo, ohi;
+    byte_range(a, &ilo, &ihi);
+    byte_range(out, &olo, &ohi);
+    if (ilo < ohi && olo < ihi) return OCN_ERR_ALIAS;
+  }
+
+  int64_t off_a = a->offset, off_o = out->offset;
+  // kept dims: drop size 1, flip to forward output strides, sort by output stride, merge
+  int n = 0;
+  for (int d = 0; d < nk; ++d) {
+    if (kd[d].size == 1) continue;
+    RDim x = kd[d];
+    if (x.so < 0) {
+      off_o += (x.size - 1) * x.so;
+      off_a += (x.size - 1) * x.sa;
+      x.so = -x.so; x.sa = -x.sa;
+    }
+    kd[n++] = x;
+  }
+  nk = sort_merge(kd, n, true);
+  // reduced dims: drop size 1, flip to forward input strides (the set of addends is the
+  // same), sort by input stride, merge
+  n = 0;
+  for (int d = 0; d < nr; ++d) {
+    if (rd[d].size == 1) continue;
+    RDim x = rd[d];
+    if (x.sa < 0) {
+      off_a += (x.size - 1) * x.sa;
+      x.sa = -x.sa;
+    }
+    rd[n++] = x;
+  }
+  nr = nred == 0 ? 0 : sort_merge(rd, n, false);
+  p.nkept = nk;
+  p.nred = nr;
+  for (int d = 0; d < nk; ++d) { p.ksize[d] = kd[d].size; p.kstride_a[d] = kd[d].sa; p.kstride_o[d] = kd[d].so; }
+  for (int d = 0; d < nr; ++d) { p.rsize[d] = rd[d].size; p.rstride_a[d] = rd[d].sa; }
+  p.off_a = off_a;
+  p.off_out = off_o;
+  p.a_ptr = (char *)a->base + off_a;
+  p.out_ptr = (char *)out->base + off_o;
+  choose_reduce_launch(p);
+  *plan = p;
+  return OCN_OK;
+}
+
+void plan_second_pass(const RedPlan &first, char *workspace, RedPlan *second) {
+  RedPlan q;
+  q.op = first.op;  // every supported reduction folds its own partial results
+  q.a_dtype = first.acc_dtype;
+  q.out_dtype = first.out_dtype;
+  q.acc_dtype = reduce_acc_dtype(q.op, q.a_dtype);
+  q.nout = first.nout;
+  q.nredtot = first.split;
+  q.a_ptr = workspace;
+  q.out_ptr = first.out_ptr;
+  q.off_a = 0;
+  q.off_out = first.off_out;
+  const int64_t es = dt_size(q.a_dtype);
+  q.nkept = first.nkept;
+  const bool rows_layout = first.kernel == OCN_KERNEL_RED_ROWS;  // [nout][split], else [split][nout]
+  int64_t lin = rows_layout ? first.split * es : es;
+  for (int d = first.nkept - 1; d >= 0; --d) {
+    q.ksize[d] = first.ksize[d];
+    q.kstride_o[d] = first.kstride_o[d];
+    q.kstride_a[d] = lin;
+    lin *= first.ksize[d];
+  }
+  q.nred = 1;
+  q.rsize[0] = first.split;
+  q.rstride_a[0] = rows_layout ? es : first.nout * es;
+  q.split = 1;
+  q.chunk = first.split;
+  q.passes = 1;
+  q.workspace_bytes = 0;
+  q.vec = 1;
+  if (rows_layout && first.split >= 32) {
+    q.kernel = OCN_KERNEL_RED_ROWS;
+    q.group = kWave;
+    q.chunk = first.split;  // vectors (vec = 1) per output
+    q.grid = (q.nout + (kBlock / kWave) - 1) / (kBlock / kWave);
+  } else if (!rows_layout && first.nkept >= 1 && q.nout < ((int64_t)1 << 31)) {
+    q.kernel = OCN_KERNEL_RED_COLS;
+    const int64_t nc = q.ksize[q.nkept - 1];
+    const int64_t colblocks = (nc + kWave - 1) / kWave;
+    q.grid = colblocks * (q.nout / nc);
+  } else {
+    q.kernel = OCN_KERNEL_RED_GENERIC;
+    q.grid = (q.nout + kBlock - 1) / kBlock;
+  }
+  *second = q;
+}
+
+// ---------------------------------------------------------------------------------------
+// plan inspection
+// ---------------------------------------------------------------------------------------
+
+void fill_info(const EwPlan &p, ocn_plan_info *info) {
+  std::memset(info, 0, sizeof *info);
+  info->kernel = p.kernel;
+  info->compute_dtype = p.T;
+  info->ndim = p.ndim;
+  for (int d = 0; d < p.ndim; ++d) {
+    info->size[d] = p.size[d];
+    info->stride_out[d] = p.out.stride[d];
+    info->stride_a[d] = p.a.stride[d];
+    info->stride_b[d] = p.b.stride[d];
+    info->tile_log2[d] = p.tile_log2[d];
+  }
+  info->offset_out = p.off_out;
+  info->offset_a = p.off_a;
+  info->offset_b = p.off_b;
+  info->vec = p.vec;
+  info->stage_a = p.stage_a;
+  info->stage_b = p.stage_b;
+  info->specialised = p.specialised;
+  info->passes = p.kernel == OCN_KERNEL_NONE ? 0 : 1;
+  info->grid = p.grid;
+  info->block = kBlock;
+  info->split = 1;
+  info->lds_bytes = p.lds_bytes;
+}
+
+void fill_info(const RedPlan &p, ocn_plan_info *info) {
+  std::memset(info, 0, sizeof *info);
+  info->kernel = p.kernel;
+  info->compute_dtype = p.acc_dtype;
+  info->ndim = p.nkept;
+  info->nred = p.nred;
+  for (int d = 0; d < p.nkept; ++d) {
+    info->size[d] = p.ksize[d];
+    info->stride_out[d] = p.kstride_o[d];
+    info->stride_a[d] = p.kstride_a[d];
+  }
+  for (int d = 0; d < p.nred; ++d) {
+    info->red_size[d] = p.rsize[d];
+    info->red_stride_a[d] = p.rstride_a[d];
+  }
+  info->offset_out = p.off_out;
+  info->offset_a = p.off_a;
+  info->vec = p.vec;
+  info->specialised = 1;
+  info->passes = p.kernel == OCN_KERNEL_NONE ? 0 : p.passes;
+  info->grid = p.grid;
+  info->block = kBlock;
+  info->split = p.split;
+}
+
+}  // namespace ocn

@@ -1,0 +1,100 @@
+// Host-side planning for the tensor engine: validation, implicit casting, overlap checks and
+// dimension canonicalisation (drop, flip, sort, merge), then kernel selection.
+//
+// This is the device-independent "module interface" work of the paper's section 2.1
+// (parameter checks, compatibility of dimensions, type resolution, broadcasting) plus the
+// one optimisation the paper names in section 4: sorting of axes and merging of consecutive
+// axes to increase memory locality and reduce the overhead of iterating over dimensions.
+// Plain C++ with no HIP dependency, so it can be built and sanitised on the host alone.
+#pragma once
+
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/ocn.h"
+
+namespace ocn {
+
+constexpr int kMaxDims = OCN_MAX_DIMS;
+constexpr int kBlock = 256;        // threads per workgroup of every kernel (4 wavefronts)
+constexpr int kWave = 64;
+
+// unsigned division by an invariant: q = (mulhi(n, m) + n) >> s, valid for n < 2^31
+struct FastDiv {
+  uint32_t d, m, s;
+};
+FastDiv make_fastdiv(uint32_t d);
+inline uint32_t fastdiv_host(uint32_t n, const FastDiv &f) {
+  return (uint32_t)((((uint64_t)n * f.m) >> 32) + n) >> f.s;
+}
+
+struct Operand {
+  char *ptr;                    // base + offset, after flips
+  int64_t stride[kMaxDims];     // bytes, canonical order (slowest first)
+  int32_t dtype;
+};
+
+struct EwPlan {
+  int kernel = OCN_KERNEL_NONE;
+  int op = 0;
+  int nin = 0;                  // 1 unary, 2 binary
+  int T = 0;                    // compute dtype
+  int ndim = 0;
+  int64_t size[kMaxDims] = {0};
+  Operand out{}, a{}, b{};
+  int64_t off_out = 0, off_a = 0, off_b = 0;  // offsets relative to the caller's base
+  int64_t numel = 0;
+  // rows kernel
+  int vec = 1;                  // elements per lane access
+  int unroll = 1;               // vectors per lane
+  bool a_inner_bcast = false, b_inner_bcast = false;
+  // tiled kernel
+  int tile_log2[kMaxDims] = {0};
+  int tile_bits = 0;            // log2 of the elements of one tile
+  bool stage_a = false, stage_b = false;
+  int pad_shift_a = 0, pad_shift_b = 0;
+  int nord = 0;                 // dims with a tile extent > 1
+  int8_t ord_o[kMaxDims] = {0}, ord_a[kMaxDims] = {0}, ord_b[kMaxDims] = {0};
+  int64_t ntiles[kMaxDims] = {0};
+  int64_t total_tiles = 0;
+  bool specialised = false;     // a dtype-specialised kernel exists for this signature
+  int64_t grid = 0;
+  int64_t lds_bytes = 0;
+};
+
+struct RedPlan {
+  int kernel = OCN_KERNEL_NONE;
+  int op = 0;
+  int nkept = 0, nred = 0;
+  int64_t ksize[kMaxDims] = {0}, kstride_a[kMaxDims] = {0}, kstride_o[kMaxDims] = {0};
+  int64_t rsize[kMaxDims] = {0}, rstride_a[kMaxDims] = {0};
+  int64_t off_a = 0, off_out = 0;
+  char *a_ptr = nullptr, *out_ptr = nullptr;
+  int a_dtype = 0, out_dtype = 0;
+  int64_t nout = 0, nredtot = 0;
+  int vec = 1;
+  int group = kBlock;           // lanes cooperating on one output (rows kernel): 64 or 256
+  int64_t split = 1;            // partial results per output
+  int64_t chunk = 0;            // reduction elements (rows: vectors) per split
+  int64_t grid = 0;
+  int acc_dtype = 0;            // dtype the partial results are stored in
+  size_t workspace_bytes = 0;
+  int passes = 1;
+};
+
+int plan_elementwise(int nin, int op, const ocn_tensor *a, const ocn_tensor *b,
+                     const ocn_tensor *out, uint32_t flags, EwPlan *plan);
+int plan_reduce(int op, const ocn_tensor *a, const int32_t *axes, int32_t naxes,
+                const ocn_tensor *out, RedPlan *plan);
+// plan for folding `split` partial results per output, stored as [nout][split] (rows) or
+// [split][nout] (cols) of acc_dtype in the workspace, into the final output
+void plan_second_pass(const RedPlan &first, char *workspace, RedPlan *second);
+
+int promote(int a, int b);
+int reduce_acc_dtype(int op, int in_dtype);
+bool reduce_supported(int op, int in_dtype);
+
+void fill_info(const EwPlan &p, ocn_plan_info *info);
+void fill_info(const RedPlan &p, ocn_plan_info *info);
+
+}  // namespace ocn

@@ -1,0 +1,51 @@
+// Kernel-argument builder for the reduction kernels (dtype independent).
+#include "red_launch.hpp"
+
+#include <cstring>
+
+namespace ocn {
+
+RedLauncher g_reduce_launchers[R_COUNT][DT_COUNT];
+
+RedArgs make_red_args(const RedPlan &p, char *partial) {
+  RedArgs r;
+  std::memset(&r, 0, sizeof r);
+  r.a = p.a_ptr;
+  r.out = p.out_ptr;
+  r.partial = partial;
+  r.nkept = p.nkept;
+  r.nred = p.nred;
+  r.out_dtype = p.out_dtype;
+  r.vec = p.vec;
+  r.group = p.group;
+  for (int k = 0; k < p.nkept; ++k) {  // fastest first
+    const int d = p.nkept - 1 - k;
+    r.ksa[k] = p.kstride_a[d];
+    r.kso[k] = p.kstride_o[d];
+    r.kdiv[k] = make_fastdiv((uint32_t)p.ksize[d]);
+    r.ksize[k] = p.ksize[d];
+  }
+  for (int k = 0; k < p.nred; ++k) {
+    const int d = p.nred - 1 - k;
+    r.rsa[k] = p.rstride_a[d];
+    r.rdiv[k] = make_fastdiv((uint32_t)p.rsize[d]);
+    r.rsize[k] = p.rsize[d];
+  }
+  r.nout = p.nout;
+  r.nredtot = p.nredtot;
+  r.split = p.split;
+  r.chunk = p.chunk;
+  if (p.kernel == OCN_KERNEL_RED_ROWS) {
+    r.n0 = p.rsize[p.nred - 1];
+    const int64_t vpr = (r.n0 + p.vec - 1) / p.vec;
+    r.vpr_div = make_fastdiv((uint32_t)(p.nred > 1 ? vpr : 1));
+    r.nvec = vpr * (p.nredtot / r.n0);
+  } else if (p.kernel == OCN_KERNEL_RED_COLS) {
+    r.nc = p.ksize[p.nkept - 1];
+    const int64_t colblocks = (r.nc + (int64_t)kWave * p.vec - 1) / ((int64_t)kWave * p.vec);
+    r.colblocks_div = make_fastdiv((uint32_t)colblocks);
+  }
+  return r;
+}
+
+}  // namespace ocn

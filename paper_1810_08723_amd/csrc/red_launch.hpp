@@ -1,0 +1,33 @@
+// Host side of the reduction kernels.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "red_kernels.hpp"
+
+namespace ocn {
+
+using RedLauncher = hipError_t (*)(const RedPlan &, char *partial, hipStream_t);
+extern RedLauncher g_reduce_launchers[R_COUNT][DT_COUNT];
+
+RedArgs make_red_args(const RedPlan &p, char *partial);
+
+#if defined(__HIPCC__)
+template <int S, int OP> hipError_t launch_red(const RedPlan &p, char *partial, hipStream_t stream) {
+  const RedArgs args = make_red_args(p, partial);
+  switch (p.kernel) {
+    case OCN_KERNEL_RED_ROWS:
+      hipLaunchKernelGGL((red_rows_kernel<S, OP>), dim3((unsigned)p.grid), dim3(kBlock), 0, stream, args);
+      break;
+    case OCN_KERNEL_RED_COLS:
+      hipLaunchKernelGGL((red_cols_kernel<S, OP>), dim3((unsigned)p.grid), dim3(kBlock), 0, stream, args);
+      break;
+    default:
+      hipLaunchKernelGGL((red_generic_kernel<S, OP>), dim3((unsigned)p.grid), dim3(kBlock), 0, stream, args);
+      break;
+  }
+  return hipGetLastError();
+}
+#endif
+
+}  // namespace ocn

@@ -1,0 +1,52 @@
+// Which (operation, operand dtypes) combinations get a dtype-specialised elementwise kernel,
+// and the per-lane vector shape those kernels use.  Everything else runs through the
+// generic-dtype kernel, which converts through runtime switches.  Shared by the host planner
+// (to report and size launches) and the kernel translation units (to instantiate).
+#pragma once
+
+#include "dtypes.hpp"
+
+namespace ocn {
+
+
+// compute type of a binary operation (section 3.2.1 of the paper and include/ocn.h)
+OCN_HD constexpr int binary_compute_dtype(int op, int sa, int sb, int so, int promoted) {
+  return is_logical(op) ? (int)DT_BOOL : is_compare(op) ? promoted : so;
+}
+
+OCN_HD constexpr bool binary_specialised(int op, int sa, int sb, int so) {
+  if (op < 0 || op >= B_COUNT) return false;
+  if (is_arith(op) || is_bitwise(op)) {
+    if (!binary_supported(op, so)) return false;
+    if (sa == so && sb == so) return true;
+    // int32 (x) float -> float arithmetic, converted on load
+    return sa == DT_I32 && sb == DT_F32 && so == DT_F32 && op <= B_DIV;
+  }
+  if (is_logical(op)) return sa == DT_BOOL && sb == DT_BOOL && so == DT_BOOL;
+  // comparisons: equal input types (so the compute type is that type), bool result
+  return sa == sb && so == DT_BOOL && binary_supported(op, sa);
+}
+
+OCN_HD constexpr int unary_compute_dtype(int op, int so) { return op == U_LNOT ? (int)DT_BOOL : so; }
+
+OCN_HD constexpr bool unary_specialised(int op, int sa, int so) {
+  if (op < 0 || op >= U_COUNT) return false;
+  if (op == U_IDENT) return true;  // the full cast matrix
+  if (op == U_LNOT) return sa == DT_BOOL && so == DT_BOOL;
+  return sa == so && unary_supported(op, so);
+}
+
+OCN_HD constexpr int imin(int a, int b) { return a < b ? a : b; }
+OCN_HD constexpr int imax(int a, int b) { return a > b ? a : b; }
+
+// Elements per lane access of the rows kernel: the narrowest operand moves 16 bytes, unless
+// that would make the widest operand move more than 64 bytes.
+OCN_HD constexpr int rows_vec(int es_min, int es_max) {
+  return imax(1, imin(16 / es_min, 64 / es_max));
+}
+// Vectors per lane, so that about 64 bytes of the widest operand are in flight per lane.
+OCN_HD constexpr int rows_unroll(int vec, int es_max) {
+  return imax(1, imin(4, 64 / (vec * es_max)));
+}
+
+}  // namespace ocn
