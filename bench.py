@@ -1,0 +1,173 @@
+"""Benchmark: effective GB/s (logical bytes moved) of the strided tensor engine on one MI355X.
+
+One "step" runs every benchmark operation once, through the C ABI, on synthetic inputs that are
+already resident in HBM: the five configurations (C1, C1x8, C2, C3, C4a-d, C5, C5m).  The
+operations touch about 3 GB of distinct memory per step, so each one starts with a cold
+256 MB Infinity Cache.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def _device_cases(cases):
+    """Upload every case's storages; returns a list of (case, callable, device tensors)."""
+    import torch
+    import paper_1810_08723_amd as ocn
+    uploaded = {}
+
+    def dev(view):
+        key = id(view.storage)
+        if key not in uploaded:
+            uploaded[key] = torch.from_numpy(view.storage).to("cuda:0")
+        return ocn.Tensor.on_storage(uploaded[key], view.dtype, view.sizes, view.strides, view.offset)
+
+    runs = []
+    for c in cases:
+        ins = [dev(v) for v in c.inputs]
+        out = dev(c.out)
+        if c.kind == "binary":
+            fn = (lambda ins=ins, out=out, c=c: ocn.binary(c.op, ins[0], ins[1], out))
+        elif c.kind == "unary":
+            fn = (lambda ins=ins, out=out, c=c: ocn.unary(c.op, ins[0], out))
+        else:
+            need = ocn.reduce_workspace_bytes(c.op, ins[0], list(c.axes), out)
+            ws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda:0")
+            fn = (lambda ins=ins, out=out, c=c, ws=ws: ocn.reduce(c.op, ins[0], list(c.axes), out, workspace=ws))
+        runs.append((c, fn, out))
+    return runs, uploaded
+
+
+def _plan_kernel(c):
+    import paper_1810_08723_amd as ocn
+
+    def fake(view, base):
+        return ocn.Tensor(base, view.dtype, view.sizes, view.strides, view.offset, 0)
+    ins = [fake(v, 0x100000000 * (i + 1)) for i, v in enumerate(c.inputs)]
+    out = fake(c.out, 0x700000000)
+    if c.kind == "binary":
+        return ocn.plan_binary(c.op, ins[0], ins[1], out)
+    if c.kind == "unary":
+        return ocn.plan_unary(c.op, ins[0], out)
+    return ocn.plan_reduce(c.op, ins[0], list(c.axes), out)
+
+
+def _cpu_baseline(seconds_budget: float = 20.0):
+    """Times the CPU oracle, as it stands, on a bounded sample: the small-size versions of the
+    same cases, repeated until the budget is spent.  Returns GB/s of logical bytes."""
+    from oracle import binding as O
+    from workloads import configs
+    cases = configs.all_cases_small()
+    total_bytes = 0
+    t0 = time.perf_counter()
+    reps = 0
+    while True:
+        for c in cases:
+            if c.kind == "binary":
+                O.binary(c.op, c.inputs[0], c.inputs[1], c.out)
+            elif c.kind == "unary":
+                O.unary(c.op, c.inputs[0], c.out)
+            else:
+                O.reduce(c.op, c.inputs[0], list(c.axes), c.out)
+            total_bytes += c.logical_bytes
+        reps += 1
+        if time.perf_counter() - t0 > seconds_budget or reps >= 50:
+            break
+    dt = time.perf_counter() - t0
+    threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return {"value": total_bytes / dt / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
+            "sample": f"{reps} passes over the reduced-size cases of all five configurations "
+                      f"({sum(c.logical_bytes for c in cases) / 1e6:.1f} MB logical per pass)"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this engine runs on one GPU; --gpus must be 1 (nothing here is distributed)",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_1810_08723_amd as ocn  # noqa: F401  (fails loudly if libocn.so is missing)
+    from workloads import configs
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+
+    cases = configs.all_cases_full()
+    runs, _keep = _device_cases(cases)
+    torch.cuda.synchronize()
+
+    for _ in range(args.warmup):
+        for _, fn, _ in runs:
+            fn()
+    torch.cuda.synchronize()
+
+    # timed region: exactly `steps` passes; per-operation device time from events recorded on
+    # the stream the kernels are launched on (torch's current stream is passed to the library)
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+           for _ in runs] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        for i, (_, fn, _) in enumerate(runs):
+            ev[s][i][0].record()
+            fn()
+            ev[s][i][1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    step_bytes = sum(c.logical_bytes for c in cases)
+    per_op = []
+    for i, (c, _, _) in enumerate(runs):
+        ms = sorted(ev[s][i][0].elapsed_time(ev[s][i][1]) for s in range(args.steps))
+        avg = sum(ms) / len(ms)
+        plan = _plan_kernel(c)
+        per_op.append({"case": c.name, "op": c.op, "kernel": plan["kernel"], "passes": plan["passes"],
+                       "logical_bytes": c.logical_bytes, "avg_us": avg * 1e3, "min_us": ms[0] * 1e3,
+                       "gbs": c.logical_bytes / (avg * 1e-3) / 1e9,
+                       "frac_of_peak": c.logical_bytes / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS})
+    device_ms = sum(p["avg_us"] for p in per_op) / 1e3
+    dom = max(per_op, key=lambda p: p["avg_us"])
+
+    result = {
+        "metric": "effective GB/s (logical bytes moved) and % of MI355X HBM peak per op",
+        "value": step_bytes * args.steps / wall / 1e9,
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32/f64/i32/i8/f16/c64 (per case)", "data": "synthetic",
+        "config": {"workload": "all five configurations in one step: C1, C1x8, C2, C3, C4a-d, C5, C5m",
+                   "logical_bytes_per_step": step_bytes, "device_ms_per_step": device_ms},
+        "roofline": {"bound": "hbm", "achieved": dom["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": dom["gbs"] / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": f"{dom['kernel']} ({dom['case']})",
+                     "bytes_per_launch": dom["logical_bytes"], "avg_us": dom["avg_us"]},
+        "per_op": per_op,
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = _cpu_baseline()
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

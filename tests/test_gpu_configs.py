@@ -1,0 +1,76 @@
+"""GPU parity on the five benchmark configurations, reduced and full size, through the C ABI,
+in the launch configuration the benchmark times.  Bit-exact for integer, bool, cast and IEEE
+elementwise results; float sums within 1e-6 * sum|x| (fp32 against the fp64-accumulating
+oracle)."""
+import numpy as np
+import pytest
+
+import gpu_harness as H
+from workloads import configs
+
+pytestmark = pytest.mark.gpu
+
+_FLOAT = {"half": np.float16, "float": np.float32, "double": np.float64}
+
+
+def _run_case(c):
+    import paper_1810_08723_amd as ocn
+    from oracle import binding as O
+    dv = H.DeviceViews()
+    ins = [dv.tensor(v) for v in c.inputs]
+    out = dv.tensor(c.out)
+    if c.kind == "binary":
+        ocn.binary(c.op, ins[0], ins[1], out)
+        dv.torch.cuda.synchronize()
+        got = dv.download(c.out)
+        O.binary(c.op, c.inputs[0], c.inputs[1], c.out)
+    elif c.kind == "unary":
+        ocn.unary(c.op, ins[0], out)
+        dv.torch.cuda.synchronize()
+        got = dv.download(c.out)
+        O.unary(c.op, c.inputs[0], c.out)
+    else:
+        ocn.reduce(c.op, ins[0], list(c.axes), out)
+        dv.torch.cuda.synchronize()
+        got = dv.download(c.out)
+        O.reduce(c.op, c.inputs[0], list(c.axes), c.out)
+    want = c.out.storage
+    if c.compare == "exact":
+        assert H.storages_equal(c.out.dtype, got, want), c.name + ": " + H.first_mismatch(c.out.dtype, got, want)
+    else:
+        # |gpu - oracle| <= rel_bound * sum|x| per output
+        ft = _FLOAT[c.out.dtype]
+        g = got.view(ft).astype(np.float64)
+        w = want.view(ft).astype(np.float64)
+        x = c.inputs[0].to_numpy().astype(np.float64)
+        bound = c.rel_bound * np.abs(x).sum(axis=c.axes)
+        err = np.abs(g - w)
+        assert np.all(err <= bound.reshape(-1)), (c.name, float(err.max()), float(bound.min()))
+        # and the two agree far better than the bound requires (both accumulate in fp64)
+        assert np.all(err <= 1e-7 * np.abs(x).sum(axis=c.axes).reshape(-1) + 1e-30)
+
+
+@pytest.mark.parametrize("idx", range(10))
+def test_small_cases(idx):
+    c = configs.all_cases_small()[idx]
+    print("case", c.name, c.op, [v.sizes for v in c.inputs], flush=True)
+    _run_case(c)
+
+
+@pytest.mark.parametrize("which", ["C1", "C1x8", "C2", "C3", "C4", "C5"])
+def test_full_size_cases(which):
+    if which == "C1":
+        cases = [configs.config1(1)]
+    elif which == "C1x8":
+        cases = [configs.config1(8)]
+    elif which == "C2":
+        cases = [configs.config2()]
+    elif which == "C3":
+        cases = [configs.config3()]
+    elif which == "C4":
+        cases = configs.config4()
+    else:
+        cases = configs.config5()
+    for c in cases:
+        print("case", c.name, c.op, [v.sizes for v in c.inputs], flush=True)
+        _run_case(c)

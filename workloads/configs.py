@@ -1,0 +1,158 @@
+"""The five benchmark configurations as seeded synthetic inputs.
+
+Each case is one call of the engine: operand views, the operation, the output view, the
+logical byte count (distinct input elements read + output elements written, broadcast
+operands counted once) and how results are compared.  The paper has no datasets; these
+tensors restate the configurations the build is measured on, "contiguous" read row-major.
+
+Seeds: PCG64(1810087230 + 10 * config + tensor_index); normals are drawn in float64 and
+rounded to the tensor dtype; NaNs of configuration 2 are planted where a uniform draw from the
+same generator, taken after the values, falls below 1e-4.
+
+Only random draws and view construction live here - none of the engine's arithmetic.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+from .values import rng_for
+from .views import View, itemsize
+
+BASE_SEED = 1810087230
+
+
+@dataclass
+class Case:
+    name: str
+    kind: str                      # "binary" | "unary" | "reduce"
+    op: str
+    inputs: List[View]
+    out: View
+    axes: Tuple[int, ...] = ()
+    logical_bytes: int = 0
+    compare: str = "exact"         # "exact" | "sum" (bounded error relative to sum |x|)
+    rel_bound: float = 0.0         # for compare == "sum"
+    note: str = ""
+
+
+def _seed(config: int, tensor: int) -> int:
+    return BASE_SEED + 10 * config + tensor
+
+
+def _uniform_pm1(seed: int, sizes) -> np.ndarray:
+    return (rng_for(seed).random(sizes, dtype=np.float32) * np.float32(2) - np.float32(1)).astype(np.float32)
+
+
+def _normal(seed: int, sizes, dtype, sigma: float = 1.0) -> np.ndarray:
+    x = rng_for(seed).standard_normal(sizes)
+    if sigma != 1.0:
+        x *= sigma
+    return x.astype(dtype)
+
+
+def config1(scale: int = 1) -> Case:
+    """fp32 add C = A + B; A, C contiguous [64,48,32]*scale; B a contiguous [32,64,48]*scale
+    buffer read with dims permuted (1,2,0)."""
+    n0, n1, n2 = 64 * scale, 48 * scale, 32 * scale
+    a = View.from_numpy(_uniform_pm1(_seed(0, 0), (n0, n1, n2)))
+    b = View.from_numpy(_uniform_pm1(_seed(0, 1), (n2, n0, n1))).permute(1, 2, 0)
+    out = View.empty("float", (n0, n1, n2))
+    n = n0 * n1 * n2
+    return Case("C1" if scale == 1 else f"C1x{scale}", "binary", "add", [a, b], out,
+                logical_bytes=12 * n, note="transposed second operand")
+
+
+def config2(rows: int = 4096, cols: int = 4096) -> Case:
+    """fp64 -> int16 cast-copy of a [rows, cols] input with rows flipped; N(0, sigma=2e4),
+    NaN at rate 1e-4."""
+    rng = rng_for(_seed(1, 0))
+    x = rng.standard_normal((rows, cols))
+    x *= 2e4
+    x[rng.random((rows, cols)) < 1e-4] = np.nan
+    src = View.from_numpy(x).flip(0)
+    out = View.empty("int16", (rows, cols))
+    return Case("C2", "unary", "ident", [src], out, logical_bytes=10 * rows * cols,
+                note="negative stride on axis 0")
+
+
+def config3(rows: int = 8192, cols: int = 8192) -> Case:
+    """C = A * B; A int32 [rows, cols] uniform in [-1000, 1000]; B float32 [1, cols] with stride
+    0 on axis 0, N(0,1); C float32."""
+    a = rng_for(_seed(2, 0)).integers(-1000, 1000, size=(rows, cols), endpoint=True, dtype=np.int64).astype(np.int32)
+    b = _normal(_seed(2, 1), (1, cols), np.float32)
+    va = View.from_numpy(a)
+    vb = View.from_numpy(b).broadcast_to((rows, cols))
+    out = View.empty("float", (rows, cols))
+    return Case("C3", "binary", "mul", [va, vb], out, logical_bytes=8 * rows * cols + 4 * cols,
+                note="broadcast row, int32 promoted on load")
+
+
+def config4(rows: int = 16384, cols: int = 4096, n_full: int = 1 << 28) -> List[Case]:
+    """Reductions: fp32 sum over axis 1 and axis 0 of [rows, cols] N(0,1); fp16 max over axis 1 of
+    the same shape; full int8 -> int64 sum over n_full elements uniform in [-128, 127]."""
+    x32 = _normal(_seed(3, 0), (rows, cols), np.float32)
+    v32 = View.from_numpy(x32)
+    x16 = _normal(_seed(3, 1), (rows, cols), np.float16)
+    v16 = View.from_numpy(x16)
+    x8 = rng_for(_seed(3, 2)).integers(-128, 127, size=n_full, endpoint=True, dtype=np.int8)
+    v8 = View.from_numpy(x8)
+    n = rows * cols
+    return [
+        Case("C4a", "reduce", "sum", [v32], View.empty("float", (rows,)), axes=(1,),
+             logical_bytes=4 * n + 4 * rows, compare="sum", rel_bound=1e-6, note="reduced axis fastest"),
+        Case("C4b", "reduce", "sum", [v32], View.empty("float", (cols,)), axes=(0,),
+             logical_bytes=4 * n + 4 * cols, compare="sum", rel_bound=1e-6, note="kept axis fastest"),
+        Case("C4c", "reduce", "max", [v16], View.empty("half", (rows,)), axes=(1,),
+             logical_bytes=2 * n + 2 * rows, note="half precision max"),
+        Case("C4d", "reduce", "sum", [v8], View.empty("int64", ()), axes=(0,),
+             logical_bytes=n_full + 8, note="full two-pass reduction"),
+    ]
+
+
+def config5(shape: Sequence[int] = (16, 32, 64, 64, 8)) -> List[Case]:
+    """complex64 multiply on logical shape [16,32,64,64,8]: A is a step-2 slice along axis 2 of a
+    buffer whose dims are permuted (4,2,0,3,1); B contiguous; C written with dims permuted
+    (3,0,4,1,2).  Also the bool mask |A| > |B| (contiguous)."""
+    s0, s1, s2, s3, s4 = shape
+    # physical buffers: view.dim[i] = buffer.dim[perm[i]]
+    pa_shape = [0] * 5
+    for i, p in enumerate((4, 2, 0, 3, 1)):
+        pa_shape[p] = (s0, s1, 2 * s2, s3, s4)[i]
+    pc_shape = [0] * 5
+    for i, p in enumerate((3, 0, 4, 1, 2)):
+        pc_shape[p] = shape[i]
+
+    def cplx(seed, sizes):
+        rng = rng_for(seed)
+        z = np.empty(sizes, dtype=np.complex64)
+        z.real = rng.standard_normal(sizes).astype(np.float32)
+        z.imag = rng.standard_normal(sizes).astype(np.float32)
+        return z
+
+    pa = View.from_numpy(cplx(_seed(4, 0), tuple(pa_shape)))
+    a = pa.permute(4, 2, 0, 3, 1).slice(2, 0, 2 * s2, 2)
+    b = View.from_numpy(cplx(_seed(4, 1), tuple(shape)))
+    pc = View.empty("cfloat", tuple(pc_shape))
+    c = pc.permute(3, 0, 4, 1, 2)
+    assert a.sizes == tuple(shape) and c.sizes == tuple(shape)
+    n = int(np.prod(shape))
+    mask = View.empty("bool", tuple(shape))
+    return [
+        Case("C5", "binary", "mul", [a, b], c, logical_bytes=24 * n, note="three different fastest axes"),
+        Case("C5m", "binary", "absgt", [a, b], mask, logical_bytes=17 * n, note="bool mask |A|>|B|"),
+    ]
+
+
+def all_cases_full() -> List[Case]:
+    """Every benchmark case at full size (about 2.6 GB of host memory)."""
+    return [config1(1), config1(8), config2(), config3(), *config4(), *config5()]
+
+
+def all_cases_small() -> List[Case]:
+    """The same cases shrunk so the CPU oracle finishes in seconds; still several tiles and a
+    ragged tail in every kernel."""
+    return [config1(1), config1(2), config2(301, 517), config3(263, 1031),
+            *config4(389, 1021, (1 << 20) + 77), *config5((6, 10, 12, 18, 8))]
