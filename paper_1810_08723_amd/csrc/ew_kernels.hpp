@@ -34,23 +34,38 @@ struct RowsArgs {
   int32_t a_bcast, b_bcast;
 };
 
+constexpr int kMaxTilePasses = 16;  // a tile holds at most 4096 elements = 16 passes of 256 lanes
+
+// One enumeration order of a tile's elements (fastest dim of some operand first).
 struct TileOrder {
+  int8_t nord;                     // tiled dims
+  int8_t vecw;                     // log2 of the vector length along the first enumerated dim
   int8_t width[kMaxDims];          // log2 tile extent of the k-th enumerated dim
   int8_t dim[kMaxDims];            // which canonical dim that is
   int8_t lds_shift[kMaxDims];      // bit position of that dim in the LDS slot number
+  int32_t niter;                   // passes of 256 lanes that cover the tile
   int64_t stride[3][kMaxDims];     // byte stride of that dim for out / a / b
+  int64_t hi_off[3][kMaxTilePasses];  // byte offsets contributed by the pass number
+  uint32_t hi_slot[kMaxTilePasses];   // LDS slot contributed by the pass number
+};
+
+// slot -> physical LDS element: slot ^ (((slot >> src) & mask) << dst)
+struct TileSwizzle {
+  uint32_t src, mask, dst;
 };
 
 struct TiledArgs {
   char *out;
   const char *a, *b;
-  int32_t ndim, nord, tile_bits;
+  int32_t ndim, tile_bits;
+  uint32_t total_tiles;
   int64_t size[kMaxDims];
   int64_t so[kMaxDims], sa[kMaxDims], sb[kMaxDims];
   int32_t tl[kMaxDims];
   FastDiv ntdiv[kMaxDims];
-  int32_t stage_a, stage_b, pad_a, pad_b;
+  int32_t stage_a, stage_b;
   uint32_t lds_off_b;              // byte offset of b's staging area in dynamic LDS
+  TileSwizzle swz[2];              // for a, b
   TileOrder ord[3];                // enumeration orders: out's, a's, b's
 };
 
@@ -64,7 +79,11 @@ struct InterpArgs {
 
 #if defined(__HIPCC__)
 
-OCN_DEV uint32_t fastdiv(uint32_t n, const FastDiv &f) { return (__umulhi(n, f.m) + n) >> f.s; }
+#define OCN_HDF __host__ __device__ __forceinline__
+
+OCN_HDF uint32_t fastdiv(uint32_t n, const FastDiv &f) {
+  return (uint32_t)((((uint64_t)n * f.m) >> 32) + n) >> f.s;
+}
 
 // ---------------------------------------------------------------------------------------
 // raw vector access
@@ -74,12 +93,21 @@ template <class S, int V> struct alignas(sizeof(S) * V >= 16 ? 16 : sizeof(S) * 
   S v[V];
 };
 
+#ifndef OCN_NT_LOAD
+#define OCN_NT_LOAD 0
+#endif
+#ifndef OCN_NT_STORE
+#define OCN_NT_STORE 0
+#endif
 template <class S, int V> OCN_DEV void load_pack(const char *p, Pack<S, V> &dst) {
   constexpr int B = sizeof(S) * V;
   if constexpr (B >= 16) {
     using Q = uint32_t __attribute__((ext_vector_type(4)));
 #pragma unroll
-    for (int i = 0; i < B / 16; ++i) reinterpret_cast<Q *>(&dst)[i] = reinterpret_cast<const Q *>(p)[i];
+    for (int i = 0; i < B / 16; ++i) {
+      if constexpr (OCN_NT_LOAD) reinterpret_cast<Q *>(&dst)[i] = __builtin_nontemporal_load(reinterpret_cast<const Q *>(p) + i);
+      else reinterpret_cast<Q *>(&dst)[i] = reinterpret_cast<const Q *>(p)[i];
+    }
   } else if constexpr (B == 8) {
     using D = uint32_t __attribute__((ext_vector_type(2)));
     *reinterpret_cast<D *>(&dst) = *reinterpret_cast<const D *>(p);
@@ -97,7 +125,10 @@ template <class S, int V> OCN_DEV void store_pack(char *p, const Pack<S, V> &src
   if constexpr (B >= 16) {
     using Q = uint32_t __attribute__((ext_vector_type(4)));
 #pragma unroll
-    for (int i = 0; i < B / 16; ++i) reinterpret_cast<Q *>(p)[i] = reinterpret_cast<const Q *>(&src)[i];
+    for (int i = 0; i < B / 16; ++i) {
+      if constexpr (OCN_NT_STORE) __builtin_nontemporal_store(reinterpret_cast<const Q *>(&src)[i], reinterpret_cast<Q *>(p) + i);
+      else reinterpret_cast<Q *>(p)[i] = reinterpret_cast<const Q *>(&src)[i];
+    }
   } else if constexpr (B == 8) {
     using D = uint32_t __attribute__((ext_vector_type(2)));
     *reinterpret_cast<D *>(p) = *reinterpret_cast<const D *>(&src);
@@ -242,168 +273,298 @@ template <class G> __global__ __launch_bounds__(kBlock) void ew_rows_kernel(cons
 // ---------------------------------------------------------------------------------------
 // tiled kernel
 // ---------------------------------------------------------------------------------------
+//
+// A workgroup owns one tile: a box of power-of-two extents over the canonical dims that are
+// the fastest axis of the output or of an input.  The tile's elements are enumerated in up to
+// three orders (the output's and each staged input's own fastest-axis-first order).  Because
+// every extent is a power of two, an enumeration index e = lane + 256 * pass splits into a
+// lane part (computed once per lane) and a pass part (the same for every lane and every
+// workgroup, tabulated by the host), so the inner loops only add two offsets.
+//
+// Staged inputs are copied global -> LDS along their own fastest axis (128-bit loads when
+// the layout allows), stored at slot = position in the OUTPUT's enumeration order, and read
+// back along the output's fastest axis.  Slots are XOR-swizzled so that neither the
+// column-wise writes nor the row-wise reads pile onto one LDS bank.
 
-// lane part and block-uniform part of a tile-local enumeration index e = lane + (j << 8):
-// every tile extent is a power of two, so the bits of e map to coordinates independently
-struct TilePos {
+struct LanePos {
   int64_t off[3];   // byte offsets for out / a / b
-  uint32_t slot;    // LDS slot (position in out's enumeration order)
+  uint32_t slot;    // LDS slot (element position in the output's enumeration order)
 };
 
-template <int NOPS> OCN_DEV TilePos tile_pos(const TileOrder &o, int nord, uint32_t e) {
-  TilePos r;
+// lane part of the position of vector number e (bits below 8 only) in enumeration order o
+template <class O> OCN_HDF LanePos lane_pos(const O &o, uint32_t e) {
+  LanePos r;
   r.off[0] = r.off[1] = r.off[2] = 0;
   r.slot = 0;
   uint32_t shift = 0;
 #pragma unroll
   for (int k = 0; k < kMaxDims; ++k) {
-    if (k < nord) {
-      const uint32_t w = o.width[k];
-      const uint32_t c = (e >> shift) & ((1u << w) - 1u);
+    if (k < o.nord) {
+      const uint32_t vw = k == 0 ? (uint32_t)o.vecw : 0u;
+      const uint32_t w = (uint32_t)o.width[k] - vw;
+      const uint32_t c = ((e >> shift) & ((1u << w) - 1u)) << vw;
       shift += w;
 #pragma unroll
-      for (int x = 0; x < NOPS; ++x) r.off[x] += (int64_t)c * o.stride[x][k];
+      for (int x = 0; x < 3; ++x) r.off[x] += (int64_t)c * o.stride[x][k];
       r.slot += c << o.lds_shift[k];
     }
   }
   return r;
 }
 
-// is element e of the enumeration inside the (possibly clipped) tile?
-OCN_DEV bool tile_inside(const TileOrder &o, int nord, uint32_t e, const uint32_t *lim) {
-  bool ok = true;
+// How many elements of vector number e lie inside a clipped tile (0 .. 1 << vecw).
+template <class O> OCN_HDF int vec_inside(const O &o, uint32_t e, const uint32_t *lim_dim) {
+  int n = 1 << o.vecw;
   uint32_t shift = 0;
 #pragma unroll
   for (int k = 0; k < kMaxDims; ++k) {
-    if (k < nord) {
-      const uint32_t w = o.width[k];
-      const uint32_t c = (e >> shift) & ((1u << w) - 1u);
+    if (k < o.nord) {
+      const uint32_t vw = k == 0 ? (uint32_t)o.vecw : 0u;
+      const uint32_t w = (uint32_t)o.width[k] - vw;
+      const uint32_t c = ((e >> shift) & ((1u << w) - 1u)) << vw;
       shift += w;
-      ok = ok && (c < lim[k]);
+      uint32_t lim = 1;
+#pragma unroll
+      for (int dd = 0; dd < kMaxDims; ++dd)
+        if (dd == o.dim[k]) lim = lim_dim[dd];
+      if (k == 0) {
+        const int left = (int)lim - (int)c;
+        n = left < n ? left : n;
+      } else if (c >= lim) {
+        n = 0;
+      }
     }
   }
-  return ok;
+  return n < 0 ? 0 : n;
 }
 
-template <class S>
-OCN_DEV void stage_operand(const TiledArgs &p, const TileOrder &ord, int which, const char *base,
-                           S *lds, int pad, bool full, const uint32_t (*lim)[kMaxDims], uint32_t tile_elems) {
-  constexpr int J = 4;  // loads in flight per lane
-  const uint32_t tid = threadIdx.x;
-  const TilePos lo = tile_pos<3>(ord, p.nord, tid);
-  for (uint32_t j0 = 0; j0 < tile_elems; j0 += kBlock * J) {
-    S vals[J];
-    uint32_t slots[J];
-    bool ok[J];
-#pragma unroll
-    for (int j = 0; j < J; ++j) {
-      const uint32_t ehi = j0 + j * kBlock;
-      const uint32_t e = ehi + tid;
-      ok[j] = e < tile_elems && (full || tile_inside(ord, p.nord, e, lim[which]));
-      const TilePos hi = tile_pos<3>(ord, p.nord, ehi);
-      slots[j] = lo.slot + hi.slot;
-      if (ok[j]) vals[j] = *reinterpret_cast<const S *>(base + lo.off[which] + hi.off[which]);
-    }
-#pragma unroll
-    for (int j = 0; j < J; ++j)
-      if (ok[j]) lds[slots[j] + (slots[j] >> pad)] = vals[j];
-  }
+OCN_HDF uint32_t swizzle(uint32_t slot, uint32_t src, uint32_t mask, uint32_t dst) {
+  return slot ^ (((slot >> src) & mask) << dst);
 }
+OCN_HDF uint32_t swizzle(uint32_t slot, const TileSwizzle &z) { return swizzle(slot, z.src, z.mask, z.dst); }
 
 extern __shared__ uint4 ocn_lds_raw[];
 
-template <class G> __global__ __launch_bounds__(kBlock) void ew_tiled_kernel(const TiledArgs p) {
-  using SAt = typename G::SAt;
-  using SBt = typename G::SBt;
-  using SOt = typename G::SOt;
-  constexpr bool BIN = G::NIN2;
-  constexpr int J = 4;
+// The kernel reads its argument struct through the constant address space (the kernarg
+// segment itself): indexing the per-pass tables with a runtime pass number then becomes a
+// scalar load instead of forcing a private copy of the whole struct.
+using KTiledArgs = const __attribute__((address_space(4))) TiledArgs;
+using KTileOrder = const __attribute__((address_space(4))) TileOrder;
 
-  // tile origin, clipped extents (block-uniform)
-  uint32_t t = blockIdx.x;
-  int64_t base_o = 0, base_a = 0, base_b = 0;
-  uint32_t lim_dim[kMaxDims];
-  bool full = true;
-#pragma unroll
-  for (int d = kMaxDims - 1; d >= 0; --d) {
-    lim_dim[d] = 1;
-    if (d < p.ndim) {
-      const uint32_t q = (d == 0) ? 0u : fastdiv(t, p.ntdiv[d]);
-      const uint32_t tc = t - q * p.ntdiv[d].d;
-      t = q;
-      const int64_t i0 = (int64_t)tc << p.tl[d];
-      const int64_t ext = (int64_t)1 << p.tl[d];
-      const int64_t rem = p.size[d] - i0;
-      lim_dim[d] = (uint32_t)(rem < ext ? rem : ext);
-      full = full && rem >= ext;
-      base_o += i0 * p.so[d];
-      base_a += i0 * p.sa[d];
-      if constexpr (BIN) base_b += i0 * p.sb[d];
-    }
-  }
-  // clipped extents in each enumeration order
-  uint32_t lim[3][kMaxDims];
-#pragma unroll
-  for (int x = 0; x < 3; ++x)
-#pragma unroll
-    for (int k = 0; k < kMaxDims; ++k) {
-      lim[x][k] = 1;
-      if (k < p.nord) {
-        const int d = p.ord[x].dim[k];
-        uint32_t l = 1;
-#pragma unroll
-        for (int dd = 0; dd < kMaxDims; ++dd)
-          if (dd == d) l = lim_dim[dd];
-        lim[x][k] = l;
-      }
-    }
-
-  const uint32_t tile_elems = 1u << p.tile_bits;
-  SAt *lds_a = reinterpret_cast<SAt *>(ocn_lds_raw);
-  SBt *lds_b = reinterpret_cast<SBt *>(reinterpret_cast<char *>(ocn_lds_raw) + p.lds_off_b);
-
-  if (p.stage_a) stage_operand<SAt>(p, p.ord[1], 1, p.a + base_a, lds_a, p.pad_a, full, lim, tile_elems);
-  if constexpr (BIN)
-    if (p.stage_b) stage_operand<SBt>(p, p.ord[2], 2, p.b + base_b, lds_b, p.pad_b, full, lim, tile_elems);
-  if (p.stage_a || p.stage_b) __syncthreads();
-
-  // compute phase, in the output's enumeration order (LDS slot == enumeration index)
+// global -> LDS copy of one staged input, enumerated in that input's own order
+// FULL: the tile is not clipped and every lane has a whole vector in every pass, so the loop
+// body carries no per-lane conditions at all.
+template <class S, int V, int WHICH, bool FULL>
+OCN_DEV void stage_operand(KTiledArgs &p, const char *base, S *lds,
+                           const uint32_t *lim_dim, uint32_t nvec) {
+  constexpr int J = V > 1 ? 2 : 4;  // vectors in flight per lane
+  KTileOrder &o = p.ord[WHICH];
+  const uint32_t zsrc = p.swz[WHICH - 1].src, zmask = p.swz[WHICH - 1].mask, zdst = p.swz[WHICH - 1].dst;
   const uint32_t tid = threadIdx.x;
-  const TileOrder &oo = p.ord[0];
-  const TilePos lo = tile_pos<3>(oo, p.nord, tid);
-  char *out = p.out + base_o;
-  const char *pa = p.a + base_a;
-  const char *pb = BIN ? p.b + base_b : nullptr;
-  for (uint32_t j0 = 0; j0 < tile_elems; j0 += kBlock * J) {
-    SAt av[J];
-    SBt bv[J];
-    int64_t offo[J];
-    bool ok[J];
+  const LanePos lo = lane_pos(o, tid);
+  const uint32_t step = 1u << o.lds_shift[0];  // slot distance between a vector's elements
+  const int niter = o.niter;
+  for (int j0 = 0; j0 < niter; j0 += J) {
+    Pack<S, V> v[J];
+    uint32_t slot[J];
+    int nv[J];
 #pragma unroll
     for (int j = 0; j < J; ++j) {
-      const uint32_t ehi = j0 + j * kBlock;
-      const uint32_t e = ehi + tid;
-      ok[j] = e < tile_elems && (full || tile_inside(oo, p.nord, e, lim[0]));
-      const TilePos hi = tile_pos<3>(oo, p.nord, ehi);
-      offo[j] = lo.off[0] + hi.off[0];
-      if (ok[j]) {
-        if (p.stage_a) av[j] = lds_a[e + (e >> p.pad_a)];
-        else av[j] = *reinterpret_cast<const SAt *>(pa + lo.off[1] + hi.off[1]);
-        if constexpr (BIN) {
-          if (p.stage_b) bv[j] = lds_b[e + (e >> p.pad_b)];
-          else bv[j] = *reinterpret_cast<const SBt *>(pb + lo.off[2] + hi.off[2]);
+      const int jj = j0 + j;
+      nv[j] = 0;
+      if (jj < niter) {
+        const uint32_t e = tid + (uint32_t)jj * kBlock;
+        int n = V;
+        if constexpr (!FULL) {
+          n = e < nvec ? V : 0;
+          if (n) n = vec_inside(o, e, lim_dim);
+        }
+        nv[j] = n;
+        slot[j] = lo.slot + o.hi_slot[jj];
+        const char *src = base + lo.off[WHICH] + o.hi_off[WHICH][jj];
+        if (FULL || n == V) {
+          load_pack<S, V>(src, v[j]);
+        } else {
+#pragma unroll
+          for (int i = 0; i < V; ++i)
+            if (i < n) v[j].v[i] = reinterpret_cast<const S *>(src)[i];
         }
       }
     }
 #pragma unroll
     for (int j = 0; j < J; ++j) {
-      if (ok[j]) {
-        SOt r;
-        if constexpr (BIN) r = G::eval(av[j], bv[j]);
-        else r = G::eval(av[j], SBt{});
-        *reinterpret_cast<SOt *>(out + offo[j]) = r;
+#pragma unroll
+      for (int i = 0; i < V; ++i)
+        if (FULL || i < nv[j]) lds[swizzle(slot[j] + (uint32_t)i * step, zsrc, zmask, zdst)] = v[j].v[i];
+    }
+  }
+}
+
+// read V consecutive slots of a staged operand (consecutive along the output's fastest axis)
+template <class S, int V>
+OCN_DEV void read_staged(const S *lds, uint32_t slot0, uint32_t zsrc, uint32_t zmask, uint32_t zdst, Pack<S, V> &dst) {
+  constexpr int EPC = (16 / (int)sizeof(S)) < V ? (16 / (int)sizeof(S)) : V;  // elements per LDS access
+  using Chunk = Pack<S, EPC>;
+#pragma unroll
+  for (int c = 0; c < V / EPC; ++c)
+    *reinterpret_cast<Chunk *>(&dst.v[c * EPC]) =
+        *reinterpret_cast<const Chunk *>(&lds[swizzle(slot0 + c * EPC, zsrc, zmask, zdst)]);
+}
+
+// V elements of a non-staged input along the output's fastest axis (byte stride s0 there)
+template <class S, int V> OCN_DEV void read_direct(const char *src, int64_t s0, int n, Pack<S, V> &dst) {
+  if (s0 == (int64_t)sizeof(S) && n == V) {
+    load_pack<S, V>(src, dst);
+  } else {
+#pragma unroll
+    for (int i = 0; i < V; ++i)
+      if (i < n) dst.v[i] = *reinterpret_cast<const S *>(src + (int64_t)i * s0);
+  }
+}
+
+template <class G, int V, bool FULL>
+OCN_DEV void tiled_compute(KTiledArgs &p, char *out, const char *pa, const char *pb,
+                           const typename G::SAt *lds_a, const typename G::SBt *lds_b,
+                           const uint32_t *lim_dim, uint32_t nvec) {
+  using SAt = typename G::SAt;
+  using SBt = typename G::SBt;
+  using SOt = typename G::SOt;
+  constexpr bool BIN = G::NIN2;
+  constexpr int J = V > 1 ? 2 : 4;
+  KTileOrder &o = p.ord[0];
+  const uint32_t tid = threadIdx.x;
+  const LanePos lo = lane_pos(o, tid);
+  const int64_t sa0 = o.stride[1][0], sb0 = o.stride[2][0];
+  const bool stage_a = p.stage_a, stage_b = p.stage_b;
+  const uint32_t asrc = p.swz[0].src, amask = p.swz[0].mask, adst = p.swz[0].dst;
+  const uint32_t bsrc = p.swz[1].src, bmask = p.swz[1].mask, bdst = p.swz[1].dst;
+  const int niter = o.niter;
+  for (int j0 = 0; j0 < niter; j0 += J) {
+    Pack<SAt, V> av[J];
+    Pack<SBt, V> bv[J];
+    int64_t offo[J];
+    int nv[J];
+#pragma unroll
+    for (int j = 0; j < J; ++j) {
+      const int jj = j0 + j;
+      nv[j] = 0;
+      if (jj < niter) {
+        const uint32_t e = tid + (uint32_t)jj * kBlock;
+        int n = V;
+        if constexpr (!FULL) {
+          n = e < nvec ? V : 0;
+          if (n) n = vec_inside(o, e, lim_dim);
+        }
+        nv[j] = n;
+        offo[j] = lo.off[0] + o.hi_off[0][jj];
+        if (FULL || n) {
+          const uint32_t slot0 = e * V;  // the output's order is the slot order
+          if (stage_a) read_staged<SAt, V>(lds_a, slot0, asrc, amask, adst, av[j]);
+          else read_direct<SAt, V>(pa + lo.off[1] + o.hi_off[1][jj], sa0, n, av[j]);
+          if constexpr (BIN) {
+            if (stage_b) read_staged<SBt, V>(lds_b, slot0, bsrc, bmask, bdst, bv[j]);
+            else read_direct<SBt, V>(pb + lo.off[2] + o.hi_off[2][jj], sb0, n, bv[j]);
+          }
+        }
       }
     }
+#pragma unroll
+    for (int j = 0; j < J; ++j) {
+      const int n = nv[j];
+      if (!FULL && n == 0) continue;
+      Pack<SOt, V> r;
+#pragma unroll
+      for (int i = 0; i < V; ++i) {
+        if constexpr (BIN) r.v[i] = G::eval(av[j].v[i], bv[j].v[i]);
+        else r.v[i] = G::eval(av[j].v[i], SBt{});
+      }
+      char *po = out + offo[j];
+      if (FULL || n == V) {
+        store_pack<SOt, V>(po, r);
+      } else {
+#pragma unroll
+        for (int i = 0; i < V; ++i)
+          if (i < n) reinterpret_cast<SOt *>(po)[i] = r.v[i];
+      }
+    }
+  }
+}
+
+template <class S, int V, int WHICH>
+OCN_DEV void stage_dispatch(KTiledArgs &p, const char *base, S *lds, bool full, const uint32_t *lim_dim,
+                            uint32_t nvec) {
+  if (full && nvec >= (uint32_t)kBlock) stage_operand<S, V, WHICH, true>(p, base, lds, lim_dim, nvec);
+  else stage_operand<S, V, WHICH, false>(p, base, lds, lim_dim, nvec);
+}
+
+// One tile per loop trip; workgroup b takes tiles b, b + gridDim.x, ...
+template <class G> __global__ __launch_bounds__(kBlock) void ew_tiled_kernel(const TiledArgs by_value) {
+  using SAt = typename G::SAt;
+  using SBt = typename G::SBt;
+  constexpr bool BIN = G::NIN2;
+  constexpr int VA = 16 / (int)sizeof(SAt) > 1 ? 16 / (int)sizeof(SAt) : 1;
+  constexpr int VB = 16 / (int)sizeof(SBt) > 1 ? 16 / (int)sizeof(SBt) : 1;
+  constexpr int VC = G::V;
+  (void)by_value;  // read through the kernarg segment instead (it is the only argument)
+  KTiledArgs &p = *(KTiledArgs *)__builtin_amdgcn_kernarg_segment_ptr();
+
+  const uint32_t tile_elems = 1u << p.tile_bits;
+  SAt *lds_a = reinterpret_cast<SAt *>(ocn_lds_raw);
+  SBt *lds_b = reinterpret_cast<SBt *>(reinterpret_cast<char *>(ocn_lds_raw) + p.lds_off_b);
+  const bool stage_a = p.stage_a, stage_b = BIN && p.stage_b;
+  const bool staged = stage_a || stage_b;
+  const uint32_t total_tiles = p.total_tiles;
+  const int ndim = p.ndim;
+
+  for (uint32_t tile = blockIdx.x; tile < total_tiles; tile += gridDim.x) {
+    // tile origin and clipped extents (uniform over the workgroup)
+    uint32_t t = tile;
+    int64_t base_o = 0, base_a = 0, base_b = 0;
+    uint32_t lim_dim[kMaxDims];
+    bool full = true;
+#pragma unroll
+    for (int d = kMaxDims - 1; d >= 0; --d) {
+      lim_dim[d] = 1;
+      if (d < ndim) {
+        const uint32_t dv = p.ntdiv[d].d, dm = p.ntdiv[d].m, ds = p.ntdiv[d].s;
+        const uint32_t q = (d == 0) ? 0u : (uint32_t)((((uint64_t)t * dm) >> 32) + t) >> ds;
+        const uint32_t tc = t - q * dv;
+        t = q;
+        const int64_t i0 = (int64_t)tc << p.tl[d];
+        const int64_t ext = (int64_t)1 << p.tl[d];
+        const int64_t rem = p.size[d] - i0;
+        lim_dim[d] = (uint32_t)(rem < ext ? rem : ext);
+        full = full && rem >= ext;
+        base_o += i0 * p.so[d];
+        base_a += i0 * p.sa[d];
+        if constexpr (BIN) base_b += i0 * p.sb[d];
+      }
+    }
+
+    if (stage_a) {
+      if (p.ord[1].vecw) stage_dispatch<SAt, VA, 1>(p, p.a + base_a, lds_a, full, lim_dim, tile_elems >> p.ord[1].vecw);
+      else stage_dispatch<SAt, 1, 1>(p, p.a + base_a, lds_a, full, lim_dim, tile_elems);
+    }
+    if constexpr (BIN) {
+      if (stage_b) {
+        if (p.ord[2].vecw) stage_dispatch<SBt, VB, 2>(p, p.b + base_b, lds_b, full, lim_dim, tile_elems >> p.ord[2].vecw);
+        else stage_dispatch<SBt, 1, 2>(p, p.b + base_b, lds_b, full, lim_dim, tile_elems);
+      }
+    }
+    if (staged) __syncthreads();
+
+    char *out = p.out + base_o;
+    const char *pa = p.a + base_a;
+    const char *pb = BIN ? p.b + base_b : nullptr;
+    if (p.ord[0].vecw) {
+      const uint32_t nvec = tile_elems >> p.ord[0].vecw;
+      if (full && nvec >= (uint32_t)kBlock) tiled_compute<G, VC, true>(p, out, pa, pb, lds_a, lds_b, lim_dim, nvec);
+      else tiled_compute<G, VC, false>(p, out, pa, pb, lds_a, lds_b, lim_dim, nvec);
+    } else {
+      if (full && tile_elems >= (uint32_t)kBlock) tiled_compute<G, 1, true>(p, out, pa, pb, lds_a, lds_b, lim_dim, tile_elems);
+      else tiled_compute<G, 1, false>(p, out, pa, pb, lds_a, lds_b, lim_dim, tile_elems);
+    }
+    if (staged && tile + gridDim.x < total_tiles) __syncthreads();  // LDS is reused by the next tile
   }
 }
 

@@ -1,6 +1,7 @@
 // Kernel-argument builders for the elementwise kernels (dtype independent).
 #include "ew_launch.hpp"
 
+#include <algorithm>
 #include <cstring>
 
 namespace ocn {
@@ -39,8 +40,8 @@ TiledArgs make_tiled_args(const EwPlan &p, int es_a) {
   t.a = p.a.ptr;
   t.b = p.b.ptr;
   t.ndim = p.ndim;
-  t.nord = p.nord;
   t.tile_bits = p.tile_bits;
+  t.total_tiles = (uint32_t)p.total_tiles;
   for (int d = 0; d < p.ndim; ++d) {
     t.size[d] = p.size[d];
     t.so[d] = p.out.stride[d];
@@ -51,10 +52,8 @@ TiledArgs make_tiled_args(const EwPlan &p, int es_a) {
   }
   t.stage_a = p.stage_a;
   t.stage_b = p.stage_b;
-  t.pad_a = p.pad_shift_a;
-  t.pad_b = p.pad_shift_b;
   const int64_t tile_elems = (int64_t)1 << p.tile_bits;
-  t.lds_off_b = p.stage_a ? (uint32_t)(((tile_elems + (tile_elems >> p.pad_shift_a) + 1) * es_a + 15) / 16 * 16) : 0u;
+  t.lds_off_b = p.stage_a ? (uint32_t)((tile_elems * es_a + 15) / 16 * 16) : 0u;
   // bit position of each tiled dim in the output's enumeration order = its LDS slot shift
   int slot_shift[kMaxDims] = {0};
   int acc = 0;
@@ -63,16 +62,52 @@ TiledArgs make_tiled_args(const EwPlan &p, int es_a) {
     acc += p.tile_log2[p.ord_o[k]];
   }
   const int8_t *ords[3] = {p.ord_o, p.ord_a, p.ord_b};
-  for (int x = 0; x < 3; ++x)
+  const int vecw[3] = {p.vecw_o, p.vecw_a, p.vecw_b};
+  for (int x = 0; x < 3; ++x) {
+    TileOrder &o = t.ord[x];
+    o.nord = (int8_t)p.nord;
+    o.vecw = (int8_t)vecw[x];
     for (int k = 0; k < p.nord; ++k) {
       const int d = ords[x][k];
-      t.ord[x].dim[k] = (int8_t)d;
-      t.ord[x].width[k] = (int8_t)p.tile_log2[d];
-      t.ord[x].lds_shift[k] = (int8_t)slot_shift[d];
-      t.ord[x].stride[0][k] = p.out.stride[d];
-      t.ord[x].stride[1][k] = p.a.stride[d];
-      t.ord[x].stride[2][k] = p.b.stride[d];
+      o.dim[k] = (int8_t)d;
+      o.width[k] = (int8_t)p.tile_log2[d];
+      o.lds_shift[k] = (int8_t)slot_shift[d];
+      o.stride[0][k] = p.out.stride[d];
+      o.stride[1][k] = p.a.stride[d];
+      o.stride[2][k] = p.b.stride[d];
     }
+    const int64_t nvec = tile_elems >> vecw[x];
+    o.niter = (int32_t)((nvec + kBlock - 1) / kBlock);
+    // contribution of the pass number (bits 8 and up of the vector index) to offsets and slot
+    for (int j = 0; j < o.niter && j < kMaxTilePasses; ++j) {
+      const LanePos hi = lane_pos(o, (uint32_t)j * kBlock);
+      for (int y = 0; y < 3; ++y) o.hi_off[y][j] = hi.off[y];
+      o.hi_slot[j] = hi.slot;
+    }
+  }
+  // XOR swizzle of a staged operand's LDS slots: the vector index along the operand's own
+  // fastest dim is folded into the low slot bits, at 16-byte granularity when the compute
+  // phase reads whole vectors and at element granularity otherwise
+  auto make_swizzle = [&](const TileOrder &o, int es) {
+    TileSwizzle z{0, 0, 0};
+    if (p.nord == 0) return z;
+    const int w_f = o.width[0] - o.vecw;             // vector positions along the operand's dim
+    const int w_0 = p.tile_log2[p.ord_o[0]];         // bits of the output's fastest dim
+    int dst = 0, want = 5;
+    if (p.vecw_o > 0) {
+      while ((1 << dst) * es < 16) ++dst;            // keep 16-byte groups intact
+      want = 3;
+    }
+    if (dst > w_0) dst = w_0;
+    int bits = std::min(want, std::min(w_f, w_0 - dst));
+    if (bits < 0) bits = 0;
+    z.src = (uint32_t)(o.lds_shift[0] + o.vecw);
+    z.mask = (1u << bits) - 1u;
+    z.dst = (uint32_t)dst;
+    return z;
+  };
+  if (p.stage_a) t.swz[0] = make_swizzle(t.ord[1], es_a);
+  if (p.stage_b) t.swz[1] = make_swizzle(t.ord[2], dt_size(p.b.dtype));
   return t;
 }
 

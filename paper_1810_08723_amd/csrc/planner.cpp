@@ -214,42 +214,70 @@ void tile_order(const EwPlan &p, const int64_t *stride, int8_t *ord) {
     for (int j = i; j > 0 && key(ord[j]) < key(ord[j - 1]); --j) std::swap(ord[j], ord[j - 1]);
 }
 
-constexpr int64_t kMaxLdsBytes = 64 * 1024;  // per workgroup: two workgroups share a CU's 160 KB
+#ifndef OCN_TILE_LDS_KB
+#define OCN_TILE_LDS_KB 32
+#endif
+constexpr int64_t kMaxLdsBytes = OCN_TILE_LDS_KB * 1024;  // per workgroup, so that several share a CU's 160 KB
 
 void choose_tiles(EwPlan &p) {
   // Operands that want coalescing along their own fastest axis: the output and every staged
-  // input.  Hand out tile bits round-robin, each operand growing its fastest unsaturated
-  // dimension, until the tile holds 2^budget elements.
-  const int es_o = dt_size(p.out.dtype), es_a = dt_size(p.a.dtype);
-  const int es_b = p.nin == 2 ? dt_size(p.b.dtype) : 0;
-  int staged_bytes = (p.stage_a ? es_a : 0) + (p.stage_b ? es_b : 0);
+  // input.  Tile bits are handed out one at a time, each to the fastest unsaturated dimension
+  // of one operand, until the tile holds 2^budget elements.  First every staged input is grown
+  // to a contiguous run of a full 128-byte cache line (a shorter read run still fetches the
+  // whole line, and the other half is fetched again by a neighbouring tile) and the output to
+  // 64 bytes (partial-line writes cost no extra traffic); the remaining bits go round-robin.
+  const int es[3] = {dt_size(p.out.dtype), dt_size(p.a.dtype), p.nin == 2 ? dt_size(p.b.dtype) : 1};
+  const int staged_bytes = (p.stage_a ? es[1] : 0) + (p.stage_b ? es[2] : 0);
   int budget = 12;
-  while (budget > 8 && ((int64_t)staged_bytes << budget) + ((int64_t)staged_bytes << (budget - 1)) > kMaxLdsBytes)
-    --budget;
-  (void)es_o;
+  while (budget > 8 && ((int64_t)staged_bytes << budget) > kMaxLdsBytes) --budget;
   const int64_t *strides[3] = {p.out.stride, p.a.stride, p.b.stride};
-  bool wants[3] = {true, p.stage_a, p.stage_b};
+  const bool wants[3] = {true, p.stage_a, p.stage_b};
   int used = 0;
   auto saturated = [&](int d) { return ((int64_t)1 << p.tile_log2[d]) >= p.size[d]; };
+  // give operand o one more bit along its fastest unsaturated dim; false if it has none
+  auto grow = [&](int o) {
+    int best = -1;
+    int64_t bs = 0;
+    for (int d = 0; d < p.ndim; ++d) {
+      if (saturated(d)) continue;
+      const int64_t s = iabs64(strides[o][d]);
+      if (s == 0) continue;
+      if (best < 0 || s < bs || (s == bs && d > best)) { best = d; bs = s; }
+    }
+    if (best < 0) return false;
+    ++p.tile_log2[best];
+    ++used;
+    return true;
+  };
+  // bytes of operand o that the tile covers contiguously, starting from its fastest dim
+  auto run_bytes = [&](int o) {
+    int64_t run = es[o];
+    bool any = true;
+    while (any) {
+      any = false;
+      for (int d = 0; d < p.ndim; ++d)
+        if (p.tile_log2[d] > 0 && iabs64(strides[o][d]) == run) {
+          const int64_t ext = std::min<int64_t>((int64_t)1 << p.tile_log2[d], p.size[d]);
+          run *= ext;
+          any = ext > 1 && ext == p.size[d] ? true : false;  // only a fully covered dim chains on
+          if (!any) return run;
+          break;
+        }
+    }
+    return run;
+  };
+  const int64_t target[3] = {64, 128, 128};
   bool progress = true;
   while (used < budget && progress) {
     progress = false;
-    for (int o = 0; o < 3 && used < budget; ++o) {
-      if (!wants[o]) continue;
-      // fastest unsaturated dim of this operand
-      int best = -1;
-      int64_t bs = 0;
-      for (int d = 0; d < p.ndim; ++d) {
-        if (saturated(d)) continue;
-        int64_t s = iabs64(strides[o][d]);
-        if (s == 0) continue;
-        if (best < 0 || s < bs || (s == bs && d > best)) { best = d; bs = s; }
-      }
-      if (best < 0) continue;
-      ++p.tile_log2[best];
-      ++used;
-      progress = true;
-    }
+    for (int o = 0; o < 3 && used < budget; ++o)
+      if (wants[o] && run_bytes(o) < target[o] && grow(o)) progress = true;
+  }
+  progress = true;
+  while (used < budget && progress) {
+    progress = false;
+    for (int o = 0; o < 3 && used < budget; ++o)
+      if (wants[o] && grow(o)) progress = true;
   }
   p.tile_bits = used;
 }
@@ -408,34 +436,64 @@ int plan_elementwise(int nin, int op, const ocn_tensor *a, const ocn_tensor *b,
   p.nord = 0;
   for (int d = 0; d < n; ++d)
     if (p.tile_log2[d] > 0) ++p.nord;
-  // LDS slot = position in the output's enumeration order; a staged operand skews its
-  // slots by one element per step of its own fastest tiled dim to spread LDS banks
-  auto pad_shift = [&](const int8_t *ord) {
-    if (p.nord == 0) return 0;
-    int shift = 0;
-    for (int k = 0; k < p.nord; ++k) {
-      if (p.ord_o[k] == ord[0]) return shift;
-      shift += p.tile_log2[p.ord_o[k]];
-    }
-    return 0;
+  // an input whose fastest tiled dim is the output's needs no staging after all
+  if (p.nord == 0 || p.ord_a[0] == p.ord_o[0]) p.stage_a = false;
+  if (p.nord == 0 || p.ord_b[0] == p.ord_o[0]) p.stage_b = false;
+
+  // ---- vector widths of the three enumeration orders -----------------------------------
+  // aligned: base pointer and every stride except the one along `skip` are multiples of vb
+  auto aligned = [&](const Operand &x, int64_t vb, int skip) {
+    if ((intptr_t)x.ptr % vb != 0) return false;
+    for (int d = 0; d < n; ++d)
+      if (d != skip && x.stride[d] % vb != 0) return false;
+    return true;
   };
-  p.pad_shift_a = p.stage_a ? pad_shift(p.ord_a) : 0;
-  p.pad_shift_b = p.stage_b ? pad_shift(p.ord_b) : 0;
-  if (p.stage_a && p.pad_shift_a == 0) p.stage_a = false;  // same fastest tiled dim after all
-  if (p.stage_b && p.pad_shift_b == 0) p.stage_b = false;
+  auto log2i = [](int v) { int l = 0; while ((1 << l) < v) ++l; return l; };
+  p.vecw_o = p.vecw_a = p.vecw_b = 0;
+  if (p.nord > 0) {
+    const int d0 = p.ord_o[0];
+    // compute phase: V consecutive elements along the output's fastest dim per lane
+    bool ok = p.out.stride[d0] == es_o && p.tile_log2[d0] >= log2i(V) && V > 1 &&
+              aligned(p.out, (int64_t)V * es_o, d0);
+    auto direct_ok = [&](const Operand &x, int es, bool staged) {
+      if (staged) return true;
+      if (x.stride[d0] != es) return true;  // broadcast or strided: element loads, no constraint
+      return aligned(x, (int64_t)V * es, d0);
+    };
+    ok = ok && direct_ok(p.a, es_a, p.stage_a) && (nin == 1 || direct_ok(p.b, es_b, p.stage_b));
+    if (ok) p.vecw_o = log2i(V);
+    auto stage_vec = [&](const Operand &x, int es, const int8_t *ord) {
+      const int v = 16 / es;
+      if (v <= 1) return 0;
+      const int f = ord[0];
+      if (x.stride[f] != es || p.tile_log2[f] < log2i(v) || !aligned(x, 16, f)) return 0;
+      return log2i(v);
+    };
+    if (p.stage_a) p.vecw_a = stage_vec(p.a, es_a, p.ord_a);
+    if (p.stage_b) p.vecw_b = stage_vec(p.b, es_b, p.ord_b);
+  }
   const int64_t tile_elems = (int64_t)1 << p.tile_bits;
-  auto lds_elems = [&](int shift) { return tile_elems + (tile_elems >> shift) + 1; };
   p.lds_bytes = 0;
-  if (p.stage_a) p.lds_bytes += (lds_elems(p.pad_shift_a) * es_a + 15) / 16 * 16;
-  if (p.stage_b) p.lds_bytes += (lds_elems(p.pad_shift_b) * es_b + 15) / 16 * 16;
+  if (p.stage_a) p.lds_bytes += (tile_elems * es_a + 15) / 16 * 16;
+  if (p.stage_b) p.lds_bytes += (tile_elems * es_b + 15) / 16 * 16;
   p.total_tiles = 1;
   for (int d = 0; d < n; ++d) {
     p.ntiles[d] = (p.size[d] + ((int64_t)1 << p.tile_log2[d]) - 1) >> p.tile_log2[d];
     p.total_tiles *= p.ntiles[d];
   }
+  // One tile per workgroup.  (Persistent workgroups looping over tiles, and handing each XCD
+  // a contiguous range of tiles, were both measured slower on MI355X.)
   p.grid = p.total_tiles;
   p.kernel = (p.stage_a || p.stage_b) ? OCN_KERNEL_EW_TILED : OCN_KERNEL_EW_GENERIC;
-  p.vec = 1;
+  p.vec = 1 << p.vecw_o;
+  if (p.total_tiles >= ((int64_t)1 << 31)) {  // tile coordinates are 32-bit: use the 64-bit generic kernel
+    p.specialised = false;
+    p.kernel = OCN_KERNEL_EW_GENERIC;
+    p.vec = 1;
+    p.stage_a = p.stage_b = false;
+    p.lds_bytes = 0;
+    p.grid = (numel + kBlock - 1) / kBlock;
+  }
   *plan = p;
   return OCN_OK;
 }

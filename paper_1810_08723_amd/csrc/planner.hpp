@@ -18,6 +18,13 @@ namespace ocn {
 constexpr int kMaxDims = OCN_MAX_DIMS;
 constexpr int kBlock = 256;        // threads per workgroup of every kernel (4 wavefronts)
 constexpr int kWave = 64;
+constexpr int64_t kNumCUs = 256;          // MI355X: 8 XCDs x 32 compute units
+constexpr uint32_t kXcds = 8;
+constexpr int64_t kLdsPerCu = 160 * 1024;  // bytes of LDS per compute unit
+#ifndef OCN_MAX_BLOCKS_PER_CU
+#define OCN_MAX_BLOCKS_PER_CU 8
+#endif
+constexpr int64_t kMaxBlocksPerCu = OCN_MAX_BLOCKS_PER_CU;  // resident 256-lane workgroups per CU worth launching
 
 // unsigned division by an invariant: q = (mulhi(n, m) + n) >> s, valid for n < 2^31
 struct FastDiv {
@@ -52,7 +59,7 @@ struct EwPlan {
   int tile_log2[kMaxDims] = {0};
   int tile_bits = 0;            // log2 of the elements of one tile
   bool stage_a = false, stage_b = false;
-  int pad_shift_a = 0, pad_shift_b = 0;
+  int vecw_o = 0, vecw_a = 0, vecw_b = 0;  // log2 vector length of each enumeration order
   int nord = 0;                 // dims with a tile extent > 1
   int8_t ord_o[kMaxDims] = {0}, ord_a[kMaxDims] = {0}, ord_b[kMaxDims] = {0};
   int64_t ntiles[kMaxDims] = {0};

@@ -45,8 +45,11 @@ OCN_HD constexpr int rows_vec(int es_min, int es_max) {
   return imax(1, imin(16 / es_min, 64 / es_max));
 }
 // Vectors per lane, so that about 64 bytes of the widest operand are in flight per lane.
+#ifndef OCN_ROWS_MAXU
+#define OCN_ROWS_MAXU 4
+#endif
 OCN_HD constexpr int rows_unroll(int vec, int es_max) {
-  return imax(1, imin(4, 64 / (vec * es_max)));
+  return imax(1, imin(OCN_ROWS_MAXU, 64 / (vec * es_max)));
 }
 
 }  // namespace ocn
