@@ -548,7 +548,10 @@ int sort_merge(RDim *d, int n, bool by_out) {
   return m;
 }
 
-constexpr int64_t kTargetWaves = 256 * 8;  // enough wavefronts to occupy every CU
+#ifndef OCN_RED_TARGET_WAVES
+#define OCN_RED_TARGET_WAVES (256 * 16)
+#endif
+constexpr int64_t kTargetWaves = OCN_RED_TARGET_WAVES;  // enough wavefronts to occupy every CU
 
 void choose_reduce_launch(RedPlan &p) {
   const int es = dt_size(p.a_dtype);
@@ -584,7 +587,10 @@ void choose_reduce_launch(RedPlan &p) {
     const int64_t n0 = p.rsize[p.nred - 1];
     const int64_t vpr = (n0 + p.vec - 1) / p.vec;         // vectors per innermost run
     const int64_t nvec = vpr * (p.nredtot / n0);          // vectors per output
-    p.group = (nvec * p.vec * es <= 32 * 1024) ? kWave : kBlock;
+#ifndef OCN_ROWS_WAVE_BYTES
+#define OCN_ROWS_WAVE_BYTES (8 * 1024)
+#endif
+    p.group = (nvec * p.vec * es <= OCN_ROWS_WAVE_BYTES) ? kWave : kBlock;
     const int64_t groups_per_block = kBlock / p.group;
     const int64_t waves = p.nout * (p.group / kWave);
     p.split = 1;
@@ -607,12 +613,18 @@ void choose_reduce_launch(RedPlan &p) {
     const int64_t colblocks = (nc + (int64_t)kWave * p.vec - 1) / ((int64_t)kWave * p.vec);
     const int64_t others = p.nout / nc;
     const int64_t blocks0 = colblocks * others;
+    // Rows are dealt to the wavefronts of a workgroup, which combine through LDS, and to
+    // `split` workgroups, which combine through the workspace.  Sixteen wavefronts per
+    // workgroup keep the partial results (and the second pass) four times smaller.
+    int nw = 4;
     p.split = 1;
-    if (blocks0 * 4 < kTargetWaves) {
-      const int64_t want = (kTargetWaves + blocks0 * 4 - 1) / (blocks0 * 4);
-      const int64_t most = std::max<int64_t>(1, p.nredtot / (4 * 16));  // >= 16 rows per wave
+    if (blocks0 * nw < kTargetWaves) {
+      if (p.nredtot >= 16 * 64 && blocks0 * 16 * 2 <= kTargetWaves) nw = 16;
+      const int64_t want = (kTargetWaves + blocks0 * nw - 1) / (blocks0 * nw);
+      const int64_t most = std::max<int64_t>(1, p.nredtot / (nw * 16));  // >= 16 rows per wave
       p.split = std::max<int64_t>(1, std::min(want, most));
     }
+    p.block = nw * kWave;
     p.chunk = (p.nredtot + p.split - 1) / p.split;
     p.split = (p.nredtot + p.chunk - 1) / p.chunk;
     p.grid = blocks0 * p.split;

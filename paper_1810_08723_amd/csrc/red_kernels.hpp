@@ -189,70 +189,210 @@ OCN_DEV int64_t reduced_offset(const RedArgs &p, uint32_t q, int first) {
 // rows
 // ---------------------------------------------------------------------------------------
 
-template <class R, int S, int V>
-OCN_DEV typename R::A rows_accumulate(const RedArgs &p, const char *base, int64_t t0, int64_t t1,
-                                      int lane, int lanes) {
-  using St = storage_t<S>;
+// A lane's running fold over whole vectors of V consecutive elements.  The generic form
+// folds element by element; two specialisations use packed instructions:
+//   * sums of 8-bit integers add four bytes per instruction (dot product with ones) into a
+//     32-bit register that is flushed into the 64-bit total long before it can overflow;
+//   * min/max of half-precision values compares order-preserving 16-bit integer keys two at
+//     a time and tracks NaNs on the side, which keeps the NaN-propagating, +0-above--0
+//     semantics exact without any floating-point comparison.
+template <int S, int OP, int V, class Enable = void> struct VecFold {
+  using R = Reducer<S, OP>;
   using A = typename R::A;
-  constexpr int U = 4;  // independent accumulators and loads in flight per lane
-  A acc[U];
+  using St = storage_t<S>;
+  struct alignas(sizeof(St) * V >= 16 ? 16 : sizeof(St) * V) Pk { St v[V]; };
+  A acc;
+  OCN_DEV void init() { acc = R::identity(); }
+  OCN_DEV void add_full(const Pk &pk) {
 #pragma unroll
-  for (int u = 0; u < U; ++u) acc[u] = R::identity();
-  const bool single_run = p.nred == 1;
-  for (int64_t t = t0 + lane; t < t1; t += (int64_t)lanes * U) {
-    struct alignas(sizeof(St) * V >= 16 ? 16 : sizeof(St) * V) Pk { St v[V]; } pk[U];
-    int nval[U];
+    for (int i = 0; i < V; ++i) acc = R::combine(acc, R::lift(from_storage<S>(pk.v[i])));
+  }
+  OCN_DEV void add_partial(const Pk &pk, int n) {
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int64_t tt = t + (int64_t)u * lanes;
-      nval[u] = 0;
-      if (tt < t1) {
-        int64_t off, iv;
-        if (single_run) {
-          iv = tt;
-          off = 0;
-        } else {
-          const uint32_t q = rfastdiv((uint32_t)tt, p.vpr_div);
-          iv = (uint32_t)tt - q * p.vpr_div.d;
-          off = reduced_offset(p, q, 1);
-        }
-        const int64_t e0 = iv * V;
-        const int64_t left = p.n0 - e0;
-        const int n = left >= V ? V : (int)left;
-        nval[u] = n;
-        const char *src = base + off + e0 * (int64_t)sizeof(St);
-        if (n == V) {
-          if constexpr (sizeof(St) * V >= 16) {
-            using Q = uint32_t __attribute__((ext_vector_type(4)));
+    for (int i = 0; i < V; ++i)
+      if (i < n) acc = R::combine(acc, R::lift(from_storage<S>(pk.v[i])));
+  }
+  OCN_DEV A result() { return acc; }
+};
+
+// sum of int8 / uint8, sixteen per vector
+template <int S, int V>
+struct VecFold<S, R_SUM, V, std::enable_if_t<(S == DT_I8 || S == DT_U8) && V == 16>> {
+  using R = Reducer<S, R_SUM>;
+  using A = typename R::A;  // int64_t or uint64_t
+  using St = storage_t<S>;
+  struct alignas(16) Pk { St v[V]; };
+  A total;
+  int32_t part;      // at most 2^11 per add_full in magnitude
+  uint32_t pending;  // add_full calls since the last flush
+  OCN_DEV void init() { total = 0; part = 0; pending = 0; }
+  OCN_DEV void flush() {
+    if constexpr (S == DT_I8) total += (A)part;
+    else total += (A)(uint32_t)part;
+    part = 0;
+    pending = 0;
+  }
+  OCN_DEV void add_full(const Pk &pk) {
+    const int32_t *w = reinterpret_cast<const int32_t *>(&pk);
 #pragma unroll
-            for (int i = 0; i < (int)(sizeof(St) * V / 16); ++i)
-              reinterpret_cast<Q *>(&pk[u])[i] = reinterpret_cast<const Q *>(src)[i];
-          } else {
-#pragma unroll
-            for (int i = 0; i < V; ++i) pk[u].v[i] = reinterpret_cast<const St *>(src)[i];
-          }
-        } else {
-#pragma unroll
-          for (int i = 0; i < V; ++i)
-            if (i < n) pk[u].v[i] = reinterpret_cast<const St *>(src)[i];
-        }
-      }
+    for (int k = 0; k < 4; ++k) {
+      if constexpr (S == DT_I8) part = __builtin_amdgcn_sdot4(w[k], 0x01010101, part, false);
+      else part = (int32_t)__builtin_amdgcn_udot4((uint32_t)w[k], 0x01010101u, (uint32_t)part, false);
     }
+    if (++pending == (1u << 19)) flush();  // 2^19 * 2^11 < 2^31 (uint8: 2^19 * 4080 < 2^32)
+  }
+  OCN_DEV void add_partial(const Pk &pk, int n) {
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      if (nval[u] == V) {
+    for (int i = 0; i < V; ++i)
+      if (i < n) total += (A)pk.v[i];
+  }
+  OCN_DEV A result() { flush(); return total; }
+};
+
+// min / max of half precision, eight per vector
+template <int OP, int V>
+struct VecFold<DT_F16, OP, V, std::enable_if_t<(OP == R_MIN || OP == R_MAX) && V == 8>> {
+  using R = Reducer<DT_F16, OP>;
+  using A = typename R::A;  // hreg
+  using St = storage_t<DT_F16>;
+  struct alignas(16) Pk { St v[V]; };
+  using s2 = short __attribute__((ext_vector_type(2)));
+  using u2 = unsigned short __attribute__((ext_vector_type(2)));
+  static constexpr bool MX = OP == R_MAX;
+  // key(x) = x ^ ((x >> 15) & 0x7fff) orders every non-NaN half as a signed 16-bit integer,
+  // with -0 just below +0; it is its own inverse
+  s2 best;   // running max (min) of keys; starts at the value no finite-or-infinite half maps to
+  u2 mag;    // running max of |bits|: above 0x7c00 means a NaN was seen
+  OCN_DEV void init() {
+    const short start = MX ? (short)-32768 : (short)32767;
+    best = s2{start, start};
+    mag = u2{0, 0};
+  }
+  OCN_DEV void add_word(uint32_t w) {
+    const s2 x = __builtin_bit_cast(s2, w);
+    const s2 sign = x >> (short)15;
+    const s2 key = x ^ (sign & s2{0x7fff, 0x7fff});
+    best = MX ? __builtin_elementwise_max(best, key) : __builtin_elementwise_min(best, key);
+    mag = __builtin_elementwise_max(mag, __builtin_bit_cast(u2, w & 0x7fff7fffu));
+  }
+  OCN_DEV void add_full(const Pk &pk) {
+    const uint32_t *w = reinterpret_cast<const uint32_t *>(&pk);
 #pragma unroll
-        for (int i = 0; i < V; ++i) acc[u] = R::combine(acc[u], R::lift(from_storage<S>(pk[u].v[i])));
-      } else {
+    for (int k = 0; k < 4; ++k) add_word(w[k]);
+  }
+  OCN_DEV void add_partial(const Pk &pk, int n) {
+    const uint16_t *h = reinterpret_cast<const uint16_t *>(&pk);
+    // pad the missing slots by repeating the first element (n >= 1 here)
 #pragma unroll
-        for (int i = 0; i < V; ++i)
-          if (i < nval[u]) acc[u] = R::combine(acc[u], R::lift(from_storage<S>(pk[u].v[i])));
-      }
+    for (int k = 0; k < 4; ++k) {
+      const uint32_t lo = 2 * k < n ? h[2 * k] : h[0];
+      const uint32_t hi = 2 * k + 1 < n ? h[2 * k + 1] : h[0];
+      add_word(lo | (hi << 16));
     }
   }
+  OCN_DEV A result() {
+    const unsigned short m = mag.x > mag.y ? mag.x : mag.y;
+    if (m > 0x7c00u) return hreg{__builtin_nanf("")};
+    const short k = MX ? (best.x > best.y ? best.x : best.y) : (best.x < best.y ? best.x : best.y);
+    if (k == (MX ? (short)-32768 : (short)32767)) return R::identity();  // this lane saw nothing
+    const unsigned short bits = (unsigned short)(k ^ ((k >> 15) & 0x7fff));
+    return hreg{(float)__builtin_bit_cast(_Float16, bits)};
+  }
+};
+
+template <class St, int V, class Pk> OCN_DEV void load_vec(const char *src, Pk &pk) {
+  if constexpr (sizeof(St) * V >= 16) {
+    using Q = uint32_t __attribute__((ext_vector_type(4)));
 #pragma unroll
-  for (int u = 1; u < U; ++u) acc[0] = R::combine(acc[0], acc[u]);
-  return acc[0];
+    for (int i = 0; i < (int)(sizeof(St) * V / 16); ++i)
+      reinterpret_cast<Q *>(&pk)[i] = reinterpret_cast<const Q *>(src)[i];
+  } else {
+#pragma unroll
+    for (int i = 0; i < V; ++i) pk.v[i] = reinterpret_cast<const St *>(src)[i];
+  }
+}
+
+// Fold vectors t0 .. t1-1 of one output's addends, `lanes` lanes cooperating.  The bulk runs
+// in a loop without any per-lane condition (every lane loads U whole vectors per trip); the
+// ragged remainder - the last few vectors, and the partial vector at the end of a run whose
+// length is not a multiple of V - goes through a checked loop.
+template <int S, int OP, int V, bool SINGLE>
+OCN_DEV typename Reducer<S, OP>::A rows_accumulate_impl(const RedArgs &p, const char *base, int64_t t0,
+                                                        int64_t t1, int lane, int lanes) {
+  using R = Reducer<S, OP>;
+  using St = storage_t<S>;
+  using F = VecFold<S, OP, V>;
+  using Pk = typename F::Pk;
+  constexpr int U = 4;  // independent folds and loads in flight per lane
+  F fold[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) fold[u].init();
+  // vectors below t_full are known to be whole
+  int64_t t_full = t0;
+  if constexpr (SINGLE) {
+    t_full = p.n0 / V;
+    if (t_full > t1) t_full = t1;
+  } else if (p.n0 % V == 0) {
+    t_full = t1;
+  }
+  auto address = [&](int64_t tt, int64_t &e0) -> const char * {
+    int64_t off = 0, iv = tt;
+    if constexpr (!SINGLE) {
+      const uint32_t q = rfastdiv((uint32_t)tt, p.vpr_div);
+      iv = (uint32_t)tt - q * p.vpr_div.d;
+      off = reduced_offset(p, q, 1);
+    }
+    e0 = iv * V;
+    return base + off + e0 * (int64_t)sizeof(St);
+  };
+  int64_t t = t0;
+  for (; t + (int64_t)lanes * U <= t_full; t += (int64_t)lanes * U) {
+    Pk pk[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      int64_t e0;
+      load_vec<St, V>(address(t + (int64_t)u * lanes + lane, e0), pk[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) fold[u].add_full(pk[u]);
+  }
+  for (; t + lanes <= t_full; t += lanes) {  // whole vectors, one per lane and trip
+    Pk pk;
+    int64_t e0;
+    load_vec<St, V>(address(t + lane, e0), pk);
+    fold[0].add_full(pk);
+  }
+  for (int64_t tt = t + lane; tt < t1; tt += lanes) {
+    Pk pk;
+    int64_t e0;
+    const char *src = address(tt, e0);
+    const int64_t left = p.n0 - e0;
+    if (left >= V) {
+      load_vec<St, V>(src, pk);
+      fold[0].add_full(pk);
+    } else {
+#pragma unroll
+      for (int i = 0; i < V; ++i)
+        if (i < (int)left) pk.v[i] = reinterpret_cast<const St *>(src)[i];
+      fold[0].add_partial(pk, (int)left);
+    }
+  }
+  typename R::A acc = fold[0].result();
+#pragma unroll
+  for (int u = 1; u < U; ++u) acc = R::combine(acc, fold[u].result());
+  return acc;
+}
+
+// Fold vectors t0 .. t1-1 of one output's addends, `lanes` lanes cooperating.  The bulk runs
+// in a loop without any per-lane condition (every lane loads U whole vectors per trip); the
+// ragged remainder - the last few vectors, and the partial vector at the end of a run whose
+// length is not a multiple of V - goes through a checked loop.  A single reduced dimension
+// (the common case) needs no index decomposition at all.
+template <int S, int OP, int V>
+OCN_DEV typename Reducer<S, OP>::A rows_accumulate(const RedArgs &p, const char *base, int64_t t0, int64_t t1,
+                                                   int lane, int lanes) {
+  if (p.nred == 1) return rows_accumulate_impl<S, OP, V, true>(p, base, t0, t1, lane, lanes);
+  return rows_accumulate_impl<S, OP, V, false>(p, base, t0, t1, lane, lanes);
 }
 
 template <int S, int OP> __global__ __launch_bounds__(kBlock) void red_rows_kernel(const RedArgs p) {
@@ -280,8 +420,8 @@ template <int S, int OP> __global__ __launch_bounds__(kBlock) void red_rows_kern
     if (t1 > p.nvec) t1 = p.nvec;
     const int lane = per_wave ? lane_in_wave : tid;
     const int lanes = per_wave ? kWave : kBlock;
-    if (p.vec > 1) acc = rows_accumulate<R, S, VF>(p, p.a + off_a, t0, t1, lane, lanes);
-    else acc = rows_accumulate<R, S, 1>(p, p.a + off_a, t0, t1, lane, lanes);
+    if (p.vec > 1) acc = rows_accumulate<S, OP, VF>(p, p.a + off_a, t0, t1, lane, lanes);
+    else acc = rows_accumulate<S, OP, 1>(p, p.a + off_a, t0, t1, lane, lanes);
     acc = wave_fold<R>(acc);
   }
   if (!per_wave) {  // combine the four wavefronts of the workgroup
@@ -308,15 +448,17 @@ template <int S, int OP> __global__ __launch_bounds__(kBlock) void red_rows_kern
 // cols
 // ---------------------------------------------------------------------------------------
 
-template <int S, int OP, int V, int VF>
-OCN_DEV void cols_body(const RedArgs &p, typename Reducer<S, OP>::A (*lds)[kWave][VF]) {
+constexpr int kColsMaxWaves = 16;  // the cols kernel runs with 4 or 16 wavefronts per workgroup
+
+template <int S, int OP, int V>
+OCN_DEV void cols_body(const RedArgs &p, typename Reducer<S, OP>::A (*lds)[kWave]) {
   using R = Reducer<S, OP>;
   using A = typename R::A;
   using St = storage_t<S>;
   const int tid = threadIdx.x;
   const int lane = tid & (kWave - 1);
   const int wave = tid / kWave;
-  constexpr int NW = kBlock / kWave;
+  const int NW = (int)blockDim.x / kWave;
 
   // block -> (split, other kept dims, column block)
   uint32_t b = blockIdx.x;
@@ -351,72 +493,59 @@ OCN_DEV void cols_body(const RedArgs &p, typename Reducer<S, OP>::A (*lds)[kWave
   const int64_t r0 = (int64_t)s * p.chunk;
   int64_t r1 = r0 + p.chunk;
   if (r1 > p.nredtot) r1 = p.nredtot;
-  constexpr int U = 4;
-  if (ncol > 0) {
-    for (int64_t r = r0 + wave; r < r1; r += NW * U) {
-      struct alignas(sizeof(St) * V >= 16 ? 16 : sizeof(St) * V) Pk { St v[V]; } pk[U];
-      bool ok[U];
+  constexpr int U = 4;  // rows in flight per wavefront
+  struct alignas(sizeof(St) * V >= 16 ? 16 : sizeof(St) * V) Pk { St v[V]; };
+  int64_t r = r0 + wave;
+  if (ncol == V) {  // whole vectors of columns: no per-element conditions
+    for (; r + (int64_t)(U - 1) * NW < r1; r += NW * U) {
+      Pk pk[U];
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int64_t rr = r + (int64_t)u * NW;
-        ok[u] = rr < r1;
-        if (ok[u]) {
-          const char *src = p.a + off_a + reduced_offset(p, (uint32_t)rr, 0);
-          if (ncol == V) {
-            if constexpr (sizeof(St) * V >= 16) {
-              using Q = uint32_t __attribute__((ext_vector_type(4)));
+      for (int u = 0; u < U; ++u)
+        load_vec<St, V>(p.a + off_a + reduced_offset(p, (uint32_t)(r + (int64_t)u * NW), 0), pk[u]);
 #pragma unroll
-              for (int i = 0; i < (int)(sizeof(St) * V / 16); ++i)
-                reinterpret_cast<Q *>(&pk[u])[i] = reinterpret_cast<const Q *>(src)[i];
-            } else {
+      for (int u = 0; u < U; ++u)
 #pragma unroll
-              for (int i = 0; i < V; ++i) pk[u].v[i] = reinterpret_cast<const St *>(src)[i];
-            }
-          } else {
+        for (int i = 0; i < V; ++i) acc[i] = R::combine(acc[i], R::lift(from_storage<S>(pk[u].v[i])));
+    }
+    for (; r < r1; r += NW) {
+      Pk pk;
+      load_vec<St, V>(p.a + off_a + reduced_offset(p, (uint32_t)r, 0), pk);
 #pragma unroll
-            for (int i = 0; i < V; ++i)
-              if (i < ncol) pk[u].v[i] = reinterpret_cast<const St *>(src)[i];
-          }
-        }
-      }
+      for (int i = 0; i < V; ++i) acc[i] = R::combine(acc[i], R::lift(from_storage<S>(pk.v[i])));
+    }
+  } else if (ncol > 0) {  // the ragged last column block
+    for (; r < r1; r += NW) {
+      const char *src = p.a + off_a + reduced_offset(p, (uint32_t)r, 0);
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        if (ok[u]) {
-#pragma unroll
-          for (int i = 0; i < V; ++i)
-            if (i < ncol) acc[i] = R::combine(acc[i], R::lift(from_storage<S>(pk[u].v[i])));
-        }
-      }
+      for (int i = 0; i < V; ++i)
+        if (i < ncol) acc[i] = R::combine(acc[i], R::lift(from_storage<S>(reinterpret_cast<const St *>(src)[i])));
     }
   }
-  // combine the wavefronts: each holds the same columns, different rows
+  // combine the wavefronts (same columns, different rows), one column of the vector at a time
 #pragma unroll
-  for (int i = 0; i < V; ++i) lds[wave][lane][i] = acc[i];
-  __syncthreads();
-  if (wave == 0 && ncol > 0) {
-#pragma unroll
-    for (int i = 0; i < V; ++i) {
-      A v = lds[0][lane][i];
-#pragma unroll
-      for (int w = 1; w < NW; ++w) v = R::combine(v, lds[w][lane][i]);
-      if (i < ncol) {
-        if (p.split == 1) {
-          store_result<A>(p.out + off_o + (int64_t)i * p.kso[0], p.out_dtype, v);
-        } else {
-          const int64_t olin = (int64_t)other * p.nc + col0 + i;
-          reinterpret_cast<typename R::P *>(p.partial)[(int64_t)s * p.nout + olin] = to_storage<R::ACC>(v);
-        }
+  for (int i = 0; i < V; ++i) {
+    lds[wave][lane] = acc[i];
+    __syncthreads();
+    if (wave == 0 && i < ncol) {
+      A v = lds[0][lane];
+      for (int w = 1; w < NW; ++w) v = R::combine(v, lds[w][lane]);
+      if (p.split == 1) {
+        store_result<A>(p.out + off_o + (int64_t)i * p.kso[0], p.out_dtype, v);
+      } else {
+        const int64_t olin = (int64_t)other * p.nc + col0 + i;
+        reinterpret_cast<typename R::P *>(p.partial)[(int64_t)s * p.nout + olin] = to_storage<R::ACC>(v);
       }
     }
+    if (i + 1 < V) __syncthreads();
   }
 }
 
-template <int S, int OP> __global__ __launch_bounds__(kBlock) void red_cols_kernel(const RedArgs p) {
+template <int S, int OP> __global__ __launch_bounds__(kColsMaxWaves * kWave) void red_cols_kernel(const RedArgs p) {
   using A = typename Reducer<S, OP>::A;
   constexpr int VF = 16 / (int)sizeof(storage_t<S>) > 0 ? 16 / (int)sizeof(storage_t<S>) : 1;
-  __shared__ A lds[kBlock / kWave][kWave][VF];
-  if (p.vec > 1) cols_body<S, OP, VF, VF>(p, lds);
-  else cols_body<S, OP, 1, VF>(p, lds);
+  __shared__ A lds[kColsMaxWaves][kWave];
+  if (p.vec > 1) cols_body<S, OP, VF>(p, lds);
+  else cols_body<S, OP, 1>(p, lds);
 }
 
 // ---------------------------------------------------------------------------------------

@@ -20,7 +20,7 @@ template <int S, int OP> hipError_t launch_red(const RedPlan &p, char *partial, 
       hipLaunchKernelGGL((red_rows_kernel<S, OP>), dim3((unsigned)p.grid), dim3(kBlock), 0, stream, args);
       break;
     case OCN_KERNEL_RED_COLS:
-      hipLaunchKernelGGL((red_cols_kernel<S, OP>), dim3((unsigned)p.grid), dim3(kBlock), 0, stream, args);
+      hipLaunchKernelGGL((red_cols_kernel<S, OP>), dim3((unsigned)p.grid), dim3((unsigned)p.block), 0, stream, args);
       break;
     default:
       hipLaunchKernelGGL((red_generic_kernel<S, OP>), dim3((unsigned)p.grid), dim3(kBlock), 0, stream, args);
