@@ -61,12 +61,20 @@ template <int DT> OCN_DEV reg_t<DT> from_storage(storage_t<DT> s) {
   else return s;
 }
 
+// float -> half, nearest even.  The empty asm makes the operand opaque to the instruction
+// selector: left alone, it fuses a preceding single-precision multiply into a mixed-precision
+// multiply-add with a +0 addend, which turns a product of -0 into +0.
+OCN_DEV _Float16 f32_to_half(float x) {
+  asm("" : "+v"(x));
+  return (_Float16)x;
+}
+
 // Rounds half-precision register values to half (nearest even) - the one rounding of a
 // half-precision operation.
 template <int DT> OCN_DEV storage_t<DT> to_storage(reg_t<DT> r) {
   if constexpr (DT == DT_BOOL) return r ? 1 : 0;
-  else if constexpr (DT == DT_F16) return (_Float16)r.v;
-  else if constexpr (DT == DT_C16) return chalf_s{(_Float16)r.re, (_Float16)r.im};
+  else if constexpr (DT == DT_F16) return f32_to_half(r.v);
+  else if constexpr (DT == DT_C16) return chalf_s{f32_to_half(r.re), f32_to_half(r.im)};
   else if constexpr (DT == DT_C32) return cfloat_s{r.re, r.im};
   else if constexpr (DT == DT_C64) return cdouble_s{r.re, r.im};
   else return r;
@@ -88,7 +96,7 @@ OCN_DEV float double_to_half_value(double x) {
     bits |= 1u;  // inexact: force the low bit (round to odd)
     f = __uint_as_float(bits);
   }
-  return (float)(_Float16)f;
+  return (float)f32_to_half(f);
 }
 
 template <class DI, class SI> OCN_DEV DI sat_int(SI s) {
@@ -166,7 +174,7 @@ OCN_DEV float im_of(cf32 r) { return r.im; }
 OCN_DEV double im_of(cf64 r) { return r.im; }
 
 // value of a float-held-half after rounding x (float) to half
-OCN_DEV float round_f32_to_half_value(float x) { return (float)(_Float16)x; }
+OCN_DEV float round_f32_to_half_value(float x) { return (float)f32_to_half(x); }
 
 // Real component of `s`, rounded once (nearest even) to the real type RT in {F16,F32,F64};
 // returned as float (F16, F32) or double (F64).  `imag` selects the imaginary component of a

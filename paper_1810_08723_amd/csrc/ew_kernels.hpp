@@ -393,6 +393,7 @@ OCN_DEV void stage_operand(KTiledArgs &p, const char *base, S *lds,
     }
 #pragma unroll
     for (int j = 0; j < J; ++j) {
+      if (j0 + j >= niter) break;  // uniform: the last batch of passes may be short
 #pragma unroll
       for (int i = 0; i < V; ++i)
         if (FULL || i < nv[j]) lds[swizzle(slot[j] + (uint32_t)i * step, zsrc, zmask, zdst)] = v[j].v[i];
@@ -470,6 +471,7 @@ OCN_DEV void tiled_compute(KTiledArgs &p, char *out, const char *pa, const char 
     }
 #pragma unroll
     for (int j = 0; j < J; ++j) {
+      if (j0 + j >= niter) break;  // uniform: the last batch of passes may be short
       const int n = nv[j];
       if (!FULL && n == 0) continue;
       Pack<SOt, V> r;

@@ -603,8 +603,9 @@ void choose_reduce_launch(RedPlan &p) {
     p.chunk = (nvec + p.split - 1) / p.split;
     p.split = (nvec + p.chunk - 1) / p.chunk;
     p.grid = (p.nout * p.split + groups_per_block - 1) / groups_per_block;
-  } else if (k_fast_dim >= 0 && k_fast == es && (p.nred == 0 || r_fast == 0 || r_fast > k_fast) &&
-             p.nredtot >= 1 && idx32 && k_fast_dim == p.nkept - 1 && p.nred >= 1) {
+  } else if (k_fast_dim >= 0 && k_fast == es && p.kstride_a[k_fast_dim] == es &&
+             (p.nred == 0 || r_fast == 0 || r_fast > k_fast) && p.nredtot >= 1 && idx32 &&
+             k_fast_dim == p.nkept - 1 && p.nred >= 1) {
     // ---- cols: a kept axis is the input's fastest; lanes own output columns -------------
     // (requires that axis to be the last canonical kept dim, i.e. also the output's fastest)
     p.kernel = OCN_KERNEL_RED_COLS;
@@ -704,6 +705,16 @@ int plan_reduce(int op, const ocn_tensor *a, const int32_t *axes, int32_t naxes,
     kd[n++] = x;
   }
   nk = sort_merge(kd, n, true);
+  // The column kernel walks the fastest kept dim forward through the input.  If making the
+  // output stride positive left the input stride there at minus one element, turn that dim
+  // around again: the kernels accept a negative output stride.
+  if (nk > 0 && kd[nk - 1].sa == -(int64_t)dt_size(a->dtype)) {
+    RDim &x = kd[nk - 1];
+    off_o += (x.size - 1) * x.so;
+    off_a += (x.size - 1) * x.sa;
+    x.so = -x.so;
+    x.sa = -x.sa;
+  }
   // reduced dims: drop size 1, flip to forward input strides (the set of addends is the
   // same), sort by input stride, merge
   n = 0;

@@ -26,12 +26,14 @@ class DeviceViews:
         key = id(view.storage)
         if key not in self._by_id:
             host = view.storage if view.storage.size else np.zeros(1, dtype=np.uint8)
-            self._by_id[key] = self.torch.from_numpy(host.copy()).to(f"cuda:{self.device}")
+            # keep the host array alive too: a freed array's id could be handed out again
+            self._by_id[key] = (view.storage, self.torch.from_numpy(host.copy()).to(f"cuda:{self.device}"))
+        assert self._by_id[key][0] is view.storage
         assert view.in_bounds()
-        return ocn.Tensor.on_storage(self._by_id[key], view.dtype, view.sizes, view.strides, view.offset)
+        return ocn.Tensor.on_storage(self._by_id[key][1], view.dtype, view.sizes, view.strides, view.offset)
 
     def download(self, view: View) -> np.ndarray:
-        got = self._by_id[id(view.storage)].cpu().numpy()
+        got = self._by_id[id(view.storage)][1].cpu().numpy()
         return got[:view.storage.size]
 
 

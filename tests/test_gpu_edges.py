@@ -1,0 +1,86 @@
+"""Edge cases on the GPU: in-place operation, zero-sized and scalar operands, eight dimensions,
+superimposed views of different types on one storage, and tensors beyond 2^31 elements."""
+import numpy as np
+import pytest
+
+import gpu_harness as H
+from workloads.values import random_view, rng_for
+from workloads.views import View
+
+pytestmark = pytest.mark.gpu
+
+
+def test_in_place_binary_and_unary():
+    rng = rng_for(13000)
+    a = random_view(rng, "float", (100, 37))
+    b = random_view(rng, "float", (37,))
+    H.check_binary("add", a, b, a)                       # A += b: out is the identical view as a
+    H.check_unary("neg", a, a)
+    t = random_view(rng, "int32", (64, 64))
+    bt = random_view(rng, "int32", (64, 64)).permute(1, 0)
+    H.check_binary("mul", t, bt, t)                      # in place with a staged (transposed) other operand
+    H.check_binary("sub", bt, t, t)                      # out aliases the second input
+
+
+def test_zero_sized_and_scalar_operands():
+    rng = rng_for(13001)
+    s = View.from_numpy(np.array(2.5, dtype=np.float32))
+    a = random_view(rng, "float", (33, 5))
+    H.check_binary("mul", a, s, View.empty("float", (33, 5)))
+    H.check_binary("mul", s, s.fresh_copy(), View.empty("float", ()))
+    z = View.empty("float", (0, 5))
+    H.check_binary("add", z, s, View.empty("float", (0, 5)))
+    H.check_unary("ident", View.empty("int8", (3, 0, 2)), View.empty("double", (3, 0, 2)))
+
+
+def test_eight_dimensions_permuted():
+    rng = rng_for(13002)
+    a = random_view(rng, "int16", (2, 3, 2, 3, 2, 3, 2, 3))
+    perm = (7, 3, 5, 1, 0, 6, 2, 4)
+    p = a.permute(*perm)
+    H.check_unary("ident", p, View.empty("int16", p.sizes))
+    H.check_binary("add", p, random_view(rng, "int16", p.sizes), View.empty("int16", p.sizes, order="F"))
+
+
+def test_imaginary_part_is_a_real_view_on_complex_storage():
+    rng = rng_for(13003)
+    z = random_view(rng, "cdouble", (40, 9), specials=False)
+    imag = z.reinterpret("double", 8)                    # same sizes and strides, +8 bytes, type double
+    real = z.reinterpret("double", 0)
+    H.check_unary("ident", imag, View.empty("double", (40, 9)))
+    H.check_binary("add", real, imag, View.empty("double", (40, 9)))
+    # write through the imaginary view: conj by negating the imaginary parts in place
+    H.check_unary("neg", imag, imag)
+
+
+def test_padded_rows_and_byte_offsets():
+    rng = rng_for(13004)
+    big = random_view(rng, "float", (50, 40))
+    v = big.slice(1, 3, 33, 1)                           # rows of 30 floats with a pitch of 40
+    H.check_unary("neg", v, View.empty("float", (50, 30)))
+    H.check_binary("add", v, v.fresh_copy(), View.empty("double", (50, 30)))
+
+
+def test_more_than_2_to_the_31_elements():
+    # flat int8 tensor of 2^31 + 2^20 elements: 64-bit vector indices in the rows kernel, 64-bit
+    # offsets in the full reduction
+    n = (1 << 31) + (1 << 20)
+    rng = rng_for(13005)
+    x = rng.integers(-128, 127, size=n, endpoint=True, dtype=np.int8)
+    a = View.from_numpy(x)
+    print("large unary", flush=True)
+    H.check_unary("neg", a, View.empty("int8", (n,)))
+    print("large reduce", flush=True)
+    got, want = H.run_reduce("sum", a, [0], View.empty("int64", ()))
+    assert np.array_equal(got, want)
+
+
+def test_tile_smaller_than_a_batch_of_passes():
+    # 256 output elements with a gap between them: one pass of the strided kernel, whose
+    # batches hold up to four passes; every element must be written exactly once
+    a = View.from_numpy(np.array([2 ** 31 - 1], dtype=np.int32)).broadcast_to((8, 32))
+    out = View.empty("double", (8, 63)).slice(1, 0, 63, 2)
+    H.check_unary("ident", a, out)
+    rng = rng_for(13006)
+    b = random_view(rng, "float", (32, 8)).permute(1, 0)
+    H.check_binary("add", random_view(rng, "float", (8, 32)), b, View.empty("float", (8, 32)))
