@@ -19,6 +19,39 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_all_cases.txt")
+
+
+def _source_digest() -> str:
+    """Fingerprint of the kernel and planner sources: measured HBM traffic is only reported
+    while the code it was measured on is unchanged."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_1810_08723_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".hpp", ".hip", ".cpp", ".inl")):
+            h.update(name.encode())
+            h.update(open(os.path.join(csrc, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def _measured_traffic():
+    """case -> HBM bytes per launch from the committed rocprofv3 counter summary, or {} when
+    the sources changed since it was taken."""
+    out = {}
+    try:
+        lines = open(TRAFFIC_FILE).read().splitlines()
+    except OSError:
+        return out
+    digest = None
+    for ln in lines:
+        if ln.startswith("source_digest:"):
+            digest = ln.split(":", 1)[1].strip()
+        if ln.startswith("traffic "):
+            f = dict(kv.split("=") for kv in ln.split()[1:])
+            out[f["case"]] = float(f["hbm_bytes"])
+    return out if digest == _source_digest() else {}
+
 
 
 def _device_cases(cases):
@@ -97,6 +130,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only", default="", help="comma-separated case names (for profiling one kernel); "
+                    "'copy' adds a plain 1 GiB float copy used to calibrate the HBM byte counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this engine runs on one GPU; --gpus must be 1 (nothing here is distributed)",
@@ -112,6 +147,16 @@ def main() -> int:
         return 3
 
     cases = configs.all_cases_full()
+    if args.only:
+        want = args.only.split(",")
+        cases = [c for c in cases if c.name in want]
+        if "copy" in want:
+            import numpy as np
+            from workloads.views import View
+            n = 1 << 28
+            src = View.from_numpy(np.ones(n, dtype=np.float32))
+            cases.append(configs.Case("copy", "unary", "ident", [src], View.empty("float", (n,)),
+                                      logical_bytes=8 * n, note="plain contiguous copy (counter calibration)"))
     runs, _keep = _device_cases(cases)
     torch.cuda.synchronize()
 
@@ -146,6 +191,9 @@ def main() -> int:
                        "frac_of_peak": c.logical_bytes / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS})
     device_ms = sum(p["avg_us"] for p in per_op) / 1e3
     dom = max(per_op, key=lambda p: p["avg_us"])
+    traffic = _measured_traffic()
+    for p in per_op:
+        p["hbm_traffic_bytes"] = traffic.get(p["case"])
 
     result = {
         "metric": "effective GB/s (logical bytes moved) and % of MI355X HBM peak per op",
@@ -155,10 +203,11 @@ def main() -> int:
         "ms_per_step": wall / args.steps * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32/f64/i32/i8/f16/c64 (per case)", "data": "synthetic",
-        "config": {"workload": "all five configurations in one step: C1, C1x8, C2, C3, C4a-d, C5, C5m",
+        "config": {"workload": ("all five configurations in one step: C1, C1x8, C2, C3, C4a-d, C5, C5m"
+                                if not args.only else "subset for profiling: " + args.only),
                    "logical_bytes_per_step": step_bytes, "device_ms_per_step": device_ms},
         "roofline": {"bound": "hbm", "achieved": dom["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": dom["gbs"] / HBM_PEAK_GBS, "traffic": None,
+                     "frac": dom["gbs"] / HBM_PEAK_GBS, "traffic": traffic.get(dom["case"]),
                      "kernel": f"{dom['kernel']} ({dom['case']})",
                      "bytes_per_launch": dom["logical_bytes"], "avg_us": dom["avg_us"]},
         "per_op": per_op,

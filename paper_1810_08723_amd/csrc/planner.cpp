@@ -839,7 +839,7 @@ void fill_info(const RedPlan &p, ocn_plan_info *info) {
   info->specialised = 1;
   info->passes = p.kernel == OCN_KERNEL_NONE ? 0 : p.passes;
   info->grid = p.grid;
-  info->block = kBlock;
+  info->block = p.block;
   info->split = p.split;
 }
 
