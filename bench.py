@@ -1,9 +1,12 @@
 """Benchmark: effective GB/s (logical bytes moved) of the strided tensor engine on one MI355X.
 
 One "step" runs every benchmark operation once, through the C ABI, on synthetic inputs that are
-already resident in HBM: the five configurations (C1, C1x8, C2, C3, C4a-d, C5, C5m).  The
-operations touch about 3 GB of distinct memory per step, so each one starts with a cold
-256 MB Infinity Cache.  Prints ONE JSON line.
+already resident in HBM: the five configurations (C1, C1x8, C2, C3, C4a-d, C5, C5m, and C5b,
+C5bm: the second reading of configuration 5's layout).  The operations touch about 3.5 GB of
+distinct memory per step, so each one starts with a cold 256 MB Infinity Cache; `avg_us` is
+that cold figure.  `warm_us` (same buffers back to back), `host_us` (host time to plan and
+enqueue one call) and `plan_us` (the planner alone, through the binding) are measured outside
+the timed region.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline]
 """
@@ -189,6 +192,24 @@ def main() -> int:
                        "logical_bytes": c.logical_bytes, "avg_us": avg * 1e3, "min_us": ms[0] * 1e3,
                        "gbs": c.logical_bytes / (avg * 1e-3) / 1e9,
                        "frac_of_peak": c.logical_bytes / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS})
+    # outside the timed region: steady-state (cache-warm) device time, and host-side cost
+    for i, (c, fn, _) in enumerate(runs):
+        reps = 12
+        wev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for a, b in wev:
+            a.record(); fn(); b.record()
+        torch.cuda.synchronize()
+        w = sorted(a.elapsed_time(b) for a, b in wev[2:])
+        per_op[i]["warm_us"] = w[len(w) // 2] * 1e3
+        t1 = time.perf_counter()
+        for _ in range(50):
+            fn()
+        per_op[i]["host_us"] = (time.perf_counter() - t1) / 50 * 1e6
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(50):
+            _plan_kernel(c)
+        per_op[i]["plan_us"] = (time.perf_counter() - t1) / 50 * 1e6
     device_ms = sum(p["avg_us"] for p in per_op) / 1e3
     dom = max(per_op, key=lambda p: p["avg_us"])
     traffic = _measured_traffic()
@@ -203,7 +224,7 @@ def main() -> int:
         "ms_per_step": wall / args.steps * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32/f64/i32/i8/f16/c64 (per case)", "data": "synthetic",
-        "config": {"workload": ("all five configurations in one step: C1, C1x8, C2, C3, C4a-d, C5, C5m"
+        "config": {"workload": ("all five configurations in one step: C1, C1x8, C2, C3, C4a-d, C5, C5m, C5b, C5bm"
                                 if not args.only else "subset for profiling: " + args.only),
                    "logical_bytes_per_step": step_bytes, "device_ms_per_step": device_ms},
         "roofline": {"bound": "hbm", "achieved": dom["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",

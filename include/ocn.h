@@ -210,6 +210,8 @@ typedef struct {
   int64_t grid, block;                /* first launch                                       */
   int64_t split;                      /* reductions: partial results per output (1 = none)  */
   int64_t lds_bytes;
+  int64_t unclipped;                  /* tiled kernel: 1 when no tile is clipped and every
+                                         access is a whole vector (the leaner kernel form)  */
 } ocn_plan_info;
 
 int ocn_plan_unary(int op, const ocn_tensor *a, const ocn_tensor *out, uint32_t flags,

@@ -55,7 +55,7 @@ class OcnPlanInfo(C.Structure):
                 ("vec", C.c_int32), ("tile_log2", C.c_int32 * MAX_DIMS), ("stage_a", C.c_int32),
                 ("stage_b", C.c_int32), ("specialised", C.c_int32), ("passes", C.c_int32),
                 ("grid", C.c_int64), ("block", C.c_int64), ("split", C.c_int64),
-                ("lds_bytes", C.c_int64)]
+                ("lds_bytes", C.c_int64), ("unclipped", C.c_int64)]
 
 
 class OcnError(RuntimeError):
@@ -201,7 +201,7 @@ def _info_dict(info: OcnPlanInfo) -> dict:
         "red_size": tuple(info.red_size[:r]), "red_stride_a": tuple(info.red_stride_a[:r]),
         "vec": info.vec, "tile_log2": tuple(info.tile_log2[:n]), "stage_a": bool(info.stage_a),
         "stage_b": bool(info.stage_b), "specialised": bool(info.specialised), "passes": info.passes,
-        "grid": info.grid, "block": info.block, "split": info.split, "lds_bytes": info.lds_bytes,
+        "grid": info.grid, "block": info.block, "split": info.split, "lds_bytes": info.lds_bytes, "unclipped": bool(info.unclipped),
     }
 
 

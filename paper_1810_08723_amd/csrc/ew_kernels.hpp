@@ -69,6 +69,41 @@ struct TiledArgs {
   TileOrder ord[3];                // enumeration orders: out's, a's, b's
 };
 
+// Arguments of the unclipped, all-vector form of the tiled kernel.  Everything that does not
+// depend on the lane is tabulated by the host, and all offsets inside a tile are unsigned
+// 32-bit, so that an access costs one scalar add (tile base + pass offset) and no vector
+// address arithmetic.  LDS addresses are XORs of three host- or once-computed terms: the
+// swizzle is linear over GF(2) and the lane, pass and element-in-vector parts of a slot number
+// occupy disjoint bits, so swizzle(lane + pass + element) is the XOR of their swizzles.
+constexpr int kFastLaneDims = 8;
+struct FastOrder {
+  int32_t nlane;                            // dims reached by the 8 lane bits
+  int32_t niter;                            // passes of 256 lanes
+  uint32_t shift[kFastLaneDims];            // bit field of the lane number holding dim k's index
+  uint32_t mask[kFastLaneDims];
+  uint32_t up[kFastLaneDims];               // left shift of the extracted index (vector length for k = 0)
+  uint32_t slot_shift[kFastLaneDims];       // bit position of dim k in the LDS slot number
+  uint32_t stride[3][kFastLaneDims];        // byte strides for out / a / b
+  uint32_t hi_off[3][kMaxTilePasses];       // byte offsets contributed by the pass number
+};
+struct FastTiledArgs {
+  char *out;
+  const char *a, *b;
+  int32_t ntd;                              // dims with more than one tile, fastest first
+  int32_t stage_a, stage_b;
+  uint32_t lds_base[2];                     // byte offset of a's / b's staging area
+  FastDiv ntdiv[kMaxDims];
+  int64_t step[3][kMaxDims];                // bytes from one tile to the next along that dim
+  TileSwizzle swz[2];
+  uint32_t es_log2[2];
+  uint32_t vc_log2;                         // log2 of the compute vector length
+  FastOrder ord[3];
+  uint32_t st_hi[2][kMaxTilePasses];        // staging writes: swizzled byte address from the pass number
+  uint32_t st_el[2][16];                    // ... from the element number inside a vector
+  uint32_t rd_hi[2][kMaxTilePasses];        // compute-phase reads: from the pass number
+  uint32_t rd_ch[2][16];                    // ... from the 16-byte chunk inside a vector
+};
+
 struct InterpArgs {
   char *out;
   const char *a, *b;
@@ -567,6 +602,174 @@ template <class G> __global__ __launch_bounds__(kBlock) void ew_tiled_kernel(con
       else tiled_compute<G, 1, false>(p, out, pa, pb, lds_a, lds_b, lim_dim, tile_elems);
     }
     if (staged && tile + gridDim.x < total_tiles) __syncthreads();  // LDS is reused by the next tile
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// tiled kernel, unclipped all-vector form
+// ---------------------------------------------------------------------------------------
+//
+// Same tiles, enumeration orders, LDS layout and swizzle as ew_tiled_kernel, for the plans the
+// host proves simple: no tile is clipped, every order moves whole 16-byte vectors, inputs
+// that are not staged are contiguous along the output's fastest axis, and all strides inside
+// a tile are non-negative and small enough for 32-bit offsets.
+
+using KFastArgs = const __attribute__((address_space(4))) FastTiledArgs;
+using KFastOrder = const __attribute__((address_space(4))) FastOrder;
+
+#ifndef OCN_FAST_J
+#define OCN_FAST_J 2
+#endif
+
+// lane part of byte offsets (operands selected by WANT: bit 0 out, 1 a, 2 b) and of the slot
+template <int WANT, class O> OCN_HDF void fast_lane(const O &o, uint32_t tid, uint32_t (&off)[3], uint32_t &slot) {
+  off[0] = off[1] = off[2] = 0;
+  slot = 0;
+  const int n = o.nlane;
+  for (int k = 0; k < n; ++k) {
+    const uint32_t c = ((tid >> o.shift[k]) & o.mask[k]) << o.up[k];
+    if constexpr ((WANT & 1) != 0) off[0] += c * o.stride[0][k];
+    if constexpr ((WANT & 2) != 0) off[1] += c * o.stride[1][k];
+    if constexpr ((WANT & 4) != 0) off[2] += c * o.stride[2][k];
+    slot += c << o.slot_shift[k];
+  }
+}
+
+template <class G> __global__ __launch_bounds__(kBlock) void ew_tiled_fast_kernel(const FastTiledArgs by_value) {
+  using SAt = typename G::SAt;
+  using SBt = typename G::SBt;
+  using SOt = typename G::SOt;
+  constexpr bool BIN = G::NIN2;
+  constexpr int VA = 16 / (int)sizeof(SAt) > 1 ? 16 / (int)sizeof(SAt) : 1;
+  constexpr int VB = 16 / (int)sizeof(SBt) > 1 ? 16 / (int)sizeof(SBt) : 1;
+  constexpr int VC = G::V;
+  constexpr int J = OCN_FAST_J;  // vectors in flight per lane and operand
+  (void)by_value;  // read through the kernarg segment instead (it is the only argument)
+  KFastArgs &p = *(KFastArgs *)__builtin_amdgcn_kernarg_segment_ptr();
+  char *lds = reinterpret_cast<char *>(ocn_lds_raw);
+
+  // tile origin (uniform over the workgroup)
+  uint32_t t = blockIdx.x;
+  int64_t bo = 0, ba = 0, bb = 0;
+  const int ntd = p.ntd;
+  for (int j = 0; j < ntd; ++j) {
+    const uint32_t dv = p.ntdiv[j].d, dm = p.ntdiv[j].m, ds = p.ntdiv[j].s;
+    const uint32_t q = (uint32_t)((((uint64_t)t * dm) >> 32) + t) >> ds;
+    const uint32_t tc = t - q * dv;
+    t = q;
+    bo += (int64_t)tc * p.step[0][j];
+    ba += (int64_t)tc * p.step[1][j];
+    if constexpr (BIN) bb += (int64_t)tc * p.step[2][j];
+  }
+  char *out = p.out + bo;
+  const char *pa = p.a + ba;
+  const char *pb = BIN ? p.b + bb : nullptr;
+
+  const uint32_t tid = threadIdx.x;
+  const bool stage_a = p.stage_a, stage_b = BIN && p.stage_b;
+
+  if (stage_a || stage_b) {
+    uint32_t offa[3] = {0, 0, 0}, offb[3] = {0, 0, 0}, slot;
+    uint32_t la = 0, lb = 0;  // lane part of the swizzled LDS byte address
+    int na = 0, nb = 0;
+    if (stage_a) {
+      fast_lane<2>(p.ord[1], tid, offa, slot);
+      la = (swizzle(slot, p.swz[0].src, p.swz[0].mask, p.swz[0].dst) << p.es_log2[0]) | p.lds_base[0];
+      na = p.ord[1].niter;
+    }
+    if constexpr (BIN) {
+      if (stage_b) {
+        fast_lane<4>(p.ord[2], tid, offb, slot);
+        lb = (swizzle(slot, p.swz[1].src, p.swz[1].mask, p.swz[1].dst) << p.es_log2[1]) | p.lds_base[1];
+        nb = p.ord[2].niter;
+      }
+    }
+    const int nmax = na > nb ? na : nb;
+    for (int j0 = 0; j0 < nmax; j0 += J) {
+      Pack<SAt, VA> va[J];
+      Pack<SBt, VB> vb[J];
+#pragma unroll
+      for (int j = 0; j < J; ++j)
+        if (j0 + j < na) load_pack<SAt, VA>(pa + p.ord[1].hi_off[1][j0 + j] + offa[1], va[j]);
+      if constexpr (BIN) {
+#pragma unroll
+        for (int j = 0; j < J; ++j)
+          if (j0 + j < nb) load_pack<SBt, VB>(pb + p.ord[2].hi_off[2][j0 + j] + offb[2], vb[j]);
+      }
+#pragma unroll
+      for (int j = 0; j < J; ++j) {
+        if (j0 + j < na) {
+          const uint32_t h = p.st_hi[0][j0 + j];
+#pragma unroll
+          for (int i = 0; i < VA; ++i) *reinterpret_cast<SAt *>(lds + (la ^ (h ^ p.st_el[0][i]))) = va[j].v[i];
+        }
+      }
+      if constexpr (BIN) {
+#pragma unroll
+        for (int j = 0; j < J; ++j) {
+          if (j0 + j < nb) {
+            const uint32_t h = p.st_hi[1][j0 + j];
+#pragma unroll
+            for (int i = 0; i < VB; ++i) *reinterpret_cast<SBt *>(lds + (lb ^ (h ^ p.st_el[1][i]))) = vb[j].v[i];
+          }
+        }
+      }
+    }
+    __syncthreads();
+  }
+
+  // compute phase, in the output's order
+  uint32_t off[3], slot_unused;
+  fast_lane<BIN ? 7 : 3>(p.ord[0], tid, off, slot_unused);
+  (void)slot_unused;
+  const uint32_t lane_slot = tid << p.vc_log2;
+  uint32_t ra = 0, rb = 0;
+  if (stage_a) ra = (swizzle(lane_slot, p.swz[0].src, p.swz[0].mask, p.swz[0].dst) << p.es_log2[0]) | p.lds_base[0];
+  if (stage_b) rb = (swizzle(lane_slot, p.swz[1].src, p.swz[1].mask, p.swz[1].dst) << p.es_log2[1]) | p.lds_base[1];
+  constexpr int EPA = (16 / (int)sizeof(SAt)) < VC ? (16 / (int)sizeof(SAt)) : VC;  // elements per LDS access
+  constexpr int EPB = (16 / (int)sizeof(SBt)) < VC ? (16 / (int)sizeof(SBt)) : VC;
+  const int no = p.ord[0].niter;
+  for (int j0 = 0; j0 < no; j0 += J) {
+    Pack<SAt, VC> av[J];
+    Pack<SBt, VC> bv[J];
+#pragma unroll
+    for (int j = 0; j < J; ++j) {
+      const int jj = j0 + j;
+      if (jj < no) {
+        if (stage_a) {
+          const uint32_t h = p.rd_hi[0][jj];
+#pragma unroll
+          for (int c = 0; c < VC / EPA; ++c)
+            *reinterpret_cast<Pack<SAt, EPA> *>(&av[j].v[c * EPA]) =
+                *reinterpret_cast<const Pack<SAt, EPA> *>(lds + (ra ^ (h ^ p.rd_ch[0][c])));
+        } else {
+          load_pack<SAt, VC>(pa + p.ord[0].hi_off[1][jj] + off[1], av[j]);
+        }
+        if constexpr (BIN) {
+          if (stage_b) {
+            const uint32_t h = p.rd_hi[1][jj];
+#pragma unroll
+            for (int c = 0; c < VC / EPB; ++c)
+              *reinterpret_cast<Pack<SBt, EPB> *>(&bv[j].v[c * EPB]) =
+                  *reinterpret_cast<const Pack<SBt, EPB> *>(lds + (rb ^ (h ^ p.rd_ch[1][c])));
+          } else {
+            load_pack<SBt, VC>(pb + p.ord[0].hi_off[2][jj] + off[2], bv[j]);
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < J; ++j) {
+      const int jj = j0 + j;
+      if (jj >= no) break;  // uniform: the last batch of passes may be short
+      Pack<SOt, VC> r;
+#pragma unroll
+      for (int i = 0; i < VC; ++i) {
+        if constexpr (BIN) r.v[i] = G::eval(av[j].v[i], bv[j].v[i]);
+        else r.v[i] = G::eval(av[j].v[i], SBt{});
+      }
+      store_pack<SOt, VC>(out + p.ord[0].hi_off[0][jj] + off[0], r);
+    }
   }
 }
 

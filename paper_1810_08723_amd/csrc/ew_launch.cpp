@@ -111,6 +111,75 @@ TiledArgs make_tiled_args(const EwPlan &p, int es_a) {
   return t;
 }
 
+FastTiledArgs make_fast_tiled_args(const EwPlan &p, int es_a) {
+  const TiledArgs t = make_tiled_args(p, es_a);
+  FastTiledArgs f;
+  std::memset(&f, 0, sizeof f);
+  f.out = t.out;
+  f.a = t.a;
+  f.b = t.b;
+  f.stage_a = t.stage_a;
+  f.stage_b = t.stage_b;
+  // tile grid: only dims with more than one tile, fastest (last canonical dim) first
+  for (int d = p.ndim - 1; d >= 0; --d) {
+    if (p.ntiles[d] <= 1) continue;
+    const int j = f.ntd++;
+    f.ntdiv[j] = t.ntdiv[d];
+    f.step[0][j] = t.so[d] * ((int64_t)1 << t.tl[d]);
+    f.step[1][j] = t.sa[d] * ((int64_t)1 << t.tl[d]);
+    f.step[2][j] = t.sb[d] * ((int64_t)1 << t.tl[d]);
+  }
+  const int es[2] = {es_a, p.nin == 2 ? dt_size(p.b.dtype) : 1};
+  auto log2i = [](int64_t v) { int l = 0; while (((int64_t)1 << l) < v) ++l; return l; };
+  const int64_t tile_elems = (int64_t)1 << p.tile_bits;
+  // the larger staging area goes first, so that the smaller one starts at a multiple of its own
+  // (power-of-two) size and the base can be OR-ed into XOR-built addresses
+  const int64_t bytes_a = p.stage_a ? tile_elems * es[0] : 0, bytes_b = p.stage_b ? tile_elems * es[1] : 0;
+  if (bytes_a >= bytes_b) { f.lds_base[0] = 0; f.lds_base[1] = (uint32_t)bytes_a; }
+  else { f.lds_base[1] = 0; f.lds_base[0] = (uint32_t)bytes_b; }
+  f.swz[0] = t.swz[0];
+  f.swz[1] = t.swz[1];
+  f.es_log2[0] = (uint32_t)log2i(es[0]);
+  f.es_log2[1] = (uint32_t)log2i(es[1]);
+  f.vc_log2 = (uint32_t)p.vecw_o;
+  for (int x = 0; x < 3; ++x) {
+    const TileOrder &o = t.ord[x];
+    FastOrder &g = f.ord[x];
+    g.niter = o.niter;
+    uint32_t shift = 0;
+    for (int k = 0; k < o.nord && shift < 8; ++k) {
+      const uint32_t vw = k == 0 ? (uint32_t)o.vecw : 0u;
+      const uint32_t w = (uint32_t)o.width[k] - vw;
+      const uint32_t wl = std::min(w, 8u - shift);  // bits of this dim's index held by the lane number
+      if (wl > 0) {
+        const int i = g.nlane++;
+        g.shift[i] = shift;
+        g.mask[i] = (1u << wl) - 1u;
+        g.up[i] = vw;
+        g.slot_shift[i] = (uint32_t)o.lds_shift[k];
+        for (int y = 0; y < 3; ++y) g.stride[y][i] = (uint32_t)o.stride[y][k];
+      }
+      shift += w;
+    }
+    for (int j = 0; j < o.niter && j < kMaxTilePasses; ++j)
+      for (int y = 0; y < 3; ++y) g.hi_off[y][j] = (uint32_t)o.hi_off[y][j];
+  }
+  for (int y = 0; y < 2; ++y) {
+    if (!(y == 0 ? p.stage_a : p.stage_b)) continue;
+    const TileOrder &o = t.ord[y + 1];
+    const TileSwizzle &z = t.swz[y];
+    const uint32_t sh = f.es_log2[y];
+    for (int j = 0; j < o.niter && j < kMaxTilePasses; ++j) f.st_hi[y][j] = swizzle(o.hi_slot[j], z) << sh;
+    for (int i = 0; i < (1 << o.vecw) && i < 16; ++i) f.st_el[y][i] = swizzle((uint32_t)i << o.lds_shift[0], z) << sh;
+    const TileOrder &oc = t.ord[0];
+    for (int j = 0; j < oc.niter && j < kMaxTilePasses; ++j)
+      f.rd_hi[y][j] = swizzle(((uint32_t)j * kBlock) << p.vecw_o, z) << sh;
+    const int epc = std::min(std::max(1, 16 / es[y]), 1 << p.vecw_o);
+    for (int c = 0; c * epc < (1 << p.vecw_o) && c < 16; ++c) f.rd_ch[y][c] = swizzle((uint32_t)(c * epc), z) << sh;
+  }
+  return f;
+}
+
 InterpArgs make_interp_args(const EwPlan &p) {
   InterpArgs a;
   std::memset(&a, 0, sizeof a);

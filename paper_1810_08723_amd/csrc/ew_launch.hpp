@@ -15,6 +15,7 @@ extern EwLauncher g_unary_launchers[U_COUNT][DT_COUNT][DT_COUNT];
 
 RowsArgs make_rows_args(const EwPlan &p);
 TiledArgs make_tiled_args(const EwPlan &p, int es_a);
+FastTiledArgs make_fast_tiled_args(const EwPlan &p, int es_a);
 InterpArgs make_interp_args(const EwPlan &p);
 hipError_t launch_interp(const EwPlan &p, hipStream_t stream);
 
@@ -25,6 +26,9 @@ hipError_t launch_ew(const EwPlan &p, hipStream_t stream) {
   if (p.kernel == OCN_KERNEL_EW_ROWS) {
     const RowsArgs args = make_rows_args(p);
     hipLaunchKernelGGL((ew_rows_kernel<G>), dim3((unsigned)p.grid), dim3(kBlock), 0, stream, args);
+  } else if (p.fast_tiled) {
+    const FastTiledArgs args = make_fast_tiled_args(p, (int)sizeof(typename G::SAt));
+    hipLaunchKernelGGL((ew_tiled_fast_kernel<G>), dim3((unsigned)p.grid), dim3(kBlock), (size_t)p.lds_bytes, stream, args);
   } else {
     const TiledArgs args = make_tiled_args(p, (int)sizeof(typename G::SAt));
     hipLaunchKernelGGL((ew_tiled_kernel<G>), dim3((unsigned)p.grid), dim3(kBlock), (size_t)p.lds_bytes, stream, args);

@@ -65,6 +65,7 @@ struct EwPlan {
   int64_t ntiles[kMaxDims] = {0};
   int64_t total_tiles = 0;
   bool specialised = false;     // a dtype-specialised kernel exists for this signature
+  bool fast_tiled = false;      // tiled kernel: the unclipped all-vector form applies
   int64_t grid = 0;
   int64_t lds_bytes = 0;
 };

@@ -7,6 +7,8 @@
 //   * every output element is written exactly once,
 //   * every LDS read in the compute phase returns the element that belongs to that output
 //     position (so staging order, slot numbering and swizzle agree), inside the LDS budget.
+// Plans that qualify for the unclipped all-vector form of the kernel are replayed a second
+// time through that form's argument tables (32-bit offsets, XOR-composed LDS addresses).
 // Exit code 0 when every case passes.
 #include <cstdio>
 #include <cstdlib>
@@ -56,7 +58,114 @@ static HostTensor make_view(int dt, int ndim, const int64_t *sizes, char *base, 
   return h;
 }
 
-static int g_stats[6];  // tiled-or-generic, staged a, staged b, vector compute, vector staging, edge tiles
+static int g_stats[7];  // tiled-or-generic, staged a, staged b, vector compute, vector staging, edge tiles, fast form
+
+// Replay of ew_tiled_fast_kernel: returns 0 when every output element is written once, from the
+// right input elements, with every access in range and aligned.
+static int check_fast(const EwPlan &p, const HostTensor &a, const HostTensor &b, const HostTensor &o, int es,
+                      int case_no) {
+  const FastTiledArgs f = make_fast_tiled_args(p, es);
+  const int VA = std::max(1, 16 / es), VC = 1 << p.vecw_o;
+  const int64_t out_elems = (o.hi - o.lo) / es;
+  std::vector<uint8_t> written(out_elems, 0);
+  const int64_t lds_bytes = p.lds_bytes;
+  std::vector<int64_t> lds(lds_bytes / es);  // global byte offset held by each LDS element, per area
+  auto in_range = [&](const HostTensor &h, const char *ptr, int bytes) {
+    const int64_t off = ptr - (char *)h.t.base;
+    return off >= h.lo && off + bytes <= h.hi;
+  };
+  auto expect = [&](int64_t out_off, int64_t &ea, int64_t &eb) {
+    ea = p.off_a; eb = p.off_b;
+    int64_t rem = out_off - p.off_out;
+    for (int d = 0; d < p.ndim; ++d) {
+      const int64_t c = rem / p.out.stride[d];
+      rem -= c * p.out.stride[d];
+      ea += c * p.a.stride[d];
+      eb += c * p.b.stride[d];
+    }
+    return rem == 0;
+  };
+#define FAIL(msg) do { std::printf("case %d (fast form): %s\n", case_no, msg); return 1; } while (0)
+  for (int64_t blk = 0; blk < p.total_tiles; ++blk) {
+    uint32_t t = (uint32_t)blk;
+    int64_t bo = 0, ba = 0, bb = 0;
+    for (int j = 0; j < f.ntd; ++j) {
+      const uint32_t q = fastdiv(t, f.ntdiv[j]);
+      const uint32_t tc = t - q * f.ntdiv[j].d;
+      t = q;
+      bo += (int64_t)tc * f.step[0][j]; ba += (int64_t)tc * f.step[1][j]; bb += (int64_t)tc * f.step[2][j];
+    }
+    if (t != 0) FAIL("tile index not exhausted");
+    std::fill(lds.begin(), lds.end(), INT64_MIN);
+    for (int y = 0; y < 2; ++y) {
+      if (!(y == 0 ? f.stage_a : f.stage_b)) continue;
+      const FastOrder &g = f.ord[y + 1];
+      const HostTensor &h = y == 0 ? a : b;
+      const char *gbase = y == 0 ? f.a + ba : f.b + bb;
+      for (uint32_t tid = 0; tid < (uint32_t)kBlock; ++tid) {
+        uint32_t off[3], slot;
+        if (y == 0) fast_lane<2>(g, tid, off, slot); else fast_lane<4>(g, tid, off, slot);
+        const uint32_t l = (swizzle(slot, f.swz[y]) << f.es_log2[y]) | f.lds_base[y];
+        for (int jj = 0; jj < g.niter; ++jj) {
+          const char *src = gbase + g.hi_off[y + 1][jj] + off[y + 1];
+          if ((uintptr_t)src % 16 != 0) FAIL("misaligned staging load");
+          if (!in_range(h, src, 16)) FAIL("staging load out of range");
+          for (int i = 0; i < VA; ++i) {
+            const uint32_t addr = l ^ (f.st_hi[y][jj] ^ f.st_el[y][i]);
+            if (addr % es != 0 || (int64_t)addr + es > lds_bytes) FAIL("LDS write out of range");
+            if (lds[addr / es] != INT64_MIN) FAIL("LDS element written twice");
+            lds[addr / es] = (src + (int64_t)i * es) - (char *)h.t.base;
+          }
+        }
+      }
+    }
+    const FastOrder &g = f.ord[0];
+    const int EP = std::min(std::max(1, 16 / es), VC);
+    for (uint32_t tid = 0; tid < (uint32_t)kBlock; ++tid) {
+      uint32_t off[3], slot;
+      fast_lane<7>(g, tid, off, slot);
+      const uint32_t lane_slot = tid << f.vc_log2;
+      uint32_t r[2];
+      for (int y = 0; y < 2; ++y) r[y] = (swizzle(lane_slot, f.swz[y]) << f.es_log2[y]) | f.lds_base[y];
+      for (int jj = 0; jj < g.niter; ++jj) {
+        char *po = f.out + bo + g.hi_off[0][jj] + off[0];
+        if ((uintptr_t)po % ((size_t)VC * es) != 0) FAIL("misaligned vector store");
+        if (!in_range(o, po, VC * es)) FAIL("store out of range");
+        for (int i = 0; i < VC; ++i) {
+          char *pe = po + (int64_t)i * es;
+          const int64_t oidx = (pe - (char *)o.t.base) / es;
+          if (written[oidx]++) FAIL("output element written twice");
+          int64_t ea, eb, got[2];
+          if (!expect(pe - (char *)o.t.base, ea, eb)) FAIL("store between elements");
+          for (int y = 0; y < 2; ++y) {
+            if (y == 0 ? f.stage_a : f.stage_b) {
+              const uint32_t addr = (r[y] ^ (f.rd_hi[y][jj] ^ f.rd_ch[y][i / EP])) + (uint32_t)(i % EP) * es;
+              if ((r[y] ^ (f.rd_hi[y][jj] ^ f.rd_ch[y][i / EP])) % ((uint32_t)EP * es) != 0) FAIL("misaligned LDS read");
+              if ((int64_t)addr + es > lds_bytes) FAIL("LDS read out of range");
+              got[y] = lds[addr / es];
+            } else {
+              const HostTensor &h = y == 0 ? a : b;
+              const char *src = (y == 0 ? f.a + ba : f.b + bb) + g.hi_off[y + 1][jj] + off[y + 1];
+              if ((uintptr_t)src % ((size_t)VC * es) != 0) FAIL("misaligned direct load");
+              if (!in_range(h, src, VC * es)) FAIL("direct load out of range");
+              got[y] = (src + (int64_t)i * es) - (char *)h.t.base;
+            }
+          }
+          if (got[0] != ea || got[1] != eb) {
+            std::printf("case %d (fast form): wrong element: a %ld want %ld, b %ld want %ld (tile %ld tid %u pass %d i %d)\n",
+                        case_no, (long)got[0], (long)ea, (long)got[1], (long)eb, (long)blk, tid, jj, i);
+            return 1;
+          }
+        }
+      }
+    }
+  }
+#undef FAIL
+  int64_t count = 0;
+  for (auto w : written) count += w;
+  if (count != p.numel) { std::printf("case %d (fast form): %ld of %ld output elements written\n", case_no, (long)count, (long)p.numel); return 1; }
+  return 0;
+}
 
 static int check_case(int dt, int ndim, const int64_t *sizes, int case_no) {
   const int es = dt_size(dt);
@@ -208,6 +317,10 @@ static int check_case(int dt, int ndim, const int64_t *sizes, int case_no) {
   int64_t count = 0;
   for (auto w : written) count += w;
   if (count != numel) { std::printf("case %d: %ld of %ld output elements written\n", case_no, (long)count, (long)numel); return 1; }
+  if (p.fast_tiled) {
+    g_stats[6]++;
+    return check_fast(p, a, b, o, es, case_no);
+  }
   return 0;
 }
 
@@ -222,6 +335,7 @@ int main(int argc, char **argv) {
     for (int i = 0; i < ndim; ++i) {
       const int kind = rnd_in(0, 3);
       sizes[i] = kind == 0 ? rnd_in(1, 4) : kind == 1 ? rnd_in(5, 20) : kind == 2 ? (1 << rnd_in(2, 6)) : rnd_in(21, 70);
+      if (c % 3 == 0) sizes[i] = 1 << rnd_in(1, 6);  // every third case: power-of-two extents (no clipped tiles)
       if (total * sizes[i] > 300000) sizes[i] = 2;
       total *= sizes[i];
     }
@@ -235,7 +349,7 @@ int main(int argc, char **argv) {
     ++tiled;
   }
   std::printf("ok: %d cases; %d used the tiled kernel (staged a %d, staged b %d, vector compute %d, "
-              "vector staging %d, clipped tile dims %d)\n", tiled, g_stats[0], g_stats[1], g_stats[2], g_stats[3],
-              g_stats[4], g_stats[5]);
+              "vector staging %d, clipped tile dims %d, all-vector form %d)\n", tiled, g_stats[0], g_stats[1], g_stats[2],
+              g_stats[3], g_stats[4], g_stats[5], g_stats[6]);
   return 0;
 }

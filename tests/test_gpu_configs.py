@@ -50,14 +50,14 @@ def _run_case(c):
         assert np.all(err <= 1e-7 * np.abs(x).sum(axis=c.axes).reshape(-1) + 1e-30)
 
 
-@pytest.mark.parametrize("idx", range(10))
+@pytest.mark.parametrize("idx", range(12))
 def test_small_cases(idx):
     c = configs.all_cases_small()[idx]
     print("case", c.name, c.op, [v.sizes for v in c.inputs], flush=True)
     _run_case(c)
 
 
-@pytest.mark.parametrize("which", ["C1", "C1x8", "C2", "C3", "C4", "C5"])
+@pytest.mark.parametrize("which", ["C1", "C1x8", "C2", "C3", "C4", "C5", "C5b"])
 def test_full_size_cases(which):
     if which == "C1":
         cases = [configs.config1(1)]
@@ -69,8 +69,10 @@ def test_full_size_cases(which):
         cases = [configs.config3()]
     elif which == "C4":
         cases = configs.config4()
-    else:
+    elif which == "C5":
         cases = configs.config5()
+    else:
+        cases = configs.config5(reading="R2")
     for c in cases:
         print("case", c.name, c.op, [v.sizes for v in c.inputs], flush=True)
         _run_case(c)

@@ -73,3 +73,90 @@ def test_fuzz_reduce(seed):
         print("fuzz-reduce", seed, it, shape, axes, op, dt, a.strides, flush=True)
         got, want = H.run_reduce(op, a, axes, out)
         assert np.array_equal(got, want), H.first_mismatch(out_dt, got, want)
+
+
+def _permuted(rng, dtype, shape, step_axis=None, writable=False):
+    """A view of `shape` over a dense buffer whose axes are stored in a random order (and with a
+    step of 2 along one axis when asked): positive strides only, power-of-two friendly."""
+    from workloads.values import random_view
+    nd = len(shape)
+    perm = [int(x) for x in rng.permutation(nd)]
+    phys = [shape[p] * (2 if p == step_axis else 1) for p in perm]
+    base = View.empty(dtype, phys) if writable else random_view(rng, dtype, phys)
+    inv = [perm.index(i) for i in range(nd)]
+    v = base.permute(*inv)
+    if step_axis is not None:
+        v = v.slice(step_axis, 0, 2 * shape[step_axis], 2)
+    assert v.sizes == tuple(shape)
+    return v
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_fuzz_unclipped_tiles(seed):
+    """Power-of-two extents with permuted storage orders: the shapes for which no tile is
+    clipped, so the lean all-vector form of the tiled kernel runs (mixed element sizes, one or
+    two staged inputs, stepped inputs)."""
+    import paper_1810_08723_amd as ocn
+    rng = rng_for(11500 + seed)
+    combos = [("add", "float", "float", "float"), ("mul", "cfloat", "cfloat", "cfloat"),
+              ("absgt", "cfloat", "cfloat", "bool"), ("sub", "int16", "int16", "int16"),
+              ("lt", "double", "double", "bool"), ("max", "uint8", "uint8", "uint8"),
+              ("mul", "int32", "float", "float"), ("add", "int64", "int64", "int64"),
+              (None, "double", None, "int16"), (None, "half", None, "float"), (None, "cdouble", None, "cfloat")]
+    for it in range(6):
+        nd = int(rng.integers(2, 6))
+        shape = [1 << int(rng.integers(1, 7)) for _ in range(nd)]
+        while int(np.prod(shape)) > (1 << 17):
+            shape[int(rng.integers(0, nd))] = 2
+        op, da, db, dout = combos[int(rng.integers(0, len(combos)))]
+        step = int(rng.integers(0, nd)) if rng.random() < 0.3 else None
+        a = _permuted(rng, da, shape, step_axis=step)
+        out = _permuted(rng, dout, shape, writable=True)
+        dv = H.DeviceViews()
+        if op is None:
+            plan = ocn.plan_unary("ident", dv.tensor(a), dv.tensor(out))
+        else:
+            b = _permuted(rng, db, shape)
+            plan = ocn.plan_binary(op, dv.tensor(a), dv.tensor(b), dv.tensor(out))
+        print("unclipped fuzz", seed, it, shape, op, da, dout, a.strides, out.strides, plan["kernel"],
+              plan["unclipped"], flush=True)
+        if op is None:
+            H.check_unary("ident", a, out)
+        else:
+            H.check_binary(op, a, b, out)
+
+
+@pytest.mark.parametrize("case", range(8))
+def test_unclipped_form_on_known_shapes(case):
+    """Shapes chosen so that the lean form certainly runs (asserted through the plan)."""
+    import paper_1810_08723_amd as ocn
+    rng = rng_for(11600 + case)
+    from workloads.values import random_view
+    spec = [
+        ("add", "float", "float", "float", (64, 96, 64), (2, 0, 1), (0, 1, 2), (0, 1, 2)),       # b transposed
+        ("mul", "cfloat", "cfloat", "cfloat", (16, 32, 16, 32), (3, 1, 0, 2), (0, 1, 2, 3), (2, 0, 3, 1)),  # three orders
+        ("absgt", "cfloat", "cfloat", "bool", (32, 64, 64), (2, 1, 0), (0, 1, 2), (0, 1, 2)),    # mixed sizes
+        (None, "double", None, "int16", (256, 128), (1, 0), None, (0, 1)),                        # transposing cast
+        ("max", "uint8", "uint8", "uint8", (256, 512), (1, 0), (0, 1), (0, 1)),                   # 16-element vectors
+        ("sub", "int16", "int16", "int16", (128, 64, 8), (1, 2, 0), (2, 0, 1), (0, 1, 2)),
+        ("lt", "double", "double", "bool", (64, 256), (1, 0), (0, 1), (0, 1)),                    # 8-byte in, 1-byte out
+        ("add", "int64", "int64", "int64", (8, 16, 32, 16), (0, 1, 2, 3), (3, 2, 1, 0), (1, 0, 3, 2)),
+    ][case]
+    op, da, db, dout, shape, pa, pb, po = spec
+
+    def view(dtype, perm, writable=False):
+        phys = [shape[p] for p in perm]
+        base = View.empty(dtype, phys) if writable else random_view(rng, dtype, phys)
+        return base.permute(*[perm.index(i) for i in range(len(shape))])
+    a = view(da, pa)
+    out = view(dout, po, writable=True)
+    dv = H.DeviceViews()
+    if op is None:
+        plan = ocn.plan_unary("ident", dv.tensor(a), dv.tensor(out))
+        assert plan["kernel"] == "ew_tiled" and plan["unclipped"], plan
+        H.check_unary("ident", a, out)
+    else:
+        b = view(db, pb)
+        plan = ocn.plan_binary(op, dv.tensor(a), dv.tensor(b), dv.tensor(out))
+        assert plan["kernel"] == "ew_tiled" and plan["unclipped"], plan
+        H.check_binary(op, a, b, out)

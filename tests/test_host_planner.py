@@ -114,6 +114,42 @@ def test_worked_plan_config5_stays_five_dimensional():
     assert plan["lds_bytes"] <= 64 * 1024
 
 
+def test_worked_plan_config5_second_reading():
+    # buffers that store the logical dims in permuted order: another stride vector, same plan kind
+    c = configs.config5(reading="R2")[0]
+    es = 8
+    assert c.inputs[0].strides == tuple(es * s for s in (2048, 1, 65536, 32, 4194304))
+    assert c.out.strides == tuple(es * s for s in (16384, 64, 1, 262144, 2048))
+    plan = ocn.plan_binary("mul", fake(c.inputs[0], 0), fake(c.inputs[1], 1), fake(c.out, 2))
+    # canonical order = original axes (3, 0, 4, 1, 2); no pair merges for all three operands
+    assert plan["size"] == (64, 16, 8, 32, 64)
+    assert plan["stride_out"] == tuple(es * s for s in (262144, 16384, 2048, 64, 1))
+    assert plan["stride_a"] == tuple(es * s for s in (32, 2048, 4194304, 1, 65536))
+    assert plan["stride_b"] == tuple(es * s for s in (8, 1048576, 1, 32768, 512))
+    assert plan["kernel"] == "ew_tiled" and plan["stage_a"] and plan["stage_b"]
+
+
+def test_unclipped_form_and_staging_budget():
+    # configuration 1 (a pure transpose of power-of-two extents) and configuration 5 take the
+    # lean form of the tiled kernel; two staged inputs share at most 16 KiB of LDS
+    c1 = configs.config1(8)
+    plan = ocn.plan_binary("add", fake(c1.inputs[0], 0), fake(c1.inputs[1], 1), fake(c1.out, 2))
+    assert plan["kernel"] == "ew_tiled" and plan["unclipped"] and plan["lds_bytes"] == 16 * 1024
+    for c in configs.config5() + configs.config5(reading="R2"):
+        plan = ocn.plan_binary(c.op, fake(c.inputs[0], 0), fake(c.inputs[1], 1), fake(c.out, 2))
+        assert plan["kernel"] == "ew_tiled" and plan["unclipped"], c.name
+        if plan["stage_a"] and plan["stage_b"]:
+            assert plan["lds_bytes"] <= 16 * 1024
+    # an extent that is not a multiple of its tile extent clips tiles: general form
+    a = View.empty("float", (48, 100)).permute(1, 0)
+    plan = ocn.plan_binary("add", fake(a, 0), fake(View.empty("float", (100, 48)), 1), fake(View.empty("float", (100, 48)), 2))
+    assert plan["kernel"] == "ew_tiled" and not plan["unclipped"]
+    # a flipped staged input has a negative stride inside the tile: general form
+    f = View.empty("float", (64, 128)).permute(1, 0).flip(1)
+    plan = ocn.plan_binary("add", fake(f, 0), fake(View.empty("float", (128, 64)), 1), fake(View.empty("float", (128, 64)), 2))
+    assert plan["kernel"] == "ew_tiled" and not plan["unclipped"]
+
+
 def test_full_reduction_plan_is_two_pass_and_flat():
     c = configs.config4(64, 64, 1 << 28)[3]
     plan = ocn.plan_reduce("sum", fake(c.inputs[0], 0), [0], fake(c.out, 2))
@@ -129,6 +165,7 @@ def test_axis_reduction_plans():
     assert p1["kernel"] == "red_rows" and p1["size"] == (16384,) and p1["red_size"] == (4096,) and p1["passes"] == 1
     p0 = ocn.plan_reduce("sum", fake(b.inputs[0], 0), [0], fake(b.out, 2))
     assert p0["kernel"] == "red_cols" and p0["size"] == (4096,) and p0["red_size"] == (16384,)
+    assert p0["split"] > 1 and p0["passes"] == 2
     assert p0["compute_dtype"] == "double"
     # reducing two adjacent axes of a contiguous tensor merges them
     v = View.empty("float", (6, 10, 12, 8))

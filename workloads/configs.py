@@ -112,18 +112,18 @@ def config4(rows: int = 16384, cols: int = 4096, n_full: int = 1 << 28) -> List[
     ]
 
 
-def config5(shape: Sequence[int] = (16, 32, 64, 64, 8)) -> List[Case]:
+def config5(shape: Sequence[int] = (16, 32, 64, 64, 8), reading: str = "R1") -> List[Case]:
     """complex64 multiply on logical shape [16,32,64,64,8]: A is a step-2 slice along axis 2 of a
-    buffer whose dims are permuted (4,2,0,3,1); B contiguous; C written with dims permuted
-    (3,0,4,1,2).  Also the bool mask |A| > |B| (contiguous)."""
+    permuted buffer (4,2,0,3,1); B contiguous; C written permuted (3,0,4,1,2).  Also the bool
+    mask |A| > |B| (contiguous).
+
+    The layout sentence admits two readings, both built here:
+      R1  view.dim[i] = buffer.dim[perm[i]] (the convention of configuration 1);
+      R2  the buffer stores the logical dims in the order perm (slowest first).
+    They are two stride vectors for the same operation; R2's cases are named C5b / C5bm."""
     s0, s1, s2, s3, s4 = shape
-    # physical buffers: view.dim[i] = buffer.dim[perm[i]]
-    pa_shape = [0] * 5
-    for i, p in enumerate((4, 2, 0, 3, 1)):
-        pa_shape[p] = (s0, s1, 2 * s2, s3, s4)[i]
-    pc_shape = [0] * 5
-    for i, p in enumerate((3, 0, 4, 1, 2)):
-        pc_shape[p] = shape[i]
+    a_logical = (s0, s1, 2 * s2, s3, s4)   # before the step-2 slice
+    perm_a, perm_c = (4, 2, 0, 3, 1), (3, 0, 4, 1, 2)
 
     def cplx(seed, sizes):
         rng = rng_for(seed)
@@ -132,27 +132,50 @@ def config5(shape: Sequence[int] = (16, 32, 64, 64, 8)) -> List[Case]:
         z.imag = rng.standard_normal(sizes).astype(np.float32)
         return z
 
+    if reading == "R1":
+        pa_shape = [0] * 5
+        for i, p in enumerate(perm_a):
+            pa_shape[p] = a_logical[i]
+        pc_shape = [0] * 5
+        for i, p in enumerate(perm_c):
+            pc_shape[p] = shape[i]
+        view_perm_a, view_perm_c = perm_a, perm_c
+        suffix = ""
+    elif reading == "R2":
+        pa_shape = [a_logical[p] for p in perm_a]
+        pc_shape = [shape[p] for p in perm_c]
+        # logical dim i sits at buffer axis perm.index(i)
+        view_perm_a = tuple(perm_a.index(i) for i in range(5))
+        view_perm_c = tuple(perm_c.index(i) for i in range(5))
+        suffix = "b"
+    else:
+        raise ValueError(reading)
+
     pa = View.from_numpy(cplx(_seed(4, 0), tuple(pa_shape)))
-    a = pa.permute(4, 2, 0, 3, 1).slice(2, 0, 2 * s2, 2)
+    a = pa.permute(*view_perm_a).slice(2, 0, 2 * s2, 2)
     b = View.from_numpy(cplx(_seed(4, 1), tuple(shape)))
     pc = View.empty("cfloat", tuple(pc_shape))
-    c = pc.permute(3, 0, 4, 1, 2)
+    c = pc.permute(*view_perm_c)
     assert a.sizes == tuple(shape) and c.sizes == tuple(shape)
     n = int(np.prod(shape))
     mask = View.empty("bool", tuple(shape))
     return [
-        Case("C5", "binary", "mul", [a, b], c, logical_bytes=24 * n, note="three different fastest axes"),
-        Case("C5m", "binary", "absgt", [a, b], mask, logical_bytes=17 * n, note="bool mask |A|>|B|"),
+        Case("C5" + suffix, "binary", "mul", [a, b], c, logical_bytes=24 * n,
+             note="three different fastest axes"),
+        Case("C5" + suffix + "m", "binary", "absgt", [a, b], mask, logical_bytes=17 * n,
+             note="bool mask |A|>|B|"),
     ]
 
 
 def all_cases_full() -> List[Case]:
-    """Every benchmark case at full size (about 2.6 GB of host memory)."""
-    return [config1(1), config1(8), config2(), config3(), *config4(), *config5()]
+    """Every benchmark case at full size (about 3.2 GB of host memory)."""
+    return [config1(1), config1(8), config2(), config3(), *config4(), *config5(),
+            *config5(reading="R2")]
 
 
 def all_cases_small() -> List[Case]:
     """The same cases shrunk so the CPU oracle finishes in seconds; still several tiles and a
     ragged tail in every kernel."""
     return [config1(1), config1(2), config2(301, 517), config3(263, 1031),
-            *config4(389, 1021, (1 << 20) + 77), *config5((6, 10, 12, 18, 8))]
+            *config4(389, 1021, (1 << 20) + 77), *config5((6, 10, 12, 18, 8)),
+            *config5((6, 10, 12, 18, 8), reading="R2")]
