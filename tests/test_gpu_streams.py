@@ -1,0 +1,111 @@
+"""Stream behaviour of the library on the GPU: calls recorded into a HIP graph and replayed
+with changing inputs, and independent chains of calls on two streams at once.  The library
+allocates nothing and clears nothing behind the caller's back, so both must just work."""
+import numpy as np
+import pytest
+
+import gpu_harness as H
+from workloads.values import random_view, rng_for
+from workloads.views import View
+
+pytestmark = pytest.mark.gpu
+
+
+def _oracle_chain(a, b, c, cast_out, red_out, full_out):
+    from oracle import binding as O
+    O.binary("add", a, b, c)                 # c = a + b^T      (tiled kernel)
+    O.unary("ident", c, cast_out)            # int16 <- float   (rows kernel)
+    O.reduce("sum", c, [0], red_out)         # column sums      (split, two launches)
+    O.reduce("max", c, [0, 1], full_out)     # full reduction   (split, two launches)
+
+
+def test_graph_capture_and_replay_with_new_inputs():
+    import torch
+    import paper_1810_08723_amd as ocn
+    rng = rng_for(14000)
+    n0, n1 = 1536, 640
+    a = random_view(rng, "float", (n0, n1), specials=False)
+    b = random_view(rng, "float", (n1, n0), specials=False).permute(1, 0)
+    c = View.empty("float", (n0, n1))
+    cast_out = View.empty("int16", (n0, n1))
+    red_out = View.empty("float", (n1,))
+    full_out = View.empty("float", ())
+    dv = H.DeviceViews()
+    ta, tb, tc = dv.tensor(a), dv.tensor(b), dv.tensor(c)
+    tcast, tred, tfull = dv.tensor(cast_out), dv.tensor(red_out), dv.tensor(full_out)
+    ws1 = torch.empty(max(256, ocn.reduce_workspace_bytes("sum", tc, [0], tred)), dtype=torch.uint8, device="cuda:0")
+    ws2 = torch.empty(max(256, ocn.reduce_workspace_bytes("max", tc, [0, 1], tfull)), dtype=torch.uint8, device="cuda:0")
+    assert ocn.plan_reduce("sum", tc, [0], tred)["passes"] == 2
+    assert ocn.plan_reduce("max", tc, [0, 1], tfull)["passes"] == 2
+
+    def enqueue():
+        ocn.binary("add", ta, tb, tc)
+        ocn.cast_copy(tc, tcast)
+        ocn.reduce("sum", tc, [0], tred, workspace=ws1)
+        ocn.reduce("max", tc, [0, 1], tfull, workspace=ws2)
+
+    enqueue()                                # eager once: warms up, and gives the reference
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        enqueue()                            # recorded on the capture stream (torch's current stream)
+    torch.cuda.synchronize()
+
+    dev_a = dv._by_id[id(a.storage)][1]
+    dev_b = dv._by_id[id(b.storage)][1]
+    for replay in range(3):
+        # new input values, uploaded by ordinary eager work between the replays
+        a.storage[:] = random_view(rng, "float", (n0, n1), specials=False).storage
+        b.storage[:] = random_view(rng, "float", (n1, n0), specials=False).storage
+        dev_a.copy_(torch.from_numpy(a.storage))
+        dev_b.copy_(torch.from_numpy(b.storage))
+        for v in (c, cast_out, red_out, full_out):          # poison the outputs
+            dv._by_id[id(v.storage)][1].fill_(0x5A)
+        torch.cuda.synchronize()
+        print("graph replay", replay, flush=True)
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [dv.download(v).copy() for v in (c, cast_out, red_out, full_out)]
+        _oracle_chain(a, b, c, cast_out, red_out, full_out)
+        assert H.storages_equal("float", got[0], c.storage)
+        assert np.array_equal(got[1], cast_out.storage)
+        x = c.to_numpy().astype(np.float64)
+        bound = 1e-6 * np.abs(x).sum(axis=0)
+        assert np.all(np.abs(got[2].view(np.float32).astype(np.float64) - red_out.storage.view(np.float32)) <= bound)
+        assert np.array_equal(got[3], full_out.storage)
+
+
+def test_two_streams_at_once():
+    import torch
+    import paper_1810_08723_amd as ocn
+    rng = rng_for(14001)
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    jobs = []
+    for k in range(2):
+        shape = (700 + 50 * k, 900)
+        a = random_view(rng, "double", shape, specials=False)
+        b = random_view(rng, "double", shape[::-1], specials=False).permute(1, 0)
+        c = View.empty("double", shape)
+        m = View.empty("bool", shape)
+        s = View.empty("double", (shape[0],))
+        dv = H.DeviceViews()
+        t = [dv.tensor(v) for v in (a, b, c, m, s)]
+        jobs.append((dv, (a, b, c, m, s), t))
+    torch.cuda.synchronize()
+    for rep in range(4):
+        for k, (dv, views, t) in enumerate(jobs):
+            st = streams[k].cuda_stream
+            ocn.binary("mul", t[0], t[1], t[2], stream=st)
+            ocn.binary("gt", t[2], t[0], t[3], stream=st)
+            ocn.reduce("sum", t[2], [1], t[4], stream=st)
+    torch.cuda.synchronize()
+    from oracle import binding as O
+    for dv, (a, b, c, m, s), t in jobs:
+        got = [dv.download(v).copy() for v in (c, m, s)]
+        O.binary("mul", a, b, c)
+        O.binary("gt", c, a, m)
+        O.reduce("sum", c, [1], s)
+        assert H.storages_equal("double", got[0], c.storage)
+        assert np.array_equal(got[1], m.storage)
+        x = c.to_numpy()
+        assert np.all(np.abs(got[2].view(np.float64) - s.storage.view(np.float64)) <= 1e-13 * np.abs(x).sum(axis=1) + 1e-300)
