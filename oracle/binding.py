@@ -106,6 +106,18 @@ def reduce(op: str, a, axes: Sequence[int], out) -> None:
     _check(lib().orc_reduce(REDUCE[op], C.byref(_desc(a)), ax, len(axes), C.byref(_desc(out))))
 
 
+def binary_reduce(ew_op: str, red_op: str, a, b, axes: Sequence[int], out, mid_dtype: str) -> None:
+    """Reduction of an elementwise result (sections 3.2 and 5 of the paper: elementwise
+    functions followed by a reduction along axes, as in the norm of the QR example), written
+    out as its definition: materialise binary(ew_op, a, b) as a tensor of type `mid_dtype`
+    and the broadcast shape, then reduce it over `axes` into `out`.  Nothing is fused here."""
+    from workloads.views import View
+    shape = tuple(int(s) for s in np.broadcast_shapes(tuple(a.sizes), tuple(b.sizes)))
+    mid = View.empty(mid_dtype, shape)
+    binary(ew_op, a, b, mid)
+    reduce(red_op, mid, axes, out)
+
+
 def promote(a: str, b: str) -> str:
     return DTYPE_NAME[lib().orc_promote(DTYPE_CODE[a], DTYPE_CODE[b])]
 
