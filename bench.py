@@ -14,6 +14,8 @@ from __future__ import annotations
 
 import argparse
 import json
+
+import numpy as np
 import os
 import sys
 import time
@@ -77,6 +79,11 @@ def _device_cases(cases):
             fn = (lambda ins=ins, out=out, c=c: ocn.binary(c.op, ins[0], ins[1], out))
         elif c.kind == "unary":
             fn = (lambda ins=ins, out=out, c=c: ocn.unary(c.op, ins[0], out))
+        elif c.kind == "binary_reduce":
+            need = ocn.binary_reduce_workspace_bytes(c.op, c.red_op, ins[0], ins[1], list(c.axes), out, c.mid_dtype)
+            ws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda:0")
+            fn = (lambda ins=ins, out=out, c=c, ws=ws: ocn.binary_reduce(c.op, c.red_op, ins[0], ins[1], list(c.axes),
+                                                                         out, c.mid_dtype, workspace=ws))
         else:
             need = ocn.reduce_workspace_bytes(c.op, ins[0], list(c.axes), out)
             ws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda:0")
@@ -96,6 +103,8 @@ def _plan_kernel(c):
         return ocn.plan_binary(c.op, ins[0], ins[1], out)
     if c.kind == "unary":
         return ocn.plan_unary(c.op, ins[0], out)
+    if c.kind == "binary_reduce":
+        return ocn.plan_binary_reduce(c.op, c.red_op, ins[0], ins[1], list(c.axes), out, c.mid_dtype)
     return ocn.plan_reduce(c.op, ins[0], list(c.axes), out)
 
 
@@ -152,9 +161,10 @@ def main() -> int:
     cases = configs.all_cases_full()
     if args.only:
         want = args.only.split(",")
+        if any(w.startswith("F") for w in want):
+            cases = cases + configs.fused_cases()
         cases = [c for c in cases if c.name in want]
         if "copy" in want:
-            import numpy as np
             from workloads.views import View
             n = 1 << 28
             src = View.from_numpy(np.ones(n, dtype=np.float32))
@@ -210,6 +220,46 @@ def main() -> int:
         for _ in range(50):
             _plan_kernel(c)
         per_op[i]["plan_us"] = (time.perf_counter() - t1) / 50 * 1e6
+    # the fused elementwise+reduce cases, outside the timed step: device time of the one fused
+    # call and of the same result computed as two calls through a temporary tensor
+    next_ops = []
+    if not args.only:
+        del runs, _keep
+        torch.cuda.empty_cache()
+        fcases = configs.fused_cases()
+        fruns, _fkeep = _device_cases(fcases)
+        for (c, fn, out) in fruns:
+            ins = [ocn.Tensor.on_storage(_fkeep[id(v.storage)], v.dtype, v.sizes, v.strides, v.offset) for v in c.inputs]
+            shape = tuple(c.inputs[0].sizes)
+            mid_t = torch.empty(int(np.prod(shape)) * ocn.dtype_size(c.mid_dtype), dtype=torch.uint8, device="cuda:0")
+            st = []
+            acc = ocn.dtype_size(c.mid_dtype)
+            for n in reversed(shape):
+                st.insert(0, acc)
+                acc *= n
+            mid = ocn.Tensor.on_storage(mid_t, c.mid_dtype, shape, tuple(st), 0)
+            need = ocn.reduce_workspace_bytes(c.red_op, mid, list(c.axes), out)
+            ws2 = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda:0")
+
+            def two_calls(c=c, ins=ins, mid=mid, out=out, ws2=ws2):
+                ocn.binary(c.op, ins[0], ins[1], mid)
+                ocn.reduce(c.red_op, mid, list(c.axes), out, workspace=ws2)
+
+            def timed(f, reps=12):
+                evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+                for a, b in evs:
+                    a.record(); f(); b.record()
+                torch.cuda.synchronize()
+                t = sorted(a.elapsed_time(b) for a, b in evs[2:])
+                return t[len(t) // 2] * 1e3
+            us = timed(fn)
+            us2 = timed(two_calls)
+            plan = _plan_kernel(c)
+            next_ops.append({"case": c.name, "op": f"{c.red_op}({c.op})", "kernel": plan["kernel"], "fused": plan["fused"],
+                             "passes": plan["passes"], "logical_bytes": c.logical_bytes, "us": us,
+                             "gbs": c.logical_bytes / (us * 1e-6) / 1e9,
+                             "frac_of_peak": c.logical_bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                             "two_calls_us": us2})
     device_ms = sum(p["avg_us"] for p in per_op) / 1e3
     dom = max(per_op, key=lambda p: p["avg_us"])
     traffic = _measured_traffic()
@@ -232,6 +282,7 @@ def main() -> int:
                      "kernel": f"{dom['kernel']} ({dom['case']})",
                      "bytes_per_launch": dom["logical_bytes"], "avg_us": dom["avg_us"]},
         "per_op": per_op,
+        "next_ops": next_ops,
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = _cpu_baseline()

@@ -155,6 +155,27 @@ int ocn_cast_copy(const ocn_tensor *src, const ocn_tensor *dst, void *stream);
 int ocn_reduce(int op, const ocn_tensor *a, const int32_t *axes, int32_t naxes,
                const ocn_tensor *out, void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Reduction of an elementwise result (sections 3.2 and 5: elementwise functions followed by a
+ * reduction along axes, as in inner products and norms): what
+ *     ocn_binary(ew_op, a, b, t);  ocn_reduce(red_op, t, axes, naxes, out, ...)
+ * gives for a temporary t of type mid_dtype and the broadcast shape of a and b (each pair of
+ * sizes equal or 1; missing leading dimensions count as 1), without t ever reaching memory
+ * where a fused kernel exists: equal input types with sums of a+b, a-b, a*b in that type
+ * (mid_dtype = the input type), or sums / any / all of ==, <, >, |a|>|b| (mid_dtype =
+ * OCN_BOOL).  Other combinations run as the two calls above with t at the start of the
+ * workspace.  axes index the broadcast shape; out has its kept dimensions.  Floating sums may
+ * differ from the two-call result by the order of additions only.  Workspace, alignment,
+ * aliasing and error rules as for ocn_reduce; out must not share bytes with a or b.
+ */
+int ocn_binary_reduce(int ew_op, int red_op, const ocn_tensor *a, const ocn_tensor *b,
+                      const int32_t *axes, int32_t naxes, const ocn_tensor *out, int32_t mid_dtype,
+                      void *workspace, size_t workspace_bytes, void *stream);
+
+size_t ocn_binary_reduce_workspace_bytes(int ew_op, int red_op, const ocn_tensor *a,
+                                         const ocn_tensor *b, const int32_t *axes, int32_t naxes,
+                                         const ocn_tensor *out, int32_t mid_dtype);
+
 /* Bytes of workspace ocn_reduce needs for these arguments (0 when it runs in one pass).
  * Returns 0 as well when the arguments are invalid; ocn_reduce then reports the error. */
 size_t ocn_reduce_workspace_bytes(int op, const ocn_tensor *a, const int32_t *axes,
@@ -212,6 +233,8 @@ typedef struct {
   int64_t lds_bytes;
   int64_t unclipped;                  /* tiled kernel: 1 when no tile is clipped and every
                                          access is a whole vector (the leaner kernel form)  */
+  int64_t fused;                      /* ocn_binary_reduce: 1 when one fused kernel does the
+                                         elementwise step and the reduction                 */
 } ocn_plan_info;
 
 int ocn_plan_unary(int op, const ocn_tensor *a, const ocn_tensor *out, uint32_t flags,
@@ -220,6 +243,9 @@ int ocn_plan_binary(int op, const ocn_tensor *a, const ocn_tensor *b, const ocn_
                     uint32_t flags, ocn_plan_info *info);
 int ocn_plan_reduce(int op, const ocn_tensor *a, const int32_t *axes, int32_t naxes,
                     const ocn_tensor *out, ocn_plan_info *info);
+int ocn_plan_binary_reduce(int ew_op, int red_op, const ocn_tensor *a, const ocn_tensor *b,
+                           const int32_t *axes, int32_t naxes, const ocn_tensor *out,
+                           int32_t mid_dtype, ocn_plan_info *info);
 
 #ifdef __cplusplus
 }

@@ -36,7 +36,8 @@ KERNELS = ("none", "ew_rows", "ew_tiled", "ew_generic", "red_rows", "red_cols", 
 
 EXPORTS = ("ocn_unary", "ocn_binary", "ocn_cast_copy", "ocn_reduce", "ocn_reduce_workspace_bytes",
            "ocn_promote", "ocn_dtype_size", "ocn_error_string", "ocn_last_hip_error",
-           "ocn_plan_unary", "ocn_plan_binary", "ocn_plan_reduce")
+           "ocn_plan_unary", "ocn_plan_binary", "ocn_plan_reduce",
+           "ocn_binary_reduce", "ocn_binary_reduce_workspace_bytes", "ocn_plan_binary_reduce")
 
 
 class OcnTensor(C.Structure):
@@ -55,7 +56,7 @@ class OcnPlanInfo(C.Structure):
                 ("vec", C.c_int32), ("tile_log2", C.c_int32 * MAX_DIMS), ("stage_a", C.c_int32),
                 ("stage_b", C.c_int32), ("specialised", C.c_int32), ("passes", C.c_int32),
                 ("grid", C.c_int64), ("block", C.c_int64), ("split", C.c_int64),
-                ("lds_bytes", C.c_int64), ("unclipped", C.c_int64)]
+                ("lds_bytes", C.c_int64), ("unclipped", C.c_int64), ("fused", C.c_int64)]
 
 
 class OcnError(RuntimeError):
@@ -94,6 +95,12 @@ def lib() -> C.CDLL:
         L.ocn_plan_unary.argtypes = [C.c_int, T, T, C.c_uint32, I]
         L.ocn_plan_binary.argtypes = [C.c_int, T, T, T, C.c_uint32, I]
         L.ocn_plan_reduce.argtypes = [C.c_int, T, C.POINTER(C.c_int32), C.c_int32, T, I]
+        A = C.POINTER(C.c_int32)
+        L.ocn_binary_reduce.argtypes = [C.c_int, C.c_int, T, T, A, C.c_int32, T, C.c_int32, C.c_void_p,
+                                        C.c_size_t, C.c_void_p]
+        L.ocn_binary_reduce_workspace_bytes.argtypes = [C.c_int, C.c_int, T, T, A, C.c_int32, T, C.c_int32]
+        L.ocn_binary_reduce_workspace_bytes.restype = C.c_size_t
+        L.ocn_plan_binary_reduce.argtypes = [C.c_int, C.c_int, T, T, A, C.c_int32, T, C.c_int32, I]
         _lib = L
     return _lib
 
@@ -181,6 +188,31 @@ def reduce(op: str, a: Tensor, axes: Sequence[int], out: Tensor, workspace=None,
                             ws_ptr, ws_bytes, _stream(stream)))
 
 
+def binary_reduce_workspace_bytes(ew_op: str, red_op: str, a: Tensor, b: Tensor, axes: Sequence[int],
+                                  out: Tensor, mid_dtype: str) -> int:
+    ax, n = _axes(axes)
+    return int(lib().ocn_binary_reduce_workspace_bytes(BINARY_CODE[ew_op], REDUCE_CODE[red_op], C.byref(a.desc()),
+                                                       C.byref(b.desc()), ax, n, C.byref(out.desc()),
+                                                       DTYPE_CODE[mid_dtype]))
+
+
+def binary_reduce(ew_op: str, red_op: str, a: Tensor, b: Tensor, axes: Sequence[int], out: Tensor,
+                  mid_dtype: str, workspace=None, stream=None) -> None:
+    """reduce(red_op, binary(ew_op, a, b) as mid_dtype, axes) -> out; `workspace` as for reduce()."""
+    ax, n = _axes(axes)
+    ws_ptr, ws_bytes = None, 0
+    if workspace is None:
+        need = binary_reduce_workspace_bytes(ew_op, red_op, a, b, axes, out, mid_dtype)
+        if need:
+            import torch
+            workspace = torch.empty(need, dtype=torch.uint8, device=f"cuda:{a.device}")
+    if workspace is not None:
+        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel()
+    _check(lib().ocn_binary_reduce(BINARY_CODE[ew_op], REDUCE_CODE[red_op], C.byref(a.desc()), C.byref(b.desc()),
+                                   ax, n, C.byref(out.desc()), DTYPE_CODE[mid_dtype], ws_ptr, ws_bytes,
+                                   _stream(stream)))
+
+
 def promote(a: str, b: str) -> str:
     rc = lib().ocn_promote(DTYPE_CODE[a], DTYPE_CODE[b])
     _check(rc if rc < 0 else OK)
@@ -202,6 +234,7 @@ def _info_dict(info: OcnPlanInfo) -> dict:
         "vec": info.vec, "tile_log2": tuple(info.tile_log2[:n]), "stage_a": bool(info.stage_a),
         "stage_b": bool(info.stage_b), "specialised": bool(info.specialised), "passes": info.passes,
         "grid": info.grid, "block": info.block, "split": info.split, "lds_bytes": info.lds_bytes, "unclipped": bool(info.unclipped),
+        "fused": bool(info.fused),
     }
 
 
@@ -215,6 +248,16 @@ def plan_binary(op: str, a: Tensor, b: Tensor, out: Tensor, flags: int = 0) -> d
     info = OcnPlanInfo()
     _check(lib().ocn_plan_binary(BINARY_CODE[op], C.byref(a.desc()), C.byref(b.desc()),
                                  C.byref(out.desc()), flags, C.byref(info)))
+    return _info_dict(info)
+
+
+def plan_binary_reduce(ew_op: str, red_op: str, a: Tensor, b: Tensor, axes: Sequence[int], out: Tensor,
+                       mid_dtype: str) -> dict:
+    info = OcnPlanInfo()
+    ax, n = _axes(axes)
+    _check(lib().ocn_plan_binary_reduce(BINARY_CODE[ew_op], REDUCE_CODE[red_op], C.byref(a.desc()),
+                                        C.byref(b.desc()), ax, n, C.byref(out.desc()), DTYPE_CODE[mid_dtype],
+                                        C.byref(info)))
     return _info_dict(info)
 
 

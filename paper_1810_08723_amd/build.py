@@ -17,12 +17,13 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 # Floating-point contraction stays off: a*b+c must round twice, as in the definition of each
 # operation.  Packed-FP32 instruction selection is switched off for the device pass.
-COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
+COMMON = ["--offload-arch=gfx950", *os.environ.get("OCN_EXTRA_FLAGS", "").split(), "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
           "-Wno-unused-command-line-argument"]
 
 SOURCES = (["api.cpp", "planner.cpp", "ew_launch.cpp", "red_launch.cpp", "ew_interp.hip"]
-           + [f"ew_slice_{i}.hip" for i in range(8)] + [f"red_slice_{i}.hip" for i in range(4)])
+           + [f"ew_slice_{i}.hip" for i in range(8)] + [f"red_slice_{i}.hip" for i in range(4)]
+           + [f"fred_slice_{i}.hip" for i in range(4)])
 
 
 def _compile(src: str) -> str:

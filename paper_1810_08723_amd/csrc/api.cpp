@@ -26,6 +26,7 @@ static_assert(R_SUM == OCN_R_SUM && R_PROD == OCN_R_PROD && R_MIN == OCN_R_MIN &
 void register_ew_slice_0(); void register_ew_slice_1(); void register_ew_slice_2(); void register_ew_slice_3();
 void register_ew_slice_4(); void register_ew_slice_5(); void register_ew_slice_6(); void register_ew_slice_7();
 void register_red_slice_0(); void register_red_slice_1(); void register_red_slice_2(); void register_red_slice_3();
+void register_fred_slice_0(); void register_fred_slice_1(); void register_fred_slice_2(); void register_fred_slice_3();
 
 static std::once_flag g_once;
 static void ensure_registered() {
@@ -33,6 +34,7 @@ static void ensure_registered() {
     register_ew_slice_0(); register_ew_slice_1(); register_ew_slice_2(); register_ew_slice_3();
     register_ew_slice_4(); register_ew_slice_5(); register_ew_slice_6(); register_ew_slice_7();
     register_red_slice_0(); register_red_slice_1(); register_red_slice_2(); register_red_slice_3();
+    register_fred_slice_0(); register_fred_slice_1(); register_fred_slice_2(); register_fred_slice_3();
   });
 }
 
@@ -52,6 +54,18 @@ static int run_elementwise(const EwPlan &p, hipStream_t stream) {
                             : g_unary_launchers[p.op][p.a.dtype][p.out.dtype];
   if (!f) return finish(launch_interp(p, stream));
   return finish(f(p, stream));
+}
+
+// first launch of a (plain or fused) reduction plan, then the fold of its partial results
+static int run_reduce(const RedPlan &p, RedLauncher first, char *workspace, hipStream_t stream) {
+  if (!first) return OCN_ERR_DTYPE;
+  int st = finish(first(p, workspace, stream));
+  if (st != OCN_OK || p.split == 1) return st;
+  RedPlan q;
+  plan_second_pass(p, workspace, &q);
+  RedLauncher g = g_reduce_launchers[q.op][q.a_dtype];
+  if (!g) return OCN_ERR_DTYPE;
+  return finish(g(q, nullptr, stream));
 }
 
 }  // namespace ocn
@@ -90,15 +104,37 @@ int ocn_reduce(int op, const ocn_tensor *a, const int32_t *axes, int32_t naxes,
     if ((uintptr_t)workspace % 256 != 0) return OCN_ERR_ALIGN;
   }
   ensure_registered();
-  RedLauncher f = g_reduce_launchers[p.op][p.a_dtype];
-  if (!f) return OCN_ERR_DTYPE;
-  int st = finish(f(p, (char *)workspace, (hipStream_t)stream));
-  if (st != OCN_OK || p.split == 1) return st;
-  RedPlan q;
-  plan_second_pass(p, (char *)workspace, &q);
-  RedLauncher g = g_reduce_launchers[q.op][q.a_dtype];
-  if (!g) return OCN_ERR_DTYPE;
-  return finish(g(q, nullptr, (hipStream_t)stream));
+  return run_reduce(p, g_reduce_launchers[p.op][p.a_dtype], (char *)workspace, (hipStream_t)stream);
+}
+
+int ocn_binary_reduce(int ew_op, int red_op, const ocn_tensor *a, const ocn_tensor *b, const int32_t *axes,
+                      int32_t naxes, const ocn_tensor *out, int32_t mid_dtype, void *workspace,
+                      size_t workspace_bytes, void *stream) {
+  FusedPlan fp;
+  const int rc = plan_binary_reduce(ew_op, red_op, a, b, axes, naxes, out, mid_dtype, (char *)workspace, &fp);
+  if (rc != OCN_OK) return rc;
+  if (fp.workspace_bytes > 0) {
+    if (!workspace || workspace_bytes < fp.workspace_bytes) return OCN_ERR_WORKSPACE;
+    if ((uintptr_t)workspace % 256 != 0) return OCN_ERR_ALIGN;
+  }
+  ensure_registered();
+  if (fp.unfused) {
+    const int st = run_elementwise(fp.ew, (hipStream_t)stream);
+    if (st != OCN_OK || fp.red.kernel == OCN_KERNEL_NONE) return st;
+    return run_reduce(fp.red, g_reduce_launchers[fp.red.op][fp.red.a_dtype], (char *)workspace + fp.mid_bytes,
+                      (hipStream_t)stream);
+  }
+  if (fp.red.kernel == OCN_KERNEL_NONE) return OCN_OK;
+  return run_reduce(fp.red, g_fused_launchers[fp.red.ew_op][fp.red.a_dtype][fp.red.op], (char *)workspace,
+                    (hipStream_t)stream);
+}
+
+size_t ocn_binary_reduce_workspace_bytes(int ew_op, int red_op, const ocn_tensor *a, const ocn_tensor *b,
+                                         const int32_t *axes, int32_t naxes, const ocn_tensor *out,
+                                         int32_t mid_dtype) {
+  FusedPlan fp;
+  if (plan_binary_reduce(ew_op, red_op, a, b, axes, naxes, out, mid_dtype, nullptr, &fp) != OCN_OK) return 0;
+  return fp.workspace_bytes;
 }
 
 size_t ocn_reduce_workspace_bytes(int op, const ocn_tensor *a, const int32_t *axes, int32_t naxes,
@@ -159,6 +195,18 @@ int ocn_plan_reduce(int op, const ocn_tensor *a, const int32_t *axes, int32_t na
   const int rc = plan_reduce(op, a, axes, naxes, out, &p);
   if (rc != OCN_OK) return rc;
   fill_info(p, info);
+  return OCN_OK;
+}
+
+int ocn_plan_binary_reduce(int ew_op, int red_op, const ocn_tensor *a, const ocn_tensor *b, const int32_t *axes,
+                           int32_t naxes, const ocn_tensor *out, int32_t mid_dtype, ocn_plan_info *info) {
+  if (!info) return OCN_ERR_NULLPTR;
+  FusedPlan fp;
+  const int rc = plan_binary_reduce(ew_op, red_op, a, b, axes, naxes, out, mid_dtype, nullptr, &fp);
+  if (rc != OCN_OK) return rc;
+  fill_info(fp.red, info);
+  info->fused = fp.unfused ? 0 : 1;
+  if (fp.unfused && fp.ew.kernel != OCN_KERNEL_NONE) info->passes += 1;
   return OCN_OK;
 }
 

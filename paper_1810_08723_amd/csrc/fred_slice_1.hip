@@ -1,0 +1,4 @@
+// Slice 1 of the fused elementwise+reduce kernels (see fred_inst.inl).
+#define OCN_SLICE 1
+#define OCN_NSLICES 4
+#include "fred_inst.inl"

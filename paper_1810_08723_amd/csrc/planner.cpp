@@ -552,10 +552,10 @@ int reduce_acc_dtype(int op, int dt) {
 
 namespace {
 
-struct RDim { int64_t size, sa, so; };
+struct RDim { int64_t size, sa, so, sb; };
 
-int sort_merge(RDim *d, int n, bool by_out) {
-  auto key = [&](const RDim &x) { return by_out ? x.so : iabs64(x.sa); };
+// sorts by decreasing key, then merges neighbours that every operand walks as one longer dim
+template <class Key> int sort_merge_by(RDim *d, int n, Key key) {
   for (int i = 1; i < n; ++i)
     for (int j = i; j > 0 && key(d[j]) > key(d[j - 1]); --j) std::swap(d[j], d[j - 1]);
   int m = 0;
@@ -563,14 +563,18 @@ int sort_merge(RDim *d, int n, bool by_out) {
     if (m > 0) {
       RDim &u = d[m - 1];
       const RDim &v = d[i];
-      if (u.sa == v.sa * v.size && u.so == v.so * v.size) {
-        u.size *= v.size; u.sa = v.sa; u.so = v.so;
+      if (u.sa == v.sa * v.size && u.so == v.so * v.size && u.sb == v.sb * v.size) {
+        u.size *= v.size; u.sa = v.sa; u.so = v.so; u.sb = v.sb;
         continue;
       }
     }
     d[m++] = d[i];
   }
   return m;
+}
+
+int sort_merge(RDim *d, int n, bool by_out) {
+  return sort_merge_by(d, n, [&](const RDim &x) { return by_out ? x.so : iabs64(x.sa); });
 }
 
 #ifndef OCN_RED_TARGET_WAVES
@@ -763,6 +767,245 @@ int plan_reduce(int op, const ocn_tensor *a, const int32_t *axes, int32_t naxes,
   p.out_ptr = (char *)out->base + off_o;
   choose_reduce_launch(p);
   *plan = p;
+  return OCN_OK;
+}
+
+namespace {
+
+// Launch shape of a fused elementwise+reduce kernel.  Same three layouts as the plain
+// reduction; an input may be broadcast (stride 0) along the vectorised dim as long as the
+// other one is contiguous there.
+void choose_fused_launch(RedPlan &p) {
+  const int es_a = dt_size(p.a_dtype), es_b = dt_size(p.b_dtype), es_m = dt_size(p.mid_dtype);
+  const int acc_es = dt_size(p.acc_dtype);
+  auto fast_ok = [&](int64_t sa, int64_t sb) {
+    return (sa == es_a || sa == 0) && (sb == es_b || sb == 0) && !(sa == 0 && sb == 0);
+  };
+  // stride in elements along a dim, of the input that moves slower there (0: both broadcast):
+  // a dim counts as fast only if no input jumps along it
+  auto elems = [&](int64_t sa, int64_t sb) {
+    return std::max(iabs64(sa) / es_a, iabs64(sb) / es_b);
+  };
+  int64_t r_fast = 0, k_fast = 0;
+  int k_fast_dim = -1;
+  if (p.nred) r_fast = elems(p.rstride_a[p.nred - 1], p.rstride_b[p.nred - 1]);
+  for (int d = 0; d < p.nkept; ++d) {
+    const int64_t e = elems(p.kstride_a[d], p.kstride_b[d]);
+    if (e && (k_fast_dim < 0 || e <= k_fast)) { k_fast = e; k_fast_dim = d; }
+  }
+  const int vfull = rows_vec(std::min({es_a, es_b, es_m}), std::max({es_a, es_b, es_m}));
+  // every stride except the one along the vectorised dim, and the base, are multiples of the
+  // vector size of each input that is not broadcast there
+  auto all_aligned = [&](int skip_kept, int skip_red, bool a_bcast, bool b_bcast) {
+    const int64_t va = a_bcast ? es_a : (int64_t)vfull * es_a, vb = b_bcast ? es_b : (int64_t)vfull * es_b;
+    if ((intptr_t)p.a_ptr % va || (intptr_t)p.b_ptr % vb) return false;
+    for (int d = 0; d < p.nkept; ++d)
+      if (d != skip_kept && (p.kstride_a[d] % va || p.kstride_b[d] % vb)) return false;
+    for (int d = 0; d < p.nred; ++d)
+      if (d != skip_red && (p.rstride_a[d] % va || p.rstride_b[d] % vb)) return false;
+    return true;
+  };
+  bool idx32 = p.nout < ((int64_t)1 << 31) && p.nredtot < ((int64_t)1 << 31);
+  for (int d = 0; d < p.nkept; ++d) idx32 = idx32 && p.ksize[d] < ((int64_t)1 << 31);
+  for (int d = 0; d < p.nred; ++d) idx32 = idx32 && p.rsize[d] < ((int64_t)1 << 31);
+  const bool flat_full = p.nkept == 0 && p.nred == 1;
+
+  p.split = 1;
+  if (p.nred >= 1 && fast_ok(p.rstride_a[p.nred - 1], p.rstride_b[p.nred - 1]) &&
+      (k_fast_dim < 0 || k_fast > r_fast) && p.nredtot >= 32 && (idx32 || flat_full)) {
+    p.kernel = OCN_KERNEL_RED_ROWS;
+    p.a_fast_bcast = p.rstride_a[p.nred - 1] == 0;
+    p.b_fast_bcast = p.rstride_b[p.nred - 1] == 0;
+    p.vec = all_aligned(-1, p.nred - 1, p.a_fast_bcast, p.b_fast_bcast) ? vfull : 1;
+    const int64_t n0 = p.rsize[p.nred - 1];
+    const int64_t vpr = (n0 + p.vec - 1) / p.vec;
+    const int64_t nvec = vpr * (p.nredtot / n0);
+    p.group = (nvec * p.vec * (es_a + es_b) <= 16 * 1024) ? kWave : kBlock;
+    const int64_t groups_per_block = kBlock / p.group;
+    const int64_t waves = p.nout * (p.group / kWave);
+    if (waves < kTargetWaves) {
+      const int64_t want = (kTargetWaves + waves - 1) / waves;
+      const int64_t most = std::max<int64_t>(1, nvec / ((int64_t)p.group * 8));
+      p.split = std::max<int64_t>(1, std::min(want, most));
+    }
+    p.chunk = (nvec + p.split - 1) / p.split;
+    p.split = (nvec + p.chunk - 1) / p.chunk;
+    p.grid = (p.nout * p.split + groups_per_block - 1) / groups_per_block;
+  } else if (k_fast_dim >= 0 && k_fast_dim == p.nkept - 1 && p.nred >= 1 && idx32 &&
+             fast_ok(p.kstride_a[k_fast_dim], p.kstride_b[k_fast_dim]) && (r_fast == 0 || r_fast > k_fast)) {
+    p.kernel = OCN_KERNEL_RED_COLS;
+    p.a_fast_bcast = p.kstride_a[k_fast_dim] == 0;
+    p.b_fast_bcast = p.kstride_b[k_fast_dim] == 0;
+    p.vec = all_aligned(p.nkept - 1, -1, p.a_fast_bcast, p.b_fast_bcast) ? vfull : 1;
+    const int64_t nc = p.ksize[p.nkept - 1];
+    const int64_t colblocks = (nc + (int64_t)kWave * p.vec - 1) / ((int64_t)kWave * p.vec);
+    const int64_t blocks0 = colblocks * (p.nout / nc);
+    const int nw = 4;
+    if (blocks0 * nw < kTargetWaves) {
+      const int64_t want = (kTargetWaves + blocks0 * nw - 1) / (blocks0 * nw);
+      const int64_t most = std::max<int64_t>(1, p.nredtot / (nw * 16));
+      p.split = std::max<int64_t>(1, std::min(want, most));
+    }
+    p.block = nw * kWave;
+    p.chunk = (p.nredtot + p.split - 1) / p.split;
+    p.split = (p.nredtot + p.chunk - 1) / p.chunk;
+    p.grid = blocks0 * p.split;
+  } else {
+    p.kernel = OCN_KERNEL_RED_GENERIC;
+    p.vec = 1;
+    p.chunk = p.nredtot;
+    p.grid = (p.nout + kBlock - 1) / kBlock;
+  }
+  p.passes = p.split > 1 ? 2 : 1;
+  p.workspace_bytes = p.split > 1 ? (size_t)(p.nout * p.split * acc_es) : 0;
+}
+
+}  // namespace
+
+int plan_binary_reduce(int ew_op, int red_op, const ocn_tensor *a, const ocn_tensor *b,
+                       const int32_t *axes, int32_t naxes, const ocn_tensor *out, int mid_dtype,
+                       char *workspace, FusedPlan *plan) {
+  FusedPlan fp;
+  RedPlan &p = fp.red;
+  int rc;
+  if ((rc = check_tensor(a)) != OCN_OK) return rc;
+  if ((rc = check_tensor(b)) != OCN_OK) return rc;
+  if ((rc = check_tensor(out)) != OCN_OK) return rc;
+  if (ew_op < 0 || ew_op >= B_COUNT || red_op < 0 || red_op >= R_COUNT) return OCN_ERR_OP;
+  if (!valid_dtype(mid_dtype)) return OCN_ERR_DTYPE;
+  if (a->device != out->device || b->device != out->device) return OCN_ERR_DEVICE;
+  // broadcast shape of the two inputs (missing leading dims count as size 1)
+  const int nd = std::max(a->ndim, b->ndim);
+  int64_t shape[kMaxDims], sa[kMaxDims], sb[kMaxDims];
+  for (int d = 0; d < nd; ++d) {
+    const int da = d - (nd - a->ndim), db = d - (nd - b->ndim);
+    const int64_t na = da >= 0 ? a->size[da] : 1, nb = db >= 0 ? b->size[db] : 1;
+    if (na != nb && na != 1 && nb != 1) return OCN_ERR_SHAPE;
+    shape[d] = na == 1 ? nb : na;
+    sa[d] = (da >= 0 && na != 1) ? a->stride[da] : 0;
+    sb[d] = (db >= 0 && nb != 1) ? b->stride[db] : 0;
+  }
+  if (naxes < 0 || naxes > nd) return OCN_ERR_SHAPE;
+  if (naxes > 0 && !axes) return OCN_ERR_NULLPTR;
+  bool reduced[kMaxDims] = {false};
+  for (int i = 0; i < naxes; ++i) {
+    if (axes[i] < 0 || axes[i] >= nd || reduced[axes[i]]) return OCN_ERR_SHAPE;
+    reduced[axes[i]] = true;
+  }
+  if (out->ndim != nd - naxes) return OCN_ERR_SHAPE;
+  const int T = binary_compute_dtype(ew_op, a->dtype, b->dtype, mid_dtype, promote(a->dtype, b->dtype));
+  if (!binary_supported(ew_op, T) || !reduce_supported(red_op, mid_dtype)) return OCN_ERR_DTYPE;
+
+  RDim kd[kMaxDims], rd[kMaxDims];
+  int nk = 0, nr = 0, j = 0;
+  int64_t nout = 1, nred = 1;
+  for (int d = 0; d < nd; ++d) {
+    if (reduced[d]) {
+      nred *= shape[d];
+      rd[nr++] = RDim{shape[d], sa[d], 0, sb[d]};
+    } else {
+      if (out->size[j] != shape[d]) return OCN_ERR_SHAPE;
+      nout *= shape[d];
+      kd[nk++] = RDim{shape[d], sa[d], out->stride[j], sb[d]};
+      ++j;
+    }
+  }
+  p.op = red_op;
+  p.fused = true;
+  p.ew_op = ew_op;
+  p.nout = nout;
+  p.nredtot = nred;
+  p.a_dtype = a->dtype;
+  p.b_dtype = b->dtype;
+  p.mid_dtype = mid_dtype;
+  p.out_dtype = out->dtype;
+  p.acc_dtype = reduce_acc_dtype(red_op, mid_dtype);
+  if (nout == 0) { *plan = fp; return OCN_OK; }
+  if ((red_op == R_MIN || red_op == R_MAX) && nred == 0) return OCN_ERR_EMPTY;
+  if ((rc = check_alignment(a)) != OCN_OK) return rc;
+  if ((rc = check_alignment(b)) != OCN_OK) return rc;
+  if ((rc = check_alignment(out)) != OCN_OK) return rc;
+  if (!provably_non_overlapping(out)) return OCN_ERR_OVERLAP_OUT;
+  if (nred > 0) {
+    intptr_t olo, ohi, ilo, ihi;
+    byte_range(out, &olo, &ohi);
+    byte_range(a, &ilo, &ihi);
+    if (ilo < ohi && olo < ihi) return OCN_ERR_ALIAS;
+    byte_range(b, &ilo, &ihi);
+    if (ilo < ohi && olo < ihi) return OCN_ERR_ALIAS;
+  }
+
+  if (!fused_specialised(ew_op, a->dtype, b->dtype, mid_dtype, red_op) || nred == 0) {
+    // no fused kernel for these types: elementwise into a temporary, then reduce it
+    fp.unfused = true;
+    ocn_tensor &m = fp.mid;
+    m.base = workspace;
+    m.offset = 0;
+    m.dtype = mid_dtype;
+    m.ndim = nd;
+    m.device = out->device;
+    int64_t acc = dt_size(mid_dtype);
+    for (int d = nd - 1; d >= 0; --d) { m.size[d] = shape[d]; m.stride[d] = acc; acc *= shape[d]; }
+    fp.mid_bytes = ((size_t)acc + 255) / 256 * 256;
+    // planned against a stand-in address when the caller only wants sizes
+    if (!workspace) m.base = (void *)(uintptr_t)0x1000;
+    if ((rc = plan_elementwise(2, ew_op, a, b, &m, 0, &fp.ew)) != OCN_OK) return rc;
+    if ((rc = plan_reduce(red_op, &m, axes, naxes, out, &fp.red)) != OCN_OK) return rc;
+    fp.workspace_bytes = fp.mid_bytes + fp.red.workspace_bytes;
+    *plan = fp;
+    return OCN_OK;
+  }
+
+  const int es_a = dt_size(a->dtype), es_b = dt_size(b->dtype);
+  int64_t off_a = a->offset, off_b = b->offset, off_o = out->offset;
+  // kept dims: drop size 1, flip to forward output strides, sort by output stride, merge
+  int n = 0;
+  for (int d = 0; d < nk; ++d) {
+    if (kd[d].size == 1) continue;
+    RDim x = kd[d];
+    if (x.so < 0) {
+      off_o += (x.size - 1) * x.so; off_a += (x.size - 1) * x.sa; off_b += (x.size - 1) * x.sb;
+      x.so = -x.so; x.sa = -x.sa; x.sb = -x.sb;
+    }
+    kd[n++] = x;
+  }
+  nk = sort_merge(kd, n, true);
+  // the column kernel walks the fastest kept dim forward through the inputs: turn it around
+  // again if the flip above left both inputs walking backwards (or broadcast) there
+  if (nk > 0) {
+    RDim &x = kd[nk - 1];
+    const bool a_back = x.sa == -(int64_t)es_a, b_back = x.sb == -(int64_t)es_b;
+    if ((a_back && (b_back || x.sb == 0)) || (b_back && x.sa == 0)) {
+      off_o += (x.size - 1) * x.so; off_a += (x.size - 1) * x.sa; off_b += (x.size - 1) * x.sb;
+      x.so = -x.so; x.sa = -x.sa; x.sb = -x.sb;
+    }
+  }
+  // reduced dims: drop size 1, flip so the faster-moving input walks forward, sort, merge
+  n = 0;
+  for (int d = 0; d < nr; ++d) {
+    if (rd[d].size == 1) continue;
+    RDim x = rd[d];
+    const int64_t lead = x.sa != 0 ? x.sa : x.sb;
+    if (lead < 0) {
+      off_a += (x.size - 1) * x.sa; off_b += (x.size - 1) * x.sb;
+      x.sa = -x.sa; x.sb = -x.sb;
+    }
+    rd[n++] = x;
+  }
+  nr = sort_merge_by(rd, n, [&](const RDim &x) { return std::max(iabs64(x.sa) / es_a, iabs64(x.sb) / es_b); });
+  p.nkept = nk;
+  p.nred = nr;
+  for (int d = 0; d < nk; ++d) {
+    p.ksize[d] = kd[d].size; p.kstride_a[d] = kd[d].sa; p.kstride_b[d] = kd[d].sb; p.kstride_o[d] = kd[d].so;
+  }
+  for (int d = 0; d < nr; ++d) { p.rsize[d] = rd[d].size; p.rstride_a[d] = rd[d].sa; p.rstride_b[d] = rd[d].sb; }
+  p.off_a = off_a; p.off_b = off_b; p.off_out = off_o;
+  p.a_ptr = (char *)a->base + off_a;
+  p.b_ptr = (char *)b->base + off_b;
+  p.out_ptr = (char *)out->base + off_o;
+  choose_fused_launch(p);
+  fp.workspace_bytes = p.workspace_bytes;
+  *plan = fp;
   return OCN_OK;
 }
 

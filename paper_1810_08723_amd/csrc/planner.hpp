@@ -89,7 +89,30 @@ struct RedPlan {
   int acc_dtype = 0;            // dtype the partial results are stored in
   size_t workspace_bytes = 0;
   int passes = 1;
+  // reduction of an elementwise result (second input b; zero strides where it is broadcast)
+  bool fused = false;
+  int ew_op = 0, b_dtype = 0, mid_dtype = 0;
+  char *b_ptr = nullptr;
+  int64_t off_b = 0;
+  int64_t kstride_b[kMaxDims] = {0}, rstride_b[kMaxDims] = {0};
+  bool a_fast_bcast = false, b_fast_bcast = false;  // broadcast along the vectorised dim
 };
+
+// out = reduce(red_op, binary(ew_op, a, b) held as mid_dtype, axes), planned either as one fused
+// kernel (plan->fused) or, when no fused kernel exists for the types, as the elementwise
+// operation into a temporary followed by the reduction: then *unfused is set, `mid` describes
+// the temporary (row-major, at the start of the workspace) and both sub-plans are filled in.
+struct FusedPlan {
+  RedPlan red;
+  bool unfused = false;
+  ocn_tensor mid{};
+  EwPlan ew;
+  size_t mid_bytes = 0;            // bytes of the temporary, rounded up to 256
+  size_t workspace_bytes = 0;      // temporary + reduction workspace
+};
+int plan_binary_reduce(int ew_op, int red_op, const ocn_tensor *a, const ocn_tensor *b,
+                       const int32_t *axes, int32_t naxes, const ocn_tensor *out, int mid_dtype,
+                       char *workspace, FusedPlan *plan);
 
 int plan_elementwise(int nin, int op, const ocn_tensor *a, const ocn_tensor *b,
                      const ocn_tensor *out, uint32_t flags, EwPlan *plan);

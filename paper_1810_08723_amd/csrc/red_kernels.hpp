@@ -37,6 +37,10 @@ struct RedArgs {
   int64_t split, chunk;
   int64_t nc;                              // cols: number of columns (fastest kept dim)
   FastDiv colblocks_div;                   // cols: column blocks per row of outputs
+  // second input of a fused elementwise+reduce kernel (unused by the plain kernels)
+  const char *b;
+  int64_t ksb[kMaxDims], rsb[kMaxDims];    // its byte strides, same order as ksa / rsa
+  int32_t a_bcast, b_bcast;                // broadcast along the vectorised dim
 };
 
 #if defined(__HIPCC__)

@@ -6,6 +6,7 @@
 namespace ocn {
 
 RedLauncher g_reduce_launchers[R_COUNT][DT_COUNT];
+RedLauncher g_fused_launchers[B_COUNT][DT_COUNT][R_COUNT];
 
 RedArgs make_red_args(const RedPlan &p, char *partial) {
   RedArgs r;
@@ -24,13 +25,18 @@ RedArgs make_red_args(const RedPlan &p, char *partial) {
     r.kso[k] = p.kstride_o[d];
     r.kdiv[k] = make_fastdiv((uint32_t)p.ksize[d]);
     r.ksize[k] = p.ksize[d];
+    r.ksb[k] = p.kstride_b[d];
   }
   for (int k = 0; k < p.nred; ++k) {
     const int d = p.nred - 1 - k;
     r.rsa[k] = p.rstride_a[d];
     r.rdiv[k] = make_fastdiv((uint32_t)p.rsize[d]);
     r.rsize[k] = p.rsize[d];
+    r.rsb[k] = p.rstride_b[d];
   }
+  r.b = p.b_ptr;
+  r.a_bcast = p.a_fast_bcast;
+  r.b_bcast = p.b_fast_bcast;
   r.nout = p.nout;
   r.nredtot = p.nredtot;
   r.split = p.split;

@@ -9,6 +9,8 @@ namespace ocn {
 
 using RedLauncher = hipError_t (*)(const RedPlan &, char *partial, hipStream_t);
 extern RedLauncher g_reduce_launchers[R_COUNT][DT_COUNT];
+// fused elementwise+reduce kernels: [elementwise op][input dtype (both inputs)][reduce op]
+extern RedLauncher g_fused_launchers[B_COUNT][DT_COUNT][R_COUNT];
 
 RedArgs make_red_args(const RedPlan &p, char *partial);
 

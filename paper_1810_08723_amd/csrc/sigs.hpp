@@ -36,6 +36,23 @@ OCN_HD constexpr bool unary_specialised(int op, int sa, int so) {
   return sa == so && unary_supported(op, so);
 }
 
+// Reductions of an elementwise result that get a fused kernel: equal input types; sums of
+// a + b, a - b, a * b in that type; sums (counts), any and all of ==, <, >, |a| > |b|.
+OCN_HD constexpr bool fused_specialised(int ew_op, int sa, int sb, int mid, int red_op) {
+  if (sa != sb || ew_op < 0 || ew_op >= B_COUNT) return false;
+  if (ew_op == B_ADD || ew_op == B_SUB || ew_op == B_MUL) {
+    if (mid != sa || red_op != R_SUM) return false;
+    return sa == DT_I32 || sa == DT_I64 || sa == DT_F16 || sa == DT_F32 || sa == DT_F64 || sa == DT_C32 ||
+           sa == DT_C64;
+  }
+  if (ew_op == B_EQ || ew_op == B_LT || ew_op == B_GT || ew_op == B_ABSGT) {
+    if (mid != DT_BOOL || !(red_op == R_SUM || red_op == R_ANY || red_op == R_ALL)) return false;
+    if (sa == DT_C32) return ew_op == B_EQ || ew_op == B_ABSGT;
+    return sa == DT_I32 || sa == DT_F32 || sa == DT_F64;
+  }
+  return false;
+}
+
 OCN_HD constexpr int imin(int a, int b) { return a < b ? a : b; }
 OCN_HD constexpr int imax(int a, int b) { return a > b ? a : b; }
 

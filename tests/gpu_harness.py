@@ -102,3 +102,16 @@ def run_reduce(op: str, a: View, axes: Sequence[int], out: View):
     got = dv.download(out)
     O.reduce(op, a, list(axes), out)
     return got, out.storage
+
+
+def run_binary_reduce(ew_op: str, red_op: str, a: View, b: View, axes: Sequence[int], out: View, mid_dtype: str):
+    """Returns (gpu storage, oracle storage) of out after reduce(red_op, binary(ew_op, a, b))."""
+    import paper_1810_08723_amd as ocn
+    from oracle import binding as O
+    dv = DeviceViews()
+    ta, tb, to = dv.tensor(a), dv.tensor(b), dv.tensor(out)
+    ocn.binary_reduce(ew_op, red_op, ta, tb, list(axes), to, mid_dtype)
+    dv.torch.cuda.synchronize()
+    got = dv.download(out)
+    O.binary_reduce(ew_op, red_op, a, b, list(axes), out, mid_dtype)
+    return got, out.storage

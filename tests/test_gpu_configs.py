@@ -29,6 +29,11 @@ def _run_case(c):
         dv.torch.cuda.synchronize()
         got = dv.download(c.out)
         O.unary(c.op, c.inputs[0], c.out)
+    elif c.kind == "binary_reduce":
+        ocn.binary_reduce(c.op, c.red_op, ins[0], ins[1], list(c.axes), out, c.mid_dtype)
+        dv.torch.cuda.synchronize()
+        got = dv.download(c.out)
+        O.binary_reduce(c.op, c.red_op, c.inputs[0], c.inputs[1], list(c.axes), c.out, c.mid_dtype)
     else:
         ocn.reduce(c.op, ins[0], list(c.axes), out)
         dv.torch.cuda.synchronize()
@@ -43,6 +48,9 @@ def _run_case(c):
         g = got.view(ft).astype(np.float64)
         w = want.view(ft).astype(np.float64)
         x = c.inputs[0].to_numpy().astype(np.float64)
+        if c.kind == "binary_reduce":       # the addends are the elementwise results (products here)
+            assert c.op == "mul"
+            x = x * c.inputs[1].to_numpy().astype(np.float64)
         bound = c.rel_bound * np.abs(x).sum(axis=c.axes)
         err = np.abs(g - w)
         assert np.all(err <= bound.reshape(-1)), (c.name, float(err.max()), float(bound.min()))
@@ -50,14 +58,14 @@ def _run_case(c):
         assert np.all(err <= 1e-7 * np.abs(x).sum(axis=c.axes).reshape(-1) + 1e-30)
 
 
-@pytest.mark.parametrize("idx", range(12))
+@pytest.mark.parametrize("idx", range(14))
 def test_small_cases(idx):
-    c = configs.all_cases_small()[idx]
+    c = (configs.all_cases_small() + configs.fused_cases(389, 1021, (1 << 20) + 77))[idx]
     print("case", c.name, c.op, [v.sizes for v in c.inputs], flush=True)
     _run_case(c)
 
 
-@pytest.mark.parametrize("which", ["C1", "C1x8", "C2", "C3", "C4", "C5", "C5b"])
+@pytest.mark.parametrize("which", ["C1", "C1x8", "C2", "C3", "C4", "C5", "C5b", "F"])
 def test_full_size_cases(which):
     if which == "C1":
         cases = [configs.config1(1)]
@@ -71,8 +79,10 @@ def test_full_size_cases(which):
         cases = configs.config4()
     elif which == "C5":
         cases = configs.config5()
-    else:
+    elif which == "C5b":
         cases = configs.config5(reading="R2")
+    else:
+        cases = configs.fused_cases()
     for c in cases:
         print("case", c.name, c.op, [v.sizes for v in c.inputs], flush=True)
         _run_case(c)

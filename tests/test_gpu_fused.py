@@ -1,0 +1,176 @@
+"""GPU parity of the fused elementwise+reduce call against the oracle's two-step definition:
+every fused signature family in the rows / columns / generic layouts, broadcast operands, split
+reductions, unaligned and reversed views, the two-call fallback, and degenerate shapes.
+Integer, bool and min/max results are bit-exact; floating sums within the reduction bounds."""
+import numpy as np
+import pytest
+
+import exactmath as X
+import gpu_harness as H
+from workloads.values import random_view, rng_for
+from workloads.views import View
+
+pytestmark = pytest.mark.gpu
+
+_F = {"half": np.float16, "float": np.float32, "double": np.float64,
+      "cfloat": np.float32, "cdouble": np.float64}
+REL = {"half": 1e-3, "float": 1e-6, "double": 1e-13, "cfloat": 1e-6, "cdouble": 1e-13}
+
+
+def _acc(red, mid):
+    if red in ("any", "all"):
+        return "bool"
+    if red in ("min", "max"):
+        return mid
+    k = X.kind(mid)
+    if k in "bi":
+        return "int64"
+    if k == "u":
+        return "uint64"
+    return {"half": "float", "float": "double", "double": "double", "cfloat": "cdouble", "cdouble": "cdouble"}[mid]
+
+
+def _check(ew, red, a, b, axes, mid, out_dtype=None, expect_fused=None):
+    import paper_1810_08723_amd as ocn
+    from oracle import binding as O
+    shape = np.broadcast_shapes(tuple(a.sizes), tuple(b.sizes))
+    kept = [s for d, s in enumerate(shape) if d not in axes]
+    out_dtype = out_dtype or _acc(red, mid)
+    out = View.empty(out_dtype, kept)
+    if expect_fused is not None:
+        dv = H.DeviceViews()
+        plan = ocn.plan_binary_reduce(ew, red, dv.tensor(a), dv.tensor(b), list(axes), dv.tensor(out), mid)
+        assert plan["fused"] == expect_fused, plan
+    print("fused", ew, red, a.dtype, a.sizes, a.strides, b.sizes, b.strides, axes, mid, flush=True)
+    got, want = H.run_binary_reduce(ew, red, a, b, axes, out, mid)
+    if not (red == "sum" and X.kind(mid) in "fc"):
+        assert H.storages_equal(out_dtype, got, want), (ew, red, a.dtype, H.first_mismatch(out_dtype, got, want))
+        return
+    # floating sum: bound relative to the sum of magnitudes of the intermediate values
+    t = View.empty(mid, shape)
+    O.binary(ew, a, b, t)
+    tv = t.to_numpy()
+    comp = _F[out_dtype]
+    g = got.view(comp).astype(np.float64)
+    w = want.view(comp).astype(np.float64)
+    if X.kind(mid) == "c":
+        mag = np.stack([np.abs(tv.real).astype(np.float64).sum(axis=tuple(axes)),
+                        np.abs(tv.imag).astype(np.float64).sum(axis=tuple(axes))], axis=-1).reshape(-1)
+    else:
+        mag = np.abs(tv.astype(np.float64)).sum(axis=tuple(axes)).reshape(-1)
+    rel = max(REL[mid], {"half": 1e-3, "float": 1e-7}.get(out_dtype, 0))
+    fin = np.isfinite(w) & np.isfinite(mag)
+    assert np.array_equal(np.isnan(g[~fin]), np.isnan(w[~fin])) or not np.isfinite(mag[~fin]).any()
+    assert np.all(np.abs(g[fin] - w[fin]) <= rel * mag[fin] + 1e-300), (ew, red, a.dtype, float(np.abs(g[fin] - w[fin]).max()))
+
+
+ARITH_T = ("int32", "int64", "half", "float", "double", "cfloat", "cdouble")
+
+
+@pytest.mark.parametrize("dt", ARITH_T)
+def test_sum_of_products_sums_differences_all_layouts(dt):
+    rng = rng_for(15000 + X.ALL.index(dt))
+    sp = X.kind(dt) not in "fc"
+    for ew in ("mul", "add", "sub"):
+        a = random_view(rng, dt, (37, 300), specials=sp)
+        b = random_view(rng, dt, (37, 300), specials=sp)
+        _check(ew, "sum", a, b, (1,), dt, expect_fused=True)          # rows
+        _check(ew, "sum", a, b, (0,), dt, expect_fused=True)          # columns
+        _check(ew, "sum", a, b, (0, 1), dt, expect_fused=True)        # full
+    # mismatched fastest axes: generic fused kernel
+    a = random_view(rng, dt, (40, 33), specials=sp)
+    bt = random_view(rng, dt, (33, 40), specials=sp).permute(1, 0)
+    _check("mul", "sum", a, bt, (1,), dt, expect_fused=True)
+    _check("mul", "sum", a, bt, (0,), dt, expect_fused=True)
+
+
+@pytest.mark.parametrize("dt", ("int32", "float", "double", "cfloat"))
+def test_counts_any_all_of_comparisons(dt):
+    rng = rng_for(15100 + X.ALL.index(dt))
+    ops = ("eq", "absgt") if dt == "cfloat" else ("eq", "lt", "gt", "absgt")
+    for ew in ops:
+        a = random_view(rng, dt, (29, 210))
+        b = random_view(rng, dt, (29, 210))
+        b.storage[: b.storage.size // 3] = a.storage[: a.storage.size // 3]   # plenty of equal elements
+        for red in ("sum", "any", "all"):
+            _check(ew, red, a, b, (1,), "bool", expect_fused=True)
+            _check(ew, red, a, b, (0,), "bool", expect_fused=True)
+        _check(ew, "sum", a, b, (0, 1), "bool", expect_fused=True)
+
+
+def test_broadcast_operands():
+    rng = rng_for(15200)
+    a = random_view(rng, "float", (120, 260), specials=False)
+    row = random_view(rng, "float", (260,), specials=False)
+    col = random_view(rng, "float", (120, 1), specials=False)
+    one = random_view(rng, "float", (), specials=False)
+    for b in (row, col, one):
+        for axes in ((1,), (0,), (0, 1)):
+            _check("mul", "sum", a, b, axes, "float", expect_fused=True)
+            _check("sub", "sum", b, a, axes, "float", expect_fused=True)     # broadcast first operand
+            _check("gt", "sum", a, b, axes, "bool", expect_fused=True)
+    # both inputs need broadcasting: outer-product sum
+    _check("mul", "sum", col, row, (1,), "float", expect_fused=True)
+    _check("mul", "sum", col, row, (0,), "float", expect_fused=True)
+    # lower-rank first operand against a 3-D second one
+    c = random_view(rng, "double", (5, 60, 70), specials=False)
+    v = random_view(rng, "double", (60, 1), specials=False)
+    for axes in ((2,), (0, 2), (1,), (0, 1, 2)):
+        _check("add", "sum", v, c, axes, "double", expect_fused=True)
+
+
+def test_split_reductions_and_output_conversion():
+    rng = rng_for(15300)
+    n = (1 << 21) + 777
+    x = random_view(rng, "float", (n,), specials=False)
+    y = random_view(rng, "float", (n,), specials=False)
+    _check("mul", "sum", x, y, (0,), "float", expect_fused=True)                     # rows, split
+    _check("mul", "sum", x, y, (0,), "float", out_dtype="double", expect_fused=True)
+    _check("gt", "sum", x, y, (0,), "bool", out_dtype="int32", expect_fused=True)
+    tall = random_view(rng, "double", (30000, 24), specials=False)
+    tall2 = random_view(rng, "double", (30000, 24), specials=False)
+    _check("sub", "sum", tall, tall2, (0,), "double", expect_fused=True)             # columns, split
+    z = random_view(rng, "cfloat", (3, 200001), specials=False)
+    w = random_view(rng, "cfloat", (3, 200001), specials=False)
+    _check("mul", "sum", z, w, (1,), "cfloat", expect_fused=True)
+    _check("absgt", "sum", z, w, (0, 1), "bool", expect_fused=True)
+
+
+def test_unaligned_reversed_and_stepped_views():
+    rng = rng_for(15400)
+    big = random_view(rng, "float", (50, 131), specials=False)
+    big2 = random_view(rng, "float", (50, 131), specials=False)
+    a = big.slice(1, 1, 128, 1)            # rows start 4 bytes off a 16-byte boundary: scalar accesses
+    b = big2.slice(1, 3, 130, 1)
+    _check("mul", "sum", a, b, (1,), "float", expect_fused=True)
+    _check("mul", "sum", a, b, (0,), "float", expect_fused=True)
+    _check("mul", "sum", big.flip(1), big2.flip(1), (1,), "float", expect_fused=True)   # both reversed
+    _check("mul", "sum", big.flip(1), big2, (1,), "float", expect_fused=True)           # one reversed
+    _check("mul", "sum", big.flip(0), big2, (0,), "float", expect_fused=True)
+    s = big.slice(1, 0, 131, 2)
+    s2 = big2.slice(1, 0, 131, 2)
+    _check("sub", "sum", s, s2, (1,), "float", expect_fused=True)                        # stepped: generic
+    out_rev = View.empty("double", (50,)).flip(0)
+    got, want = H.run_binary_reduce("mul", "sum", big, big2, [1], out_rev, "float")
+    assert np.allclose(got.view(np.float64), want.view(np.float64), rtol=1e-6, atol=1e-6)
+
+
+def test_two_call_fallback_and_degenerate_shapes():
+    rng = rng_for(15500)
+    f = random_view(rng, "float", (90, 70), specials=False)
+    g = random_view(rng, "float", (90, 70), specials=False)
+    _check("div", "sum", f, g, (1,), "float", expect_fused=False)
+    _check("max", "min", f, g, (0,), "float", expect_fused=False)
+    i = random_view(rng, "int32", (90, 70))
+    _check("mul", "sum", i, g, (1,), "float", expect_fused=False)           # mixed input types
+    _check("mul", "sum", i, i.fresh_copy(), (1,), "int64", expect_fused=False)   # wider intermediate
+    _check("le", "all", f, g, (0, 1), "bool", expect_fused=False)
+    u = random_view(rng, "uint8", (64, 64))
+    _check("bxor", "sum", u, u.permute(1, 0), (0,), "uint8", expect_fused=False)
+    # nothing to reduce over, a reduced extent of one, empty outputs, empty sums
+    _check("mul", "sum", f, g, (), "float")
+    one = random_view(rng, "float", (90, 1), specials=False)
+    _check("mul", "sum", one, one.fresh_copy(), (1,), "float")
+    _check("mul", "sum", View.empty("float", (0, 5)), View.empty("float", (0, 5)), (1,), "float")
+    _check("mul", "sum", View.empty("float", (4, 0)), View.empty("float", (4, 0)), (1,), "float")
+    _check("gt", "any", View.empty("float", (4, 0)), View.empty("float", (4, 0)), (1,), "bool")

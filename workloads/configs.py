@@ -27,7 +27,7 @@ BASE_SEED = 1810087230
 @dataclass
 class Case:
     name: str
-    kind: str                      # "binary" | "unary" | "reduce"
+    kind: str                      # "binary" | "unary" | "reduce" | "binary_reduce"
     op: str
     inputs: List[View]
     out: View
@@ -36,6 +36,8 @@ class Case:
     compare: str = "exact"         # "exact" | "sum" (bounded error relative to sum |x|)
     rel_bound: float = 0.0         # for compare == "sum"
     note: str = ""
+    red_op: str = ""               # kind == "binary_reduce": reduce(red_op, binary(op, a, b) as mid_dtype, axes)
+    mid_dtype: str = ""
 
 
 def _seed(config: int, tensor: int) -> int:
@@ -164,6 +166,23 @@ def config5(shape: Sequence[int] = (16, 32, 64, 64, 8), reading: str = "R1") -> 
              note="three different fastest axes"),
         Case("C5" + suffix + "m", "binary", "absgt", [a, b], mask, logical_bytes=17 * n,
              note="bool mask |A|>|B|"),
+    ]
+
+
+def fused_cases(rows: int = 16384, cols: int = 4096, n_flat: int = 1 << 26) -> List[Case]:
+    """Reductions of an elementwise result (the step after the five configurations): row-wise
+    inner products of two fp32 [rows, cols] matrices N(0,1), and the count of a > b over two flat
+    fp32 vectors.  Logical bytes: both inputs once plus the output."""
+    a = View.from_numpy(_normal(_seed(5, 0), (rows, cols), np.float32))
+    b = View.from_numpy(_normal(_seed(5, 1), (rows, cols), np.float32))
+    x = View.from_numpy(_normal(_seed(5, 2), (n_flat,), np.float32))
+    y = View.from_numpy(_normal(_seed(5, 3), (n_flat,), np.float32))
+    return [
+        Case("F1", "binary_reduce", "mul", [a, b], View.empty("float", (rows,)), axes=(1,),
+             logical_bytes=8 * rows * cols + 4 * rows, compare="sum", rel_bound=1e-6,
+             note="row-wise inner products", red_op="sum", mid_dtype="float"),
+        Case("F2", "binary_reduce", "gt", [x, y], View.empty("int64", ()), axes=(0,),
+             logical_bytes=8 * n_flat + 8, note="count of a > b", red_op="sum", mid_dtype="bool"),
     ]
 
 
