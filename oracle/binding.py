@@ -20,7 +20,8 @@ DTYPE_CODE = {name: i for i, name in enumerate(
      "half", "float", "double", "chalf", "cfloat", "cdouble"])}
 DTYPE_NAME = {v: k for k, v in DTYPE_CODE.items()}
 
-UNARY = {name: i for i, name in enumerate(["ident", "neg", "abs", "conj", "lnot", "bnot", "sqrt"])}
+UNARY = {name: i for i, name in enumerate(["ident", "neg", "abs", "conj", "lnot", "bnot", "sqrt",
+                                           "sin", "cos", "tan", "exp", "log"])}
 BINARY = {name: i for i, name in enumerate(
     ["add", "sub", "mul", "div", "min", "max", "band", "bor", "bxor", "land", "lor", "lxor",
      "eq", "ne", "lt", "le", "gt", "ge", "absgt"])}

@@ -19,6 +19,7 @@
  */
 #include "ocn_oracle.h"
 
+#include <complex.h>
 #include <math.h>
 #include <string.h>
 
@@ -512,9 +513,48 @@ static int unary_supported(int op, int T) {
     case ORC_U_NEG: return k != K_BOOL;
     case ORC_U_ABS: return k != K_BOOL && k != K_CPLX; /* complex modulus is not an exact op */
     case ORC_U_BNOT: return k == K_BOOL || k == K_SINT || k == K_UINT;
-    case ORC_U_SQRT: return k == K_REAL;
+    case ORC_U_SQRT: return k == K_REAL || k == K_CPLX;
+    case ORC_U_SIN: case ORC_U_COS: case ORC_U_TAN: case ORC_U_EXP: case ORC_U_LOG:
+      return k == K_REAL || k == K_CPLX;
     default: return 0;
   }
+}
+
+/* Elementary functions that are not exactly representable (section 3.2: trigonometric
+ * operations on all real and complex floating-point types; the paper gives no accuracy).
+ * Reading: the value of the C library's double-precision routine (principal branches for the
+ * complex ones), rounded once to the arithmetic type of T - single precision for half and
+ * float types, double otherwise.  The kernels are held to a few units in the last place of
+ * this value, not to its bits. */
+static double round_arith(arith_t t, double y) { return t == A_F64 ? y : (double)(float)y; }
+
+static val_t apply_elementary(int op, int T, val_t a) {
+  val_t r = a;
+  arith_t t = arith_of(T);
+  if (kind_of(T) == K_REAL) {
+    double y = 0;
+    switch (op) {
+      case ORC_U_SIN: y = sin(a.re); break;
+      case ORC_U_COS: y = cos(a.re); break;
+      case ORC_U_TAN: y = tan(a.re); break;
+      case ORC_U_EXP: y = exp(a.re); break;
+      case ORC_U_LOG: y = log(a.re); break;
+    }
+    r.re = round_arith(t, y);
+  } else {
+    double complex z = CMPLX(a.re, a.im), w = z;
+    switch (op) {
+      case ORC_U_SIN: w = csin(z); break;
+      case ORC_U_COS: w = ccos(z); break;
+      case ORC_U_TAN: w = ctan(z); break;
+      case ORC_U_EXP: w = cexp(z); break;
+      case ORC_U_LOG: w = clog(z); break;
+      case ORC_U_SQRT: w = csqrt(z); break;
+    }
+    r.re = round_arith(t, creal(w));
+    r.im = round_arith(t, cimag(w));
+  }
+  return r;
 }
 
 static val_t apply_unary(int op, int T, val_t a) {
@@ -544,8 +584,11 @@ static val_t apply_unary(int op, int T, val_t a) {
       else r.u = wrap_u(~a.u, bits);
       break;
     case ORC_U_SQRT:
+      if (k == K_CPLX) return apply_elementary(op, T, a);
       r.re = r_sqrt(arith_of(T), a.re);
       break;
+    case ORC_U_SIN: case ORC_U_COS: case ORC_U_TAN: case ORC_U_EXP: case ORC_U_LOG:
+      return apply_elementary(op, T, a);
   }
   return r;
 }
