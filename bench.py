@@ -226,9 +226,27 @@ def main() -> int:
     if not args.only:
         del runs, _keep
         torch.cuda.empty_cache()
-        fcases = configs.fused_cases()
+        fcases = configs.fused_cases() + configs.elementary_cases()
         fruns, _fkeep = _device_cases(fcases)
+
+        def timed(f, reps=12):
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+            for a, b in evs:
+                a.record(); f(); b.record()
+            torch.cuda.synchronize()
+            t = sorted(a.elapsed_time(b) for a, b in evs[2:])
+            return t[len(t) // 2] * 1e3
+
         for (c, fn, out) in fruns:
+            if c.kind != "binary_reduce":
+                us = timed(fn)
+                plan = _plan_kernel(c)
+                next_ops.append({"case": c.name, "op": c.op, "kernel": plan["kernel"], "fused": False,
+                                 "passes": plan["passes"], "logical_bytes": c.logical_bytes, "us": us,
+                                 "gbs": c.logical_bytes / (us * 1e-6) / 1e9,
+                                 "frac_of_peak": c.logical_bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                                 "two_calls_us": None})
+                continue
             ins = [ocn.Tensor.on_storage(_fkeep[id(v.storage)], v.dtype, v.sizes, v.strides, v.offset) for v in c.inputs]
             shape = tuple(c.inputs[0].sizes)
             mid_t = torch.empty(int(np.prod(shape)) * ocn.dtype_size(c.mid_dtype), dtype=torch.uint8, device="cuda:0")
@@ -245,13 +263,6 @@ def main() -> int:
                 ocn.binary(c.op, ins[0], ins[1], mid)
                 ocn.reduce(c.red_op, mid, list(c.axes), out, workspace=ws2)
 
-            def timed(f, reps=12):
-                evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
-                for a, b in evs:
-                    a.record(); f(); b.record()
-                torch.cuda.synchronize()
-                t = sorted(a.elapsed_time(b) for a, b in evs[2:])
-                return t[len(t) // 2] * 1e3
             us = timed(fn)
             us2 = timed(two_calls)
             plan = _plan_kernel(c)

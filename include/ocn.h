@@ -64,7 +64,13 @@ typedef enum { /* section 3.2: basic arithmetic; complex types add conjugation (
   OCN_U_CONJ,      /* complex conjugate; identity on real types                */
   OCN_U_LNOT,      /* !(a != 0)                                                */
   OCN_U_BNOT,      /* ~a for integers, ! for bool                              */
-  OCN_U_SQRT,      /* correctly rounded square root, real floating types       */
+  OCN_U_SQRT,      /* square root: correctly rounded on real floating types;
+                      principal branch on complex types (a few ulp, as below) */
+  OCN_U_SIN,       /* elementary functions on real and complex floating types  */
+  OCN_U_COS,       /* (section 3.2: trigonometric operations): evaluated in    */
+  OCN_U_TAN,       /* single precision for half and float types, in double     */
+  OCN_U_EXP,       /* otherwise; accurate to a few units in the last place,    */
+  OCN_U_LOG,       /* not bit-reproducible against another math library        */
   OCN_NUM_UNARY
 } ocn_unary_op;
 

@@ -18,7 +18,8 @@ static_assert(B_ADD == OCN_B_ADD && B_MAX == OCN_B_MAX && B_BAND == OCN_B_BAND &
               B_EQ == OCN_B_EQ && B_GE == OCN_B_GE && B_ABSGT == OCN_B_ABSGT && B_COUNT == OCN_NUM_BINARY,
               "binary op numbering");
 static_assert(U_IDENT == OCN_U_IDENT && U_NEG == OCN_U_NEG && U_ABS == OCN_U_ABS && U_CONJ == OCN_U_CONJ &&
-              U_LNOT == OCN_U_LNOT && U_BNOT == OCN_U_BNOT && U_SQRT == OCN_U_SQRT && U_COUNT == OCN_NUM_UNARY,
+              U_LNOT == OCN_U_LNOT && U_BNOT == OCN_U_BNOT && U_SQRT == OCN_U_SQRT && U_SIN == OCN_U_SIN &&
+              U_LOG == OCN_U_LOG && U_COUNT == OCN_NUM_UNARY,
               "unary op numbering");
 static_assert(R_SUM == OCN_R_SUM && R_PROD == OCN_R_PROD && R_MIN == OCN_R_MIN && R_MAX == OCN_R_MAX &&
               R_ANY == OCN_R_ANY && R_ALL == OCN_R_ALL && R_COUNT == OCN_NUM_REDUCE, "reduce op numbering");

@@ -345,6 +345,94 @@ template <int OP, int T> OCN_DEV reg_t<binary_result_dtype(OP, T)> apply_binary(
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// elementary functions (section 3.2: trigonometric operations on real and complex floating
+// types).  Real arguments use the device math library; complex ones are composed from it by
+// the textbook identities, written so that no intermediate overflows before the result does.
+// ---------------------------------------------------------------------------------------
+
+template <int OP, class F> OCN_DEV F elementary_real(F x) {
+  if constexpr (sizeof(F) == 4) {
+    if constexpr (OP == U_SIN) return sinf(x);
+    else if constexpr (OP == U_COS) return cosf(x);
+    else if constexpr (OP == U_TAN) return tanf(x);
+    else if constexpr (OP == U_EXP) return expf(x);
+    else return logf(x);
+  } else {
+    if constexpr (OP == U_SIN) return sin(x);
+    else if constexpr (OP == U_COS) return cos(x);
+    else if constexpr (OP == U_TAN) return tan(x);
+    else if constexpr (OP == U_EXP) return exp(x);
+    else return log(x);
+  }
+}
+
+template <class F> OCN_DEV void sincos_any(F x, F &s, F &c) {
+  if constexpr (sizeof(F) == 4) { s = sinf(x); c = cosf(x); }
+  else { s = sin(x); c = cos(x); }
+}
+template <class F> OCN_DEV F exp_any(F x) { if constexpr (sizeof(F) == 4) return expf(x); else return exp(x); }
+template <class F> OCN_DEV F log_any(F x) { if constexpr (sizeof(F) == 4) return logf(x); else return log(x); }
+template <class F> OCN_DEV F log1p_any(F x) { if constexpr (sizeof(F) == 4) return log1pf(x); else return log1p(x); }
+template <class F> OCN_DEV F sqrt_any(F x) { if constexpr (sizeof(F) == 4) return __builtin_sqrtf(x); else return __builtin_sqrt(x); }
+template <class F> OCN_DEV F hypot_any(F x, F y) { if constexpr (sizeof(F) == 4) return hypotf(x, y); else return hypot(x, y); }
+template <class F> OCN_DEV F atan2_any(F y, F x) { if constexpr (sizeof(F) == 4) return atan2f(y, x); else return atan2(y, x); }
+template <class F> OCN_DEV F sinh_any(F x) { if constexpr (sizeof(F) == 4) return sinhf(x); else return sinh(x); }
+template <class F> OCN_DEV F cosh_any(F x) { if constexpr (sizeof(F) == 4) return coshf(x); else return cosh(x); }
+template <class F> OCN_DEV F abs_any(F x) { if constexpr (sizeof(F) == 4) return __builtin_fabsf(x); else return __builtin_fabs(x); }
+template <class F> OCN_DEV F copysign_any(F x, F y) { if constexpr (sizeof(F) == 4) return __builtin_copysignf(x, y); else return __builtin_copysign(x, y); }
+
+template <int OP, class F> OCN_DEV void elementary_complex(F x, F y, F &re, F &im) {
+  if constexpr (OP == U_SIN) {          // sin x cosh y + i cos x sinh y
+    F s, c;
+    sincos_any(x, s, c);
+    re = s * cosh_any(y);
+    im = c * sinh_any(y);
+  } else if constexpr (OP == U_COS) {   // cos x cosh y - i sin x sinh y
+    F s, c;
+    sincos_any(x, s, c);
+    re = c * cosh_any(y);
+    im = -(s * sinh_any(y));
+  } else if constexpr (OP == U_TAN) {   // (sin x cos x + i sinh y cosh y) / (cos^2 x + sinh^2 y)
+    const F big = sizeof(F) == 4 ? (F)20 : (F)40;
+    F s, c;
+    sincos_any(x, s, c);
+    if (abs_any(y) > big) {              // sinh^2 y swamps cos^2 x (and would overflow): tan -> +-i
+      re = 4 * s * c * exp_any(-2 * abs_any(y));
+      im = copysign_any((F)1, y);
+    } else {
+      const F sh = sinh_any(y), ch = cosh_any(y);
+      const F den = c * c + sh * sh;     // a sum of squares: no cancellation
+      re = s * c / den;
+      im = sh * ch / den;
+    }
+  } else if constexpr (OP == U_EXP) {   // e^x (cos y + i sin y)
+    F s, c;
+    sincos_any(y, s, c);
+    const F e = exp_any(x);
+    re = e * c;
+    im = e * s;
+  } else if constexpr (OP == U_LOG) {   // log |z| + i arg z
+    const F h = hypot_any(x, y);
+    if (h > (F)0.5 && h < (F)2) {        // near the unit circle: log |z| = log1p(|z|^2 - 1) / 2 without cancellation
+      const F ax = abs_any(x);
+      re = (F)0.5 * log1p_any((ax - 1) * (ax + 1) + y * y);
+    } else {
+      re = log_any(h);
+    }
+    im = atan2_any(y, x);
+  } else {                              // U_SQRT, principal branch, signed zeros as in C
+    if (x == 0 && y == 0) {
+      re = 0;
+      im = y;
+    } else {
+      const F t = sqrt_any((abs_any(x) + hypot_any(x, y)) * (F)0.5);
+      if (x >= 0) { re = t; im = y / (2 * t); }
+      else { re = abs_any(y) / (2 * t); im = copysign_any(t, y); }
+    }
+  }
+}
+
 template <int OP, int T> OCN_DEV reg_t<unary_result_dtype(OP, T)> apply_unary(reg_t<T> a) {
   constexpr int k = dt_kind(T);
   using R = reg_t<T>;
@@ -367,10 +455,19 @@ template <int OP, int T> OCN_DEV reg_t<unary_result_dtype(OP, T)> apply_unary(re
   } else if constexpr (OP == U_BNOT) {
     if constexpr (k == K_BOOL) return !a;
     else return (R)~a;
-  } else {  // U_SQRT, real types
+  } else if constexpr (OP == U_SQRT && k == K_REAL) {
     if constexpr (T == DT_F16) return hreg{__builtin_sqrtf(a.v)};
     else if constexpr (T == DT_F32) return __builtin_sqrtf(a);
     else return __builtin_sqrt(a);
+  } else if constexpr (k == K_REAL) {  // elementary functions: single precision for half and float
+    if constexpr (T == DT_F16) return hreg{elementary_real<OP, float>(a.v)};
+    else if constexpr (T == DT_F32) return elementary_real<OP, float>(a);
+    else return elementary_real<OP, double>(a);
+  } else {  // complex elementary functions and the complex square root
+    using F = decltype(a.re);
+    F re, im;
+    elementary_complex<OP, F>(a.re, a.im, re, im);
+    return R{re, im};
   }
 }
 

@@ -32,7 +32,13 @@ template <int I> void register_unary() {
 }
 
 template <int... I> void register_all_binary(std::integer_sequence<int, I...>) { (register_binary<I>(), ...); }
-template <int... I> void register_all_unary(std::integer_sequence<int, I...>) { (register_unary<I>(), ...); }
+// two levels (per operation, then per type pair) keep each fold expression short
+template <int OP, int... I> void register_unary_op(std::integer_sequence<int, I...>) {
+  (register_unary<OP * DT_COUNT * DT_COUNT + I>(), ...);
+}
+template <int... OP> void register_all_unary(std::integer_sequence<int, OP...>) {
+  (register_unary_op<OP>(std::make_integer_sequence<int, DT_COUNT * DT_COUNT>{}), ...);
+}
 
 }  // namespace
 
@@ -40,7 +46,7 @@ template <int... I> void register_all_unary(std::integer_sequence<int, I...>) { 
 #define OCN_CAT(a, b) OCN_CAT2(a, b)
 void OCN_CAT(register_ew_slice_, OCN_SLICE)() {
   register_all_binary(std::make_integer_sequence<int, B_COUNT * DT_COUNT>{});
-  register_all_unary(std::make_integer_sequence<int, U_COUNT * DT_COUNT * DT_COUNT>{});
+  register_all_unary(std::make_integer_sequence<int, U_COUNT>{});
 }
 
 }  // namespace ocn

@@ -42,6 +42,16 @@ def _run_case(c):
     want = c.out.storage
     if c.compare == "exact":
         assert H.storages_equal(c.out.dtype, got, want), c.name + ": " + H.first_mismatch(c.out.dtype, got, want)
+    elif c.compare == "ulp":
+        # elementary functions: within rel_bound units in the last place of the oracle value
+        cplx = c.out.dtype == "cfloat"
+        g = got.view(np.complex64 if cplx else np.float32)
+        w = want.view(np.complex64 if cplx else np.float32)
+        mag = np.abs(w).astype(np.float32)
+        ulp = np.spacing(mag).astype(np.float64)
+        for part in ((np.real, np.imag) if cplx else (np.asarray,)):
+            err = np.abs(part(g).astype(np.float64) - part(w).astype(np.float64))
+            assert np.all(err <= c.rel_bound * ulp), (c.name, float((err / ulp).max()))
     else:
         # |gpu - oracle| <= rel_bound * sum|x| per output
         ft = _FLOAT[c.out.dtype]
@@ -65,7 +75,7 @@ def test_small_cases(idx):
     _run_case(c)
 
 
-@pytest.mark.parametrize("which", ["C1", "C1x8", "C2", "C3", "C4", "C5", "C5b", "F"])
+@pytest.mark.parametrize("which", ["C1", "C1x8", "C2", "C3", "C4", "C5", "C5b", "F", "E"])
 def test_full_size_cases(which):
     if which == "C1":
         cases = [configs.config1(1)]
@@ -81,8 +91,10 @@ def test_full_size_cases(which):
         cases = configs.config5()
     elif which == "C5b":
         cases = configs.config5(reading="R2")
-    else:
+    elif which == "F":
         cases = configs.fused_cases()
+    else:
+        cases = configs.elementary_cases()
     for c in cases:
         print("case", c.name, c.op, [v.sizes for v in c.inputs], flush=True)
         _run_case(c)

@@ -1,0 +1,129 @@
+"""GPU parity of the elementary functions (sin, cos, tan, exp, log, complex sqrt) against the
+oracle, in the tolerance class these operations have: a few units in the last place of the
+output type (real: |gpu - oracle| <= K ulp of the oracle value; complex: each component within
+K ulp of the magnitude of the oracle value), special values exactly."""
+import numpy as np
+import pytest
+
+import gpu_harness as H
+from workloads.values import rng_for
+from workloads.views import View
+
+pytestmark = pytest.mark.gpu
+
+REAL = {"half": np.float16, "float": np.float32, "double": np.float64}
+CPLX = {"chalf": np.float16, "cfloat": np.float32, "cdouble": np.float64}
+K_ULP = {"half": 1, "float": 4, "double": 4, "chalf": 2, "cfloat": 8, "cdouble": 8}
+
+
+def _run(op, a: View, out: View):
+    import paper_1810_08723_amd as ocn
+    from oracle import binding as O
+    dv = H.DeviceViews()
+    ta, to = dv.tensor(a), dv.tensor(out)
+    ocn.unary(op, ta, to)
+    dv.torch.cuda.synchronize()
+    got_storage = dv.download(out).copy()
+    O.unary(op, a, out)
+    got = View(got_storage, out.dtype, out.sizes, out.strides, out.offset).to_numpy()
+    return got, out.to_numpy()
+
+
+def _inputs(rng, op, n, comp):
+    if op == "log":
+        x = np.exp(rng.uniform(-8, 8, n))
+    elif op == "exp":
+        x = rng.uniform(-9, 9, n)
+    else:
+        x = rng.uniform(-30, 30, n)
+    return x.astype(comp)
+
+
+def _check_real(got, want, dt):
+    comp = REAL[dt]
+    g, w = got.astype(np.float64), want.astype(np.float64)
+    assert np.array_equal(np.isnan(g), np.isnan(w))
+    fin = np.isfinite(w)
+    assert np.array_equal(g[~fin & ~np.isnan(w)], w[~fin & ~np.isnan(w)])           # infinities exactly
+    ulp = np.spacing(np.abs(want[fin]).astype(comp)).astype(np.float64)
+    err = np.abs(g[fin] - w[fin])
+    assert np.all(err <= K_ULP[dt] * ulp), (dt, float((err / ulp).max()))
+
+
+def _check_complex(got, want, dt):
+    comp = CPLX[dt]
+    mag = np.abs(want.astype(np.complex128))
+    fin = np.isfinite(mag)
+    ulp = np.spacing(mag[fin].astype(comp)).astype(np.float64)
+    for part in (np.real, np.imag):
+        err = np.abs(part(got).astype(np.float64)[fin] - part(want).astype(np.float64)[fin])
+        assert np.all(err <= K_ULP[dt] * ulp), (dt, float((err / ulp).max()))
+
+
+@pytest.mark.parametrize("dt", tuple(REAL))
+@pytest.mark.parametrize("op", ("sin", "cos", "tan", "exp", "log"))
+def test_real_elementary_functions(op, dt):
+    rng = rng_for(16000)
+    comp = REAL[dt]
+    x = _inputs(rng, op, 40000, comp)
+    if op == "tan":      # keep away from the poles, where one ulp of the argument moves the value by many
+        x = x[np.abs(np.cos(x.astype(np.float64))) > 0.05]
+    a = View.from_numpy(x)
+    got, want = _run(op, a, View.empty(dt, a.sizes))
+    _check_real(got, want, dt)
+    # a strided, transposed view goes through the tiled kernel: same values
+    m = View.from_numpy(x[: 128 * 96].reshape(128, 96).copy()).permute(1, 0)
+    got, want = _run(op, m, View.empty(dt, m.sizes))
+    _check_real(got, want, dt)
+
+
+def _complex_view(z, dt):
+    if dt == "chalf":
+        pairs = np.stack([z.real, z.imag], axis=-1).astype(np.float16)
+        return View(np.ascontiguousarray(pairs).view(np.uint8).reshape(-1).copy(), "chalf", z.shape,
+                    tuple(4 * s // z.itemsize for s in z.strides) if z.ndim else (), 0)
+    return View.from_numpy(z.astype({"cfloat": np.complex64, "cdouble": np.complex128}[dt]))
+
+
+@pytest.mark.parametrize("dt", ("cfloat", "cdouble"))
+@pytest.mark.parametrize("op", ("sin", "cos", "tan", "exp", "log", "sqrt"))
+def test_complex_elementary_functions(op, dt):
+    rng = rng_for(16100)
+    n = 30000
+    z = rng.uniform(-5, 5, n) + 1j * rng.uniform(-5, 5, n)
+    if op == "tan":      # away from the poles on the real axis, where the value is ill-conditioned
+        z = z[np.abs(np.cos(z)) > 0.1]
+    a = _complex_view(z, dt)
+    got, want = _run(op, a, View.empty(dt, a.sizes))
+    _check_complex(got, want, dt)
+
+
+def test_special_values_and_branch_cuts():
+    x = View.from_numpy(np.array([0.0, -0.0, np.inf, -np.inf, np.nan, 1.0, -1.0], dtype=np.float32))
+    for op in ("sin", "cos", "exp", "log"):
+        got, want = _run(op, x, View.empty("float", x.sizes))
+        assert np.array_equal(np.isnan(got), np.isnan(want)), op
+        fin = ~np.isnan(want)
+        assert np.allclose(got[fin], want[fin], rtol=1e-6, atol=0), (op, got, want)
+        assert np.array_equal(np.signbit(got[fin]), np.signbit(want[fin])), op
+    z = View.from_numpy(np.array([complex(-1, 0.0), complex(-1, -0.0), complex(-4, 0.0), 0j, complex(0.0, -0.0),
+                                  1j, -1j, complex(3, 4)], dtype=np.complex64))
+    got, want = _run("sqrt", z, View.empty("cfloat", z.sizes))
+    assert np.allclose(got, want, rtol=1e-6, atol=0) and np.array_equal(np.signbit(got.imag), np.signbit(want.imag))
+    got, want = _run("log", z.slice(0, 0, 3, 1), View.empty("cfloat", (3,)))
+    assert np.allclose(got, want, rtol=1e-6, atol=1e-7) and np.array_equal(np.signbit(got.imag), np.signbit(want.imag))
+
+
+def test_mixed_types_and_errors():
+    import paper_1810_08723_amd as ocn
+    rng = rng_for(16200)
+    # integer input, floating output: converted on load, evaluated in the output type (generic-dtype kernel)
+    i = View.from_numpy(rng.integers(-20, 20, size=(500,), dtype=np.int32))
+    got, want = _run("exp", i, View.empty("double", (500,)))
+    _check_real(got, want, "double")
+    got, want = _run("sin", View.from_numpy(rng.uniform(-3, 3, 300).astype(np.float64)), View.empty("float", (300,)))
+    _check_real(got, want, "float")
+    dv = H.DeviceViews()
+    with pytest.raises(ocn.OcnError) as e:       # no elementary functions in integer arithmetic
+        ocn.unary("sin", dv.tensor(i), dv.tensor(View.empty("int32", (500,))))
+    assert e.value.code == ocn.binding.ERR["DTYPE"]

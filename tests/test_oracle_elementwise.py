@@ -236,8 +236,9 @@ def test_unsupported_combinations_are_rejected():
         assert e.value.code == O.ERR_DTYPE
     with pytest.raises(O.OracleError):
         O.unary("abs", c, c.fresh_copy())
+    i = View.from_numpy(np.zeros(3, dtype=np.int32))
     with pytest.raises(O.OracleError):
-        O.unary("sqrt", c, c.fresh_copy())
+        O.unary("sqrt", i, i.fresh_copy())
 
 
 def test_strict_types_flag():

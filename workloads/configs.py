@@ -33,7 +33,8 @@ class Case:
     out: View
     axes: Tuple[int, ...] = ()
     logical_bytes: int = 0
-    compare: str = "exact"         # "exact" | "sum" (bounded error relative to sum |x|)
+    compare: str = "exact"         # "exact" | "sum" (bounded error relative to sum |x|) | "ulp" (rel_bound units
+                                   # in the last place of the oracle value; complex: of its magnitude)
     rel_bound: float = 0.0         # for compare == "sum"
     note: str = ""
     red_op: str = ""               # kind == "binary_reduce": reduce(red_op, binary(op, a, b) as mid_dtype, axes)
@@ -183,6 +184,22 @@ def fused_cases(rows: int = 16384, cols: int = 4096, n_flat: int = 1 << 26) -> L
              note="row-wise inner products", red_op="sum", mid_dtype="float"),
         Case("F2", "binary_reduce", "gt", [x, y], View.empty("int64", ()), axes=(0,),
              logical_bytes=8 * n_flat + 8, note="count of a > b", red_op="sum", mid_dtype="bool"),
+    ]
+
+
+def elementary_cases(n_flat: int = 1 << 26, n_cplx: int = 1 << 24) -> List[Case]:
+    """Elementary functions: exp over a flat fp32 vector uniform in [-9, 9), sin over a complex64
+    vector with parts uniform in [-5, 5).  Compared within a few units in the last place."""
+    x = (rng_for(_seed(6, 0)).random(n_flat, dtype=np.float32) * np.float32(18) - np.float32(9)).astype(np.float32)
+    rng = rng_for(_seed(6, 1))
+    z = np.empty(n_cplx, dtype=np.complex64)
+    z.real = rng.random(n_cplx, dtype=np.float32) * np.float32(10) - np.float32(5)
+    z.imag = rng.random(n_cplx, dtype=np.float32) * np.float32(10) - np.float32(5)
+    return [
+        Case("E1", "unary", "exp", [View.from_numpy(x)], View.empty("float", (n_flat,)),
+             logical_bytes=8 * n_flat, compare="ulp", rel_bound=4, note="exp, fp32"),
+        Case("E2", "unary", "sin", [View.from_numpy(z)], View.empty("cfloat", (n_cplx,)),
+             logical_bytes=16 * n_cplx, compare="ulp", rel_bound=8, note="complex sine"),
     ]
 
 
