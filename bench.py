@@ -271,6 +271,32 @@ def main() -> int:
                              "gbs": c.logical_bytes / (us * 1e-6) / 1e9,
                              "frac_of_peak": c.logical_bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS,
                              "two_calls_us": us2})
+    # boolean-mask selection a[mask] over 2^26 fp32 values with half of them selected: the mask
+    # is compacted to offsets (three launches), then the elements are gathered
+    if not args.only:
+        n = 1 << 26
+        rng = np.random.default_rng(configs.BASE_SEED + 70)
+        mask_h = rng.random(n) < 0.5
+        a_d = torch.from_numpy(rng.standard_normal(n, dtype=np.float32)).to("cuda:0")
+        m_d = torch.from_numpy(mask_h.view(np.uint8)).to("cuda:0")
+        count_h = int(mask_h.sum())
+        offs_d = torch.empty(count_h, dtype=torch.int64, device="cuda:0")
+        out_d = torch.empty(count_h, dtype=torch.float32, device="cuda:0")
+        cnt_d = torch.zeros(1, dtype=torch.int64, device="cuda:0")
+        tm = ocn.Tensor(m_d.data_ptr(), "bool", (n,), (1,), 0, 0, m_d)
+        ta = ocn.Tensor(a_d.data_ptr(), "float", (), (), 0, 0, a_d)
+        to = ocn.Tensor(out_d.data_ptr(), "float", (count_h,), (4,), 0, 0, out_d)
+        ws = torch.empty(8 * (n // 4096 + 2), dtype=torch.uint8, device="cuda:0")
+        f_bind = lambda: ocn.mask_offsets(tm, [4], offs_d, cnt_d, workspace=ws)
+        f_gather = lambda: ocn.gather(ta, offs_d, 0, 4 * (n - 1), to)
+        us_b, us_g = timed(f_bind), timed(f_gather)
+        assert int(cnt_d.cpu()[0]) == count_h
+        for name, us, lb, note in (("G1", us_b, n + 8 * count_h, "mask -> offsets (count, scan, write)"),
+                                   ("G2", us_g, 8 * count_h + 4 * n + 4 * count_h,
+                                    "gather by offsets (every line of the source is touched)")):
+            next_ops.append({"case": name, "op": note, "kernel": "index", "fused": False, "passes": 3 if name == "G1" else 1,
+                             "logical_bytes": lb, "us": us, "gbs": lb / (us * 1e-6) / 1e9,
+                             "frac_of_peak": lb / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, "two_calls_us": None})
     device_ms = sum(p["avg_us"] for p in per_op) / 1e3
     dom = max(per_op, key=lambda p: p["avg_us"])
     traffic = _measured_traffic()

@@ -182,6 +182,49 @@ size_t ocn_binary_reduce_workspace_bytes(int ew_op, int red_op, const ocn_tensor
                                          const ocn_tensor *b, const int32_t *axes, int32_t naxes,
                                          const ocn_tensor *out, int32_t mid_dtype);
 
+/*
+ * Index binding, gather and scatter (section 3.2.2: index arrays are checked for validity and
+ * negative indices converted; boolean masks are counted and converted to explicit indices;
+ * bound to a tensor's strides both become relative offsets into its data, after which indexed
+ * elements are copied out of, or into, the tensor).  Offsets are int64 byte offsets relative
+ * to element (0, ..., 0) of the tensor being indexed, in DEVICE memory.
+ *
+ * ocn_index_offsets: index and offsets are OCN_INT64 tensors of equal shape (any strides).
+ * offsets[k] = i * stride_bytes with i = index[k], or index[k] + dim_size when negative;
+ * indices outside [-dim_size, dim_size) give offset 0 and are counted into *invalid_count
+ * (DEVICE int64, overwritten).
+ */
+int ocn_index_offsets(const ocn_tensor *index, int64_t dim_size, int64_t stride_bytes,
+                      const ocn_tensor *offsets, void *invalid_count, void *stream);
+
+/*
+ * ocn_mask_offsets: mask is an OCN_BOOL tensor (any strides, fewer than 2^31 elements);
+ * target_strides (HOST, mask->ndim entries) are the byte strides of the tensor the mask will
+ * index.  Writes the offsets sum_d i_d * target_strides[d] of the selected positions, in
+ * row-major order of the mask's dimensions, to offsets[0 .. min(count, capacity)) and the
+ * number selected to *count (DEVICE int64).  workspace: DEVICE scratch of
+ * ocn_mask_offsets_workspace_bytes(mask) bytes, 8-byte aligned.  Three kernel launches.
+ */
+size_t ocn_mask_offsets_workspace_bytes(const ocn_tensor *mask);
+int ocn_mask_offsets(const ocn_tensor *mask, const int64_t *target_strides, void *offsets,
+                     int64_t capacity, void *count, void *workspace, size_t workspace_bytes,
+                     void *stream);
+
+/*
+ * ocn_gather:  out[j, i...] = the element of the indexed tensor at offsets[j] + (inner offset
+ * of i...), for j < n.  a_inner describes ONE indexed sub-tensor: its base + offset is
+ * element (0, ..., 0) of the indexed tensor, its sizes and strides those of the dimensions that
+ * are not indexed (ndim 0 for element-wise selection).  out has shape [n, a_inner sizes...]
+ * and the same dtype.  An offset outside [lo, hi] is not followed: that row of out keeps its
+ * old contents (pass the smallest and largest offset that stays inside the storage).
+ * ocn_scatter: the reverse copy, src[j, i...] into the indexed tensor; offsets that repeat
+ * leave one of the written values, which one is not defined.
+ */
+int ocn_gather(const ocn_tensor *a_inner, const void *offsets, int64_t n, int64_t lo, int64_t hi,
+               const ocn_tensor *out, void *stream);
+int ocn_scatter(const ocn_tensor *src, const void *offsets, int64_t n, int64_t lo, int64_t hi,
+                const ocn_tensor *out_inner, void *stream);
+
 /* Bytes of workspace ocn_reduce needs for these arguments (0 when it runs in one pass).
  * Returns 0 as well when the arguments are invalid; ocn_reduce then reports the error. */
 size_t ocn_reduce_workspace_bytes(int op, const ocn_tensor *a, const int32_t *axes,

@@ -37,7 +37,9 @@ KERNELS = ("none", "ew_rows", "ew_tiled", "ew_generic", "red_rows", "red_cols", 
 EXPORTS = ("ocn_unary", "ocn_binary", "ocn_cast_copy", "ocn_reduce", "ocn_reduce_workspace_bytes",
            "ocn_promote", "ocn_dtype_size", "ocn_error_string", "ocn_last_hip_error",
            "ocn_plan_unary", "ocn_plan_binary", "ocn_plan_reduce",
-           "ocn_binary_reduce", "ocn_binary_reduce_workspace_bytes", "ocn_plan_binary_reduce")
+           "ocn_binary_reduce", "ocn_binary_reduce_workspace_bytes", "ocn_plan_binary_reduce",
+           "ocn_index_offsets", "ocn_mask_offsets", "ocn_mask_offsets_workspace_bytes", "ocn_gather",
+           "ocn_scatter")
 
 
 class OcnTensor(C.Structure):
@@ -101,6 +103,13 @@ def lib() -> C.CDLL:
         L.ocn_binary_reduce_workspace_bytes.argtypes = [C.c_int, C.c_int, T, T, A, C.c_int32, T, C.c_int32]
         L.ocn_binary_reduce_workspace_bytes.restype = C.c_size_t
         L.ocn_plan_binary_reduce.argtypes = [C.c_int, C.c_int, T, T, A, C.c_int32, T, C.c_int32, I]
+        L.ocn_index_offsets.argtypes = [T, C.c_int64, C.c_int64, T, C.c_void_p, C.c_void_p]
+        L.ocn_mask_offsets_workspace_bytes.argtypes = [T]
+        L.ocn_mask_offsets_workspace_bytes.restype = C.c_size_t
+        L.ocn_mask_offsets.argtypes = [T, C.POINTER(C.c_int64), C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
+                                       C.c_size_t, C.c_void_p]
+        L.ocn_gather.argtypes = [T, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, T, C.c_void_p]
+        L.ocn_scatter.argtypes = [T, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, T, C.c_void_p]
         _lib = L
     return _lib
 
@@ -211,6 +220,36 @@ def binary_reduce(ew_op: str, red_op: str, a: Tensor, b: Tensor, axes: Sequence[
     _check(lib().ocn_binary_reduce(BINARY_CODE[ew_op], REDUCE_CODE[red_op], C.byref(a.desc()), C.byref(b.desc()),
                                    ax, n, C.byref(out.desc()), DTYPE_CODE[mid_dtype], ws_ptr, ws_bytes,
                                    _stream(stream)))
+
+
+def index_offsets(index: Tensor, dim_size: int, stride_bytes: int, offsets: Tensor, invalid_count, stream=None) -> None:
+    """`invalid_count`: a 1-element int64 torch tensor on the device (overwritten)."""
+    _check(lib().ocn_index_offsets(C.byref(index.desc()), dim_size, stride_bytes, C.byref(offsets.desc()),
+                                   invalid_count.data_ptr(), _stream(stream)))
+
+
+def mask_offsets(mask: Tensor, target_strides: Sequence[int], offsets, count, workspace=None, stream=None) -> None:
+    """`offsets`: int64 torch tensor on the device (its length is the capacity); `count`: 1-element
+    int64 torch tensor; `workspace`: uint8 torch tensor or None to allocate one through torch."""
+    need = int(lib().ocn_mask_offsets_workspace_bytes(C.byref(mask.desc())))
+    if workspace is None:
+        import torch
+        workspace = torch.empty(max(need, 8), dtype=torch.uint8, device=f"cuda:{mask.device}")
+    ts = (C.c_int64 * max(len(target_strides), 1))(*target_strides)
+    _check(lib().ocn_mask_offsets(C.byref(mask.desc()), ts, offsets.data_ptr() if offsets.numel() else None,
+                                  offsets.numel(), count.data_ptr(), workspace.data_ptr(), workspace.numel(),
+                                  _stream(stream)))
+
+
+def gather(a_inner: Tensor, offsets, lo: int, hi: int, out: Tensor, stream=None) -> None:
+    """`offsets`: int64 torch tensor on the device, one entry per row of `out`."""
+    _check(lib().ocn_gather(C.byref(a_inner.desc()), offsets.data_ptr() if offsets.numel() else None,
+                            offsets.numel(), lo, hi, C.byref(out.desc()), _stream(stream)))
+
+
+def scatter(src: Tensor, offsets, lo: int, hi: int, out_inner: Tensor, stream=None) -> None:
+    _check(lib().ocn_scatter(C.byref(src.desc()), offsets.data_ptr() if offsets.numel() else None,
+                             offsets.numel(), lo, hi, C.byref(out_inner.desc()), _stream(stream)))
 
 
 def promote(a: str, b: str) -> str:

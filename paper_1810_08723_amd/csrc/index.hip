@@ -1,0 +1,472 @@
+// Index binding, gather and scatter for gfx950 (section 3.2.2 of the paper: index arrays are
+// checked and negative indices converted; boolean masks are counted and converted to explicit
+// indices; bound to strides both become relative offsets into the data buffer, after which the
+// indexed elements are copied out of, or into, the tensor).
+//
+//   ocn_index_offsets  one lane per index: wrap, range check, multiply by the stride; invalid
+//                      indices are counted (one integer atomic per wavefront that saw any)
+//   ocn_mask_offsets   stream compaction in the mask's row-major order, three launches and no
+//                      waiting between workgroups: per-workgroup counts, an exclusive scan of
+//                      the counts by one workgroup, then every workgroup writes the offsets of
+//                      its selected elements behind its prefix (staged in LDS so that the
+//                      stores are coalesced).  Lanes own 16 consecutive mask bytes (one 128-bit
+//                      load when the mask is contiguous).
+//   ocn_gather/scatter one lane per copied element, rows of `inner` elements per offset; the
+//                      offset array is read coalesced, rows are walked along their fastest
+//                      dimension.  Offsets outside the stated range are skipped, never followed.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstring>
+
+#include "../../include/ocn.h"
+#include "dtypes.hpp"
+#include "planner.hpp"
+
+namespace ocn {
+namespace {
+
+constexpr int kMaskPerLane = 16;                       // mask elements per lane
+constexpr int kMaskChunk = kBlock * kMaskPerLane;      // per workgroup
+constexpr int kScanBlock = 1024;
+
+__device__ __forceinline__ uint32_t fdiv(uint32_t n, const FastDiv &f) { return (__umulhi(n, f.m) + n) >> f.s; }
+
+// ---------------------------------------------------------------------------------------
+// index arrays
+// ---------------------------------------------------------------------------------------
+
+struct IndexArgs {
+  const char *idx;
+  char *off;
+  int32_t ndim;
+  int64_t size[kMaxDims], si[kMaxDims], so[kMaxDims];  // row-major: last dim fastest
+  int64_t n, dim_size, stride;
+  unsigned long long *invalid;
+};
+
+__global__ void fill_u64_kernel(unsigned long long *p, unsigned long long v) { *p = v; }
+
+__global__ __launch_bounds__(kBlock) void index_offsets_kernel(const IndexArgs p) {
+  const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  bool bad = false;
+  if (e < p.n) {
+    int64_t rem = e, oi = 0, oo = 0;
+#pragma unroll
+    for (int d = kMaxDims - 1; d >= 0; --d) {
+      if (d < p.ndim) {
+        const int64_t q = rem / p.size[d];
+        const int64_t i = rem - q * p.size[d];
+        rem = q;
+        oi += i * p.si[d];
+        oo += i * p.so[d];
+      }
+    }
+    int64_t i = *reinterpret_cast<const int64_t *>(p.idx + oi);
+    if (i < 0) i += p.dim_size;
+    bad = i < 0 || i >= p.dim_size;
+    *reinterpret_cast<int64_t *>(p.off + oo) = bad ? 0 : i * p.stride;
+  }
+  const unsigned long long votes = __ballot(bad);
+  if (votes != 0 && (threadIdx.x & (kWave - 1)) == 0) atomicAdd(p.invalid, (unsigned long long)__popcll(votes));
+}
+
+// ---------------------------------------------------------------------------------------
+// boolean masks
+// ---------------------------------------------------------------------------------------
+
+struct MaskArgs {
+  const char *mask;
+  int32_t ndim;                       // canonical dims, row-major: last fastest
+  FastDiv div[kMaxDims];
+  int64_t sm[kMaxDims], st[kMaxDims]; // mask / target byte strides
+  uint32_t n;                         // mask elements (< 2^31)
+  int32_t contig;                     // the mask is one contiguous, 16-byte aligned run
+  int64_t *block_counts;              // [nblocks]; after the scan: exclusive prefixes
+  uint32_t nblocks;
+  int64_t *offsets;
+  int64_t capacity;
+  int64_t *count;
+};
+
+__device__ __forceinline__ void mask_decode(const MaskArgs &p, uint32_t e, int64_t &om, int64_t &ot) {
+  om = 0;
+  ot = 0;
+#pragma unroll
+  for (int d = kMaxDims - 1; d >= 0; --d) {
+    if (d < p.ndim) {
+      const uint32_t q = d == 0 ? 0u : fdiv(e, p.div[d]);
+      const uint32_t i = e - q * p.div[d].d;
+      e = q;
+      om += (int64_t)i * p.sm[d];
+      ot += (int64_t)i * p.st[d];
+    }
+  }
+}
+
+// bit k set: element e0 + k is selected
+__device__ __forceinline__ uint32_t mask_flags(const MaskArgs &p, uint32_t e0) {
+  uint32_t flags = 0;
+  if (e0 >= p.n) return 0;
+  if (p.contig && e0 + kMaskPerLane <= p.n) {
+    const uint4 v = *reinterpret_cast<const uint4 *>(p.mask + e0);
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int k = 0; k < kMaskPerLane; ++k)
+      if ((w[k >> 2] >> (8 * (k & 3))) & 0xffu) flags |= 1u << k;
+    return flags;
+  }
+#pragma unroll 4
+  for (int k = 0; k < kMaskPerLane; ++k) {
+    const uint32_t e = e0 + (uint32_t)k;
+    if (e < p.n) {
+      int64_t om, ot;
+      mask_decode(p, e, om, ot);
+      if (*reinterpret_cast<const uint8_t *>(p.mask + om) != 0) flags |= 1u << k;
+    }
+  }
+  return flags;
+}
+
+// exclusive prefix of `v` over the workgroup's lanes; total in `sum` (all lanes)
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *lds, uint32_t &sum) {
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  uint32_t inc = v;
+#pragma unroll
+  for (int d = 1; d < kWave; d <<= 1) {
+    const uint32_t up = (uint32_t)__shfl_up((int)inc, d, kWave);
+    if (lane >= d) inc += up;
+  }
+  if (lane == kWave - 1) lds[wave] = inc;
+  __syncthreads();
+  uint32_t before = 0, total = 0;
+#pragma unroll
+  for (int w = 0; w < kBlock / kWave; ++w) {
+    if (w < wave) before += lds[w];
+    total += lds[w];
+  }
+  sum = total;
+  return before + inc - v;
+}
+
+__global__ __launch_bounds__(kBlock) void mask_count_kernel(const MaskArgs p) {
+  __shared__ uint32_t lds[kBlock / kWave];
+  const uint32_t e0 = (blockIdx.x * kBlock + threadIdx.x) * kMaskPerLane;
+  const uint32_t c = (uint32_t)__popc(mask_flags(p, e0));
+  uint32_t sum;
+  (void)block_exclusive_scan(c, lds, sum);
+  if (threadIdx.x == 0) p.block_counts[blockIdx.x] = (int64_t)sum;
+}
+
+// one workgroup: block_counts[i] := sum of block_counts[0 .. i), *count := total
+__global__ __launch_bounds__(kScanBlock) void mask_scan_kernel(const MaskArgs p) {
+  __shared__ int64_t part[kScanBlock];
+  const uint32_t per = (p.nblocks + kScanBlock - 1) / kScanBlock;
+  const uint32_t lo = threadIdx.x * per, hi = lo + per < p.nblocks ? lo + per : p.nblocks;
+  int64_t s = 0;
+  for (uint32_t i = lo; i < hi; ++i) s += p.block_counts[i];
+  part[threadIdx.x] = s;
+  __syncthreads();
+  for (int d = 1; d < kScanBlock; d <<= 1) {   // Hillis-Steele over the 1024 partial sums
+    const int64_t add = (int)threadIdx.x >= d ? part[threadIdx.x - d] : 0;
+    __syncthreads();
+    part[threadIdx.x] += add;
+    __syncthreads();
+  }
+  int64_t run = part[threadIdx.x] - s;        // exclusive prefix of this lane's segment
+  for (uint32_t i = lo; i < hi; ++i) {
+    const int64_t c = p.block_counts[i];
+    p.block_counts[i] = run;
+    run += c;
+  }
+  if (threadIdx.x == kScanBlock - 1) *p.count = part[kScanBlock - 1];
+}
+
+__global__ __launch_bounds__(kBlock) void mask_write_kernel(const MaskArgs p) {
+  __shared__ uint32_t lds[kBlock / kWave];
+  __shared__ int64_t staged[kMaskChunk];     // this workgroup's offsets, in order
+  const uint32_t e0 = (blockIdx.x * kBlock + threadIdx.x) * kMaskPerLane;
+  const uint32_t flags = mask_flags(p, e0);
+  uint32_t sum;
+  uint32_t slot = block_exclusive_scan((uint32_t)__popc(flags), lds, sum);
+  uint32_t f = flags;
+  while (f) {
+    const int k = __ffs((int)f) - 1;
+    f &= f - 1;
+    int64_t om, ot;
+    mask_decode(p, e0 + (uint32_t)k, om, ot);
+    staged[slot++] = ot;
+  }
+  __syncthreads();
+  // coalesced copy of the staged offsets behind this workgroup's prefix
+  const int64_t base = p.block_counts[blockIdx.x];
+  for (uint32_t i = threadIdx.x; i < sum; i += kBlock)
+    if (base + i < p.capacity) p.offsets[base + i] = staged[i];
+}
+
+// ---------------------------------------------------------------------------------------
+// gather / scatter
+// ---------------------------------------------------------------------------------------
+
+struct GatherArgs {
+  const char *src;                    // gather: the indexed tensor; scatter: the rows
+  char *dst;
+  const int64_t *offsets;
+  int64_t n, lo, hi;
+  int32_t ndim;                       // canonical inner dims, last fastest
+  FastDiv div[kMaxDims];
+  int64_t ss[kMaxDims], sd[kMaxDims]; // inner byte strides on the source / destination side
+  int64_t row_stride;                 // bytes between rows on the side that is not indexed
+  uint32_t inner;                     // elements per row
+  FastDiv chunks_div;                 // workgroups per row
+};
+
+template <int ES> struct Bytes { unsigned char b[ES]; };
+template <> struct alignas(2) Bytes<2> { unsigned char b[2]; };
+template <> struct alignas(4) Bytes<4> { unsigned char b[4]; };
+template <> struct alignas(8) Bytes<8> { unsigned char b[8]; };
+template <> struct alignas(16) Bytes<16> { unsigned char b[16]; };
+
+// SCATTER = false: dst[j, i] = src[offsets[j] + i];  true: dst[offsets[j] + i] = src[j, i]
+template <int ES, bool SCATTER> __global__ __launch_bounds__(kBlock) void gather_kernel(const GatherArgs p) {
+  int64_t j;
+  uint32_t i;
+  if (p.inner == 1) {
+    j = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    i = 0;
+    if (j >= p.n) return;
+  } else {
+    const uint32_t row = fdiv(blockIdx.x, p.chunks_div);
+    j = row;
+    i = (blockIdx.x - row * p.chunks_div.d) * kBlock + threadIdx.x;
+    if (i >= p.inner) return;
+  }
+  const int64_t off = p.offsets[j];
+  if (off < p.lo || off > p.hi) return;
+  int64_t os = 0, od = 0;
+  uint32_t rem = i;
+#pragma unroll
+  for (int d = kMaxDims - 1; d >= 0; --d) {
+    if (d < p.ndim) {
+      const uint32_t q = d == 0 ? 0u : fdiv(rem, p.div[d]);
+      const uint32_t k = rem - q * p.div[d].d;
+      rem = q;
+      os += (int64_t)k * p.ss[d];
+      od += (int64_t)k * p.sd[d];
+    }
+  }
+  if (SCATTER) { os += j * p.row_stride; od += off; }
+  else { os += off; od += j * p.row_stride; }
+  *reinterpret_cast<Bytes<ES> *>(p.dst + od) = *reinterpret_cast<const Bytes<ES> *>(p.src + os);
+}
+
+thread_local int g_index_hip_error = 0;
+int done(hipError_t e) {
+  if (e == hipSuccess) return OCN_OK;
+  g_index_hip_error = (int)e;
+  return OCN_ERR_LAUNCH;
+}
+
+bool bad_tensor(const ocn_tensor *t) {
+  if (!t || t->ndim < 0 || t->ndim > kMaxDims || t->dtype < 0 || t->dtype >= DT_COUNT) return true;
+  for (int d = 0; d < t->ndim; ++d)
+    if (t->size[d] < 0) return true;
+  return false;
+}
+int64_t numel_of(const ocn_tensor *t) {
+  int64_t n = 1;
+  for (int d = 0; d < t->ndim; ++d) n *= t->size[d];
+  return n;
+}
+
+int plan_mask(const ocn_tensor *mask, const int64_t *target_strides, MaskArgs *m) {
+  if (bad_tensor(mask)) return mask ? OCN_ERR_SHAPE : OCN_ERR_NULLPTR;
+  if (mask->dtype != DT_BOOL) return OCN_ERR_DTYPE;
+  if (mask->ndim > 0 && !target_strides) return OCN_ERR_NULLPTR;
+  const int64_t n = numel_of(mask);
+  if (n >= ((int64_t)1 << 31)) return OCN_ERR_SHAPE;
+  std::memset(m, 0, sizeof *m);
+  m->n = (uint32_t)n;
+  m->mask = (const char *)mask->base + mask->offset;
+  // canonical dims in the mask's own (row-major) order: drop size 1, merge neighbours that both
+  // the mask and the target walk as one longer dim
+  int nd = 0;
+  int64_t size[kMaxDims];
+  for (int d = 0; d < mask->ndim; ++d) {
+    if (mask->size[d] == 1) continue;
+    const int64_t sz = mask->size[d], sm = mask->stride[d], st = target_strides[d];
+    if (nd > 0 && m->sm[nd - 1] == sm * sz && m->st[nd - 1] == st * sz) {
+      size[nd - 1] *= sz;
+      m->sm[nd - 1] = sm;
+      m->st[nd - 1] = st;
+    } else {
+      size[nd] = sz; m->sm[nd] = sm; m->st[nd] = st;
+      ++nd;
+    }
+  }
+  m->ndim = nd;
+  for (int d = 0; d < nd; ++d) m->div[d] = make_fastdiv((uint32_t)size[d]);
+  m->contig = (nd == 0 || (nd == 1 && m->sm[0] == 1)) && ((uintptr_t)m->mask % 16 == 0);
+  m->nblocks = (uint32_t)((n + kMaskChunk - 1) / kMaskChunk);
+  return OCN_OK;
+}
+
+}  // namespace
+}  // namespace ocn
+
+using namespace ocn;
+
+extern "C" {
+
+int ocn_index_offsets(const ocn_tensor *index, int64_t dim_size, int64_t stride_bytes, const ocn_tensor *offsets,
+                      void *invalid_count, void *stream) {
+  if (bad_tensor(index) || bad_tensor(offsets)) return (!index || !offsets) ? OCN_ERR_NULLPTR : OCN_ERR_SHAPE;
+  if (!invalid_count) return OCN_ERR_NULLPTR;
+  if (index->dtype != DT_I64 || offsets->dtype != DT_I64) return OCN_ERR_DTYPE;
+  if (index->ndim != offsets->ndim || dim_size < 0) return OCN_ERR_SHAPE;
+  if (index->device != offsets->device) return OCN_ERR_DEVICE;
+  IndexArgs a;
+  std::memset(&a, 0, sizeof a);
+  a.n = 1;
+  for (int d = 0; d < index->ndim; ++d) {
+    if (index->size[d] != offsets->size[d]) return OCN_ERR_SHAPE;
+    a.size[d] = index->size[d];
+    a.si[d] = index->stride[d];
+    a.so[d] = offsets->stride[d];
+    a.n *= index->size[d];
+  }
+  if (((intptr_t)index->base + index->offset) % 8 || ((intptr_t)offsets->base + offsets->offset) % 8) return OCN_ERR_ALIGN;
+  for (int d = 0; d < index->ndim; ++d)
+    if (index->size[d] > 1 && (a.si[d] % 8 || a.so[d] % 8)) return OCN_ERR_ALIGN;
+  a.ndim = index->ndim;
+  a.idx = (const char *)index->base + index->offset;
+  a.off = (char *)offsets->base + offsets->offset;
+  a.dim_size = dim_size;
+  a.stride = stride_bytes;
+  a.invalid = (unsigned long long *)invalid_count;
+  hipStream_t s = (hipStream_t)stream;
+  hipLaunchKernelGGL(fill_u64_kernel, dim3(1), dim3(1), 0, s, a.invalid, 0ull);
+  if (a.n > 0) {
+    if (!index->base || !offsets->base) return OCN_ERR_NULLPTR;
+    const int64_t grid = (a.n + kBlock - 1) / kBlock;
+    if (grid >= ((int64_t)1 << 31)) return OCN_ERR_SHAPE;
+    hipLaunchKernelGGL(index_offsets_kernel, dim3((unsigned)grid), dim3(kBlock), 0, s, a);
+  }
+  return done(hipGetLastError());
+}
+
+size_t ocn_mask_offsets_workspace_bytes(const ocn_tensor *mask) {
+  if (bad_tensor(mask)) return 0;
+  const int64_t n = numel_of(mask);
+  return (size_t)((n + kMaskChunk - 1) / kMaskChunk + 1) * sizeof(int64_t);
+}
+
+int ocn_mask_offsets(const ocn_tensor *mask, const int64_t *target_strides, void *offsets, int64_t capacity,
+                     void *count, void *workspace, size_t workspace_bytes, void *stream) {
+  MaskArgs m;
+  const int rc = plan_mask(mask, target_strides, &m);
+  if (rc != OCN_OK) return rc;
+  if (!count || capacity < 0 || (capacity > 0 && !offsets)) return OCN_ERR_NULLPTR;
+  if (((uintptr_t)offsets % 8) || ((uintptr_t)count % 8)) return OCN_ERR_ALIGN;
+  hipStream_t s = (hipStream_t)stream;
+  if (m.n == 0) {
+    hipLaunchKernelGGL(fill_u64_kernel, dim3(1), dim3(1), 0, s, (unsigned long long *)count, 0ull);
+    return done(hipGetLastError());
+  }
+  if (!mask->base) return OCN_ERR_NULLPTR;
+  if (!workspace || workspace_bytes < ocn_mask_offsets_workspace_bytes(mask)) return OCN_ERR_WORKSPACE;
+  if ((uintptr_t)workspace % 8) return OCN_ERR_ALIGN;
+  m.block_counts = (int64_t *)workspace;
+  m.offsets = (int64_t *)offsets;
+  m.capacity = capacity;
+  m.count = (int64_t *)count;
+  hipLaunchKernelGGL(mask_count_kernel, dim3(m.nblocks), dim3(kBlock), 0, s, m);
+  hipLaunchKernelGGL(mask_scan_kernel, dim3(1), dim3(kScanBlock), 0, s, m);
+  hipLaunchKernelGGL(mask_write_kernel, dim3(m.nblocks), dim3(kBlock), 0, s, m);
+  return done(hipGetLastError());
+}
+
+// shared by gather and scatter: `rows` has shape [n, inner...], `inner` describes one indexed
+// sub-tensor of the tensor the offsets point into
+static int run_gather(bool scatter, const ocn_tensor *inner, const void *offsets, int64_t n, int64_t lo, int64_t hi,
+                      const ocn_tensor *rows, void *stream) {
+  if (bad_tensor(inner) || bad_tensor(rows)) return (!inner || !rows) ? OCN_ERR_NULLPTR : OCN_ERR_SHAPE;
+  if (inner->dtype != rows->dtype) return OCN_ERR_DTYPE;
+  if (inner->device != rows->device) return OCN_ERR_DEVICE;
+  if (n < 0 || rows->ndim != inner->ndim + 1 || rows->size[0] != n) return OCN_ERR_SHAPE;
+  for (int d = 0; d < inner->ndim; ++d)
+    if (rows->size[d + 1] != inner->size[d]) return OCN_ERR_SHAPE;
+  const int es = dt_size(inner->dtype);
+  const int sc = dt_size(dt_real_of(inner->dtype));
+  GatherArgs g;
+  std::memset(&g, 0, sizeof g);
+  const int64_t inner_elems = numel_of(inner);
+  if (n == 0 || inner_elems == 0) return OCN_OK;
+  if (!offsets || !inner->base || !rows->base) return OCN_ERR_NULLPTR;
+  if ((uintptr_t)offsets % 8) return OCN_ERR_ALIGN;
+  if (((intptr_t)inner->base + inner->offset) % sc || ((intptr_t)rows->base + rows->offset) % sc || rows->stride[0] % sc)
+    return OCN_ERR_ALIGN;
+  if (inner_elems >= ((int64_t)1 << 31)) return OCN_ERR_SHAPE;
+  // canonical inner dims: drop size 1, order by the stride on the rows side (slowest first), merge
+  struct D { int64_t size, si, sr; } d[kMaxDims];
+  int nd = 0;
+  for (int k = 0; k < inner->ndim; ++k) {
+    if (inner->size[k] == 1) continue;
+    if (inner->stride[k] % sc || rows->stride[k + 1] % sc) return OCN_ERR_ALIGN;
+    d[nd++] = D{inner->size[k], inner->stride[k], rows->stride[k + 1]};
+  }
+  auto mag = [](int64_t v) { return v < 0 ? -v : v; };
+  for (int a = 1; a < nd; ++a)
+    for (int b = a; b > 0 && mag(d[b].sr) > mag(d[b - 1].sr); --b) std::swap(d[b], d[b - 1]);
+  int m = 0;
+  for (int k = 0; k < nd; ++k) {
+    if (m > 0 && d[m - 1].si == d[k].si * d[k].size && d[m - 1].sr == d[k].sr * d[k].size) {
+      d[m - 1].size *= d[k].size; d[m - 1].si = d[k].si; d[m - 1].sr = d[k].sr;
+    } else {
+      d[m++] = d[k];
+    }
+  }
+  g.ndim = m;
+  for (int k = 0; k < m; ++k) {
+    g.div[k] = make_fastdiv((uint32_t)d[k].size);
+    g.ss[k] = scatter ? d[k].sr : d[k].si;
+    g.sd[k] = scatter ? d[k].si : d[k].sr;
+  }
+  g.src = scatter ? (const char *)rows->base + rows->offset : (const char *)inner->base + inner->offset;
+  g.dst = scatter ? (char *)inner->base + inner->offset : (char *)rows->base + rows->offset;
+  g.offsets = (const int64_t *)offsets;
+  g.n = n;
+  g.lo = lo;
+  g.hi = hi;
+  g.row_stride = rows->stride[0];
+  g.inner = (uint32_t)inner_elems;
+  const int64_t chunks = (inner_elems + kBlock - 1) / kBlock;
+  g.chunks_div = make_fastdiv((uint32_t)chunks);
+  const int64_t grid = inner_elems == 1 ? (n + kBlock - 1) / kBlock : n * chunks;
+  if (grid >= ((int64_t)1 << 31)) return OCN_ERR_SHAPE;
+  hipStream_t s = (hipStream_t)stream;
+#define OCN_LAUNCH(ES)                                                                                        \
+  if (scatter) hipLaunchKernelGGL((gather_kernel<ES, true>), dim3((unsigned)grid), dim3(kBlock), 0, s, g);   \
+  else hipLaunchKernelGGL((gather_kernel<ES, false>), dim3((unsigned)grid), dim3(kBlock), 0, s, g);
+  switch (es) {
+    case 1: OCN_LAUNCH(1) break;
+    case 2: OCN_LAUNCH(2) break;
+    case 4: OCN_LAUNCH(4) break;
+    case 8: OCN_LAUNCH(8) break;
+    default: OCN_LAUNCH(16) break;
+  }
+#undef OCN_LAUNCH
+  return done(hipGetLastError());
+}
+
+int ocn_gather(const ocn_tensor *a_inner, const void *offsets, int64_t n, int64_t lo, int64_t hi,
+               const ocn_tensor *out, void *stream) {
+  return run_gather(false, a_inner, offsets, n, lo, hi, out, stream);
+}
+
+int ocn_scatter(const ocn_tensor *src, const void *offsets, int64_t n, int64_t lo, int64_t hi,
+                const ocn_tensor *out_inner, void *stream) {
+  return run_gather(true, out_inner, offsets, n, lo, hi, src, stream);
+}
+
+}  // extern "C"

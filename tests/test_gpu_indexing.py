@@ -1,0 +1,191 @@
+"""GPU parity of index binding, mask compaction, gather and scatter against the oracle, bit for
+bit (everything here is integer or byte work), plus end-to-end agreement with NumPy's fancy and
+boolean indexing."""
+import numpy as np
+import pytest
+
+import gpu_harness as H
+from oracle import indexing as OI
+from workloads.values import random_view, rng_for
+from workloads.views import View, itemsize
+
+pytestmark = pytest.mark.gpu
+
+
+def _dev_i64(arr):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(arr, dtype=np.int64)).to("cuda:0")
+
+
+def _mask_offsets_gpu(mask: View, strides, capacity=None):
+    import torch
+    import paper_1810_08723_amd as ocn
+    dv = H.DeviceViews()
+    n = mask.numel
+    cap = n if capacity is None else capacity
+    offs = torch.full((max(cap, 0),), -7, dtype=torch.int64, device="cuda:0")
+    count = torch.full((1,), -1, dtype=torch.int64, device="cuda:0")
+    ocn.mask_offsets(dv.tensor(mask), list(strides), offs, count)
+    torch.cuda.synchronize()
+    return offs.cpu().numpy(), int(count.cpu()[0])
+
+
+def test_index_binding():
+    import torch
+    import paper_1810_08723_amd as ocn
+    rng = rng_for(17000)
+    idx = rng.integers(-70, 70, size=(37, 53)).astype(np.int64)          # dim_size 64: some invalid
+    iv = View.from_numpy(idx).permute(1, 0)                                # strided index tensor
+    ov = View.empty("int64", (53, 37))
+    dv = H.DeviceViews()
+    bad = torch.full((1,), 123, dtype=torch.int64, device="cuda:0")
+    ocn.index_offsets(dv.tensor(iv), 64, 24, dv.tensor(ov), bad)
+    torch.cuda.synchronize()
+    want, nbad = OI.index_offsets(iv.to_numpy(), 64, 24)
+    got = View(dv.download(ov), "int64", ov.sizes, ov.strides, 0).to_numpy()
+    assert np.array_equal(got, want) and int(bad.cpu()[0]) == nbad and nbad > 0
+    # all valid; 1-D; zero-sized
+    idx = rng.integers(-64, 64, size=(5000,)).astype(np.int64)
+    ov = View.empty("int64", (5000,))
+    dv = H.DeviceViews()
+    ocn.index_offsets(dv.tensor(View.from_numpy(idx)), 64, -8, dv.tensor(ov), bad)
+    torch.cuda.synchronize()
+    want, nbad = OI.index_offsets(idx, 64, -8)
+    assert np.array_equal(dv.download(ov).view(np.int64), want) and int(bad.cpu()[0]) == 0
+    ocn.index_offsets(dv.tensor(View.empty("int64", (0,))), 64, 8, dv.tensor(View.empty("int64", (0,))), bad)
+    torch.cuda.synchronize()
+    assert int(bad.cpu()[0]) == 0
+
+
+@pytest.mark.parametrize("density", (0.0, 0.03, 0.5, 1.0))
+def test_mask_offsets_contiguous(density):
+    rng = rng_for(17100)
+    n = 3 * 4096 * 5 + 1234                                               # several workgroups and a ragged tail
+    m = rng.random(n) < density
+    mask = View.from_numpy(m)
+    got, count = _mask_offsets_gpu(mask, (4,))
+    want = OI.mask_offsets(mask, (4,))
+    assert count == len(want) == int(m.sum())
+    assert np.array_equal(got[:count], want) and np.all(got[count:] == -7)
+    # a 3-D contiguous mask bound to a permuted target: merged on the mask side only where both merge
+    m3 = rng.random((33, 20, 50)) < density
+    strides = (8, 8 * 33 * 50, 8 * 33)                                     # target stored as (1, 2, 0)
+    got, count = _mask_offsets_gpu(View.from_numpy(m3), strides)
+    want = OI.mask_offsets(View.from_numpy(m3), strides)
+    assert count == len(want) and np.array_equal(got[:count], want)
+
+
+def test_mask_offsets_strided_masks_capacity_and_degenerate():
+    rng = rng_for(17101)
+    m = rng.random((40, 33, 21)) < 0.4
+    mask = View.from_numpy(m).permute(2, 0, 1).slice(1, 0, 40, 2)         # shape (21, 20, 33), strided
+    strides = (4, 4 * 21 * 33, 4 * 21)
+    got, count = _mask_offsets_gpu(mask, strides)
+    want = OI.mask_offsets(mask, strides)
+    assert count == len(want) and np.array_equal(got[:count], want)
+    # capacity smaller than the count: the first `capacity` offsets, the full count
+    got, count = _mask_offsets_gpu(mask, strides, capacity=100)
+    assert count == len(want) and np.array_equal(got, want[:100])
+    # unaligned contiguous mask (starts one byte into its storage), scalar mask, empty mask
+    big = View.from_numpy(rng.random(10001) < 0.5)
+    off1 = big.slice(0, 1, 10001, 1)
+    got, count = _mask_offsets_gpu(off1, (2,))
+    want = OI.mask_offsets(off1, (2,))
+    assert count == len(want) and np.array_equal(got[:count], want)
+    for val in (True, False):
+        got, count = _mask_offsets_gpu(View.from_numpy(np.array(val)), ())
+        assert count == int(val) and (not val or got[0] == 0)
+    got, count = _mask_offsets_gpu(View.from_numpy(np.zeros((0, 5), dtype=np.bool_)), (40, 8), capacity=0)
+    assert count == 0
+
+
+@pytest.mark.parametrize("dt", ("int8", "half", "float", "double", "cfloat", "cdouble"))
+def test_gather_scatter_elementwise_by_mask(dt):
+    import torch
+    import paper_1810_08723_amd as ocn
+    rng = rng_for(17200 + itemsize(dt))
+    a = random_view(rng, dt, (57, 40, 9)).permute(1, 2, 0)                 # shape (40, 9, 57), strided
+    m = rng.random((40, 9, 57)) < 0.35
+    mask = View.from_numpy(m)
+    offs_want = OI.mask_offsets(mask, a.strides)
+    got, count = _mask_offsets_gpu(mask, a.strides)
+    assert count == len(offs_want) and np.array_equal(got[:count], offs_want)
+    lo, hi = 0, a.storage.size - itemsize(dt) - a.offset
+    scalar = View(a.storage, dt, (), (), a.offset)
+    out = View.empty(dt, (count,))
+    dv = H.DeviceViews()
+    offs_dev = _dev_i64(offs_want)
+    ocn.gather(dv.tensor(scalar), offs_dev, lo, hi, dv.tensor(out))
+    torch.cuda.synchronize()
+    got_rows = dv.download(out).copy()
+    OI.gather(scalar, offs_want, out, lo, hi)
+    assert np.array_equal(got_rows, out.storage)
+    # the same selection as NumPy sees it
+    assert View(got_rows, dt, (count,), out.strides, 0).to_numpy().tobytes() == a.to_numpy()[m].tobytes()
+    # scatter new values to the selected places
+    vals = random_view(rng, dt, (count,))
+    dv = H.DeviceViews()
+    ocn.scatter(dv.tensor(vals), offs_dev, lo, hi, dv.tensor(scalar))
+    torch.cuda.synchronize()
+    got_a = dv.download(scalar).copy()
+    OI.scatter(vals, offs_want, scalar, lo, hi)
+    assert np.array_equal(got_a, a.storage)
+
+
+def test_gather_rows_by_index_array_and_skipped_offsets():
+    import torch
+    import paper_1810_08723_amd as ocn
+    rng = rng_for(17300)
+    a = random_view(rng, "float", (300, 70, 6), specials=False)
+    idx = rng.integers(-300, 300, size=(500,)).astype(np.int64)
+    offs, bad = OI.index_offsets(idx, 300, a.strides[0])
+    assert bad == 0
+    inner = View(a.storage, "float", (70, 6), a.strides[1:], a.offset)
+    for out in (View.empty("float", (500, 70, 6)), View.empty("float", (70, 500, 6)).permute(1, 0, 2)):
+        dv = H.DeviceViews()
+        ocn.gather(dv.tensor(inner), _dev_i64(offs), 0, 299 * a.strides[0], dv.tensor(out))
+        torch.cuda.synchronize()
+        got = dv.download(out).copy()
+        OI.gather(inner, offs, out, 0, 299 * a.strides[0])
+        assert np.array_equal(got, out.storage)
+        assert np.array_equal(View(got, "float", out.sizes, out.strides, 0).to_numpy(), a.to_numpy()[idx])
+    # index along the middle axis of the same tensor: the inner view is what is left of it
+    idx2 = np.array([69, 0, -1, 5], dtype=np.int64)
+    offs2, _ = OI.index_offsets(idx2, 70, a.strides[1])
+    inner2 = View(a.storage, "float", (300, 6), (a.strides[0], a.strides[2]), a.offset)
+    out = View.empty("float", (4, 300, 6))
+    dv = H.DeviceViews()
+    ocn.gather(dv.tensor(inner2), _dev_i64(offs2), 0, 69 * a.strides[1], dv.tensor(out))
+    torch.cuda.synchronize()
+    assert np.array_equal(View(dv.download(out), "float", out.sizes, out.strides, 0).to_numpy(),
+                          np.moveaxis(a.to_numpy()[:, idx2, :], 1, 0))
+    # offsets outside [lo, hi] are not followed: those rows keep their old contents
+    offs3 = offs.copy()
+    offs3[::7] = 10 ** 12
+    offs3[3::7] = -8
+    out = View.empty("float", (500, 70, 6))
+    dv = H.DeviceViews()
+    ocn.gather(dv.tensor(inner), _dev_i64(offs3), 0, 299 * a.strides[0], dv.tensor(out))
+    torch.cuda.synchronize()
+    got = dv.download(out).copy()
+    OI.gather(inner, offs3, out, 0, 299 * a.strides[0])
+    assert np.array_equal(got, out.storage)
+
+
+def test_scatter_rows():
+    import torch
+    import paper_1810_08723_amd as ocn
+    rng = rng_for(17301)
+    a = random_view(rng, "int16", (200, 33))
+    perm = rng.permutation(200)[:150].astype(np.int64)                    # distinct rows
+    offs, _ = OI.index_offsets(perm, 200, a.strides[0])
+    src = random_view(rng, "int16", (150, 33))
+    inner = View(a.storage, "int16", (33,), a.strides[1:], a.offset)
+    dv = H.DeviceViews()
+    ocn.scatter(dv.tensor(src), _dev_i64(offs), 0, 199 * a.strides[0], dv.tensor(inner))
+    torch.cuda.synchronize()
+    got = dv.download(inner).copy()
+    want = a.to_numpy().copy()
+    want[perm] = src.to_numpy()
+    OI.scatter(src, offs, inner, 0, 199 * a.strides[0])
+    assert np.array_equal(got, a.storage) and np.array_equal(a.to_numpy(), want)
