@@ -513,6 +513,7 @@ static int unary_supported(int op, int T) {
     case ORC_U_NEG: return k != K_BOOL;
     case ORC_U_ABS: return k != K_BOOL && k != K_CPLX; /* complex modulus is not an exact op */
     case ORC_U_BNOT: return k == K_BOOL || k == K_SINT || k == K_UINT;
+    case ORC_U_BSWAP: return k == K_BOOL || k == K_SINT || k == K_UINT;
     case ORC_U_SQRT: return k == K_REAL || k == K_CPLX;
     case ORC_U_SIN: case ORC_U_COS: case ORC_U_TAN: case ORC_U_EXP: case ORC_U_LOG:
       return k == K_REAL || k == K_CPLX;
@@ -583,6 +584,14 @@ static val_t apply_unary(int op, int T, val_t a) {
       else if (k == K_SINT) r.i = ~a.i; /* stays in range */
       else r.u = wrap_u(~a.u, bits);
       break;
+    case ORC_U_BSWAP: { /* section 3.1.3: data in the other byte order; reverse the element's bytes */
+      int nbytes = k == K_BOOL ? 1 : bits / 8;
+      uint64_t x = k == K_UINT ? a.u : (uint64_t)a.i, y = 0;
+      for (int b = 0; b < nbytes; ++b) y |= ((x >> (8 * b)) & 0xff) << (8 * (nbytes - 1 - b));
+      if (k == K_UINT) r.u = y;
+      else if (k == K_SINT) r.i = wrap_s(y, bits);
+      else r.i = a.i;
+    } break;
     case ORC_U_SQRT:
       if (k == K_CPLX) return apply_elementary(op, T, a);
       r.re = r_sqrt(arith_of(T), a.re);

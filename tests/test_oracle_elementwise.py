@@ -257,3 +257,39 @@ def test_shape_errors():
     with pytest.raises(O.OracleError) as e:
         O.binary("add", a, b, View.empty("float", (2, 3)))
     assert e.value.code == O.ERR_SHAPE
+
+
+def test_byte_swap_matches_numpy_and_is_an_involution():
+    rng = rng_for(77)
+    for dt, npdt in (("int16", np.int16), ("uint16", np.uint16), ("int32", np.int32), ("uint32", np.uint32),
+                     ("int64", np.int64), ("uint64", np.uint64), ("int8", np.int8), ("uint8", np.uint8)):
+        x = rng.integers(np.iinfo(npdt).min, np.iinfo(npdt).max, size=(7, 9), dtype=npdt, endpoint=True)
+        a = View.from_numpy(x).permute(1, 0)
+        out = View.empty(dt, a.sizes)
+        O.unary("bswap", a, out)
+        assert np.array_equal(out.to_numpy(), a.to_numpy().byteswap())
+        back = View.empty(dt, a.sizes)
+        O.unary("bswap", out, back)
+        assert np.array_equal(back.to_numpy(), a.to_numpy())
+    # a float stored in the other byte order, viewed as unsigned integers of its size
+    f = np.array([1.5, -2.25, 3e10], dtype=np.float32)
+    swapped = View.from_numpy(f.byteswap().view(np.uint32))
+    out = View.empty("uint32", (3,))
+    O.unary("bswap", swapped, out)
+    assert np.array_equal(out.to_numpy().view(np.float32), f)
+    with pytest.raises(O.OracleError):
+        O.unary("bswap", View.from_numpy(f), View.empty("float", (3,)))
+
+
+def test_domain_check():
+    rng = rng_for(78)
+    x = np.abs(rng.standard_normal((40, 30))).astype(np.float32)
+    assert not O.domain_check("sqrt", View.from_numpy(x))
+    assert not O.domain_check("log", View.from_numpy(x).permute(1, 0))
+    x[17, 3] = -1e-30
+    assert O.domain_check("sqrt", View.from_numpy(x)) and O.domain_check("log", View.from_numpy(x))
+    assert not O.domain_check("exp", View.from_numpy(x))
+    y = np.array([0.0, -0.0, np.nan, np.inf], dtype=np.float64)       # zeros, NaN and +Inf are inside the domain
+    assert not O.domain_check("sqrt", View.from_numpy(y))
+    assert O.domain_check("sqrt", View.from_numpy(np.array([-np.inf])))
+    assert O.domain_check("log", View.from_numpy(np.array([3, -1, 2], dtype=np.int32)))
