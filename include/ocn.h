@@ -71,6 +71,9 @@ typedef enum { /* section 3.2: basic arithmetic; complex types add conjugation (
   OCN_U_TAN,       /* single precision for half and float types, in double     */
   OCN_U_EXP,       /* otherwise; accurate to a few units in the last place,    */
   OCN_U_LOG,       /* not bit-reproducible against another math library        */
+  OCN_U_BSWAP,     /* integer types: the element with its bytes reversed (section
+                      3.1.3: data in the other byte order; view floating data as
+                      unsigned integers of the scalar size to bring it to native order) */
   OCN_NUM_UNARY
 } ocn_unary_op;
 
@@ -224,6 +227,19 @@ int ocn_gather(const ocn_tensor *a_inner, const void *offsets, int64_t n, int64_
                const ocn_tensor *out, void *stream);
 int ocn_scatter(const ocn_tensor *src, const void *offsets, int64_t n, int64_t lo, int64_t hi,
                 const ocn_tensor *out_inner, void *stream);
+
+/*
+ * Domain check of the compute modes (section 3.2.1: the warning, error and complex modes first
+ * check the elements against the operator's domain).  *flag (a 0-dimensional OCN_BOOL tensor on
+ * the device) := some element of a lies outside the real domain of the unary operation op:
+ * negative for OCN_U_SQRT and OCN_U_LOG; every other operation, and complex or bool input, is
+ * defined everywhere.  NaN elements do not count.  What to do with the answer - warn, fail, or
+ * switch to a complex result type - is the caller's policy.  workspace: DEVICE scratch of
+ * ocn_domain_check_workspace_bytes(op, a) bytes (at least 256), 256-byte aligned.
+ */
+size_t ocn_domain_check_workspace_bytes(int op, const ocn_tensor *a);
+int ocn_domain_check(int op, const ocn_tensor *a, const ocn_tensor *flag, void *workspace,
+                     size_t workspace_bytes, void *stream);
 
 /* Bytes of workspace ocn_reduce needs for these arguments (0 when it runs in one pass).
  * Returns 0 as well when the arguments are invalid; ocn_reduce then reports the error. */

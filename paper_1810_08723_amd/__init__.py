@@ -6,13 +6,13 @@ All computation happens in hand-written HIP kernels behind the C ABI of include/
 package only marshals arguments.
 """
 from .binding import (BINARY_OPS, DTYPES, REDUCE_OPS, STRICT_TYPES, UNARY_OPS, OcnError, Tensor,
-                      binary, binary_reduce, binary_reduce_workspace_bytes, cast_copy, dtype_size,
+                      binary, binary_reduce, binary_reduce_workspace_bytes, cast_copy, domain_check, dtype_size,
                       gather, index_offsets, mask_offsets, scatter,
                       plan_binary, plan_binary_reduce, plan_reduce, plan_unary, promote, reduce,
                       reduce_workspace_bytes, unary)
 
 __all__ = ["BINARY_OPS", "DTYPES", "REDUCE_OPS", "STRICT_TYPES", "UNARY_OPS", "OcnError", "Tensor",
-           "binary", "binary_reduce", "binary_reduce_workspace_bytes", "cast_copy", "dtype_size",
+           "binary", "binary_reduce", "binary_reduce_workspace_bytes", "cast_copy", "domain_check", "dtype_size",
            "gather", "index_offsets", "mask_offsets", "scatter",
            "plan_binary", "plan_binary_reduce", "plan_reduce", "plan_unary", "promote", "reduce",
            "reduce_workspace_bytes", "unary"]

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(HERE, "libocn.so")
 DTYPES = ("bool", "int8", "int16", "int32", "int64", "uint8", "uint16", "uint32", "uint64",
           "half", "float", "double", "chalf", "cfloat", "cdouble")
 DTYPE_CODE = {n: i for i, n in enumerate(DTYPES)}
-UNARY_OPS = ("ident", "neg", "abs", "conj", "lnot", "bnot", "sqrt", "sin", "cos", "tan", "exp", "log")
+UNARY_OPS = ("ident", "neg", "abs", "conj", "lnot", "bnot", "sqrt", "sin", "cos", "tan", "exp", "log", "bswap")
 BINARY_OPS = ("add", "sub", "mul", "div", "min", "max", "band", "bor", "bxor", "land", "lor",
               "lxor", "eq", "ne", "lt", "le", "gt", "ge", "absgt")
 REDUCE_OPS = ("sum", "prod", "min", "max", "any", "all")
@@ -39,7 +39,7 @@ EXPORTS = ("ocn_unary", "ocn_binary", "ocn_cast_copy", "ocn_reduce", "ocn_reduce
            "ocn_plan_unary", "ocn_plan_binary", "ocn_plan_reduce",
            "ocn_binary_reduce", "ocn_binary_reduce_workspace_bytes", "ocn_plan_binary_reduce",
            "ocn_index_offsets", "ocn_mask_offsets", "ocn_mask_offsets_workspace_bytes", "ocn_gather",
-           "ocn_scatter")
+           "ocn_scatter", "ocn_domain_check", "ocn_domain_check_workspace_bytes")
 
 
 class OcnTensor(C.Structure):
@@ -103,6 +103,9 @@ def lib() -> C.CDLL:
         L.ocn_binary_reduce_workspace_bytes.argtypes = [C.c_int, C.c_int, T, T, A, C.c_int32, T, C.c_int32]
         L.ocn_binary_reduce_workspace_bytes.restype = C.c_size_t
         L.ocn_plan_binary_reduce.argtypes = [C.c_int, C.c_int, T, T, A, C.c_int32, T, C.c_int32, I]
+        L.ocn_domain_check_workspace_bytes.argtypes = [C.c_int, T]
+        L.ocn_domain_check_workspace_bytes.restype = C.c_size_t
+        L.ocn_domain_check.argtypes = [C.c_int, T, T, C.c_void_p, C.c_size_t, C.c_void_p]
         L.ocn_index_offsets.argtypes = [T, C.c_int64, C.c_int64, T, C.c_void_p, C.c_void_p]
         L.ocn_mask_offsets_workspace_bytes.argtypes = [T]
         L.ocn_mask_offsets_workspace_bytes.restype = C.c_size_t
@@ -250,6 +253,21 @@ def gather(a_inner: Tensor, offsets, lo: int, hi: int, out: Tensor, stream=None)
 def scatter(src: Tensor, offsets, lo: int, hi: int, out_inner: Tensor, stream=None) -> None:
     _check(lib().ocn_scatter(C.byref(src.desc()), offsets.data_ptr() if offsets.numel() else None,
                              offsets.numel(), lo, hi, C.byref(out_inner.desc()), _stream(stream)))
+
+
+def domain_check(op: str, a: Tensor, flag=None, workspace=None, stream=None):
+    """Enqueues the domain check of unary `op` over `a` into `flag` (a 1-element bool torch tensor
+    on the device; created when None) and returns that tensor without synchronising."""
+    import torch
+    if flag is None:
+        flag = torch.zeros(1, dtype=torch.bool, device=f"cuda:{a.device}")
+    tf = Tensor(flag.data_ptr(), "bool", (), (), 0, a.device, flag)
+    if workspace is None:
+        need = int(lib().ocn_domain_check_workspace_bytes(UNARY_CODE[op], C.byref(a.desc())))
+        workspace = torch.empty(need, dtype=torch.uint8, device=f"cuda:{a.device}")
+    _check(lib().ocn_domain_check(UNARY_CODE[op], C.byref(a.desc()), C.byref(tf.desc()), workspace.data_ptr(),
+                                  workspace.numel(), _stream(stream)))
+    return flag
 
 
 def promote(a: str, b: str) -> str:

@@ -1,6 +1,7 @@
 // C ABI of the tensor engine (see include/ocn.h): argument checks, planning, launch.
 #include <hip/hip_runtime.h>
 
+#include <cstring>
 #include <mutex>
 
 #include "../../include/ocn.h"
@@ -19,7 +20,7 @@ static_assert(B_ADD == OCN_B_ADD && B_MAX == OCN_B_MAX && B_BAND == OCN_B_BAND &
               "binary op numbering");
 static_assert(U_IDENT == OCN_U_IDENT && U_NEG == OCN_U_NEG && U_ABS == OCN_U_ABS && U_CONJ == OCN_U_CONJ &&
               U_LNOT == OCN_U_LNOT && U_BNOT == OCN_U_BNOT && U_SQRT == OCN_U_SQRT && U_SIN == OCN_U_SIN &&
-              U_LOG == OCN_U_LOG && U_COUNT == OCN_NUM_UNARY,
+              U_LOG == OCN_U_LOG && U_BSWAP == OCN_U_BSWAP && U_COUNT == OCN_NUM_UNARY,
               "unary op numbering");
 static_assert(R_SUM == OCN_R_SUM && R_PROD == OCN_R_PROD && R_MIN == OCN_R_MIN && R_MAX == OCN_R_MAX &&
               R_ANY == OCN_R_ANY && R_ALL == OCN_R_ALL && R_COUNT == OCN_NUM_REDUCE, "reduce op numbering");
@@ -197,6 +198,78 @@ int ocn_plan_reduce(int op, const ocn_tensor *a, const int32_t *axes, int32_t na
   if (rc != OCN_OK) return rc;
   fill_info(p, info);
   return OCN_OK;
+}
+
+// all-zero bytes read as the value 0 of every dtype: the scalar the domain check compares with
+static __device__ __align__(16) unsigned char g_zero_scalar[16];
+
+static int domain_plan(int op, const ocn_tensor *a, const ocn_tensor *flag, char *workspace, FusedPlan *fp, bool *trivial) {
+  if (!a || !flag) return OCN_ERR_NULLPTR;
+  if (op < 0 || op >= U_COUNT) return OCN_ERR_OP;
+  if (flag->dtype != DT_BOOL || flag->ndim != 0) return OCN_ERR_SHAPE;
+  *trivial = !(op == U_SQRT || op == U_LOG);
+  if (*trivial) return OCN_OK;
+  if (dt_kind(a->dtype) == K_CPLX || dt_kind(a->dtype) == K_BOOL) { *trivial = true; return OCN_OK; }
+  void *zero = nullptr;
+  if (workspace) {  // a real call (not a size query): the device address of the zero scalar
+    if (hipGetSymbolAddress(&zero, HIP_SYMBOL(g_zero_scalar)) != hipSuccess || !zero) return finish(hipGetLastError());
+  } else {
+    zero = (void *)((uintptr_t)1 << 60);  // size query: stand-in addresses far from the temporary's
+  }
+  ocn_tensor z;
+  std::memset(&z, 0, sizeof z);
+  z.base = zero;
+  z.dtype = a->dtype;
+  z.ndim = 0;
+  z.device = a->device;
+  int32_t axes[OCN_MAX_DIMS];
+  for (int d = 0; d < a->ndim && d < OCN_MAX_DIMS; ++d) axes[d] = d;
+  return plan_binary_reduce(B_LT, R_ANY, a, &z, axes, a->ndim, flag, DT_BOOL, workspace, fp);
+}
+
+size_t ocn_domain_check_workspace_bytes(int op, const ocn_tensor *a) {
+  ocn_tensor flag;
+  std::memset(&flag, 0, sizeof flag);
+  flag.base = (void *)(((uintptr_t)1 << 60) + 4096);
+  flag.dtype = DT_BOOL;
+  if (a) flag.device = a->device;
+  FusedPlan fp;
+  bool trivial = false;
+  if (domain_plan(op, a, &flag, nullptr, &fp, &trivial) != OCN_OK || trivial) return 256;
+  return fp.workspace_bytes < 256 ? 256 : fp.workspace_bytes;
+}
+
+int ocn_domain_check(int op, const ocn_tensor *a, const ocn_tensor *flag, void *workspace, size_t workspace_bytes,
+                     void *stream) {
+  if (!workspace || workspace_bytes < 256) return OCN_ERR_WORKSPACE;
+  if ((uintptr_t)workspace % 256 != 0) return OCN_ERR_ALIGN;
+  FusedPlan fp;
+  bool trivial = false;
+  int rc = domain_plan(op, a, flag, (char *)workspace, &fp, &trivial);
+  if (rc != OCN_OK) return rc;
+  if (trivial) {
+    // every element is inside the domain: flag := cast(false), through the ordinary cast copy
+    // of a zero scalar (no separate fill kernel, nothing a graph capture would mind)
+    void *zero = nullptr;
+    if (hipGetSymbolAddress(&zero, HIP_SYMBOL(g_zero_scalar)) != hipSuccess || !zero) return finish(hipGetLastError());
+    ocn_tensor z;
+    std::memset(&z, 0, sizeof z);
+    z.base = zero;
+    z.dtype = DT_BOOL;
+    z.device = flag->device;
+    return ocn_cast_copy(&z, flag, stream);
+  }
+  if (fp.workspace_bytes > workspace_bytes) return OCN_ERR_WORKSPACE;
+  ensure_registered();
+  if (fp.unfused) {
+    const int st = run_elementwise(fp.ew, (hipStream_t)stream);
+    if (st != OCN_OK || fp.red.kernel == OCN_KERNEL_NONE) return st;
+    return run_reduce(fp.red, g_reduce_launchers[fp.red.op][fp.red.a_dtype], (char *)workspace + fp.mid_bytes,
+                      (hipStream_t)stream);
+  }
+  if (fp.red.kernel == OCN_KERNEL_NONE) return OCN_OK;
+  return run_reduce(fp.red, g_fused_launchers[fp.red.ew_op][fp.red.a_dtype][fp.red.op], (char *)workspace,
+                    (hipStream_t)stream);
 }
 
 int ocn_plan_binary_reduce(int ew_op, int red_op, const ocn_tensor *a, const ocn_tensor *b, const int32_t *axes,

@@ -455,6 +455,11 @@ template <int OP, int T> OCN_DEV reg_t<unary_result_dtype(OP, T)> apply_unary(re
   } else if constexpr (OP == U_BNOT) {
     if constexpr (k == K_BOOL) return !a;
     else return (R)~a;
+  } else if constexpr (OP == U_BSWAP) {  // integer types: reverse the element's bytes
+    if constexpr (sizeof(R) == 2) return (R)__builtin_bswap16((uint16_t)a);
+    else if constexpr (sizeof(R) == 4) return (R)__builtin_bswap32((uint32_t)a);
+    else if constexpr (sizeof(R) == 8) return (R)__builtin_bswap64((uint64_t)a);
+    else return a;
   } else if constexpr (OP == U_SQRT && k == K_REAL) {
     if constexpr (T == DT_F16) return hreg{__builtin_sqrtf(a.v)};
     else if constexpr (T == DT_F32) return __builtin_sqrtf(a);
