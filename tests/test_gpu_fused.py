@@ -174,3 +174,29 @@ def test_two_call_fallback_and_degenerate_shapes():
     _check("mul", "sum", View.empty("float", (0, 5)), View.empty("float", (0, 5)), (1,), "float")
     _check("mul", "sum", View.empty("float", (4, 0)), View.empty("float", (4, 0)), (1,), "float")
     _check("gt", "any", View.empty("float", (4, 0)), View.empty("float", (4, 0)), (1,), "bool")
+
+
+FUSED_SIGS = [(ew, dt, "sum") for ew in ("mul", "add", "sub") for dt in ARITH_T] + \
+             [(ew, dt, red) for ew in ("eq", "lt", "gt", "absgt") for dt in ("int32", "float", "double")
+              for red in ("sum", "any", "all")] + \
+             [(ew, "cfloat", red) for ew in ("eq", "absgt") for red in ("sum", "any", "all")]
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_fuzz_fused(seed):
+    """Random shapes, broadcast patterns, axis sets and strided views through every fused signature."""
+    from workloads.fuzz import random_shape, random_strided_view
+    rng = rng_for(15600 + seed)
+    for it in range(10):
+        shape = random_shape(rng, max_ndim=5, max_elems=30000)
+        ew, dt, red = FUSED_SIGS[int(rng.integers(0, len(FUSED_SIGS)))]
+        mid = "bool" if ew in ("eq", "lt", "gt", "absgt") else dt
+        # each input keeps or drops leading axes and may have broadcast axes (the generator's zero strides)
+        a = random_strided_view(rng, dt, shape, specials=X.kind(dt) not in "fc")
+        b = random_strided_view(rng, dt, shape, specials=X.kind(dt) not in "fc")
+        if len(shape) >= 2 and rng.random() < 0.3:
+            b = random_strided_view(rng, dt, shape[1:], specials=X.kind(dt) not in "fc")   # lower rank
+        nd = len(np.broadcast_shapes(tuple(a.sizes), tuple(b.sizes)))   # the generator may drop leading axes
+        naxes = int(rng.integers(0, nd + 1))
+        axes = tuple(sorted(int(x) for x in rng.permutation(nd)[:naxes]))
+        _check(ew, red, a, b, axes, mid)
