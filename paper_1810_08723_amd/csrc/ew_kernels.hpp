@@ -32,6 +32,7 @@ struct RowsArgs {
   int64_t inner;     // elements per row
   int64_t nvec;      // vectors in total
   int32_t a_bcast, b_bcast;
+  int32_t nt_store;  // stream the output past the caches
 };
 
 constexpr int kMaxTilePasses = 16;  // a tile holds at most 4096 elements = 16 passes of 256 lanes
@@ -64,6 +65,7 @@ struct TiledArgs {
   int32_t tl[kMaxDims];
   FastDiv ntdiv[kMaxDims];
   int32_t stage_a, stage_b;
+  int32_t nt_store;                // stream the output past the caches
   uint32_t lds_off_b;              // byte offset of b's staging area in dynamic LDS
   TileSwizzle swz[2];              // for a, b
   TileOrder ord[3];                // enumeration orders: out's, a's, b's
@@ -91,6 +93,7 @@ struct FastTiledArgs {
   const char *a, *b;
   int32_t ntd;                              // dims with more than one tile, fastest first
   int32_t stage_a, stage_b;
+  int32_t nt_store;                         // stream the output past the caches
   uint32_t lds_base[2];                     // byte offset of a's / b's staging area
   FastDiv ntdiv[kMaxDims];
   int64_t step[3][kMaxDims];                // bytes from one tile to the next along that dim
@@ -128,20 +131,13 @@ template <class S, int V> struct alignas(sizeof(S) * V >= 16 ? 16 : sizeof(S) * 
   S v[V];
 };
 
-#ifndef OCN_NT_LOAD
-#define OCN_NT_LOAD 0
-#endif
-#ifndef OCN_NT_STORE
-#define OCN_NT_STORE 0
-#endif
 template <class S, int V> OCN_DEV void load_pack(const char *p, Pack<S, V> &dst) {
   constexpr int B = sizeof(S) * V;
   if constexpr (B >= 16) {
     using Q = uint32_t __attribute__((ext_vector_type(4)));
 #pragma unroll
     for (int i = 0; i < B / 16; ++i) {
-      if constexpr (OCN_NT_LOAD) reinterpret_cast<Q *>(&dst)[i] = __builtin_nontemporal_load(reinterpret_cast<const Q *>(p) + i);
-      else reinterpret_cast<Q *>(&dst)[i] = reinterpret_cast<const Q *>(p)[i];
+      reinterpret_cast<Q *>(&dst)[i] = reinterpret_cast<const Q *>(p)[i];
     }
   } else if constexpr (B == 8) {
     using D = uint32_t __attribute__((ext_vector_type(2)));
@@ -155,20 +151,43 @@ template <class S, int V> OCN_DEV void load_pack(const char *p, Pack<S, V> &dst)
   }
 }
 
-template <class S, int V> OCN_DEV void store_pack(char *p, const Pack<S, V> &src) {
+// `nt`: a streaming (non-temporal) store.  Outputs too large to stay in the Infinity Cache are
+// written this way: an ordinary store leaves the lines dirty in that cache, and the next
+// kernel then pays for writing them back while it reads (measured: up to a third of its time).
+// (The empty asm statements fence the streaming branch: without them the compiler merges the
+// two stores of an if/else into one and drops the hint.)
+#define OCN_KEEP_BRANCH() asm volatile("")
+template <class S, int V> OCN_DEV void store_pack(char *p, const Pack<S, V> &src, bool nt = false) {
   constexpr int B = sizeof(S) * V;
   if constexpr (B >= 16) {
     using Q = uint32_t __attribute__((ext_vector_type(4)));
 #pragma unroll
     for (int i = 0; i < B / 16; ++i) {
-      if constexpr (OCN_NT_STORE) __builtin_nontemporal_store(reinterpret_cast<const Q *>(&src)[i], reinterpret_cast<Q *>(p) + i);
-      else reinterpret_cast<Q *>(p)[i] = reinterpret_cast<const Q *>(&src)[i];
+      if (nt) {
+        OCN_KEEP_BRANCH();
+        __builtin_nontemporal_store(reinterpret_cast<const Q *>(&src)[i], reinterpret_cast<Q *>(p) + i);
+        OCN_KEEP_BRANCH();
+      } else {
+        reinterpret_cast<Q *>(p)[i] = reinterpret_cast<const Q *>(&src)[i];
+      }
     }
   } else if constexpr (B == 8) {
     using D = uint32_t __attribute__((ext_vector_type(2)));
-    *reinterpret_cast<D *>(p) = *reinterpret_cast<const D *>(&src);
+    if (nt) {
+      OCN_KEEP_BRANCH();
+      __builtin_nontemporal_store(*reinterpret_cast<const D *>(&src), reinterpret_cast<D *>(p));
+      OCN_KEEP_BRANCH();
+    } else {
+      *reinterpret_cast<D *>(p) = *reinterpret_cast<const D *>(&src);
+    }
   } else if constexpr (B == 4) {
-    *reinterpret_cast<uint32_t *>(p) = *reinterpret_cast<const uint32_t *>(&src);
+    if (nt) {
+      OCN_KEEP_BRANCH();
+      __builtin_nontemporal_store(*reinterpret_cast<const uint32_t *>(&src), reinterpret_cast<uint32_t *>(p));
+      OCN_KEEP_BRANCH();
+    } else {
+      *reinterpret_cast<uint32_t *>(p) = *reinterpret_cast<const uint32_t *>(&src);
+    }
   } else if constexpr (B == 2) {
     *reinterpret_cast<uint16_t *>(p) = *reinterpret_cast<const uint16_t *>(&src);
   } else {
@@ -297,7 +316,7 @@ template <class G> __global__ __launch_bounds__(kBlock) void ew_rows_kernel(cons
     }
     char *po = p.out + oo[u];
     if (n == V) {
-      store_pack<SOt, V>(po, r);
+      store_pack<SOt, V>(po, r, p.nt_store != 0);
     } else {
 #pragma unroll
       for (int i = 0; i < V; ++i)
@@ -518,7 +537,7 @@ OCN_DEV void tiled_compute(KTiledArgs &p, char *out, const char *pa, const char 
       }
       char *po = out + offo[j];
       if (FULL || n == V) {
-        store_pack<SOt, V>(po, r);
+        store_pack<SOt, V>(po, r, p.nt_store != 0);
       } else {
 #pragma unroll
         for (int i = 0; i < V; ++i)
@@ -769,7 +788,7 @@ template <class G> __global__ __launch_bounds__(kBlock) void ew_tiled_fast_kerne
         if constexpr (BIN) r.v[i] = G::eval(av[j].v[i], bv[j].v[i]);
         else r.v[i] = G::eval(av[j].v[i], SBt{});
       }
-      store_pack<SOt, VC>(out + p.ord[0].hi_off[0][jj] + off[0], r);
+      store_pack<SOt, VC>(out + p.ord[0].hi_off[0][jj] + off[0], r, p.nt_store != 0);
     }
   }
 }

@@ -30,6 +30,7 @@ RowsArgs make_rows_args(const EwPlan &p) {
   r.nvec = vpr * (p.numel / r.inner);
   r.a_bcast = p.a_inner_bcast;
   r.b_bcast = p.b_inner_bcast;
+  r.nt_store = p.nt_store;
   return r;
 }
 
@@ -52,6 +53,7 @@ TiledArgs make_tiled_args(const EwPlan &p, int es_a) {
   }
   t.stage_a = p.stage_a;
   t.stage_b = p.stage_b;
+  t.nt_store = p.nt_store;
   const int64_t tile_elems = (int64_t)1 << p.tile_bits;
   t.lds_off_b = p.stage_a ? (uint32_t)((tile_elems * es_a + 15) / 16 * 16) : 0u;
   // bit position of each tiled dim in the output's enumeration order = its LDS slot shift
@@ -120,6 +122,7 @@ FastTiledArgs make_fast_tiled_args(const EwPlan &p, int es_a) {
   f.b = t.b;
   f.stage_a = t.stage_a;
   f.stage_b = t.stage_b;
+  f.nt_store = t.nt_store;
   // tile grid: only dims with more than one tile, fastest (last canonical dim) first
   for (int d = p.ndim - 1; d >= 0; --d) {
     if (p.ntiles[d] <= 1) continue;

@@ -87,6 +87,7 @@ struct MaskArgs {
   int64_t *offsets;
   int64_t capacity;
   int64_t *count;
+  int32_t nt_store;                   // large result: streaming stores
 };
 
 __device__ __forceinline__ void mask_decode(const MaskArgs &p, uint32_t e, int64_t &om, int64_t &ot) {
@@ -201,7 +202,15 @@ __global__ __launch_bounds__(kBlock) void mask_write_kernel(const MaskArgs p) {
   // coalesced copy of the staged offsets behind this workgroup's prefix
   const int64_t base = p.block_counts[blockIdx.x];
   for (uint32_t i = threadIdx.x; i < sum; i += kBlock)
-    if (base + i < p.capacity) p.offsets[base + i] = staged[i];
+    if (base + i < p.capacity) {
+      if (p.nt_store) {  // (the empty asm keeps the compiler from merging the two stores and dropping the hint)
+        asm volatile("");
+        __builtin_nontemporal_store(staged[i], p.offsets + base + i);
+        asm volatile("");
+      } else {
+        p.offsets[base + i] = staged[i];
+      }
+    }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -380,6 +389,7 @@ int ocn_mask_offsets(const ocn_tensor *mask, const int64_t *target_strides, void
   m.offsets = (int64_t *)offsets;
   m.capacity = capacity;
   m.count = (int64_t *)count;
+  m.nt_store = std::min<int64_t>(capacity, m.n) * 8 >= ((int64_t)32 << 20);  // too large to stay cached
   hipLaunchKernelGGL(mask_count_kernel, dim3(m.nblocks), dim3(kBlock), 0, s, m);
   hipLaunchKernelGGL(mask_scan_kernel, dim3(1), dim3(kScanBlock), 0, s, m);
   hipLaunchKernelGGL(mask_write_kernel, dim3(m.nblocks), dim3(kBlock), 0, s, m);

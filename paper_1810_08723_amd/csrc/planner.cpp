@@ -380,6 +380,10 @@ int plan_elementwise(int nin, int op, const ocn_tensor *a, const ocn_tensor *b,
 
   // ---- kernel selection ------------------------------------------------------------------
   const int es_o = dt_size(so), es_a = dt_size(sa), es_b = dt_size(sb);
+  // An output of 32 MiB or more will not be found in the caches by whoever reads it next
+  // (4 MB of L2 per XCD, 256 MB of Infinity Cache shared with the inputs): write it with
+  // streaming stores, so that its dirty lines do not burden the next kernel.
+  p.nt_store = numel * es_o >= ((int64_t)32 << 20);
   const int inner = n - 1;
   const int es_min = std::min({es_o, es_a, nin == 2 ? es_b : es_a});
   const int es_max = std::max({es_o, es_a, nin == 2 ? es_b : es_a});

@@ -66,6 +66,7 @@ struct EwPlan {
   int64_t total_tiles = 0;
   bool specialised = false;     // a dtype-specialised kernel exists for this signature
   bool fast_tiled = false;      // tiled kernel: the unclipped all-vector form applies
+  bool nt_store = false;        // the output is too large to stay cached: stream it past the caches
   int64_t grid = 0;
   int64_t lds_bytes = 0;
 };
