@@ -10,8 +10,8 @@
  * Build with contraction of a*b+c into fused multiply-adds switched off and no fast-math,
  * so that every floating-point operation below rounds exactly once in its own type.
  *
- * Conventions where the paper is silent are this build's readings (listed with the
- * design notes): float->integer casts truncate toward zero, saturate, and map NaN to 0;
+ * Conventions where the paper is silent are readings made here (listed with the design
+ * notes): float->integer casts truncate toward zero, saturate, and map NaN to 0;
  * integer->narrower-integer casts saturate; conversions to floating types round to nearest
  * even in one step; half-precision types (real and complex) compute in single precision
  * and round once when stored; integer arithmetic wraps; min/max propagate NaN and rank +0
