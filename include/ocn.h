@@ -274,8 +274,8 @@ typedef enum {
 } ocn_kernel_kind;
 
 /* What the host planner decided for a call: the canonical dimension list after dropping
- * size-1 dimensions, flipping, sorting by stride and merging (section 4 of the paper:
- * "sorting of axes and merging of consecutive axes"), slowest dimension first. */
+ * size-1 dimensions, flipping, sorting by stride and merging (the optimisation section 4 of
+ * the paper names: axes are sorted and consecutive ones merged), slowest dimension first. */
 typedef struct {
   int32_t kernel;                     /* ocn_kernel_kind                                    */
   int32_t compute_dtype;              /* T                                                  */

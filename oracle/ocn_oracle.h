@@ -95,8 +95,8 @@ int orc_binary(int op, const orc_tensor *a, const orc_tensor *b, const orc_tenso
 /* dst[i] = convert(src[i]) (section 3.2.1, explicit type casting on one device). */
 int orc_cast_copy(const orc_tensor *src, const orc_tensor *dst);
 
-/* Reduction along the listed axes (section 3.2, "tensor reductions along one or more
- * axes"): out has the kept dimensions of a in their original order. */
+/* Reduction along the listed axes (section 3.2 lists reductions over one or several axes):
+ * out has the kept dimensions of a in their original order. */
 int orc_reduce(int op, const orc_tensor *a, const int32_t *axes, int32_t naxes,
                const orc_tensor *out);
 

@@ -6,15 +6,13 @@ from oracle import binding as O
 
 
 def test_examples_printed_in_the_paper():
-    # "addition of signed and unsigned 8-bit integers would give a 16-bit signed integer"
-    assert O.promote("int8", "uint8") == "int16"
-    assert O.promote("uint8", "int8") == "int16"
-    # "an exception is made for 64-bit integers and floating-point numbers, which result in
-    # double-precision floats"
-    for f in ("half", "float", "double"):
-        assert O.promote("int64", f) == "double"
-        assert O.promote("uint64", f) == "double"
-        assert O.promote(f, "int64") == "double"
+    """The worked examples of section 3.2.1, kept as a text fixture with their citation."""
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "promotion_examples.txt")
+    rows = [ln.split() for ln in open(path) if ln.strip() and not ln.startswith("#")]
+    assert len(rows) == 7
+    for a, b, want in rows:
+        assert O.promote(a, b) == want and O.promote(b, a) == want, (a, b)
 
 
 def test_matches_brute_force_containment_over_all_pairs():
