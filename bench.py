@@ -110,9 +110,10 @@ def _plan_kernel(c):
     return ocn.plan_reduce(c.op, ins[0], list(c.axes), out)
 
 
-def _cpu_baseline(seconds_budget: float = 20.0):
+def _cpu_baseline(seconds_budget: float = 12.0):
     """Times the CPU oracle, as it stands, on a bounded sample: the small-size versions of the
-    same cases, repeated until the budget is spent.  Returns GB/s of logical bytes."""
+    same cases, repeated until the budget (about 12 s of CPU work) is spent.  Returns GB/s of
+    logical bytes."""
     from oracle import binding as O
     from workloads import configs
     cases = configs.all_cases_small()
@@ -129,7 +130,7 @@ def _cpu_baseline(seconds_budget: float = 20.0):
                 O.reduce(c.op, c.inputs[0], list(c.axes), c.out)
             total_bytes += c.logical_bytes
         reps += 1
-        if time.perf_counter() - t0 > seconds_budget or reps >= 50:
+        if time.perf_counter() - t0 > seconds_budget or reps >= 20000:
             break
     dt = time.perf_counter() - t0
     threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))

@@ -74,6 +74,8 @@ typedef enum { /* section 3.2: basic arithmetic; complex types add conjugation (
   OCN_U_BSWAP,     /* integer types: the element with its bytes reversed (section
                       3.1.3: data in the other byte order; view floating data as
                       unsigned integers of the scalar size to bring it to native order) */
+  OCN_U_ASIN, OCN_U_ACOS, OCN_U_ATAN,   /* inverse trigonometric and hyperbolic functions,  */
+  OCN_U_SINH, OCN_U_COSH, OCN_U_TANH,   /* real floating types only, same accuracy class    */
   OCN_NUM_UNARY
 } ocn_unary_op;
 
@@ -232,8 +234,8 @@ int ocn_scatter(const ocn_tensor *src, const void *offsets, int64_t n, int64_t l
  * Domain check of the compute modes (section 3.2.1: the warning, error and complex modes first
  * check the elements against the operator's domain).  *flag (a 0-dimensional OCN_BOOL tensor on
  * the device) := some element of a lies outside the real domain of the unary operation op:
- * negative for OCN_U_SQRT and OCN_U_LOG; every other operation, and complex or bool input, is
- * defined everywhere.  NaN elements do not count.  What to do with the answer - warn, fail, or
+ * negative for OCN_U_SQRT and OCN_U_LOG, of magnitude above one for OCN_U_ASIN and OCN_U_ACOS;
+ * every other operation, and complex or bool input, is defined everywhere.  NaN elements do not count.  What to do with the answer - warn, fail, or
  * switch to a complex result type - is the caller's policy.  workspace: DEVICE scratch of
  * ocn_domain_check_workspace_bytes(op, a) bytes (at least 256), 256-byte aligned.
  */

@@ -21,7 +21,8 @@ DTYPE_CODE = {name: i for i, name in enumerate(
 DTYPE_NAME = {v: k for k, v in DTYPE_CODE.items()}
 
 UNARY = {name: i for i, name in enumerate(["ident", "neg", "abs", "conj", "lnot", "bnot", "sqrt",
-                                           "sin", "cos", "tan", "exp", "log", "bswap"])}
+                                           "sin", "cos", "tan", "exp", "log", "bswap",
+                                           "asin", "acos", "atan", "sinh", "cosh", "tanh"])}
 BINARY = {name: i for i, name in enumerate(
     ["add", "sub", "mul", "div", "min", "max", "band", "bor", "bxor", "land", "lor", "lxor",
      "eq", "ne", "lt", "le", "gt", "ge", "absgt"])}
@@ -122,14 +123,20 @@ def binary_reduce(ew_op: str, red_op: str, a, b, axes: Sequence[int], out, mid_d
 def domain_check(op: str, a) -> bool:
     """Compute modes (section 3.2.1: warning, error and complex modes check the elements against
     the operator's domain first): True if some element of `a` lies outside the real domain of
-    `op` - negative for sqrt and log; the other operations are defined everywhere.  NaNs do not
-    count.  Written as its definition: any(a < 0) through the elementwise and reduction oracle."""
+    `op` - negative for sqrt and log, of magnitude above one for asin and acos (the paper's own
+    example); the other operations are defined everywhere.  NaNs do not count.  Written as its
+    definition: any(a < 0), any(|a| > |1|), through the elementwise and reduction oracle."""
     from workloads.views import View
-    if op not in ("sqrt", "log"):
-        return False
-    zero = View(np.zeros(16, dtype=np.uint8), a.dtype, (), (), 0)
     out = View.empty("bool", ())
-    binary_reduce("lt", "any", a, zero, list(range(a.ndim)), out, "bool")
+    if op in ("sqrt", "log"):
+        zero = View(np.zeros(16, dtype=np.uint8), a.dtype, (), (), 0)
+        binary_reduce("lt", "any", a, zero, list(range(a.ndim)), out, "bool")
+    elif op in ("asin", "acos"):
+        one = View.empty(a.dtype, ())
+        cast_copy(View.from_numpy(np.array(1, dtype=np.int8)), one)
+        binary_reduce("absgt", "any", a, one, list(range(a.ndim)), out, "bool")
+    else:
+        return False
     return bool(out.to_numpy())
 
 

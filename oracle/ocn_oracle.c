@@ -517,6 +517,8 @@ static int unary_supported(int op, int T) {
     case ORC_U_SQRT: return k == K_REAL || k == K_CPLX;
     case ORC_U_SIN: case ORC_U_COS: case ORC_U_TAN: case ORC_U_EXP: case ORC_U_LOG:
       return k == K_REAL || k == K_CPLX;
+    case ORC_U_ASIN: case ORC_U_ACOS: case ORC_U_ATAN: case ORC_U_SINH: case ORC_U_COSH: case ORC_U_TANH:
+      return k == K_REAL; /* the inverse and hyperbolic functions are built for real types only */
     default: return 0;
   }
 }
@@ -540,6 +542,12 @@ static val_t apply_elementary(int op, int T, val_t a) {
       case ORC_U_TAN: y = tan(a.re); break;
       case ORC_U_EXP: y = exp(a.re); break;
       case ORC_U_LOG: y = log(a.re); break;
+      case ORC_U_ASIN: y = asin(a.re); break;
+      case ORC_U_ACOS: y = acos(a.re); break;
+      case ORC_U_ATAN: y = atan(a.re); break;
+      case ORC_U_SINH: y = sinh(a.re); break;
+      case ORC_U_COSH: y = cosh(a.re); break;
+      case ORC_U_TANH: y = tanh(a.re); break;
     }
     r.re = round_arith(t, y);
   } else {
@@ -597,6 +605,7 @@ static val_t apply_unary(int op, int T, val_t a) {
       r.re = r_sqrt(arith_of(T), a.re);
       break;
     case ORC_U_SIN: case ORC_U_COS: case ORC_U_TAN: case ORC_U_EXP: case ORC_U_LOG:
+    case ORC_U_ASIN: case ORC_U_ACOS: case ORC_U_ATAN: case ORC_U_SINH: case ORC_U_COSH: case ORC_U_TANH:
       return apply_elementary(op, T, a);
   }
   return r;

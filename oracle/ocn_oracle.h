@@ -55,6 +55,7 @@ typedef struct {
 enum { /* unary operations */
   ORC_U_IDENT = 0, ORC_U_NEG, ORC_U_ABS, ORC_U_CONJ, ORC_U_LNOT, ORC_U_BNOT, ORC_U_SQRT,
   ORC_U_SIN, ORC_U_COS, ORC_U_TAN, ORC_U_EXP, ORC_U_LOG, ORC_U_BSWAP,
+  ORC_U_ASIN, ORC_U_ACOS, ORC_U_ATAN, ORC_U_SINH, ORC_U_COSH, ORC_U_TANH,
   ORC_NUM_UNARY
 };
 enum { /* binary operations */

@@ -18,7 +18,8 @@ LIB_PATH = os.path.join(HERE, "libocn.so")
 DTYPES = ("bool", "int8", "int16", "int32", "int64", "uint8", "uint16", "uint32", "uint64",
           "half", "float", "double", "chalf", "cfloat", "cdouble")
 DTYPE_CODE = {n: i for i, n in enumerate(DTYPES)}
-UNARY_OPS = ("ident", "neg", "abs", "conj", "lnot", "bnot", "sqrt", "sin", "cos", "tan", "exp", "log", "bswap")
+UNARY_OPS = ("ident", "neg", "abs", "conj", "lnot", "bnot", "sqrt", "sin", "cos", "tan", "exp", "log", "bswap",
+             "asin", "acos", "atan", "sinh", "cosh", "tanh")
 BINARY_OPS = ("add", "sub", "mul", "div", "min", "max", "band", "bor", "bxor", "land", "lor",
               "lxor", "eq", "ne", "lt", "le", "gt", "ge", "absgt")
 REDUCE_OPS = ("sum", "prod", "min", "max", "any", "all")

@@ -20,7 +20,8 @@ static_assert(B_ADD == OCN_B_ADD && B_MAX == OCN_B_MAX && B_BAND == OCN_B_BAND &
               "binary op numbering");
 static_assert(U_IDENT == OCN_U_IDENT && U_NEG == OCN_U_NEG && U_ABS == OCN_U_ABS && U_CONJ == OCN_U_CONJ &&
               U_LNOT == OCN_U_LNOT && U_BNOT == OCN_U_BNOT && U_SQRT == OCN_U_SQRT && U_SIN == OCN_U_SIN &&
-              U_LOG == OCN_U_LOG && U_BSWAP == OCN_U_BSWAP && U_COUNT == OCN_NUM_UNARY,
+              U_LOG == OCN_U_LOG && U_BSWAP == OCN_U_BSWAP && U_ASIN == OCN_U_ASIN &&
+              U_TANH == OCN_U_TANH && U_COUNT == OCN_NUM_UNARY,
               "unary op numbering");
 static_assert(R_SUM == OCN_R_SUM && R_PROD == OCN_R_PROD && R_MIN == OCN_R_MIN && R_MAX == OCN_R_MAX &&
               R_ANY == OCN_R_ANY && R_ALL == OCN_R_ALL && R_COUNT == OCN_NUM_REDUCE, "reduce op numbering");
@@ -202,17 +203,29 @@ int ocn_plan_reduce(int op, const ocn_tensor *a, const int32_t *axes, int32_t na
 
 // all-zero bytes read as the value 0 of every dtype: the scalar the domain check compares with
 static __device__ __align__(16) unsigned char g_zero_scalar[16];
+// the value 1 in every dtype (little-endian bytes), one 16-byte slot each, in dtype order
+static __device__ __align__(16) unsigned char g_one_scalars[DT_COUNT][16] = {
+    {1}, {1}, {1, 0}, {1, 0, 0, 0}, {1, 0, 0, 0, 0, 0, 0, 0},                      // bool, int8..int64
+    {1}, {1, 0}, {1, 0, 0, 0}, {1, 0, 0, 0, 0, 0, 0, 0},                           // uint8..uint64
+    {0x00, 0x3c}, {0, 0, 0x80, 0x3f}, {0, 0, 0, 0, 0, 0, 0xf0, 0x3f},              // half, float, double
+    {0x00, 0x3c, 0, 0}, {0, 0, 0x80, 0x3f, 0, 0, 0, 0},                            // chalf, cfloat
+    {0, 0, 0, 0, 0, 0, 0xf0, 0x3f, 0, 0, 0, 0, 0, 0, 0, 0}};                       // cdouble
 
 static int domain_plan(int op, const ocn_tensor *a, const ocn_tensor *flag, char *workspace, FusedPlan *fp, bool *trivial) {
   if (!a || !flag) return OCN_ERR_NULLPTR;
   if (op < 0 || op >= U_COUNT) return OCN_ERR_OP;
   if (flag->dtype != DT_BOOL || flag->ndim != 0) return OCN_ERR_SHAPE;
-  *trivial = !(op == U_SQRT || op == U_LOG);
+  const bool negative = op == U_SQRT || op == U_LOG, above_one = op == U_ASIN || op == U_ACOS;
+  *trivial = !(negative || above_one);
   if (*trivial) return OCN_OK;
+  if (a->dtype < 0 || a->dtype >= DT_COUNT) return OCN_ERR_DTYPE;
   if (dt_kind(a->dtype) == K_CPLX || dt_kind(a->dtype) == K_BOOL) { *trivial = true; return OCN_OK; }
   void *zero = nullptr;
-  if (workspace) {  // a real call (not a size query): the device address of the zero scalar
-    if (hipGetSymbolAddress(&zero, HIP_SYMBOL(g_zero_scalar)) != hipSuccess || !zero) return finish(hipGetLastError());
+  if (workspace) {  // a real call (not a size query): the device address of the scalar compared with
+    const hipError_t e = negative ? hipGetSymbolAddress(&zero, HIP_SYMBOL(g_zero_scalar))
+                                  : hipGetSymbolAddress(&zero, HIP_SYMBOL(g_one_scalars));
+    if (e != hipSuccess || !zero) return finish(hipGetLastError());
+    if (above_one) zero = (char *)zero + 16 * a->dtype;
   } else {
     zero = (void *)((uintptr_t)1 << 60);  // size query: stand-in addresses far from the temporary's
   }
@@ -224,7 +237,7 @@ static int domain_plan(int op, const ocn_tensor *a, const ocn_tensor *flag, char
   z.device = a->device;
   int32_t axes[OCN_MAX_DIMS];
   for (int d = 0; d < a->ndim && d < OCN_MAX_DIMS; ++d) axes[d] = d;
-  return plan_binary_reduce(B_LT, R_ANY, a, &z, axes, a->ndim, flag, DT_BOOL, workspace, fp);
+  return plan_binary_reduce(negative ? B_LT : B_ABSGT, R_ANY, a, &z, axes, a->ndim, flag, DT_BOOL, workspace, fp);
 }
 
 size_t ocn_domain_check_workspace_bytes(int op, const ocn_tensor *a) {

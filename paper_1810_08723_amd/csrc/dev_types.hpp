@@ -357,13 +357,25 @@ template <int OP, class F> OCN_DEV F elementary_real(F x) {
     else if constexpr (OP == U_COS) return cosf(x);
     else if constexpr (OP == U_TAN) return tanf(x);
     else if constexpr (OP == U_EXP) return expf(x);
-    else return logf(x);
+    else if constexpr (OP == U_LOG) return logf(x);
+    else if constexpr (OP == U_ASIN) return asinf(x);
+    else if constexpr (OP == U_ACOS) return acosf(x);
+    else if constexpr (OP == U_ATAN) return atanf(x);
+    else if constexpr (OP == U_SINH) return sinhf(x);
+    else if constexpr (OP == U_COSH) return coshf(x);
+    else return tanhf(x);
   } else {
     if constexpr (OP == U_SIN) return sin(x);
     else if constexpr (OP == U_COS) return cos(x);
     else if constexpr (OP == U_TAN) return tan(x);
     else if constexpr (OP == U_EXP) return exp(x);
-    else return log(x);
+    else if constexpr (OP == U_LOG) return log(x);
+    else if constexpr (OP == U_ASIN) return asin(x);
+    else if constexpr (OP == U_ACOS) return acos(x);
+    else if constexpr (OP == U_ATAN) return atan(x);
+    else if constexpr (OP == U_SINH) return sinh(x);
+    else if constexpr (OP == U_COSH) return cosh(x);
+    else return tanh(x);
   }
 }
 

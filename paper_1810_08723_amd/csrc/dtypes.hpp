@@ -36,7 +36,8 @@ enum : int {  // numbering shared with the public header (checked by static_asse
   B_ADD = 0, B_SUB, B_MUL, B_DIV, B_MIN, B_MAX, B_BAND, B_BOR, B_BXOR, B_LAND, B_LOR, B_LXOR,
   B_EQ, B_NE, B_LT, B_LE, B_GT, B_GE, B_ABSGT, B_COUNT
 };
-enum : int { U_IDENT = 0, U_NEG, U_ABS, U_CONJ, U_LNOT, U_BNOT, U_SQRT, U_SIN, U_COS, U_TAN, U_EXP, U_LOG, U_BSWAP, U_COUNT };
+enum : int { U_IDENT = 0, U_NEG, U_ABS, U_CONJ, U_LNOT, U_BNOT, U_SQRT, U_SIN, U_COS, U_TAN, U_EXP, U_LOG, U_BSWAP,
+              U_ASIN, U_ACOS, U_ATAN, U_SINH, U_COSH, U_TANH, U_COUNT };
 enum : int { R_SUM = 0, R_PROD, R_MIN, R_MAX, R_ANY, R_ALL, R_COUNT };
 
 OCN_HD constexpr bool is_arith(int op) { return op >= B_ADD && op <= B_MAX; }
@@ -63,6 +64,7 @@ OCN_HD constexpr bool unary_supported(int op, int T) {
     case U_BNOT: case U_BSWAP: return k == K_BOOL || k == K_SINT || k == K_UINT;
     case U_SQRT: return k == K_REAL || k == K_CPLX;
     case U_SIN: case U_COS: case U_TAN: case U_EXP: case U_LOG: return k == K_REAL || k == K_CPLX;
+    case U_ASIN: case U_ACOS: case U_ATAN: case U_SINH: case U_COSH: case U_TANH: return k == K_REAL;
     default: return false;
   }
 }

@@ -69,7 +69,8 @@ template <int T> OCN_DEV void interp_body(const InterpArgs &p, const char *pa, c
 #define OCN_CASE(O) case O: unary_one<T, O>(p, a, po); break;
       OCN_CASE(U_IDENT) OCN_CASE(U_NEG) OCN_CASE(U_ABS) OCN_CASE(U_CONJ) OCN_CASE(U_LNOT)
       OCN_CASE(U_BNOT) OCN_CASE(U_SQRT) OCN_CASE(U_SIN) OCN_CASE(U_COS) OCN_CASE(U_TAN) OCN_CASE(U_EXP)
-      OCN_CASE(U_LOG) OCN_CASE(U_BSWAP)
+      OCN_CASE(U_LOG) OCN_CASE(U_BSWAP) OCN_CASE(U_ASIN) OCN_CASE(U_ACOS) OCN_CASE(U_ATAN) OCN_CASE(U_SINH)
+      OCN_CASE(U_COSH) OCN_CASE(U_TANH)
 #undef OCN_CASE
       default: break;
     }

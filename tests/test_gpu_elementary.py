@@ -30,6 +30,10 @@ def _run(op, a: View, out: View):
 
 
 def _inputs(rng, op, n, comp):
+    if op in ("asin", "acos"):
+        return rng.uniform(-1, 1, n).astype(comp)
+    if op in ("sinh", "cosh", "tanh"):
+        return rng.uniform(-8, 8, n).astype(comp)
     if op == "log":
         x = np.exp(rng.uniform(-8, 8, n))
     elif op == "exp":
@@ -61,7 +65,7 @@ def _check_complex(got, want, dt):
 
 
 @pytest.mark.parametrize("dt", tuple(REAL))
-@pytest.mark.parametrize("op", ("sin", "cos", "tan", "exp", "log"))
+@pytest.mark.parametrize("op", ("sin", "cos", "tan", "exp", "log", "asin", "acos", "atan", "sinh", "cosh", "tanh"))
 def test_real_elementary_functions(op, dt):
     rng = rng_for(16000)
     comp = REAL[dt]

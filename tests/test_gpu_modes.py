@@ -56,6 +56,24 @@ def test_domain_check(dt):
         assert bool(ocn.domain_check("log", H.DeviceViews().tensor(w)).cpu()[0])
 
 
+@pytest.mark.parametrize("dt", ("float", "double", "half", "int16"))
+def test_domain_check_of_inverse_sine_and_cosine(dt):
+    import paper_1810_08723_amd as ocn
+    rng = rng_for(18200)
+    npdt = {"float": np.float32, "double": np.float64, "half": np.float16, "int16": np.int16}[dt]
+    x = (rng.uniform(-1, 1, (200, 130)) if dt != "int16" else rng.integers(-1, 2, (200, 130))).astype(npdt)
+    for plant in (None, (0, 0), (199, 129)):
+        y = x.copy()
+        if plant is not None:
+            y[plant] = npdt(2) if dt == "int16" else np.nextafter(npdt(1), npdt(2))
+        for view in (View.from_numpy(y), View.from_numpy(y).permute(1, 0)):
+            dv = H.DeviceViews()
+            for op in ("asin", "acos", "atan", "cosh"):
+                flag = ocn.domain_check(op, dv.tensor(view))
+                dv.torch.cuda.synchronize()
+                assert bool(flag.cpu()[0]) == O.domain_check(op, view), (dt, plant, op)
+
+
 def test_domain_check_on_complex_is_always_clear():
     import paper_1810_08723_amd as ocn
     z = View.from_numpy(np.array([-1 + 0j, -2 - 3j], dtype=np.complex64))

@@ -293,3 +293,12 @@ def test_domain_check():
     assert not O.domain_check("sqrt", View.from_numpy(y))
     assert O.domain_check("sqrt", View.from_numpy(np.array([-np.inf])))
     assert O.domain_check("log", View.from_numpy(np.array([3, -1, 2], dtype=np.int32)))
+    # the inverse sine and cosine are defined on [-1, 1]
+    u = rng.uniform(-1, 1, (30, 20)).astype(np.float32)
+    u[0, 0], u[29, 19] = 1.0, -1.0
+    assert not O.domain_check("acos", View.from_numpy(u)) and not O.domain_check("asin", View.from_numpy(u))
+    u[11, 7] = np.float32(-1.0000001)
+    assert O.domain_check("acos", View.from_numpy(u)) and O.domain_check("asin", View.from_numpy(u).permute(1, 0))
+    assert not O.domain_check("atan", View.from_numpy(u)) and not O.domain_check("tanh", View.from_numpy(u))
+    assert O.domain_check("asin", View.from_numpy(np.array([0, 2, 1], dtype=np.int16)))
+    assert not O.domain_check("asin", View.from_numpy(np.array([np.nan, 0.5], dtype=np.float64)))
