@@ -42,6 +42,7 @@ static void ensure_registered() {
 }
 
 static thread_local int g_last_hip_error = 0;
+void record_hip_error(int code) { g_last_hip_error = code; }
 
 static int finish(hipError_t e) {
   if (e == hipSuccess) return OCN_OK;

@@ -269,10 +269,9 @@ template <int ES, bool SCATTER> __global__ __launch_bounds__(kBlock) void gather
   *reinterpret_cast<Bytes<ES> *>(p.dst + od) = *reinterpret_cast<const Bytes<ES> *>(p.src + os);
 }
 
-thread_local int g_index_hip_error = 0;
 int done(hipError_t e) {
   if (e == hipSuccess) return OCN_OK;
-  g_index_hip_error = (int)e;
+  record_hip_error((int)e);
   return OCN_ERR_LAUNCH;
 }
 

@@ -127,6 +127,9 @@ int promote(int a, int b);
 int reduce_acc_dtype(int op, int in_dtype);
 bool reduce_supported(int op, int in_dtype);
 
+// remembers a failed HIP call for ocn_last_hip_error (per host thread)
+void record_hip_error(int code);
+
 void fill_info(const EwPlan &p, ocn_plan_info *info);
 void fill_info(const RedPlan &p, ocn_plan_info *info);
 
