@@ -84,3 +84,18 @@ def test_tile_smaller_than_a_batch_of_passes():
     rng = rng_for(13006)
     b = random_view(rng, "float", (32, 8)).permute(1, 0)
     H.check_binary("add", random_view(rng, "float", (8, 32)), b, View.empty("float", (8, 32)))
+
+
+def test_diagonal_views():
+    # the diagonal of a matrix is a 1-D view whose stride is the sum of the two strides
+    rng = rng_for(13010)
+    m = random_view(rng, "double", (130, 130), specials=False)
+    diag = View(m.storage, "double", (130,), (m.strides[0] + m.strides[1],), m.offset)
+    H.check_unary("neg", diag, View.empty("double", (130,)))             # read the diagonal
+    ones = View.from_numpy(np.ones((), dtype=np.float64))
+    H.check_binary("add", diag, ones, diag)                              # update it in place
+    anti = View(m.storage, "double", (130,), (m.strides[0] - m.strides[1],), m.offset + 129 * m.strides[1])
+    H.check_binary("mul", diag, anti, View.empty("double", (130,)))     # diagonal times anti-diagonal
+    r = View.empty("double", ())
+    got, want = H.run_reduce("sum", diag, [0], r)                        # the trace
+    assert np.allclose(got.view(np.float64), want.view(np.float64), rtol=1e-13)
