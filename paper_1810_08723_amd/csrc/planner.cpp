@@ -214,24 +214,27 @@ void tile_order(const EwPlan &p, const int64_t *stride, int8_t *ord) {
     for (int j = i; j > 0 && key(ord[j]) < key(ord[j - 1]); --j) std::swap(ord[j], ord[j - 1]);
 }
 
-// LDS per workgroup, so that several share a CU's 160 KB.  With both inputs staged a tile goes
-// through three dependent phases (two staging round trips, then compute), and halving the tile
-// so that twice as many workgroups are resident measured faster on MI355X.
+// LDS per workgroup, so that several share a CU's 160 KB: a tile grows to the run lengths every
+// operand wants within 32 KiB, and beyond that only while it stays within 16 KiB (more
+// resident workgroups measured faster than larger tiles on MI355X).
 constexpr int64_t kMaxLdsBytes = 32 * 1024;
-constexpr int64_t kMaxLdsBytesTwoStaged = 16 * 1024;
+constexpr int64_t kPreferredLdsBytes = 16 * 1024;
 
 void choose_tiles(EwPlan &p) {
   // Operands that want coalescing along their own fastest axis: the output and every staged
   // input.  Tile bits are handed out one at a time, each to the fastest unsaturated dimension
-  // of one operand, until the tile holds 2^budget elements.  First every staged input is grown
-  // to a contiguous run of a full 128-byte cache line (a shorter read run still fetches the
-  // whole line, and the other half is fetched again by a neighbouring tile) and the output to
-  // 64 bytes (partial-line writes cost no extra traffic); the remaining bits go round-robin.
+  // of one operand.  First every staged input is grown to a contiguous run of a full 128-byte
+  // cache line (a shorter read run still fetches the whole line, and the other half is fetched
+  // again by a neighbouring tile); the output to a full line as well when it is written with
+  // streaming stores (partial-line streaming writes run at half rate), else to 64 bytes
+  // (partial-line writes into the cache cost no extra traffic).  The remaining bits go
+  // round-robin while the staging areas stay within the preferred LDS footprint.
   const int es[3] = {dt_size(p.out.dtype), dt_size(p.a.dtype), p.nin == 2 ? dt_size(p.b.dtype) : 1};
   const int staged_bytes = (p.stage_a ? es[1] : 0) + (p.stage_b ? es[2] : 0);
   int budget = 12;
-  const int64_t lds_cap = (p.stage_a && p.stage_b) ? kMaxLdsBytesTwoStaged : kMaxLdsBytes;
-  while (budget > 8 && ((int64_t)staged_bytes << budget) > lds_cap) --budget;
+  while (budget > 8 && ((int64_t)staged_bytes << budget) > kMaxLdsBytes) --budget;
+  int preferred = budget;
+  while (preferred > 8 && ((int64_t)staged_bytes << preferred) > kPreferredLdsBytes) --preferred;
   const int64_t *strides[3] = {p.out.stride, p.a.stride, p.b.stride};
   const bool wants[3] = {true, p.stage_a, p.stage_b};
   int used = 0;
@@ -268,7 +271,7 @@ void choose_tiles(EwPlan &p) {
     }
     return run;
   };
-  const int64_t target[3] = {64, 128, 128};
+  const int64_t target[3] = {p.nt_store ? 128 : 64, 128, 128};
   bool progress = true;
   while (used < budget && progress) {
     progress = false;
@@ -276,9 +279,9 @@ void choose_tiles(EwPlan &p) {
       if (wants[o] && run_bytes(o) < target[o] && grow(o)) progress = true;
   }
   progress = true;
-  while (used < budget && progress) {
+  while (used < preferred && progress) {
     progress = false;
-    for (int o = 0; o < 3 && used < budget; ++o)
+    for (int o = 0; o < 3 && used < preferred; ++o)
       if (wants[o] && grow(o)) progress = true;
   }
   p.tile_bits = used;
