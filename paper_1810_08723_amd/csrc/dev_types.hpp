@@ -379,9 +379,9 @@ template <int OP, class F> OCN_DEV F elementary_real(F x) {
   }
 }
 
-template <class F> OCN_DEV void sincos_any(F x, F &s, F &c) {
-  if constexpr (sizeof(F) == 4) { s = sinf(x); c = cosf(x); }
-  else { s = sin(x); c = cos(x); }
+template <class F> OCN_DEV void sincos_any(F x, F &s, F &c) {  // one argument reduction for both
+  if constexpr (sizeof(F) == 4) sincosf(x, &s, &c);
+  else sincos(x, &s, &c);
 }
 template <class F> OCN_DEV F exp_any(F x) { if constexpr (sizeof(F) == 4) return expf(x); else return exp(x); }
 template <class F> OCN_DEV F log_any(F x) { if constexpr (sizeof(F) == 4) return logf(x); else return log(x); }
