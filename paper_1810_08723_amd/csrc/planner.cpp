@@ -214,11 +214,10 @@ void tile_order(const EwPlan &p, const int64_t *stride, int8_t *ord) {
     for (int j = i; j > 0 && key(ord[j]) < key(ord[j - 1]); --j) std::swap(ord[j], ord[j - 1]);
 }
 
-// LDS per workgroup, so that several share a CU's 160 KB: a tile grows to the run lengths every
-// operand wants within 32 KiB, and beyond that only while it stays within 16 KiB (more
-// resident workgroups measured faster than larger tiles on MI355X).
+// LDS per workgroup, so that several share a CU's 160 KB.  A tile grows to the run lengths its
+// operands want and no further: small tiles, i.e. many resident workgroups, measured faster
+// than large ones on MI355X once every run is a full cache line.
 constexpr int64_t kMaxLdsBytes = 32 * 1024;
-constexpr int64_t kPreferredLdsBytes = 16 * 1024;
 
 void choose_tiles(EwPlan &p) {
   // Operands that want coalescing along their own fastest axis: the output and every staged
@@ -227,14 +226,17 @@ void choose_tiles(EwPlan &p) {
   // cache line (a shorter read run still fetches the whole line, and the other half is fetched
   // again by a neighbouring tile); the output to a full line as well when it is written with
   // streaming stores (partial-line streaming writes run at half rate), else to 64 bytes
-  // (partial-line writes into the cache cost no extra traffic).  The remaining bits go
-  // round-robin while the staging areas stay within the preferred LDS footprint.
+  // (partial-line writes into the cache cost no extra traffic).  After that the tile only
+  // grows, round-robin, until every enumeration order has a whole vector for each of the 256
+  // lanes (which the lean kernel form needs).
   const int es[3] = {dt_size(p.out.dtype), dt_size(p.a.dtype), p.nin == 2 ? dt_size(p.b.dtype) : 1};
   const int staged_bytes = (p.stage_a ? es[1] : 0) + (p.stage_b ? es[2] : 0);
   int budget = 12;
   while (budget > 8 && ((int64_t)staged_bytes << budget) > kMaxLdsBytes) --budget;
-  int preferred = budget;
-  while (preferred > 8 && ((int64_t)staged_bytes << preferred) > kPreferredLdsBytes) --preferred;
+  const int es_min = std::min({es[0], es[1], es[2]}), es_max = std::max({es[0], es[1], p.nin == 2 ? es[2] : es[1]});
+  int vbits = 0;
+  while ((1 << vbits) < rows_vec(es_min, es_max)) ++vbits;
+  const int preferred = std::min(budget, 8 + vbits);
   const int64_t *strides[3] = {p.out.stride, p.a.stride, p.b.stride};
   const bool wants[3] = {true, p.stage_a, p.stage_b};
   int used = 0;

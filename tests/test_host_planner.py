@@ -132,10 +132,11 @@ def test_worked_plan_config5_second_reading():
 def test_unclipped_form_and_staging_budget():
     # configuration 1 (a pure transpose of power-of-two extents) and configuration 5 take the
     # lean form of the tiled kernel.  Tiles grow to full-line runs within 32 KiB of LDS and
-    # beyond that only within 16 KiB.
+    # beyond that only until each of the 256 lanes has a whole vector in every order.
     c1 = configs.config1(8)
     plan = ocn.plan_binary("add", fake(c1.inputs[0], 0), fake(c1.inputs[1], 1), fake(c1.out, 2))
-    assert plan["kernel"] == "ew_tiled" and plan["unclipped"] and plan["lds_bytes"] == 16 * 1024
+    assert plan["kernel"] == "ew_tiled" and plan["unclipped"]
+    assert plan["tile_log2"] == (5, 5) and plan["lds_bytes"] == 4 * 1024   # 128 B runs both ways
     for c in configs.config5() + configs.config5(reading="R2"):
         plan = ocn.plan_binary(c.op, fake(c.inputs[0], 0), fake(c.inputs[1], 1), fake(c.out, 2))
         assert plan["kernel"] == "ew_tiled" and plan["unclipped"], c.name
