@@ -7,7 +7,7 @@
 //                      indices are counted (one integer atomic per wavefront that saw any)
 //   ocn_mask_offsets   stream compaction in the mask's row-major order, three launches and no
 //                      waiting between workgroups: per-workgroup counts, an exclusive scan of
-//                      the counts by one workgroup, then every workgroup writes the offsets of
+//                      the counts by one workgroup (through LDS, coalesced both ways), then every workgroup writes the offsets of
 //                      its selected elements behind its prefix (staged in LDS so that the
 //                      stores are coalesced).  Lanes own 16 consecutive mask bytes (one 128-bit
 //                      load when the mask is contiguous).
@@ -159,28 +159,62 @@ __global__ __launch_bounds__(kBlock) void mask_count_kernel(const MaskArgs p) {
   if (threadIdx.x == 0) p.block_counts[blockIdx.x] = (int64_t)sum;
 }
 
-// one workgroup: block_counts[i] := sum of block_counts[0 .. i), *count := total
+// one workgroup: block_counts[i] := sum of block_counts[0 .. i), *count := total.  Rounds of
+// 1024 x 16 counts: read coalesced into LDS, each lane adds up 16 consecutive ones, the lane
+// sums are scanned with wavefront shuffles, and the prefixes go back through LDS so that the
+// stores are coalesced too.  Counts are at most kMaskChunk and a round's total stays below
+// 2^26, so LDS holds 32-bit values; the carry between rounds is 64-bit.
 __global__ __launch_bounds__(kScanBlock) void mask_scan_kernel(const MaskArgs p) {
-  __shared__ int64_t part[kScanBlock];
-  const uint32_t per = (p.nblocks + kScanBlock - 1) / kScanBlock;
-  const uint32_t lo = threadIdx.x * per, hi = lo + per < p.nblocks ? lo + per : p.nblocks;
-  int64_t s = 0;
-  for (uint32_t i = lo; i < hi; ++i) s += p.block_counts[i];
-  part[threadIdx.x] = s;
-  __syncthreads();
-  for (int d = 1; d < kScanBlock; d <<= 1) {   // Hillis-Steele over the 1024 partial sums
-    const int64_t add = (int)threadIdx.x >= d ? part[threadIdx.x - d] : 0;
+  constexpr int kPer = 16, kRound = kScanBlock * kPer, kWaves = kScanBlock / kWave;
+  __shared__ uint32_t tile[kRound + kRound / kPer];   // one pad word per lane segment: no bank conflicts
+  __shared__ uint32_t wave_sum[kWaves];
+  const int t = threadIdx.x, lane = t & (kWave - 1), wave = t / kWave;
+  int64_t carry = 0;
+  for (int64_t base = 0; base < (int64_t)p.nblocks; base += kRound) {
+#pragma unroll
+    for (int k = 0; k < kPer; ++k) {
+      const int64_t i = base + k * kScanBlock + t;
+      const int j = k * kScanBlock + t;
+      tile[j + j / kPer] = i < (int64_t)p.nblocks ? (uint32_t)p.block_counts[i] : 0u;
+    }
     __syncthreads();
-    part[threadIdx.x] += add;
+    uint32_t own[kPer], s = 0;
+#pragma unroll
+    for (int k = 0; k < kPer; ++k) {
+      own[k] = tile[t * (kPer + 1) + k];
+      s += own[k];
+    }
+    uint32_t inc = s;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+      const uint32_t up = (uint32_t)__shfl_up((int)inc, d, kWave);
+      if (lane >= d) inc += up;
+    }
+    if (lane == kWave - 1) wave_sum[wave] = inc;
     __syncthreads();
+    uint32_t before = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      if (w < wave) before += wave_sum[w];
+      total += wave_sum[w];
+    }
+    uint32_t run = before + inc - s;
+#pragma unroll
+    for (int k = 0; k < kPer; ++k) {
+      tile[t * (kPer + 1) + k] = run;
+      run += own[k];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < kPer; ++k) {
+      const int64_t i = base + k * kScanBlock + t;
+      const int j = k * kScanBlock + t;
+      if (i < (int64_t)p.nblocks) p.block_counts[i] = carry + (int64_t)tile[j + j / kPer];
+    }
+    carry += (int64_t)total;
+    __syncthreads();   // the next round overwrites tile and wave_sum
   }
-  int64_t run = part[threadIdx.x] - s;        // exclusive prefix of this lane's segment
-  for (uint32_t i = lo; i < hi; ++i) {
-    const int64_t c = p.block_counts[i];
-    p.block_counts[i] = run;
-    run += c;
-  }
-  if (threadIdx.x == kScanBlock - 1) *p.count = part[kScanBlock - 1];
+  if (t == 0) *p.count = carry;
 }
 
 __global__ __launch_bounds__(kBlock) void mask_write_kernel(const MaskArgs p) {

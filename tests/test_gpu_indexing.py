@@ -99,6 +99,24 @@ def test_mask_offsets_strided_masks_capacity_and_degenerate():
     assert count == 0
 
 
+def test_mask_offsets_large_by_properties():
+    # more workgroup counts than one round of the scan holds (16384), and a ragged tail.  The
+    # result is the only strictly increasing sequence of `count` selected positions, which is
+    # checked as such; a window at the boundary between the rounds is compared with the oracle.
+    rng = rng_for(17102)
+    n = 16384 * 4096 + 3 * 4096 + 77
+    m = rng.random(n, dtype=np.float32) < 0.02
+    got, count = _mask_offsets_gpu(View.from_numpy(m), (8,), capacity=int(m.sum()) + 5)
+    assert count == int(np.count_nonzero(m))
+    sel = got[:count]
+    assert np.all(sel % 8 == 0) and np.all(np.diff(sel) > 0) and sel[0] >= 0 and sel[-1] < 8 * n
+    assert m[sel // 8].all() and np.all(got[count:] == -7)
+    lo, hi = 16384 * 4096 - 3000, 16384 * 4096 + 3000
+    want = OI.mask_offsets(View.from_numpy(m[lo:hi].copy()), (8,)) + 8 * lo
+    first = int(np.count_nonzero(m[:lo]))
+    assert np.array_equal(sel[first:first + len(want)], want)
+
+
 @pytest.mark.parametrize("dt", ("int8", "half", "float", "double", "cfloat", "cdouble"))
 def test_gather_scatter_elementwise_by_mask(dt):
     import torch
