@@ -617,22 +617,38 @@ void choose_reduce_launch(RedPlan &p) {
   // a flat contiguous full reduction may be longer than 2^31 elements
   const bool flat_full = p.nkept == 0 && p.nred == 1;
 
-  if (p.nred >= 1 && r_fast == es && (k_fast_dim < 0 || k_fast > r_fast) && p.nredtot >= 32 &&
-      (idx32 || flat_full)) {
-    // ---- rows: the reduced axis is the input's fastest ---------------------------------
+  const bool rows_contig = p.nred >= 1 && r_fast == es && (k_fast_dim < 0 || k_fast > r_fast);
+  const bool cols_ok = k_fast_dim >= 0 && k_fast == es && p.kstride_a[k_fast_dim] == es &&
+                       (p.nred == 0 || r_fast == 0 || r_fast > k_fast) && p.nredtot >= 1 && idx32 &&
+                       k_fast_dim == p.nkept - 1 && p.nred >= 1;
+  if (p.nred >= 1 && (idx32 || flat_full) && (rows_contig || !cols_ok)) {
+    // ---- rows: lanes share an output ---------------------------------------------------
+    // With the reduced axis the input's fastest, lanes load whole vectors; any other layout
+    // goes element by element with the innermost reduced stride.
     p.kernel = OCN_KERNEL_RED_ROWS;
-    p.vec = all_aligned((int64_t)vfull * es, -1, p.nred - 1) ? vfull : 1;
+    p.vec = rows_contig && all_aligned((int64_t)vfull * es, -1, p.nred - 1) ? vfull : 1;
     const int64_t n0 = p.rsize[p.nred - 1];
     const int64_t vpr = (n0 + p.vec - 1) / p.vec;         // vectors per innermost run
     const int64_t nvec = vpr * (p.nredtot / n0);          // vectors per output
 #ifndef OCN_ROWS_WAVE_BYTES
 #define OCN_ROWS_WAVE_BYTES (8 * 1024)
 #endif
-    p.group = (nvec * p.vec * es <= OCN_ROWS_WAVE_BYTES) ? kWave : kBlock;
+    int64_t cover = 1;                                    // lanes one output can keep busy
+    while (cover < nvec && cover < kBlock) cover <<= 1;
+    if (rows_contig || k_fast_dim < 0 || r_fast < k_fast) {
+      // neighbouring lanes read neighbouring addends
+      p.group = (nvec * p.vec * es <= OCN_ROWS_WAVE_BYTES) ? (int)std::min<int64_t>(cover, kWave) : kBlock;
+    } else {
+      // a kept axis is faster: neighbouring lanes take neighbouring outputs, and share one
+      // only as far as it takes to fill the device
+      int64_t need = 1;
+      while (need * p.nout < kTargetWaves * kWave && need < cover) need <<= 1;
+      p.group = need > kWave ? kBlock : (int)need;
+    }
     const int64_t groups_per_block = kBlock / p.group;
-    const int64_t waves = p.nout * (p.group / kWave);
+    const int64_t waves = (p.nout * p.group + kWave - 1) / kWave;
     p.split = 1;
-    if (waves < kTargetWaves) {
+    if (p.group >= kWave && waves < kTargetWaves) {
       // split long reductions so the device fills; keep >= 16 vectors per lane per split
       const int64_t want = (kTargetWaves + waves - 1) / waves;
       const int64_t most = std::max<int64_t>(1, nvec / ((int64_t)p.group * 16));
@@ -641,15 +657,18 @@ void choose_reduce_launch(RedPlan &p) {
     p.chunk = (nvec + p.split - 1) / p.split;
     p.split = (nvec + p.chunk - 1) / p.chunk;
     p.grid = (p.nout * p.split + groups_per_block - 1) / groups_per_block;
-  } else if (k_fast_dim >= 0 && k_fast == es && p.kstride_a[k_fast_dim] == es &&
-             (p.nred == 0 || r_fast == 0 || r_fast > k_fast) && p.nredtot >= 1 && idx32 &&
-             k_fast_dim == p.nkept - 1 && p.nred >= 1) {
+  } else if (cols_ok) {
     // ---- cols: a kept axis is the input's fastest; lanes own output columns -------------
     // (requires that axis to be the last canonical kept dim, i.e. also the output's fastest)
     p.kernel = OCN_KERNEL_RED_COLS;
     p.vec = all_aligned((int64_t)vfull * es, p.nkept - 1, -1) ? vfull : 1;
     const int64_t nc = p.ksize[p.nkept - 1];
-    const int64_t colblocks = (nc + (int64_t)kWave * p.vec - 1) / ((int64_t)kWave * p.vec);
+    // few columns: a wavefront covers 64 / cpw rows at a time
+    const int64_t col_lanes = (nc + p.vec - 1) / p.vec;
+    p.cpw = kWave;
+    while (p.cpw > 1 && p.cpw / 2 >= col_lanes) p.cpw /= 2;
+    const int rpw = kWave / p.cpw;
+    const int64_t colblocks = (nc + (int64_t)p.cpw * p.vec - 1) / ((int64_t)p.cpw * p.vec);
     const int64_t others = p.nout / nc;
     const int64_t blocks0 = colblocks * others;
     // Rows are dealt to the wavefronts of a workgroup, which combine through LDS, and to
@@ -658,9 +677,9 @@ void choose_reduce_launch(RedPlan &p) {
     int nw = 4;
     p.split = 1;
     if (blocks0 * nw < kTargetWaves) {
-      if (p.nredtot >= 16 * 64 && blocks0 * 16 * 2 <= kTargetWaves) nw = 16;
+      if (p.nredtot >= 16 * 64 * rpw && blocks0 * 16 * 2 <= kTargetWaves) nw = 16;
       const int64_t want = (kTargetWaves + blocks0 * nw - 1) / (blocks0 * nw);
-      const int64_t most = std::max<int64_t>(1, p.nredtot / (nw * 16));  // >= 16 rows per wave
+      const int64_t most = std::max<int64_t>(1, p.nredtot / ((int64_t)nw * rpw * 16));  // >= 16 rows per lane
       p.split = std::max<int64_t>(1, std::min(want, most));
     }
     p.block = nw * kWave;
@@ -1048,16 +1067,19 @@ void plan_second_pass(const RedPlan &first, char *workspace, RedPlan *second) {
   q.passes = 1;
   q.workspace_bytes = 0;
   q.vec = 1;
-  if (rows_layout && first.split >= 32) {
+  if (rows_layout) {
     q.kernel = OCN_KERNEL_RED_ROWS;
-    q.group = kWave;
+    q.group = 1;                       // lanes per output: the partials of one output are adjacent
+    while (q.group < first.split && q.group < kWave) q.group <<= 1;
     q.chunk = first.split;  // vectors (vec = 1) per output
-    q.grid = (q.nout + (kBlock / kWave) - 1) / (kBlock / kWave);
+    q.grid = (q.nout * q.group + kBlock - 1) / kBlock;
   } else if (!rows_layout && first.nkept >= 1 && q.nout < ((int64_t)1 << 31)) {
     q.kernel = OCN_KERNEL_RED_COLS;
     const int64_t nc = q.ksize[q.nkept - 1];
-    const int64_t colblocks = (nc + kWave - 1) / kWave;
+    while (q.cpw > 1 && q.cpw / 2 >= nc) q.cpw /= 2;
+    const int64_t colblocks = (nc + q.cpw - 1) / q.cpw;
     q.grid = colblocks * (q.nout / nc);
+    if (first.split >= 64) q.block = 16 * kWave;   // many partials per column: more wavefronts share them
   } else {
     q.kernel = OCN_KERNEL_RED_GENERIC;
     q.grid = (q.nout + kBlock - 1) / kBlock;

@@ -82,8 +82,9 @@ struct RedPlan {
   int a_dtype = 0, out_dtype = 0;
   int64_t nout = 0, nredtot = 0;
   int vec = 1;
-  int group = kBlock;           // lanes cooperating on one output (rows kernel): 64 or 256
+  int group = kBlock;           // lanes cooperating on one output (rows kernel): a power of two up to 64, or 256
   int block = kBlock;           // threads per workgroup (the cols kernel may use 1024)
+  int cpw = kWave;              // cols kernel: lanes per row of columns (power of two, at most a wavefront)
   int64_t split = 1;            // partial results per output
   int64_t chunk = 0;            // reduction elements (rows: vectors) per split
   int64_t grid = 0;

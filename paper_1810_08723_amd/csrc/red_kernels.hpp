@@ -1,16 +1,18 @@
 // Reduction kernels of the tensor engine for gfx950 (section 3.2 of the paper: tensor
 // reductions along one or more axes).
 //
-//   red_rows_kernel     the reduced axis is the input's fastest: a wavefront (short rows) or a
-//                       whole workgroup (long rows) streams one output's addends with 128-bit
-//                       loads, lanes fold privately, then a wavefront shuffle tree and an LDS
-//                       step combine them.  Long reductions with few outputs are split over
+//   red_rows_kernel     lanes share an output: a power-of-two group of 1 to 64 lanes (short
+//                       rows: a wavefront then covers several outputs) or a whole workgroup
+//                       (long rows) streams one output's addends, with 128-bit loads when the
+//                       reduced axis is the input's fastest; lanes fold privately, then a
+//                       shuffle tree and an LDS step combine them.  Long reductions with few outputs are split over
 //                       several workgroups; each writes a partial result to the workspace and a
 //                       second launch folds the partials (two-pass grid reduction).
-//   red_cols_kernel     a kept axis is the input's fastest: lanes own adjacent output columns,
-//                       the four wavefronts of a workgroup take interleaved rows and are
-//                       combined through LDS; row ranges can be split the same way.
-//   red_generic_kernel  any layout: one output per lane, sequential fold.
+//   red_cols_kernel     a kept axis is the input's fastest: lanes own adjacent output columns
+//                       (with few columns a wavefront covers several rows at a time), the
+//                       wavefronts of a workgroup take interleaved rows and are combined
+//                       through LDS; row ranges can be split the same way.
+//   red_generic_kernel  any layout and 64-bit extents: one output per lane, sequential fold.
 // No floating-point atomics anywhere: the grouping of addends is fixed by the launch
 // geometry, so results are reproducible bit for bit.
 #pragma once
@@ -41,6 +43,7 @@ struct RedArgs {
   const char *b;
   int64_t ksb[kMaxDims], rsb[kMaxDims];    // its byte strides, same order as ksa / rsa
   int32_t a_bcast, b_bcast;                // broadcast along the vectorised dim
+  int32_t cpw;                             // cols: lanes per row of columns (power of two <= 64)
 };
 
 #if defined(__HIPCC__)
@@ -141,6 +144,15 @@ template <class A> OCN_DEV A shfl_down_any(A v, int delta) {
 template <class R> OCN_DEV typename R::A wave_fold(typename R::A v) {
 #pragma unroll
   for (int d = kWave / 2; d >= 1; d >>= 1) v = R::combine(v, shfl_down_any(v, d));
+  return v;
+}
+
+// the same over aligned groups of `width` lanes (a power of two, the same for the whole
+// wavefront): the first lane of every group ends up with its group's fold
+template <class R> OCN_DEV typename R::A group_fold(typename R::A v, int width) {
+#pragma unroll
+  for (int d = kWave / 2; d >= 1; d >>= 1)
+    if (d < width) v = R::combine(v, shfl_down_any(v, d));
   return v;
 }
 
@@ -347,7 +359,8 @@ OCN_DEV typename Reducer<S, OP>::A rows_accumulate_impl(const RedArgs &p, const 
       off = reduced_offset(p, q, 1);
     }
     e0 = iv * V;
-    return base + off + e0 * (int64_t)sizeof(St);
+    // single elements may be strided along the innermost reduced dim, vectors are contiguous
+    return base + off + e0 * (V == 1 ? p.rsa[0] : (int64_t)sizeof(St));
   };
   int64_t t = t0;
   for (; t + (int64_t)lanes * U <= t_full; t += (int64_t)lanes * U) {
@@ -408,10 +421,13 @@ template <int S, int OP> __global__ __launch_bounds__(kBlock) void red_rows_kern
   const int tid = threadIdx.x;
   const int lane_in_wave = tid & (kWave - 1);
   const int wave = tid / kWave;
-  const bool per_wave = p.group == kWave;
-  const int64_t gidx = per_wave ? (int64_t)blockIdx.x * (kBlock / kWave) + wave : (int64_t)blockIdx.x;
+  // p.group lanes share one output: a whole workgroup, or a power of two up to a wavefront
+  const bool per_block = p.group == kBlock;
+  const int width = per_block ? kWave : p.group;
+  const int64_t gidx = per_block ? (int64_t)blockIdx.x : ((int64_t)blockIdx.x * kBlock + tid) >> (__ffs(width) - 1);
   const int64_t ngroups = p.nout * p.split;
   const bool active = gidx < ngroups;
+  const int lane = per_block ? tid : (lane_in_wave & (width - 1));
   A acc = R::identity();
   int64_t o = 0, s = 0;
   if (active) {
@@ -422,13 +438,12 @@ template <int S, int OP> __global__ __launch_bounds__(kBlock) void red_rows_kern
     const int64_t t0 = s * p.chunk;
     int64_t t1 = t0 + p.chunk;
     if (t1 > p.nvec) t1 = p.nvec;
-    const int lane = per_wave ? lane_in_wave : tid;
-    const int lanes = per_wave ? kWave : kBlock;
+    const int lanes = per_block ? kBlock : width;
     if (p.vec > 1) acc = rows_accumulate<S, OP, VF>(p, p.a + off_a, t0, t1, lane, lanes);
     else acc = rows_accumulate<S, OP, 1>(p, p.a + off_a, t0, t1, lane, lanes);
-    acc = wave_fold<R>(acc);
   }
-  if (!per_wave) {  // combine the four wavefronts of the workgroup
+  acc = group_fold<R>(acc, width);   // every lane takes part, whether its group has work or not
+  if (per_block) {  // combine the four wavefronts of the workgroup
     if (lane_in_wave == 0) lds[wave] = acc;
     __syncthreads();
     if (tid == 0) {
@@ -436,8 +451,7 @@ template <int S, int OP> __global__ __launch_bounds__(kBlock) void red_rows_kern
       for (int w = 1; w < kBlock / kWave; ++w) acc = R::combine(acc, lds[w]);
     }
   }
-  const bool writer = active && (per_wave ? lane_in_wave == 0 : tid == 0);
-  if (writer) {
+  if (active && lane == 0) {
     if (p.split == 1) {
       int64_t off_a, off_o;
       kept_offsets(p, (uint32_t)o, off_a, off_o);
@@ -471,7 +485,12 @@ OCN_DEV void cols_body(const RedArgs &p, typename Reducer<S, OP>::A (*lds)[kWave
   b -= s * per_split;
   const uint32_t other = rfastdiv(b, p.colblocks_div);
   const uint32_t cb = b - other * p.colblocks_div.d;
-  const int64_t col0 = ((int64_t)cb * kWave + lane) * V;
+  // p.cpw lanes (a power of two) cover one row of columns; with fewer than 64 of them a
+  // wavefront takes 64 / cpw rows at a time
+  const int cpw_log2 = __ffs(p.cpw) - 1;
+  const int lc = lane & (p.cpw - 1), lr = lane >> cpw_log2;
+  const int RPW = kWave >> cpw_log2;
+  const int64_t col0 = ((int64_t)cb * p.cpw + lc) * V;
   const int64_t left = p.nc - col0;
   const int ncol = left >= V ? V : (left > 0 ? (int)left : 0);
 
@@ -499,38 +518,47 @@ OCN_DEV void cols_body(const RedArgs &p, typename Reducer<S, OP>::A (*lds)[kWave
   if (r1 > p.nredtot) r1 = p.nredtot;
   constexpr int U = 4;  // rows in flight per wavefront
   struct alignas(sizeof(St) * V >= 16 ? 16 : sizeof(St) * V) Pk { St v[V]; };
-  int64_t r = r0 + wave;
+  const int RS = NW * RPW;           // rows between two rows of the same lane
+  int64_t r = r0 + wave * RPW + lr;
   if (ncol == V) {  // whole vectors of columns: no per-element conditions
-    for (; r + (int64_t)(U - 1) * NW < r1; r += NW * U) {
+    for (; r + (int64_t)(U - 1) * RS < r1; r += RS * U) {
       Pk pk[U];
 #pragma unroll
       for (int u = 0; u < U; ++u)
-        load_vec<St, V>(p.a + off_a + reduced_offset(p, (uint32_t)(r + (int64_t)u * NW), 0), pk[u]);
+        load_vec<St, V>(p.a + off_a + reduced_offset(p, (uint32_t)(r + (int64_t)u * RS), 0), pk[u]);
 #pragma unroll
       for (int u = 0; u < U; ++u)
 #pragma unroll
         for (int i = 0; i < V; ++i) acc[i] = R::combine(acc[i], R::lift(from_storage<S>(pk[u].v[i])));
     }
-    for (; r < r1; r += NW) {
+    for (; r < r1; r += RS) {
       Pk pk;
       load_vec<St, V>(p.a + off_a + reduced_offset(p, (uint32_t)r, 0), pk);
 #pragma unroll
       for (int i = 0; i < V; ++i) acc[i] = R::combine(acc[i], R::lift(from_storage<S>(pk.v[i])));
     }
   } else if (ncol > 0) {  // the ragged last column block
-    for (; r < r1; r += NW) {
+    for (; r < r1; r += RS) {
       const char *src = p.a + off_a + reduced_offset(p, (uint32_t)r, 0);
 #pragma unroll
       for (int i = 0; i < V; ++i)
         if (i < ncol) acc[i] = R::combine(acc[i], R::lift(from_storage<S>(reinterpret_cast<const St *>(src)[i])));
     }
   }
+  // lanes of a wavefront that hold the same columns of different rows: fold onto the first
+  if (RPW > 1) {
+#pragma unroll
+    for (int i = 0; i < V; ++i)
+#pragma unroll
+      for (int d = kWave / 2; d >= 1; d >>= 1)
+        if (d >= p.cpw) acc[i] = R::combine(acc[i], shfl_down_any(acc[i], d));
+  }
   // combine the wavefronts (same columns, different rows), one column of the vector at a time
 #pragma unroll
   for (int i = 0; i < V; ++i) {
     lds[wave][lane] = acc[i];
     __syncthreads();
-    if (wave == 0 && i < ncol) {
+    if (wave == 0 && lr == 0 && i < ncol) {
       A v = lds[0][lane];
       for (int w = 1; w < NW; ++w) v = R::combine(v, lds[w][lane]);
       if (p.split == 1) {

@@ -48,7 +48,8 @@ RedArgs make_red_args(const RedPlan &p, char *partial) {
     r.nvec = vpr * (p.nredtot / r.n0);
   } else if (p.kernel == OCN_KERNEL_RED_COLS) {
     r.nc = p.ksize[p.nkept - 1];
-    const int64_t colblocks = (r.nc + (int64_t)kWave * p.vec - 1) / ((int64_t)kWave * p.vec);
+    r.cpw = p.cpw;
+    const int64_t colblocks = (r.nc + (int64_t)p.cpw * p.vec - 1) / ((int64_t)p.cpw * p.vec);
     r.colblocks_div = make_fastdiv((uint32_t)colblocks);
   }
   return r;

@@ -115,3 +115,11 @@ def run_binary_reduce(ew_op: str, red_op: str, a: View, b: View, axes: Sequence[
     got = dv.download(out)
     O.binary_reduce(ew_op, red_op, a, b, list(axes), out, mid_dtype)
     return got, out.storage
+
+
+def plan_reduce(op: str, a: View, axes: Sequence[int], out: View) -> dict:
+    """The planner's decision for a reduction (no launch; stand-in base addresses)."""
+    import paper_1810_08723_amd as ocn
+    ta = ocn.Tensor(1 << 40, a.dtype, a.sizes, a.strides, a.offset, 0)
+    to = ocn.Tensor(1 << 41, out.dtype, out.sizes, out.strides, out.offset, 0)
+    return ocn.plan_reduce(op, ta, list(axes), to)

@@ -222,3 +222,80 @@ def test_kept_axis_fastest_with_reversed_output():
     out = View.empty("double", (257,)).flip(0)
     got, want = H.run_reduce("sum", f, [0], out)
     assert np.allclose(got.view(np.float64), want.view(np.float64), rtol=1e-12, atol=1e-9)
+
+
+@pytest.mark.parametrize("row", (1, 2, 3, 4, 7, 16, 33, 64, 100, 129))
+def test_short_rows_share_a_wavefront(row):
+    # rows shorter than a wavefront's worth of vectors: groups of 1 .. 64 lanes per output,
+    # several outputs per wavefront, the last wavefront partly idle
+    rng = rng_for(10320 + row)
+    for dt in ("float", "int8", "half", "double", "cfloat"):
+        a = random_view(rng, dt, (301, row), specials=False)
+        plan = H.plan_reduce("sum", a, [1], View.empty(_acc_dtype("sum", dt), (301,)))
+        assert plan["kernel"] == ("red_rows" if row > 1 else "red_generic"), plan   # a length-1 axis is dropped
+        _check("sum", a, [1])
+        if dt not in ("cfloat",):
+            _check("max", a, [1])
+    # the same rows inside a wider buffer (row stride larger than the row) and misaligned
+    wide = random_view(rng, "float", (150, row + 5), specials=False).slice(1, 1, row + 1, 1)
+    _check("sum", wide, [1])
+
+
+def test_reductions_over_strided_axes_are_parallel():
+    import paper_1810_08723_amd as ocn
+    rng = rng_for(10340)
+    # full reduction of an every-other-element view: lanes share the single output
+    a = random_view(rng, "float", (200001,), specials=False).slice(0, 0, 200001, 2)
+    plan = H.plan_reduce("sum", a, [0], View.empty("double", ()))
+    assert plan["kernel"] == "red_rows" and plan["passes"] == 2, plan
+    _check("sum", a, [0])
+    _check("min", a, [0])
+    i8 = random_view(rng, "int8", (99991,)).slice(0, 3, 99991, 3)
+    _check("sum", i8, [0])
+    # strided along the reduced axis and along the kept axis (no contiguous axis at all)
+    b = random_view(rng, "float", (130, 70, 2), specials=False).select(2, 1)
+    for axes in ([0], [1], [0, 1]):
+        _check("sum", b, axes)
+        _check("max", b, axes)
+    # kept axis faster than the reduced one, but not contiguous: few outputs, long reduction
+    c = random_view(rng, "double", (5000, 12, 2), specials=False).select(2, 0)
+    plan = H.plan_reduce("sum", c, [0], View.empty("double", (12,)))
+    assert plan["kernel"] == "red_rows", plan
+    _check("sum", c, [0])
+    # two reduced axes, neither contiguous, permuted
+    d = random_view(rng, "int32", (40, 9, 50, 2)).select(3, 1).permute(2, 0, 1)
+    for axes in ([0, 1], [1, 2], [0, 2], [0, 1, 2]):
+        _check("sum", d, axes)
+
+
+def test_second_pass_with_few_and_many_partials():
+    rng = rng_for(10350)
+    # rows split into fewer than 32 parts, and kept-fastest columns split into many
+    a = random_view(rng, "float", (3, 300000), specials=False)
+    plan = H.plan_reduce("sum", a, [1], View.empty("double", (3,)))
+    assert plan["passes"] == 2, plan
+    _check("sum", a, [1])
+    b = random_view(rng, "float", (40000, 70), specials=False)
+    plan = H.plan_reduce("sum", b, [0], View.empty("double", (70,)))
+    assert plan["kernel"] == "red_cols" and plan["passes"] == 2 and plan["split"] >= 64, plan
+    _check("sum", b, [0])
+    _check("max", b, [0])
+
+
+@pytest.mark.parametrize("ncol", (1, 2, 3, 5, 8, 16, 31, 40, 64, 100))
+def test_few_columns_share_a_wavefront(ncol):
+    # kept-fastest layouts with fewer column lanes than a wavefront: several rows per wavefront
+    rng = rng_for(10360 + ncol)
+    for dt in ("float", "int8", "double", "half", "cfloat"):
+        a = random_view(rng, dt, (1237, ncol), specials=False)
+        if ncol > 1:
+            plan = H.plan_reduce("sum", a, [0], View.empty(_acc_dtype("sum", dt), (ncol,)))
+            assert plan["kernel"] == "red_cols", plan
+        _check("sum", a, [0])
+        if dt != "cfloat":
+            _check("min", a, [0])
+    # more kept dims in front of the columns, and a long reduction that is split
+    b = random_view(rng, "float", (7, 50, ncol), specials=False)
+    _check("sum", b, [1])
+    c = random_view(rng, "int16", (70000, ncol))
+    _check("sum", c, [0])
