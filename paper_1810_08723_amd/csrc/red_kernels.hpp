@@ -147,12 +147,29 @@ template <class R> OCN_DEV typename R::A wave_fold(typename R::A v) {
   return v;
 }
 
-// the same over aligned groups of `width` lanes (a power of two, the same for the whole
-// wavefront): the first lane of every group ends up with its group's fold
-template <class R> OCN_DEV typename R::A group_fold(typename R::A v, int width) {
+// lane i receives lane i + N of its row of 16 lanes (data-parallel primitive "row shift left";
+// lanes past the end of the row read zero)
+template <int N, class A> OCN_DEV A row_down_any(A v) {
+  constexpr int W = (sizeof(A) + 3) / 4;
+  union { A a; uint32_t w[W]; } u, r;
 #pragma unroll
-  for (int d = kWave / 2; d >= 1; d >>= 1)
-    if (d < width) v = R::combine(v, shfl_down_any(v, d));
+  for (int i = 0; i < W; ++i) u.w[i] = 0;
+  u.a = v;
+#pragma unroll
+  for (int i = 0; i < W; ++i) r.w[i] = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)u.w[i], 0x100 + N, 0xf, 0xf, true);
+  return r.a;
+}
+
+// the same over aligned groups of `width` lanes (a power of two, the same for the whole
+// wavefront): the first lane of every group ends up with its group's fold.  Steps that stay
+// inside a row of 16 lanes use the row shift, which costs one instruction per 32-bit word.
+template <class R> OCN_DEV typename R::A group_fold(typename R::A v, int width) {
+  if (width > 32) v = R::combine(v, shfl_down_any(v, 32));
+  if (width > 16) v = R::combine(v, shfl_down_any(v, 16));
+  if (width > 8) v = R::combine(v, row_down_any<8>(v));
+  if (width > 4) v = R::combine(v, row_down_any<4>(v));
+  if (width > 2) v = R::combine(v, row_down_any<2>(v));
+  if (width > 1) v = R::combine(v, row_down_any<1>(v));
   return v;
 }
 
@@ -340,17 +357,6 @@ OCN_DEV typename Reducer<S, OP>::A rows_accumulate_impl(const RedArgs &p, const 
   using F = VecFold<S, OP, V>;
   using Pk = typename F::Pk;
   constexpr int U = 4;  // independent folds and loads in flight per lane
-  F fold[U];
-#pragma unroll
-  for (int u = 0; u < U; ++u) fold[u].init();
-  // vectors below t_full are known to be whole
-  int64_t t_full = t0;
-  if constexpr (SINGLE) {
-    t_full = p.n0 / V;
-    if (t_full > t1) t_full = t1;
-  } else if (p.n0 % V == 0) {
-    t_full = t1;
-  }
   auto address = [&](int64_t tt, int64_t &e0) -> const char * {
     int64_t off = 0, iv = tt;
     if constexpr (!SINGLE) {
@@ -362,6 +368,38 @@ OCN_DEV typename Reducer<S, OP>::A rows_accumulate_impl(const RedArgs &p, const 
     // single elements may be strided along the innermost reduced dim, vectors are contiguous
     return base + off + e0 * (V == 1 ? p.rsa[0] : (int64_t)sizeof(St));
   };
+  if (t1 - t0 <= lanes) {  // short rows: at most one vector per lane, no loops
+    F one;
+    one.init();
+    const int64_t tt = t0 + lane;
+    if (tt < t1) {
+      Pk pk;
+      int64_t e0;
+      const char *src = address(tt, e0);
+      const int64_t left = p.n0 - e0;
+      if (left >= V) {
+        load_vec<St, V>(src, pk);
+        one.add_full(pk);
+      } else {
+#pragma unroll
+        for (int i = 0; i < V; ++i)
+          if (i < (int)left) pk.v[i] = reinterpret_cast<const St *>(src)[i];
+        one.add_partial(pk, (int)left);
+      }
+    }
+    return one.result();
+  }
+  F fold[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) fold[u].init();
+  // vectors below t_full are known to be whole
+  int64_t t_full = t0;
+  if constexpr (SINGLE) {
+    t_full = p.n0 / V;
+    if (t_full > t1) t_full = t1;
+  } else if (p.n0 % V == 0) {
+    t_full = t1;
+  }
   int64_t t = t0;
   for (; t + (int64_t)lanes * U <= t_full; t += (int64_t)lanes * U) {
     Pk pk[U];
@@ -429,15 +467,19 @@ template <int S, int OP> __global__ __launch_bounds__(kBlock) void red_rows_kern
   const bool active = gidx < ngroups;
   const int lane = per_block ? tid : (lane_in_wave & (width - 1));
   A acc = R::identity();
-  int64_t o = 0, s = 0;
+  int64_t o = 0, s = 0, off_o = 0;
   if (active) {
-    o = p.split == 1 ? gidx : gidx / p.split;
-    s = gidx - o * p.split;
-    int64_t off_a, off_o;
+    int64_t t0 = 0, t1 = p.nvec;
+    o = gidx;
+    if (p.split != 1) {
+      o = gidx / p.split;
+      s = gidx - o * p.split;
+      t0 = s * p.chunk;
+      t1 = t0 + p.chunk;
+      if (t1 > p.nvec) t1 = p.nvec;
+    }
+    int64_t off_a;
     kept_offsets(p, (uint32_t)o, off_a, off_o);
-    const int64_t t0 = s * p.chunk;
-    int64_t t1 = t0 + p.chunk;
-    if (t1 > p.nvec) t1 = p.nvec;
     const int lanes = per_block ? kBlock : width;
     if (p.vec > 1) acc = rows_accumulate<S, OP, VF>(p, p.a + off_a, t0, t1, lane, lanes);
     else acc = rows_accumulate<S, OP, 1>(p, p.a + off_a, t0, t1, lane, lanes);
@@ -453,8 +495,6 @@ template <int S, int OP> __global__ __launch_bounds__(kBlock) void red_rows_kern
   }
   if (active && lane == 0) {
     if (p.split == 1) {
-      int64_t off_a, off_o;
-      kept_offsets(p, (uint32_t)o, off_a, off_o);
       store_result<A>(p.out + off_o, p.out_dtype, acc);
     } else {
       reinterpret_cast<typename R::P *>(p.partial)[o * p.split + s] = to_storage<R::ACC>(acc);
