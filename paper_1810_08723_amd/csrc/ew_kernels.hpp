@@ -210,7 +210,7 @@ template <int OP, int SA, int SB, int SO, int NIN> struct Sig {
   static constexpr int ES_MAX = imax(imax((int)sizeof(SAt), (int)sizeof(SOt)), NIN == 2 ? (int)sizeof(SBt) : 1);
   static constexpr bool NIN2 = NIN == 2;
   static constexpr int SA_DT = SA, SB_DT = SB, SO_DT = SO;
-  static constexpr int V = rows_vec(ES_MIN, ES_MAX);
+  static constexpr int V = rows_vec((int)sizeof(SOt), ES_MAX);
   static constexpr int U = rows_unroll(V, ES_MAX);
 
   OCN_DEV static SOt eval(SAt a, SBt b) {

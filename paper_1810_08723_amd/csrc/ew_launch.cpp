@@ -88,8 +88,9 @@ TiledArgs make_tiled_args(const EwPlan &p, int es_a) {
     }
   }
   // XOR swizzle of a staged operand's LDS slots: the vector index along the operand's own
-  // fastest dim is folded into the low slot bits, at 16-byte granularity when the compute
-  // phase reads whole vectors and at element granularity otherwise
+  // fastest dim is folded into the low slot bits, at the granularity of one LDS access of the
+  // compute phase (the elements of a vector, at most 16 bytes), over as many bits as it takes
+  // to spread the accesses of a wavefront over 128 bytes of banks
   auto make_swizzle = [&](const TileOrder &o, int es) {
     TileSwizzle z{0, 0, 0};
     if (p.nord == 0) return z;
@@ -97,8 +98,9 @@ TiledArgs make_tiled_args(const EwPlan &p, int es_a) {
     const int w_0 = p.tile_log2[p.ord_o[0]];         // bits of the output's fastest dim
     int dst = 0, want = 5;
     if (p.vecw_o > 0) {
-      while ((1 << dst) * es < 16) ++dst;            // keep 16-byte groups intact
-      want = 3;
+      while (dst < p.vecw_o && (2 << dst) * es <= 16) ++dst;   // keep the groups read at once intact
+      want = 0;
+      while (((es << dst) << want) < 128) ++want;
     }
     if (dst > w_0) dst = w_0;
     int bits = std::min(want, std::min(w_f, w_0 - dst));

@@ -233,9 +233,10 @@ void choose_tiles(EwPlan &p) {
   const int staged_bytes = (p.stage_a ? es[1] : 0) + (p.stage_b ? es[2] : 0);
   int budget = 12;
   while (budget > 8 && ((int64_t)staged_bytes << budget) > kMaxLdsBytes) --budget;
-  const int es_min = std::min({es[0], es[1], es[2]}), es_max = std::max({es[0], es[1], p.nin == 2 ? es[2] : es[1]});
+  const int es_max = std::max({es[0], es[1], p.nin == 2 ? es[2] : es[1]});
+  const int vmax = std::max({rows_vec(es[0], es_max), p.stage_a ? 16 / es[1] : 1, p.stage_b ? 16 / es[2] : 1});
   int vbits = 0;
-  while ((1 << vbits) < rows_vec(es_min, es_max)) ++vbits;
+  while ((1 << vbits) < vmax) ++vbits;
   const int preferred = std::min(budget, 8 + vbits);
   const int64_t *strides[3] = {p.out.stride, p.a.stride, p.b.stride};
   const bool wants[3] = {true, p.stage_a, p.stage_b};
@@ -390,9 +391,8 @@ int plan_elementwise(int nin, int op, const ocn_tensor *a, const ocn_tensor *b,
   // streaming stores, so that its dirty lines do not burden the next kernel.
   p.nt_store = numel * es_o >= ((int64_t)32 << 20);
   const int inner = n - 1;
-  const int es_min = std::min({es_o, es_a, nin == 2 ? es_b : es_a});
   const int es_max = std::max({es_o, es_a, nin == 2 ? es_b : es_a});
-  const int V = rows_vec(es_min, es_max);
+  const int V = rows_vec(es_o, es_max);
   auto inner_ok = [&](int64_t stride, int es) { return stride == es || stride == 0; };
   bool rows = p.specialised && p.out.stride[inner] == es_o && inner_ok(p.a.stride[inner], es_a) &&
               (nin == 1 || inner_ok(p.b.stride[inner], es_b));
@@ -821,7 +821,7 @@ void choose_fused_launch(RedPlan &p) {
     const int64_t e = elems(p.kstride_a[d], p.kstride_b[d]);
     if (e && (k_fast_dim < 0 || e <= k_fast)) { k_fast = e; k_fast_dim = d; }
   }
-  const int vfull = rows_vec(std::min({es_a, es_b, es_m}), std::max({es_a, es_b, es_m}));
+  const int vfull = rows_vec(es_m, std::max({es_a, es_b, es_m}));  // as Sig::V with the intermediate type as output
   // every stride except the one along the vectorised dim, and the base, are multiples of the
   // vector size of each input that is not broadcast there
   auto all_aligned = [&](int skip_kept, int skip_red, bool a_bcast, bool b_bcast) {

@@ -56,10 +56,14 @@ OCN_HD constexpr bool fused_specialised(int ew_op, int sa, int sb, int mid, int 
 OCN_HD constexpr int imin(int a, int b) { return a < b ? a : b; }
 OCN_HD constexpr int imax(int a, int b) { return a > b ? a : b; }
 
-// Elements per lane access of the rows kernel: the narrowest operand moves 16 bytes, unless
-// that would make the widest operand move more than 64 bytes.
-OCN_HD constexpr int rows_vec(int es_min, int es_max) {
-  return imax(1, imin(16 / es_min, 64 / es_max));
+// Elements per lane access of the elementwise kernels: the output moves 16 bytes, so that
+// every store instruction of a wavefront writes whole cache lines (a wider output vector
+// would be written in several instructions of 16 bytes at a lane stride of the whole vector,
+// i.e. in partial lines, which streaming stores do at a fraction of the rate), unless that
+// would make the widest input move more than 64 bytes.  Inputs narrower than the output are
+// read with accordingly narrower loads.
+OCN_HD constexpr int rows_vec(int es_out, int es_max) {
+  return imax(1, imin(16 / es_out, 64 / es_max));
 }
 // Vectors per lane, so that about 64 bytes of the widest operand are in flight per lane.
 #ifndef OCN_ROWS_MAXU
