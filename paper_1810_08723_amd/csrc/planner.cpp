@@ -219,7 +219,7 @@ void tile_order(const EwPlan &p, const int64_t *stride, int8_t *ord) {
 // than large ones on MI355X once every run is a full cache line.
 constexpr int64_t kMaxLdsBytes = 32 * 1024;
 
-void choose_tiles(EwPlan &p) {
+void choose_tiles(EwPlan &p, bool general_form) {
   // Operands that want coalescing along their own fastest axis: the output and every staged
   // input.  Tile bits are handed out one at a time, each to the fastest unsaturated dimension
   // of one operand.  First every staged input is grown to a contiguous run of a full 128-byte
@@ -228,7 +228,8 @@ void choose_tiles(EwPlan &p) {
   // streaming stores (partial-line streaming writes run at half rate), else to 64 bytes
   // (partial-line writes into the cache cost no extra traffic).  After that the tile only
   // grows, round-robin, until every enumeration order has a whole vector for each of the 256
-  // lanes (which the lean kernel form needs).
+  // lanes (which the lean kernel form needs); for the general form it grows on while the
+  // staging areas stay within 16 KiB.
   const int es[3] = {dt_size(p.out.dtype), dt_size(p.a.dtype), p.nin == 2 ? dt_size(p.b.dtype) : 1};
   const int staged_bytes = (p.stage_a ? es[1] : 0) + (p.stage_b ? es[2] : 0);
   int budget = 12;
@@ -237,7 +238,11 @@ void choose_tiles(EwPlan &p) {
   const int vmax = std::max({rows_vec(es[0], es_max), p.stage_a ? 16 / es[1] : 1, p.stage_b ? 16 / es[2] : 1});
   int vbits = 0;
   while ((1 << vbits) < vmax) ++vbits;
-  const int preferred = std::min(budget, 8 + vbits);
+  int preferred = std::min(budget, 8 + vbits);
+  if (general_form) {  // larger tiles, within 16 KiB of LDS
+    preferred = budget;
+    while (preferred > 8 && ((int64_t)staged_bytes << preferred) > 16 * 1024) --preferred;
+  }
   const int64_t *strides[3] = {p.out.stride, p.a.stride, p.b.stride};
   const bool wants[3] = {true, p.stage_a, p.stage_b};
   int used = 0;
@@ -440,7 +445,22 @@ int plan_elementwise(int nin, int op, const ocn_tensor *a, const ocn_tensor *b,
   const int fb = nin == 2 ? fastest_dim(n, [&](int d) { return p.b.stride[d]; }) : -1;
   p.stage_a = fa >= 0 && fa != fo;
   p.stage_b = fb >= 0 && fb != fo;
-  choose_tiles(p);
+  // First the small tiles that suit the unclipped all-vector form of the tiled kernel.  A plan
+  // that cannot take that form is laid out again for the general form, which wants larger
+  // tiles (its per-tile overhead is higher), and without staging for inputs whose own fastest
+  // axis is shorter than 32 bytes: coalescing along such an axis gains less than the general
+  // form's staging costs (measured on channel-last to channel-first copies with 3 channels).
+  bool stage_a0 = p.stage_a, stage_b0 = p.stage_b;
+  for (int attempt = 0; attempt < 2; ++attempt) {
+  if (attempt == 1) {
+    if (stage_a0 && p.size[fa] * es_a < 32) stage_a0 = false;
+    if (stage_b0 && p.size[fb] * es_b < 32) stage_b0 = false;
+  }
+  p.stage_a = stage_a0;
+  p.stage_b = stage_b0;
+  for (int d = 0; d < kMaxDims; ++d) p.tile_log2[d] = 0;
+  p.fast_tiled = false;
+  choose_tiles(p, attempt == 1);
   tile_order(p, p.out.stride, p.ord_o);
   tile_order(p, p.a.stride, p.ord_a);
   tile_order(p, p.b.stride, p.ord_b);
@@ -519,6 +539,8 @@ int plan_elementwise(int nin, int op, const ocn_tensor *a, const ocn_tensor *b,
     const int64_t lim = ((int64_t)1 << 31) - 64;
     p.fast_tiled = ok && span_o < lim && span_a < lim && span_b < lim;
   }
+  if (p.fast_tiled) break;
+  }  // attempts
   p.vec = 1 << p.vecw_o;
   if (p.total_tiles >= ((int64_t)1 << 31)) {  // tile coordinates are 32-bit: use the 64-bit generic kernel
     p.specialised = false;
