@@ -985,8 +985,8 @@ int plan_binary_reduce(int ew_op, int red_op, const ocn_tensor *a, const ocn_ten
     if (ilo < ohi && olo < ihi) return OCN_ERR_ALIAS;
   }
 
-  if (!fused_specialised(ew_op, a->dtype, b->dtype, mid_dtype, red_op) || nred == 0) {
-    // no fused kernel for these types: elementwise into a temporary, then reduce it
+  // elementwise into a temporary, then reduce it
+  auto plan_unfused = [&]() -> int {
     fp.unfused = true;
     ocn_tensor &m = fp.mid;
     m.base = workspace;
@@ -999,12 +999,15 @@ int plan_binary_reduce(int ew_op, int red_op, const ocn_tensor *a, const ocn_ten
     fp.mid_bytes = ((size_t)acc + 255) / 256 * 256;
     // planned against a stand-in address when the caller only wants sizes
     if (!workspace) m.base = (void *)(uintptr_t)0x1000;
-    if ((rc = plan_elementwise(2, ew_op, a, b, &m, 0, &fp.ew)) != OCN_OK) return rc;
-    if ((rc = plan_reduce(red_op, &m, axes, naxes, out, &fp.red)) != OCN_OK) return rc;
+    int rc2;
+    if ((rc2 = plan_elementwise(2, ew_op, a, b, &m, 0, &fp.ew)) != OCN_OK) return rc2;
+    if ((rc2 = plan_reduce(red_op, &m, axes, naxes, out, &fp.red)) != OCN_OK) return rc2;
     fp.workspace_bytes = fp.mid_bytes + fp.red.workspace_bytes;
     *plan = fp;
     return OCN_OK;
-  }
+  };
+  // no fused kernel for these types
+  if (!fused_specialised(ew_op, a->dtype, b->dtype, mid_dtype, red_op) || nred == 0) return plan_unfused();
 
   const int es_a = dt_size(a->dtype), es_b = dt_size(b->dtype);
   int64_t off_a = a->offset, off_b = b->offset, off_o = out->offset;
@@ -1054,6 +1057,10 @@ int plan_binary_reduce(int ew_op, int red_op, const ocn_tensor *a, const ocn_ten
   p.b_ptr = (char *)b->base + off_b;
   p.out_ptr = (char *)out->base + off_o;
   choose_fused_launch(p);
+  // The fused kernels cover the two layouts with a contiguous axis.  Anything else would fold
+  // each output in a single lane: for long reductions the two-launch route, whose kernels
+  // spread every layout over the device, is faster despite the temporary.
+  if (p.kernel == OCN_KERNEL_RED_GENERIC && p.nredtot >= 1024) return plan_unfused();
   fp.workspace_bytes = p.workspace_bytes;
   *plan = fp;
   return OCN_OK;

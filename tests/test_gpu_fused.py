@@ -200,3 +200,21 @@ def test_fuzz_fused(seed):
         naxes = int(rng.integers(0, nd + 1))
         axes = tuple(sorted(int(x) for x in rng.permutation(nd)[:naxes]))
         _check(ew, red, a, b, axes, mid)
+
+
+def test_layouts_without_a_contiguous_axis_take_two_launches():
+    # neither fused layout applies (every axis strided): with many addends per output the
+    # call goes through the elementwise and reduction kernels, which run any layout in parallel
+    rng = rng_for(16200)
+    a = random_view(rng, "float", (50001,), specials=False).slice(0, 0, 50001, 2)
+    b = random_view(rng, "float", (50001,), specials=False).slice(0, 1, 50001, 2)
+    a, b = a.slice(0, 0, 25000, 1), b.slice(0, 0, 25000, 1)
+    _check("gt", "sum", a, b, [0], "bool", expect_fused=False)
+    _check("mul", "sum", a, b, [0], "float", expect_fused=False)
+    c = random_view(rng, "int32", (3000, 40, 2)).select(2, 1)
+    d = random_view(rng, "int32", (3000, 40, 2)).select(2, 0)
+    _check("mul", "sum", c, d, [0], "int32", expect_fused=False)
+    # few addends: still one fused launch
+    e = random_view(rng, "int32", (8, 40, 2)).select(2, 1)
+    f = random_view(rng, "int32", (8, 40, 2)).select(2, 0)
+    _check("mul", "sum", e, f, [0], "int32", expect_fused=True)

@@ -206,3 +206,46 @@ def test_reduce_plan_preserves_addend_sets(seed):
         for ridx in itertools.product(*[range(s) for s in plan["red_size"]]):
             got.setdefault(oo, []).append(base + sum(i * s for i, s in zip(ridx, plan["red_stride_a"])))
     assert {k: sorted(v) for k, v in raw.items()} == {k: sorted(v) for k, v in got.items()}
+
+
+def test_vector_length_follows_the_output_width():
+    # a lane stores 16 bytes per vector whatever the inputs' widths: widening operations read
+    # narrower pieces, narrowing ones several 16-byte pieces (at most 64 bytes)
+    def vec(din, dout):
+        return ocn.plan_unary("ident", fake(View.empty(din, (1 << 16,)), 0), fake(View.empty(dout, (1 << 16,)), 2))["vec"]
+    assert vec("int8", "int32") == 4 and vec("half", "float") == 4 and vec("float", "double") == 2
+    assert vec("double", "int16") == 8 and vec("double", "float") == 4 and vec("cdouble", "bool") == 4
+    assert vec("float", "float") == 4 and vec("int8", "int8") == 16 and vec("cdouble", "cdouble") == 1
+
+
+def test_general_form_layout_and_short_fastest_axes():
+    # channel-last -> channel-first copy: with 4 channels the all-vector tiled form applies;
+    # with 3 it cannot (3 is not a multiple of any tile extent), and a 12-byte axis is not
+    # worth staging: the input is read in place, along the output's order
+    def nhwc_to_nchw(c):
+        a = View.empty("float", (8, 64, 64, c)).permute(0, 3, 1, 2)
+        return ocn.plan_unary("ident", fake(a, 0), fake(View.empty("float", (8, c, 64, 64)), 2))
+    p4, p3 = nhwc_to_nchw(4), nhwc_to_nchw(3)
+    assert p4["kernel"] == "ew_tiled" and p4["unclipped"] and p4["stage_a"]
+    assert p3["kernel"] == "ew_generic" and not p3["stage_a"] and p3["vec"] == 4
+    # a transpose with odd extents: general form, with the larger tiles it prefers
+    a = View.empty("float", (701, 500)).permute(1, 0)
+    p = ocn.plan_binary("add", fake(a, 0), fake(View.empty("float", (500, 701)), 1), fake(View.empty("float", (500, 701)), 2))
+    assert p["kernel"] == "ew_tiled" and not p["unclipped"] and p["tile_log2"] == (6, 6)
+
+
+def test_reduction_layouts():
+    def plan(a, axes, odt="double"):
+        kept = [s for d, s in enumerate(a.sizes) if d not in axes]
+        return ocn.plan_reduce("sum", fake(a, 0), list(axes), fake(View.empty(odt, kept), 2))
+    # rows of any length, long or short, share lanes; a full reduction of a strided view is
+    # split over workgroups like a contiguous one
+    assert plan(View.empty("float", (1000, 7)), [1])["kernel"] == "red_rows"
+    assert plan(View.empty("float", (1000, 64)), [1])["kernel"] == "red_rows"
+    p = plan(View.empty("float", (1 << 22,)).slice(0, 0, 1 << 22, 2), [0])
+    assert p["kernel"] == "red_rows" and p["passes"] == 2 and p["vec"] == 1
+    # few columns: still the column kernel (several rows per wavefront)
+    p = plan(View.empty("float", (1 << 20, 16)), [0])
+    assert p["kernel"] == "red_cols" and p["passes"] == 2
+    # no contiguous axis at all
+    assert plan(View.empty("float", (300, 50, 2)).select(2, 1), [0])["kernel"] == "red_rows"
