@@ -679,6 +679,8 @@ void choose_reduce_launch(RedPlan &p) {
     p.chunk = (nvec + p.split - 1) / p.split;
     p.split = (nvec + p.chunk - 1) / p.chunk;
     p.grid = (p.nout * p.split + groups_per_block - 1) / groups_per_block;
+    p.short_rows = p.group <= kWave && nvec <= p.group && p.nred == 1 && p.split == 1 &&
+                   p.nout * p.group < ((int64_t)1 << 32) && n0 < ((int64_t)1 << 31);
   } else if (cols_ok) {
     // ---- cols: a kept axis is the input's fastest; lanes own output columns -------------
     // (requires that axis to be the last canonical kept dim, i.e. also the output's fastest)

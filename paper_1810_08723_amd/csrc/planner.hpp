@@ -84,6 +84,7 @@ struct RedPlan {
   int vec = 1;
   int group = kBlock;           // lanes cooperating on one output (rows kernel): a power of two up to 64, or 256
   int block = kBlock;           // threads per workgroup (the cols kernel may use 1024)
+  bool short_rows = false;      // rows kernel: every row fits one vector per lane of its group (loop-free kernel)
   int cpw = kWave;              // cols kernel: lanes per row of columns (power of two, at most a wavefront)
   int64_t split = 1;            // partial results per output
   int64_t chunk = 0;            // reduction elements (rows: vectors) per split

@@ -8,6 +8,7 @@
 //                       shuffle tree and an LDS step combine them.  Long reductions with few outputs are split over
 //                       several workgroups; each writes a partial result to the workspace and a
 //                       second launch folds the partials (two-pass grid reduction).
+//   red_rows_short_kernel  the same for rows of at most one vector per lane, without loops
 //   red_cols_kernel     a kept axis is the input's fastest: lanes own adjacent output columns
 //                       (with few columns a wavefront covers several rows at a time), the
 //                       wavefronts of a workgroup take interleaved rows and are combined
@@ -500,6 +501,54 @@ template <int S, int OP> __global__ __launch_bounds__(kBlock) void red_rows_kern
       reinterpret_cast<typename R::P *>(p.partial)[o * p.split + s] = to_storage<R::ACC>(acc);
     }
   }
+}
+
+// Rows of at most one vector per lane of their group, a single reduced dim, no split: the
+// same groups, loads and fold order as red_rows_kernel without its loops and its 64-bit
+// bookkeeping (short rows are bound by instruction issue, not by memory).
+template <int S, int OP, int V>
+OCN_DEV typename Reducer<S, OP>::A short_row_fold(const RedArgs &p, const char *base, uint32_t lane) {
+  using St = storage_t<S>;
+  using F = VecFold<S, OP, V>;
+  using Pk = typename F::Pk;
+  F one;
+  one.init();
+  if (lane < (uint32_t)p.nvec) {
+    Pk pk;
+    const uint32_t e0 = lane * V;
+    const char *src = base + (int64_t)e0 * (V == 1 ? p.rsa[0] : (int64_t)sizeof(St));
+    const uint32_t left = (uint32_t)p.n0 - e0;
+    if (left >= (uint32_t)V) {
+      load_vec<St, V>(src, pk);
+      one.add_full(pk);
+    } else {
+#pragma unroll
+      for (int i = 0; i < V; ++i)
+        if (i < (int)left) pk.v[i] = reinterpret_cast<const St *>(src)[i];
+      one.add_partial(pk, (int)left);
+    }
+  }
+  return one.result();
+}
+
+template <int S, int OP> __global__ __launch_bounds__(kBlock) void red_rows_short_kernel(const RedArgs p) {
+  using R = Reducer<S, OP>;
+  using A = typename R::A;
+  constexpr int VF = 16 / (int)sizeof(storage_t<S>) > 0 ? 16 / (int)sizeof(storage_t<S>) : 1;
+  const uint32_t width = (uint32_t)p.group;
+  const uint32_t gl = blockIdx.x * kBlock + threadIdx.x;
+  const uint32_t o = gl >> (__ffs(p.group) - 1), lane = gl & (width - 1);
+  const bool active = o < (uint32_t)p.nout;
+  A acc = R::identity();
+  int64_t off_o = 0;
+  if (active) {
+    int64_t off_a;
+    kept_offsets(p, o, off_a, off_o);
+    if (p.vec > 1) acc = short_row_fold<S, OP, VF>(p, p.a + off_a, lane);
+    else acc = short_row_fold<S, OP, 1>(p, p.a + off_a, lane);
+  }
+  acc = group_fold<R>(acc, (int)width);
+  if (active && lane == 0) store_result<A>(p.out + off_o, p.out_dtype, acc);
 }
 
 // ---------------------------------------------------------------------------------------

@@ -19,6 +19,10 @@ template <int S, int OP> hipError_t launch_red(const RedPlan &p, char *partial, 
   const RedArgs args = make_red_args(p, partial);
   switch (p.kernel) {
     case OCN_KERNEL_RED_ROWS:
+      if (p.short_rows) {
+        hipLaunchKernelGGL((red_rows_short_kernel<S, OP>), dim3((unsigned)p.grid), dim3(kBlock), 0, stream, args);
+        break;
+      }
       hipLaunchKernelGGL((red_rows_kernel<S, OP>), dim3((unsigned)p.grid), dim3(kBlock), 0, stream, args);
       break;
     case OCN_KERNEL_RED_COLS:
