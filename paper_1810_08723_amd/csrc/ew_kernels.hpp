@@ -113,6 +113,8 @@ struct InterpArgs {
   int32_t ndim, nin, op, T, dt_a, dt_b, dt_o;
   int64_t size[kMaxDims], so[kMaxDims], sa[kMaxDims], sb[kMaxDims];
   int64_t numel;
+  int32_t idx32;              // fewer than 2^31 elements: 32-bit multiply-shift index arithmetic
+  FastDiv div[kMaxDims];
 };
 
 #if defined(__HIPCC__)

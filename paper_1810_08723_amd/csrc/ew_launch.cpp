@@ -205,6 +205,9 @@ InterpArgs make_interp_args(const EwPlan &p) {
     a.sb[d] = p.b.stride[d];
   }
   a.numel = p.numel;
+  a.idx32 = p.numel < ((int64_t)1 << 31);
+  if (a.idx32)
+    for (int d = 0; d < p.ndim; ++d) a.div[d] = make_fastdiv((uint32_t)p.size[d]);
   return a;
 }
 

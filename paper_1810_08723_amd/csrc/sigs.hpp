@@ -14,13 +14,33 @@ OCN_HD constexpr int binary_compute_dtype(int op, int sa, int sb, int so, int pr
   return is_logical(op) ? (int)DT_BOOL : is_compare(op) ? promoted : so;
 }
 
+// Mixed input types whose +, -, *, / get kernels that convert on load (section 3.2.1: operands
+// of different types are converted to a common one): an integer or narrower float with a
+// float, either with a double, a real with a complex, in both operand orders, computed in the
+// output type.
+struct MixedPair { int sa, sb, so; };
+constexpr MixedPair kMixedPairs[] = {
+    {DT_I32, DT_F32, DT_F32}, {DT_F32, DT_I32, DT_F32}, {DT_F16, DT_F32, DT_F32}, {DT_F32, DT_F16, DT_F32},
+    {DT_F32, DT_F64, DT_F64}, {DT_F64, DT_F32, DT_F64}, {DT_I32, DT_F64, DT_F64}, {DT_F64, DT_I32, DT_F64},
+    {DT_I64, DT_F64, DT_F64}, {DT_F64, DT_I64, DT_F64}, {DT_F32, DT_C32, DT_C32}, {DT_C32, DT_F32, DT_C32},
+    {DT_F64, DT_C64, DT_C64}, {DT_C64, DT_F64, DT_C64}};
+constexpr int kNumMixedPairs = (int)(sizeof(kMixedPairs) / sizeof(kMixedPairs[0]));
+constexpr int kNumMixedOps = 4;  // B_ADD, B_SUB, B_MUL, B_DIV
+static_assert(B_ADD == 0 && B_DIV == 3, "the mixed-type kernels cover the first four binary operations");
+
+OCN_HD constexpr bool mixed_arith_specialised(int op, int sa, int sb, int so) {
+  if (op < 0 || op >= kNumMixedOps) return false;
+  for (int k = 0; k < kNumMixedPairs; ++k)
+    if (kMixedPairs[k].sa == sa && kMixedPairs[k].sb == sb && kMixedPairs[k].so == so) return true;
+  return false;
+}
+
 OCN_HD constexpr bool binary_specialised(int op, int sa, int sb, int so) {
   if (op < 0 || op >= B_COUNT) return false;
   if (is_arith(op) || is_bitwise(op)) {
     if (!binary_supported(op, so)) return false;
     if (sa == so && sb == so) return true;
-    // int32 (x) float -> float arithmetic, converted on load
-    return sa == DT_I32 && sb == DT_F32 && so == DT_F32 && op <= B_DIV;
+    return mixed_arith_specialised(op, sa, sb, so);
   }
   if (is_logical(op)) return sa == DT_BOOL && sb == DT_BOOL && so == DT_BOOL;
   // comparisons: equal input types (so the compute type is that type), bool result

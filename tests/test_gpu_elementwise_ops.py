@@ -83,6 +83,36 @@ def test_mixed_types_through_the_generic_kernel(op, da, db, dout):
         H.check_binary(op, a, b, out)
 
 
+CONVERT_ON_LOAD = [("int32", "float", "float"), ("float", "int32", "float"), ("half", "float", "float"),
+                   ("float", "half", "float"), ("float", "double", "double"), ("double", "float", "double"),
+                   ("int32", "double", "double"), ("double", "int32", "double"), ("int64", "double", "double"),
+                   ("double", "int64", "double"), ("float", "cfloat", "cfloat"), ("cfloat", "float", "cfloat"),
+                   ("double", "cdouble", "cdouble"), ("cdouble", "double", "cdouble")]
+
+
+@pytest.mark.parametrize("da,db,dout", CONVERT_ON_LOAD)
+def test_mixed_types_with_kernels_that_convert_on_load(da, db, dout):
+    import paper_1810_08723_amd as ocn
+    rng = rng_for(9700 + sum(map(ord, da + db + dout)))
+    for op in ("add", "sub", "mul", "div"):
+        for layout in LAYOUTS + ("unclipped", "long rows"):
+            if layout == "unclipped":          # power-of-two transpose: the all-vector tiled form
+                a = random_view(rng, da, (64, 128))
+                b = random_view(rng, db, (128, 64)).permute(1, 0)
+                out = View.empty(dout, (64, 128))
+            elif layout == "long rows":        # several vectors per lane and a ragged tail
+                a = random_view(rng, da, (3, 5003))
+                b = random_view(rng, db, (3, 5003))
+                out = View.empty(dout, (3, 5003))
+            else:
+                a, b, out = _operands(rng, da, db, dout, layout)
+            dv = H.DeviceViews()
+            plan = ocn.plan_binary(op, dv.tensor(a), dv.tensor(b), dv.tensor(out))
+            assert plan["specialised"], (op, da, db, dout, layout)
+            print("mixed", op, da, db, dout, layout, plan["kernel"], flush=True)
+            H.check_binary(op, a, b, out)
+
+
 def test_lnot_and_casts_of_predicates_to_non_bool_outputs():
     rng = rng_for(9700)
     a = random_view(rng, "float", (50, 20))
