@@ -302,6 +302,9 @@ typedef struct {
                                          access is a whole vector (the leaner kernel form)  */
   int64_t fused;                      /* ocn_binary_reduce: 1 when one fused kernel does the
                                          elementwise step and the reduction                 */
+  int64_t tile_group;                 /* tiled kernel: consecutive tiles that share cache
+                                         lines of an input and are started on one XCD
+                                         (1, 2 or 4)                                        */
 } ocn_plan_info;
 
 int ocn_plan_unary(int op, const ocn_tensor *a, const ocn_tensor *out, uint32_t flags,

@@ -59,7 +59,8 @@ class OcnPlanInfo(C.Structure):
                 ("vec", C.c_int32), ("tile_log2", C.c_int32 * MAX_DIMS), ("stage_a", C.c_int32),
                 ("stage_b", C.c_int32), ("specialised", C.c_int32), ("passes", C.c_int32),
                 ("grid", C.c_int64), ("block", C.c_int64), ("split", C.c_int64),
-                ("lds_bytes", C.c_int64), ("unclipped", C.c_int64), ("fused", C.c_int64)]
+                ("lds_bytes", C.c_int64), ("unclipped", C.c_int64), ("fused", C.c_int64),
+                ("tile_group", C.c_int64)]
 
 
 class OcnError(RuntimeError):
@@ -292,7 +293,7 @@ def _info_dict(info: OcnPlanInfo) -> dict:
         "vec": info.vec, "tile_log2": tuple(info.tile_log2[:n]), "stage_a": bool(info.stage_a),
         "stage_b": bool(info.stage_b), "specialised": bool(info.specialised), "passes": info.passes,
         "grid": info.grid, "block": info.block, "split": info.split, "lds_bytes": info.lds_bytes, "unclipped": bool(info.unclipped),
-        "fused": bool(info.fused),
+        "fused": bool(info.fused), "tile_group": info.tile_group,
     }
 
 

@@ -94,6 +94,7 @@ struct FastTiledArgs {
   int32_t ntd;                              // dims with more than one tile, fastest first
   int32_t stage_a, stage_b;
   int32_t nt_store;                         // stream the output past the caches
+  int32_t pair_log2;                        // groups of 1 << pair_log2 consecutive tiles share input lines
   uint32_t lds_base[2];                     // byte offset of a's / b's staging area
   FastDiv ntdiv[kMaxDims];
   int64_t step[3][kMaxDims];                // bytes from one tile to the next along that dim
@@ -670,8 +671,15 @@ template <class G> __global__ __launch_bounds__(kBlock) void ew_tiled_fast_kerne
   KFastArgs &p = *(KFastArgs *)__builtin_amdgcn_kernarg_segment_ptr();
   char *lds = reinterpret_cast<char *>(ocn_lds_raw);
 
-  // tile origin (uniform over the workgroup)
+  // tile origin (uniform over the workgroup).  Workgroups go to the eight XCDs in turn, each
+  // with an L2 of its own: tiles that share input lines (consecutive tile numbers, in groups
+  // of 2 or 4) are given to workgroups b, b + 8, ... which the same XCD starts one after the
+  // other, so that the line is fetched from memory once.
   uint32_t t = blockIdx.x;
+  if (p.pair_log2) {
+    const uint32_t lg = (uint32_t)p.pair_log2, r = t & 7u, h = (t >> 3) & ((1u << lg) - 1u), q = t >> (3 + lg);
+    t = (q << (3 + lg)) | (r << lg) | h;
+  }
   int64_t bo = 0, ba = 0, bb = 0;
   const int ntd = p.ntd;
   for (int j = 0; j < ntd; ++j) {

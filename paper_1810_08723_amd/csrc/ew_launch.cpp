@@ -125,8 +125,12 @@ FastTiledArgs make_fast_tiled_args(const EwPlan &p, int es_a) {
   f.stage_a = t.stage_a;
   f.stage_b = t.stage_b;
   f.nt_store = t.nt_store;
-  // tile grid: only dims with more than one tile, fastest (last canonical dim) first
-  for (int d = p.ndim - 1; d >= 0; --d) {
+  // tile grid: only dims with more than one tile; the dim along which neighbouring tiles share
+  // input lines varies fastest, then the last canonical dim and so on
+  f.pair_log2 = p.pair_dim >= 0 ? p.pair_log2 : 0;
+  for (int k = p.ndim; k >= 0; --k) {
+    const int d = k == p.ndim ? p.pair_dim : k;
+    if (d < 0 || (k < p.ndim && d == p.pair_dim)) continue;
     if (p.ntiles[d] <= 1) continue;
     const int j = f.ntd++;
     f.ntdiv[j] = t.ntdiv[d];

@@ -539,7 +539,37 @@ int plan_elementwise(int nin, int op, const ocn_tensor *a, const ocn_tensor *b,
     const int64_t lim = ((int64_t)1 << 31) - 64;
     p.fast_tiled = ok && span_o < lim && span_a < lim && span_b < lim;
   }
-  if (p.fast_tiled) break;
+  if (p.fast_tiled) {
+    // An input whose contiguous run inside a tile is a fraction of a 128-byte line shares its
+    // lines with the neighbouring tiles along the dim that continues the run.  Such tiles are
+    // handed to workgroups that land on the same XCD one after the other (see the kernel), so
+    // that the line is fetched into that L2 once instead of once per tile.
+    p.pair_dim = -1;
+    p.pair_log2 = 0;
+    const Operand *ins[2] = {&p.a, &p.b};
+    const int es_in[2] = {es_a, es_b};
+    for (int x = 0; x < nin && p.pair_dim < 0; ++x) {
+      int64_t run = es_in[x];
+      int cont = -1;
+      for (bool more = true; more;) {
+        more = false;
+        for (int d = 0; d < n; ++d) {
+          if (iabs64(ins[x]->stride[d]) != run || p.size[d] == 1) continue;
+          const int64_t ext = (int64_t)1 << p.tile_log2[d];
+          if (ext >= p.size[d]) { run *= p.size[d]; more = true; }   // fully covered: the run goes on
+          else if (ext > 1) run *= ext;                              // partly covered: it ends here
+          else cont = d;                                             // not in the tile: the neighbours continue it
+          break;
+        }
+      }
+      if (cont < 0 || run >= 128 || 128 % run != 0 || ins[x]->stride[cont] < 0) continue;
+      const int lg = run == 64 ? 1 : run == 32 ? 2 : 0;
+      if (lg == 0 || p.ntiles[cont] % (1 << lg) != 0 || p.total_tiles % (8 << lg) != 0) continue;
+      p.pair_dim = cont;
+      p.pair_log2 = lg;
+    }
+    break;
+  }
   }  // attempts
   p.vec = 1 << p.vecw_o;
   if (p.total_tiles >= ((int64_t)1 << 31)) {  // tile coordinates are 32-bit: use the 64-bit generic kernel
@@ -1147,6 +1177,7 @@ void fill_info(const EwPlan &p, ocn_plan_info *info) {
   info->split = 1;
   info->lds_bytes = p.lds_bytes;
   info->unclipped = p.fast_tiled ? 1 : 0;
+  info->tile_group = p.fast_tiled && p.pair_dim >= 0 ? (int64_t)1 << p.pair_log2 : 1;
 }
 
 void fill_info(const RedPlan &p, ocn_plan_info *info) {

@@ -69,6 +69,8 @@ struct EwPlan {
   bool nt_store = false;        // the output is too large to stay cached: stream it past the caches
   int64_t grid = 0;
   int64_t lds_bytes = 0;
+  int pair_dim = -1;            // all-vector tiled form: tiles that are neighbours along this dim share
+  int pair_log2 = 0;            // cache lines of an input, in groups of 1 << pair_log2 tiles
 };
 
 struct RedPlan {

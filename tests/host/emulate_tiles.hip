@@ -88,6 +88,10 @@ static int check_fast(const EwPlan &p, const HostTensor &a, const HostTensor &b,
 #define FAIL(msg) do { std::printf("case %d (fast form): %s\n", case_no, msg); return 1; } while (0)
   for (int64_t blk = 0; blk < p.total_tiles; ++blk) {
     uint32_t t = (uint32_t)blk;
+    if (f.pair_log2) {   // the kernel's workgroup -> tile map
+      const uint32_t lg = (uint32_t)f.pair_log2, r = t & 7u, h = (t >> 3) & ((1u << lg) - 1u), q = t >> (3 + lg);
+      t = (q << (3 + lg)) | (r << lg) | h;
+    }
     int64_t bo = 0, ba = 0, bb = 0;
     for (int j = 0; j < f.ntd; ++j) {
       const uint32_t q = fastdiv(t, f.ntdiv[j]);

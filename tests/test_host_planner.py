@@ -144,6 +144,9 @@ def test_unclipped_form_and_staging_budget():
             # three different fastest axes: 16 elements (128 B) along the output's and a's,
             # 8 (all there is) along b's
             assert plan["lds_bytes"] == 32 * 1024 and sorted(plan["tile_log2"]) == [0, 0, 3, 4, 4]
+            # b's runs are half lines, continued by the next tile along another dim: such tiles
+            # are started in pairs on one XCD
+            assert plan["tile_group"] == 2, (c.name, plan["tile_group"])
         else:
             assert plan["lds_bytes"] == 16 * 1024
     # an extent that is not a multiple of its tile extent clips tiles: general form
