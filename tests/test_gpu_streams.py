@@ -109,3 +109,77 @@ def test_two_streams_at_once():
         assert np.array_equal(got[1], m.storage)
         x = c.to_numpy()
         assert np.all(np.abs(got[2].view(np.float64) - s.storage.view(np.float64)) <= 1e-13 * np.abs(x).sum(axis=1) + 1e-300)
+
+
+def test_graph_of_fused_reduce_mask_compaction_gather_and_domain_check():
+    # the later entry points under capture: every buffer (outputs, workspaces, the count) is
+    # allocated before the capture, the calls only launch kernels.  Each replay is compared
+    # with the oracle on the inputs of that replay; ordinary eager work runs in between.
+    import torch
+    import paper_1810_08723_amd as ocn
+    from oracle import binding as O
+    from oracle import indexing as OI
+    rng = rng_for(14002)
+    n0, n1 = 96, 200
+    a = random_view(rng, "float", (n0, n1), specials=False)
+    b = random_view(rng, "float", (n0, n1), specials=False)
+    dots = View.empty("float", (n0,))            # row-wise inner products, one fused kernel
+    total = View.empty("int64", ())              # count of a > b over everything: split, two launches
+    mask = View.empty("bool", (n0, n1))
+    dv = H.DeviceViews()
+    ta, tb, tdots, ttotal, tmask = (dv.tensor(v) for v in (a, b, dots, total, mask))
+    dev = "cuda:0"
+    ws_d = torch.empty(max(256, ocn.binary_reduce_workspace_bytes("mul", "sum", ta, tb, [1], tdots, "float")), dtype=torch.uint8, device=dev)
+    ws_t = torch.empty(max(256, ocn.binary_reduce_workspace_bytes("gt", "sum", ta, tb, [0, 1], ttotal, "bool")), dtype=torch.uint8, device=dev)
+    offs = torch.full((n0 * n1,), -1, dtype=torch.int64, device=dev)
+    count = torch.zeros(1, dtype=torch.int64, device=dev)
+    ws_m = torch.empty(1 << 16, dtype=torch.uint8, device=dev)
+    picked = torch.zeros(n0 * n1, dtype=torch.float32, device=dev)
+    tpicked = ocn.Tensor.on_storage(picked.view(torch.uint8), "float", (n0 * n1,), (4,))
+    inner = ocn.Tensor.on_storage(dv._by_id[id(a.storage)][1], "float", (), ())
+    flag = torch.zeros(1, dtype=torch.bool, device=dev)
+    ws_f = torch.empty(1 << 16, dtype=torch.uint8, device=dev)
+
+    def enqueue():
+        ocn.binary_reduce("mul", "sum", ta, tb, [1], tdots, "float", workspace=ws_d)
+        ocn.binary_reduce("gt", "sum", ta, tb, [0, 1], ttotal, "bool", workspace=ws_t)
+        ocn.binary("gt", ta, tb, tmask)
+        ocn.mask_offsets(tmask, (n1 * 4, 4), offs, count, workspace=ws_m)
+        ocn.gather(inner, offs, 0, (n0 * n1 - 1) * 4, tpicked)    # offsets past the count are -1: skipped
+        ocn.domain_check("sqrt", ta, flag, workspace=ws_f)
+
+    enqueue()                                    # eager once (also resolves the library's device constants)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        enqueue()
+    torch.cuda.synchronize()
+    dev_a, dev_b = dv._by_id[id(a.storage)][1], dv._by_id[id(b.storage)][1]
+    for replay in range(3):
+        fresh = random_view(rng, "float", (n0, n1), specials=False)
+        a.storage[:] = fresh.storage
+        if replay == 1:                          # no negative value: the square root's domain check must say so
+            a.storage[:] = np.abs(a.to_numpy()).view(np.uint8).reshape(-1)
+        b.storage[:] = random_view(rng, "float", (n0, n1), specials=False).storage
+        dev_a.copy_(torch.from_numpy(a.storage))
+        dev_b.copy_(torch.from_numpy(b.storage))
+        offs.fill_(-1)
+        picked.fill_(-7.0)
+        torch.cuda.synchronize()
+        print("graph replay", replay, flush=True)
+        graph.replay()
+        torch.cuda.synchronize()
+        O.binary_reduce("mul", "sum", a, b, [1], dots, "float")
+        x = (a.to_numpy().astype(np.float64) * b.to_numpy().astype(np.float64))
+        got_dots = dv.download(dots).view(np.float32).astype(np.float64)
+        assert np.all(np.abs(got_dots - dots.storage.view(np.float32)) <= 2e-6 * np.abs(x).sum(axis=1))
+        O.binary_reduce("gt", "sum", a, b, [0, 1], total, "bool")
+        assert np.array_equal(dv.download(total), total.storage)
+        O.binary("gt", a, b, mask)
+        want_offs = OI.mask_offsets(mask, (n1 * 4, 4))
+        n = int(count.cpu()[0])
+        assert n == len(want_offs) == int(total.storage.view(np.int64)[0])
+        assert np.array_equal(offs.cpu().numpy()[:n], want_offs)
+        got_picked = picked.cpu().numpy()
+        assert np.array_equal(got_picked[:n], a.to_numpy().reshape(-1)[want_offs // 4]) and np.all(got_picked[n:] == -7.0)
+        assert bool(flag.cpu()[0]) == bool((a.to_numpy() < 0).any()) == (replay != 1)
