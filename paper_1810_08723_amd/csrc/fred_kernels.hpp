@@ -150,27 +150,33 @@ template <class G, int OP> __global__ __launch_bounds__(kBlock) void fred_rows_k
   const int tid = threadIdx.x;
   const int lane_in_wave = tid & (kWave - 1);
   const int wave = tid / kWave;
-  const bool per_wave = p.group == kWave;
-  const int64_t gidx = per_wave ? (int64_t)blockIdx.x * (kBlock / kWave) + wave : (int64_t)blockIdx.x;
+  // p.group lanes share one output: a whole workgroup, or a power of two up to a wavefront
+  const bool per_block = p.group == kBlock;
+  const int width = per_block ? kWave : p.group;
+  const int64_t gidx = per_block ? (int64_t)blockIdx.x : ((int64_t)blockIdx.x * kBlock + tid) >> (__ffs(width) - 1);
   const int64_t ngroups = p.nout * p.split;
   const bool active = gidx < ngroups;
+  const int lane = per_block ? tid : (lane_in_wave & (width - 1));
   A acc = R::identity();
   int64_t o = 0, s = 0, off_o = 0;
   if (active) {
-    o = p.split == 1 ? gidx : gidx / p.split;
-    s = gidx - o * p.split;
+    int64_t t0 = 0, t1 = p.nvec;
+    o = gidx;
+    if (p.split != 1) {
+      o = gidx / p.split;
+      s = gidx - o * p.split;
+      t0 = s * p.chunk;
+      t1 = t0 + p.chunk;
+      if (t1 > p.nvec) t1 = p.nvec;
+    }
     int64_t off_a, off_b;
     kept_offsets2(p, (uint32_t)o, off_a, off_b, off_o);
-    const int64_t t0 = s * p.chunk;
-    int64_t t1 = t0 + p.chunk;
-    if (t1 > p.nvec) t1 = p.nvec;
-    const int lane = per_wave ? lane_in_wave : tid;
-    const int lanes = per_wave ? kWave : kBlock;
+    const int lanes = per_block ? kBlock : width;
     if (p.vec > 1) acc = fred_rows_accumulate<G, OP, G::V>(p, p.a + off_a, p.b + off_b, t0, t1, lane, lanes);
     else acc = fred_rows_accumulate<G, OP, 1>(p, p.a + off_a, p.b + off_b, t0, t1, lane, lanes);
-    acc = wave_fold<R>(acc);
   }
-  if (!per_wave) {  // combine the four wavefronts of the workgroup
+  acc = group_fold<R>(acc, width);   // every lane takes part, whether its group has work or not
+  if (per_block) {  // combine the four wavefronts of the workgroup
     if (lane_in_wave == 0) lds[wave] = acc;
     __syncthreads();
     if (tid == 0) {
@@ -178,8 +184,7 @@ template <class G, int OP> __global__ __launch_bounds__(kBlock) void fred_rows_k
       for (int w = 1; w < kBlock / kWave; ++w) acc = R::combine(acc, lds[w]);
     }
   }
-  const bool writer = active && (per_wave ? lane_in_wave == 0 : tid == 0);
-  if (writer) {
+  if (active && lane == 0) {
     if (p.split == 1) store_result<A>(p.out + off_o, p.out_dtype, acc);
     else reinterpret_cast<typename R::P *>(p.partial)[o * p.split + s] = to_storage<R::ACC>(acc);
   }
@@ -208,7 +213,12 @@ OCN_DEV void fred_cols_body(const RedArgs &p, typename FusedFold<G, OP>::A (*lds
   b -= s * per_split;
   const uint32_t other = rfastdiv(b, p.colblocks_div);
   const uint32_t cb = b - other * p.colblocks_div.d;
-  const int64_t col0 = ((int64_t)cb * kWave + lane) * V;
+  // p.cpw lanes (a power of two) cover one row of columns; with fewer than 64 of them a
+  // wavefront takes 64 / cpw rows at a time
+  const int cpw_log2 = __ffs(p.cpw) - 1;
+  const int lc = lane & (p.cpw - 1), lr = lane >> cpw_log2;
+  const int RPW = kWave >> cpw_log2;
+  const int64_t col0 = ((int64_t)cb * p.cpw + lc) * V;
   const int64_t left = p.nc - col0;
   const int ncol = left >= V ? V : (left > 0 ? (int)left : 0);
 
@@ -235,15 +245,16 @@ OCN_DEV void fred_cols_body(const RedArgs &p, typename FusedFold<G, OP>::A (*lds
   int64_t r1 = r0 + p.chunk;
   if (r1 > p.nredtot) r1 = p.nredtot;
   constexpr int U = 2;
-  int64_t r = r0 + wave;
+  const int RS = NW * RPW;           // rows between two rows of the same lane
+  int64_t r = r0 + wave * RPW + lr;
   if (ncol == V) {
-    for (; r + (int64_t)(U - 1) * NW < r1; r += NW * U) {
+    for (; r + (int64_t)(U - 1) * RS < r1; r += RS * U) {
       Pack<SAt, V> va[U];
       Pack<SBt, V> vb[U];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         int64_t oa, ob;
-        reduced_offset2(p, (uint32_t)(r + (int64_t)u * NW), 0, oa, ob);
+        reduced_offset2(p, (uint32_t)(r + (int64_t)u * RS), 0, oa, ob);
         fused_load<SAt, V>(p.a + off_a + oa, abc, va[u]);
         fused_load<SBt, V>(p.b + off_b + ob, bbc, vb[u]);
       }
@@ -254,7 +265,7 @@ OCN_DEV void fred_cols_body(const RedArgs &p, typename FusedFold<G, OP>::A (*lds
     }
   }
   if (ncol > 0) {  // remaining rows, and the ragged last column block
-    for (; r < r1; r += NW) {
+    for (; r < r1; r += RS) {
       int64_t oa, ob;
       reduced_offset2(p, (uint32_t)r, 0, oa, ob);
       const char *qa = p.a + off_a + oa, *qb = p.b + off_b + ob;
@@ -265,11 +276,19 @@ OCN_DEV void fred_cols_body(const RedArgs &p, typename FusedFold<G, OP>::A (*lds
                           reinterpret_cast<const SBt *>(qb)[bbc ? 0 : i]);
     }
   }
+  // lanes of a wavefront that hold the same columns of different rows: fold onto the first
+  if (RPW > 1) {
+#pragma unroll
+    for (int i = 0; i < V; ++i)
+#pragma unroll
+      for (int d = kWave / 2; d >= 1; d >>= 1)
+        if (d >= p.cpw) acc[i] = R::combine(acc[i], shfl_down_any(acc[i], d));
+  }
 #pragma unroll
   for (int i = 0; i < V; ++i) {
     lds[wave][lane] = acc[i];
     __syncthreads();
-    if (wave == 0 && i < ncol) {
+    if (wave == 0 && lr == 0 && i < ncol) {
       A v = lds[0][lane];
       for (int w = 1; w < NW; ++w) v = R::combine(v, lds[w][lane]);
       if (p.split == 1) {

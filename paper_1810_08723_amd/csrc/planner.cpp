@@ -894,7 +894,7 @@ void choose_fused_launch(RedPlan &p) {
 
   p.split = 1;
   if (p.nred >= 1 && fast_ok(p.rstride_a[p.nred - 1], p.rstride_b[p.nred - 1]) &&
-      (k_fast_dim < 0 || k_fast > r_fast) && p.nredtot >= 32 && (idx32 || flat_full)) {
+      (k_fast_dim < 0 || k_fast > r_fast) && (idx32 || flat_full)) {
     p.kernel = OCN_KERNEL_RED_ROWS;
     p.a_fast_bcast = p.rstride_a[p.nred - 1] == 0;
     p.b_fast_bcast = p.rstride_b[p.nred - 1] == 0;
@@ -902,10 +902,12 @@ void choose_fused_launch(RedPlan &p) {
     const int64_t n0 = p.rsize[p.nred - 1];
     const int64_t vpr = (n0 + p.vec - 1) / p.vec;
     const int64_t nvec = vpr * (p.nredtot / n0);
-    p.group = (nvec * p.vec * (es_a + es_b) <= 16 * 1024) ? kWave : kBlock;
+    int64_t cover = 1;                                    // lanes one output can keep busy
+    while (cover < nvec && cover < kWave) cover <<= 1;
+    p.group = (nvec * p.vec * (es_a + es_b) <= 16 * 1024) ? (int)cover : kBlock;
     const int64_t groups_per_block = kBlock / p.group;
-    const int64_t waves = p.nout * (p.group / kWave);
-    if (waves < kTargetWaves) {
+    const int64_t waves = (p.nout * p.group + kWave - 1) / kWave;
+    if (p.group >= kWave && waves < kTargetWaves) {
       const int64_t want = (kTargetWaves + waves - 1) / waves;
       const int64_t most = std::max<int64_t>(1, nvec / ((int64_t)p.group * 8));
       p.split = std::max<int64_t>(1, std::min(want, most));
@@ -920,12 +922,17 @@ void choose_fused_launch(RedPlan &p) {
     p.b_fast_bcast = p.kstride_b[k_fast_dim] == 0;
     p.vec = all_aligned(p.nkept - 1, -1, p.a_fast_bcast, p.b_fast_bcast) ? vfull : 1;
     const int64_t nc = p.ksize[p.nkept - 1];
-    const int64_t colblocks = (nc + (int64_t)kWave * p.vec - 1) / ((int64_t)kWave * p.vec);
+    // few columns: a wavefront covers 64 / cpw rows at a time
+    const int64_t col_lanes = (nc + p.vec - 1) / p.vec;
+    p.cpw = kWave;
+    while (p.cpw > 1 && p.cpw / 2 >= col_lanes) p.cpw /= 2;
+    const int rpw = kWave / p.cpw;
+    const int64_t colblocks = (nc + (int64_t)p.cpw * p.vec - 1) / ((int64_t)p.cpw * p.vec);
     const int64_t blocks0 = colblocks * (p.nout / nc);
     const int nw = 4;
     if (blocks0 * nw < kTargetWaves) {
       const int64_t want = (kTargetWaves + blocks0 * nw - 1) / (blocks0 * nw);
-      const int64_t most = std::max<int64_t>(1, p.nredtot / (nw * 16));
+      const int64_t most = std::max<int64_t>(1, p.nredtot / ((int64_t)nw * rpw * 16));
       p.split = std::max<int64_t>(1, std::min(want, most));
     }
     p.block = nw * kWave;

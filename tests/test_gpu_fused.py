@@ -218,3 +218,34 @@ def test_layouts_without_a_contiguous_axis_take_two_launches():
     e = random_view(rng, "int32", (8, 40, 2)).select(2, 1)
     f = random_view(rng, "int32", (8, 40, 2)).select(2, 0)
     _check("mul", "sum", e, f, [0], "int32", expect_fused=True)
+
+
+@pytest.mark.parametrize("row", (2, 3, 5, 16, 31, 64, 100))
+def test_short_rows_share_a_wavefront(row):
+    # rows of fewer vectors than a wavefront has lanes: groups of 1 .. 64 lanes per output
+    rng = rng_for(16300 + row)
+    for dt in ("float", "double", "int32", "cfloat"):
+        a = random_view(rng, dt, (517, row), specials=False)
+        b = random_view(rng, dt, (517, row), specials=False)
+        _check("mul", "sum", a, b, [1], dt, expect_fused=True)
+        if dt != "cfloat":
+            _check("gt", "sum", a, b, [1], "bool", expect_fused=True)
+    # one operand broadcast along the rows, the other along the kept axis
+    a = random_view(rng, "float", (517, row), specials=False)
+    _check("mul", "sum", a, random_view(rng, "float", (row,), specials=False), [1], "float", expect_fused=True)
+    _check("sub", "sum", a, random_view(rng, "float", (517, 1), specials=False), [1], "float", expect_fused=True)
+
+
+@pytest.mark.parametrize("ncol", (1, 2, 5, 16, 40, 64))
+def test_few_columns_share_a_wavefront(ncol):
+    # kept-fastest layouts with fewer column lanes than a wavefront: several rows per wavefront
+    rng = rng_for(16400 + ncol)
+    for dt in ("float", "double", "int32"):
+        a = random_view(rng, dt, (1237, ncol), specials=False)
+        b = random_view(rng, dt, (1237, ncol), specials=False)
+        _check("mul", "sum", a, b, [0], dt, expect_fused=True)
+        _check("lt", "sum", a, b, [0], "bool", expect_fused=True)
+    a = random_view(rng, "float", (9, 700, ncol), specials=False)
+    _check("add", "sum", a, random_view(rng, "float", (700, 1), specials=False), [1], "float", expect_fused=True)
+    big = random_view(rng, "int32", (70000, ncol))
+    _check("gt", "sum", big, random_view(rng, "int32", (70000, ncol)), [0], "bool", expect_fused=True)
