@@ -11,9 +11,9 @@
 //                      its selected elements behind its prefix (staged in LDS so that the
 //                      stores are coalesced).  Lanes own 16 consecutive mask bytes (one 128-bit
 //                      load when the mask is contiguous).
-//   ocn_gather/scatter one lane per copied element, rows of `inner` elements per offset; the
-//                      offset array is read coalesced, rows are walked along their fastest
-//                      dimension.  Offsets outside the stated range are skipped, never followed.
+//   ocn_gather/scatter one lane per copied item (an element, or 16 bytes where the rows' fastest
+//                      dimension is contiguous and aligned), rows of `inner` elements per offset;
+//                      short rows share a workgroup, long ones take several.  Offsets outside the stated range are skipped, never followed.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -261,6 +261,10 @@ struct GatherArgs {
   int64_t ss[kMaxDims], sd[kMaxDims]; // inner byte strides on the source / destination side
   int64_t row_stride;                 // bytes between rows on the side that is not indexed
   uint32_t inner;                     // elements per row
+  uint32_t vec;                       // elements a lane copies at once (1, or 16 bytes' worth)
+  uint32_t items;                     // lane items per row: inner / vec
+  int32_t items_log2;                 // >= 0: rows of at most 256 items, padded to 1 << items_log2 lanes,
+                                      // 256 >> items_log2 rows per workgroup; -1: workgroups per row below
   FastDiv chunks_div;                 // workgroups per row
 };
 
@@ -271,23 +275,27 @@ template <> struct alignas(8) Bytes<8> { unsigned char b[8]; };
 template <> struct alignas(16) Bytes<16> { unsigned char b[16]; };
 
 // SCATTER = false: dst[j, i] = src[offsets[j] + i];  true: dst[offsets[j] + i] = src[j, i]
+// A lane copies one item: an element, or 16 bytes of the rows' fastest dim when that dim is
+// contiguous and aligned on both sides (an offset that is not a multiple of 16 falls back to
+// element copies for its row).  Short rows share a workgroup.
 template <int ES, bool SCATTER> __global__ __launch_bounds__(kBlock) void gather_kernel(const GatherArgs p) {
+  constexpr int V = 16 / ES;
   int64_t j;
-  uint32_t i;
-  if (p.inner == 1) {
-    j = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    i = 0;
+  uint32_t item;
+  if (p.items_log2 >= 0) {
+    j = (int64_t)blockIdx.x * (kBlock >> p.items_log2) + (threadIdx.x >> p.items_log2);
+    item = threadIdx.x & ((1u << p.items_log2) - 1u);
     if (j >= p.n) return;
   } else {
     const uint32_t row = fdiv(blockIdx.x, p.chunks_div);
     j = row;
-    i = (blockIdx.x - row * p.chunks_div.d) * kBlock + threadIdx.x;
-    if (i >= p.inner) return;
+    item = (blockIdx.x - row * p.chunks_div.d) * kBlock + threadIdx.x;
   }
+  if (item >= p.items) return;
   const int64_t off = p.offsets[j];
   if (off < p.lo || off > p.hi) return;
   int64_t os = 0, od = 0;
-  uint32_t rem = i;
+  uint32_t rem = item * p.vec;
 #pragma unroll
   for (int d = kMaxDims - 1; d >= 0; --d) {
     if (d < p.ndim) {
@@ -300,7 +308,17 @@ template <int ES, bool SCATTER> __global__ __launch_bounds__(kBlock) void gather
   }
   if (SCATTER) { os += j * p.row_stride; od += off; }
   else { os += off; od += j * p.row_stride; }
-  *reinterpret_cast<Bytes<ES> *>(p.dst + od) = *reinterpret_cast<const Bytes<ES> *>(p.src + os);
+  if (V > 1 && p.vec > 1) {
+    if ((off & 15) == 0) {
+      *reinterpret_cast<Bytes<16> *>(p.dst + od) = *reinterpret_cast<const Bytes<16> *>(p.src + os);
+    } else {
+#pragma unroll
+      for (int e = 0; e < V; ++e)
+        *reinterpret_cast<Bytes<ES> *>(p.dst + od + e * ES) = *reinterpret_cast<const Bytes<ES> *>(p.src + os + e * ES);
+    }
+  } else {
+    *reinterpret_cast<Bytes<ES> *>(p.dst + od) = *reinterpret_cast<const Bytes<ES> *>(p.src + os);
+  }
 }
 
 int done(hipError_t e) {
@@ -483,10 +501,33 @@ static int run_gather(bool scatter, const ocn_tensor *inner, const void *offsets
   g.hi = hi;
   g.row_stride = rows->stride[0];
   g.inner = (uint32_t)inner_elems;
-  const int64_t chunks = (inner_elems + kBlock - 1) / kBlock;
-  g.chunks_div = make_fastdiv((uint32_t)chunks);
-  const int64_t grid = inner_elems == 1 ? (n + kBlock - 1) / kBlock : n * chunks;
-  if (grid >= ((int64_t)1 << 31)) return OCN_ERR_SHAPE;
+  // 16-byte items along the rows' fastest dim when it is contiguous and everything else keeps
+  // such items aligned (the offsets themselves are checked row by row in the kernel)
+  const int vfull = 16 / es;
+  g.vec = 1;
+  if (vfull > 1 && m > 0 && d[m - 1].si == es && d[m - 1].sr == es && d[m - 1].size % vfull == 0 &&
+      ((intptr_t)inner->base + inner->offset) % 16 == 0 && ((intptr_t)rows->base + rows->offset) % 16 == 0 &&
+      rows->stride[0] % 16 == 0) {
+    bool ok = true;
+    for (int k = 0; k + 1 < m; ++k) ok = ok && d[k].si % 16 == 0 && d[k].sr % 16 == 0;
+    if (ok) g.vec = (uint32_t)vfull;
+  }
+  g.items = (uint32_t)(inner_elems / g.vec);
+  int64_t grid;
+  if (g.items <= (uint32_t)kBlock) {   // short rows share a workgroup
+    g.items_log2 = 0;
+    while ((1u << g.items_log2) < g.items) ++g.items_log2;
+    const int64_t rows_per_block = kBlock >> g.items_log2;
+    grid = (n + rows_per_block - 1) / rows_per_block;
+    g.chunks_div = make_fastdiv(1);
+  } else {
+    g.items_log2 = -1;
+    const int64_t chunks = ((int64_t)g.items + kBlock - 1) / kBlock;
+    g.chunks_div = make_fastdiv((uint32_t)chunks);
+    grid = n * chunks;
+  }
+  // the launch may not exceed 2^32 lanes
+  if (grid >= ((int64_t)1 << 32) / kBlock) return OCN_ERR_SHAPE;
   hipStream_t s = (hipStream_t)stream;
 #define OCN_LAUNCH(ES)                                                                                        \
   if (scatter) hipLaunchKernelGGL((gather_kernel<ES, true>), dim3((unsigned)grid), dim3(kBlock), 0, s, g);   \

@@ -207,3 +207,49 @@ def test_scatter_rows():
     want[perm] = src.to_numpy()
     OI.scatter(src, offs, inner, 0, 199 * a.strides[0])
     assert np.array_equal(got, a.storage) and np.array_equal(a.to_numpy(), want)
+
+
+@pytest.mark.parametrize("dt,inner_len", [("float", 1), ("float", 3), ("float", 4), ("float", 12), ("float", 100),
+                                          ("float", 256), ("float", 1028), ("int8", 48), ("int8", 50), ("half", 40),
+                                          ("double", 6), ("cdouble", 5), ("cfloat", 34)])
+def test_gather_scatter_row_lengths_and_alignments(dt, inner_len):
+    # short rows share a workgroup, long rows take several; rows whose length, placement and
+    # strides allow it move in 16-byte items, rows starting at other offsets element by element
+    import torch
+    import paper_1810_08723_amd as ocn
+    rng = rng_for(17400 + inner_len + sum(map(ord, dt)))
+    nrows, pick = 333, 777
+    es = itemsize(dt)
+    a = random_view(rng, dt, (nrows, inner_len))
+    idx = rng.integers(0, nrows, size=(pick,)).astype(np.int64)
+    offs, _ = OI.index_offsets(idx, nrows, a.strides[0])
+    inner = View(a.storage, dt, (inner_len,), a.strides[1:], a.offset)
+    out = View.empty(dt, (pick, inner_len))
+    dv = H.DeviceViews()
+    ocn.gather(dv.tensor(inner), _dev_i64(offs), 0, (nrows - 1) * a.strides[0], dv.tensor(out))
+    torch.cuda.synchronize()
+    got = dv.download(out).copy()
+    OI.gather(inner, offs, out, 0, (nrows - 1) * a.strides[0])
+    assert np.array_equal(got, out.storage)
+    # window rows: overlapping windows of a long vector, starting at arbitrary elements
+    vec = random_view(rng, dt, (5000,))
+    starts = rng.integers(0, 5000 - inner_len, size=(pick,)).astype(np.int64)
+    woffs = starts * es
+    win = View(vec.storage, dt, (inner_len,), (es,), vec.offset)
+    out2 = View.empty(dt, (pick, inner_len))
+    dv = H.DeviceViews()
+    ocn.gather(dv.tensor(win), _dev_i64(woffs), 0, (5000 - inner_len) * es, dv.tensor(out2))
+    torch.cuda.synchronize()
+    got2 = dv.download(out2).copy()
+    OI.gather(win, woffs, out2, 0, (5000 - inner_len) * es)
+    assert np.array_equal(got2, out2.storage)
+    # scatter distinct rows back
+    perm = rng.permutation(nrows)[:200].astype(np.int64)
+    poffs, _ = OI.index_offsets(perm, nrows, a.strides[0])
+    src = random_view(rng, dt, (200, inner_len))
+    dv = H.DeviceViews()
+    ocn.scatter(dv.tensor(src), _dev_i64(poffs), 0, (nrows - 1) * a.strides[0], dv.tensor(inner))
+    torch.cuda.synchronize()
+    got3 = dv.download(inner).copy()
+    OI.scatter(src, poffs, inner, 0, (nrows - 1) * a.strides[0])
+    assert np.array_equal(got3, a.storage)
