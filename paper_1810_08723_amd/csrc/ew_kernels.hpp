@@ -91,13 +91,13 @@ struct FastOrder {
 struct FastTiledArgs {
   char *out;
   const char *a, *b;
-  int32_t ntd;                              // dims with more than one tile, fastest first
+  int32_t ntd;                              // entries of the tile-number decomposition, fastest first
   int32_t stage_a, stage_b;
   int32_t nt_store;                         // stream the output past the caches
   int32_t pair_log2;                        // groups of 1 << pair_log2 consecutive tiles share input lines
   uint32_t lds_base[2];                     // byte offset of a's / b's staging area
-  FastDiv ntdiv[kMaxDims];
-  int64_t step[3][kMaxDims];                // bytes from one tile to the next along that dim
+  FastDiv ntdiv[kMaxDims + 1];              // (one more than dims: a dim's tile index may be split in two)
+  int64_t step[3][kMaxDims + 1];            // bytes from one tile to the next along that dim
   TileSwizzle swz[2];
   uint32_t es_log2[2];
   uint32_t vc_log2;                         // log2 of the compute vector length

@@ -125,18 +125,24 @@ FastTiledArgs make_fast_tiled_args(const EwPlan &p, int es_a) {
   f.stage_a = t.stage_a;
   f.stage_b = t.stage_b;
   f.nt_store = t.nt_store;
-  // tile grid: only dims with more than one tile; the dim along which neighbouring tiles share
-  // input lines varies fastest, then the last canonical dim and so on
+  // tile grid: only dims with more than one tile, fastest (last canonical dim) first.  Where
+  // neighbouring tiles along one dim share input lines, that dim's tile index is split: its low
+  // part (the group of tiles sharing a line) varies fastest of all, its high part stays in place.
   f.pair_log2 = p.pair_dim >= 0 ? p.pair_log2 : 0;
-  for (int k = p.ndim; k >= 0; --k) {
-    const int d = k == p.ndim ? p.pair_dim : k;
-    if (d < 0 || (k < p.ndim && d == p.pair_dim)) continue;
-    if (p.ntiles[d] <= 1) continue;
+  auto add_dim = [&](int d, int64_t count, int64_t mult) {
     const int j = f.ntd++;
-    f.ntdiv[j] = t.ntdiv[d];
-    f.step[0][j] = t.so[d] * ((int64_t)1 << t.tl[d]);
-    f.step[1][j] = t.sa[d] * ((int64_t)1 << t.tl[d]);
-    f.step[2][j] = t.sb[d] * ((int64_t)1 << t.tl[d]);
+    f.ntdiv[j] = make_fastdiv((uint32_t)count);
+    f.step[0][j] = t.so[d] * ((int64_t)mult << t.tl[d]);
+    f.step[1][j] = t.sa[d] * ((int64_t)mult << t.tl[d]);
+    f.step[2][j] = t.sb[d] * ((int64_t)mult << t.tl[d]);
+  };
+  const int64_t group = (int64_t)1 << f.pair_log2;
+  if (f.pair_log2) add_dim(p.pair_dim, group, 1);
+  for (int d = p.ndim - 1; d >= 0; --d) {
+    const bool paired = f.pair_log2 && d == p.pair_dim;
+    const int64_t count = paired ? p.ntiles[d] / group : p.ntiles[d];
+    if (count <= 1) continue;
+    add_dim(d, count, paired ? group : 1);
   }
   const int es[2] = {es_a, p.nin == 2 ? dt_size(p.b.dtype) : 1};
   auto log2i = [](int64_t v) { int l = 0; while (((int64_t)1 << l) < v) ++l; return l; };
