@@ -99,3 +99,31 @@ def test_diagonal_views():
     r = View.empty("double", ())
     got, want = H.run_reduce("sum", diag, [0], r)                        # the trace
     assert np.allclose(got.view(np.float64), want.view(np.float64), rtol=1e-13)
+
+
+@pytest.mark.parametrize("n", (47104, 46500))
+def test_transpose_of_more_than_2_to_the_31_elements(n):
+    # n x n int8, n*n > 2^31: tile origins need 64 bits, offsets inside a tile stay 32-bit.
+    # 47104 = 2^11 * 23 takes the all-vector tiled form, 46500 the general form (clipped tiles).
+    # Checked against the definition directly (out[i, j] = x[j, i]) and, on a slab, the oracle.
+    import torch
+    import paper_1810_08723_amd as ocn
+    from oracle import binding as O
+    assert n * n > 1 << 31
+    rng = rng_for(13100 + n)
+    x = rng.integers(-128, 127, size=(n, n), endpoint=True, dtype=np.int8)
+    a = View.from_numpy(x).permute(1, 0)
+    out = View.empty("int8", (n, n))
+    dv = H.DeviceViews()
+    plan = ocn.plan_unary("ident", dv.tensor(a), dv.tensor(out))
+    assert plan["kernel"] == "ew_tiled" and plan["unclipped"] == (n == 47104), plan
+    print("large transpose", n, flush=True)
+    ocn.unary("ident", dv.tensor(a), dv.tensor(out))
+    torch.cuda.synchronize()
+    got = dv.download(out).reshape(n, n).view(np.int8)
+    assert np.array_equal(got, x.T)
+    # the same through the oracle on a slab of the view (the last 64 rows of the output)
+    slab = a.slice(0, n - 64, n, 1)
+    want = View.empty("int8", (64, n))
+    O.unary("ident", slab, want)
+    assert np.array_equal(got[n - 64:], want.to_numpy())
