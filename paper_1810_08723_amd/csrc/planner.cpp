@@ -452,124 +452,128 @@ int plan_elementwise(int nin, int op, const ocn_tensor *a, const ocn_tensor *b,
   // form's staging costs (measured on channel-last to channel-first copies with 3 channels).
   bool stage_a0 = p.stage_a, stage_b0 = p.stage_b;
   for (int attempt = 0; attempt < 2; ++attempt) {
-  if (attempt == 1) {
-    if (stage_a0 && p.size[fa] * es_a < 32) stage_a0 = false;
-    if (stage_b0 && p.size[fb] * es_b < 32) stage_b0 = false;
-  }
-  p.stage_a = stage_a0;
-  p.stage_b = stage_b0;
-  for (int d = 0; d < kMaxDims; ++d) p.tile_log2[d] = 0;
-  p.fast_tiled = false;
-  choose_tiles(p, attempt == 1);
-  tile_order(p, p.out.stride, p.ord_o);
-  tile_order(p, p.a.stride, p.ord_a);
-  tile_order(p, p.b.stride, p.ord_b);
-  p.nord = 0;
-  for (int d = 0; d < n; ++d)
-    if (p.tile_log2[d] > 0) ++p.nord;
-  // an input whose fastest tiled dim is the output's needs no staging after all
-  if (p.nord == 0 || p.ord_a[0] == p.ord_o[0]) p.stage_a = false;
-  if (p.nord == 0 || p.ord_b[0] == p.ord_o[0]) p.stage_b = false;
-
-  // ---- vector widths of the three enumeration orders -----------------------------------
-  // aligned: base pointer and every stride except the one along `skip` are multiples of vb
-  auto aligned = [&](const Operand &x, int64_t vb, int skip) {
-    if ((intptr_t)x.ptr % vb != 0) return false;
+    if (attempt == 1) {
+      if (stage_a0 && p.size[fa] * es_a < 32) stage_a0 = false;
+      if (stage_b0 && p.size[fb] * es_b < 32) stage_b0 = false;
+    }
+    p.stage_a = stage_a0;
+    p.stage_b = stage_b0;
+    for (int d = 0; d < kMaxDims; ++d) p.tile_log2[d] = 0;
+    p.fast_tiled = false;
+    choose_tiles(p, attempt == 1);
+    tile_order(p, p.out.stride, p.ord_o);
+    tile_order(p, p.a.stride, p.ord_a);
+    tile_order(p, p.b.stride, p.ord_b);
+    p.nord = 0;
     for (int d = 0; d < n; ++d)
-      if (d != skip && x.stride[d] % vb != 0) return false;
-    return true;
-  };
-  auto log2i = [](int v) { int l = 0; while ((1 << l) < v) ++l; return l; };
-  p.vecw_o = p.vecw_a = p.vecw_b = 0;
-  if (p.nord > 0) {
-    const int d0 = p.ord_o[0];
-    // compute phase: V consecutive elements along the output's fastest dim per lane
-    bool ok = p.out.stride[d0] == es_o && p.tile_log2[d0] >= log2i(V) && V > 1 &&
-              aligned(p.out, (int64_t)V * es_o, d0);
-    auto direct_ok = [&](const Operand &x, int es, bool staged) {
-      if (staged) return true;
-      if (x.stride[d0] != es) return true;  // broadcast or strided: element loads, no constraint
-      return aligned(x, (int64_t)V * es, d0);
+      if (p.tile_log2[d] > 0) ++p.nord;
+    // an input whose fastest tiled dim is the output's needs no staging after all
+    if (p.nord == 0 || p.ord_a[0] == p.ord_o[0]) p.stage_a = false;
+    if (p.nord == 0 || p.ord_b[0] == p.ord_o[0]) p.stage_b = false;
+
+    // ---- vector widths of the three enumeration orders -----------------------------------
+    // aligned: base pointer and every stride except the one along `skip` are multiples of vb
+    auto aligned = [&](const Operand &x, int64_t vb, int skip) {
+      if ((intptr_t)x.ptr % vb != 0) return false;
+      for (int d = 0; d < n; ++d)
+        if (d != skip && x.stride[d] % vb != 0) return false;
+      return true;
     };
-    ok = ok && direct_ok(p.a, es_a, p.stage_a) && (nin == 1 || direct_ok(p.b, es_b, p.stage_b));
-    if (ok) p.vecw_o = log2i(V);
-    auto stage_vec = [&](const Operand &x, int es, const int8_t *ord) {
-      const int v = 16 / es;
-      if (v <= 1) return 0;
-      const int f = ord[0];
-      if (x.stride[f] != es || p.tile_log2[f] < log2i(v) || !aligned(x, 16, f)) return 0;
-      return log2i(v);
-    };
-    if (p.stage_a) p.vecw_a = stage_vec(p.a, es_a, p.ord_a);
-    if (p.stage_b) p.vecw_b = stage_vec(p.b, es_b, p.ord_b);
-  }
-  const int64_t tile_elems = (int64_t)1 << p.tile_bits;
-  p.lds_bytes = 0;
-  if (p.stage_a) p.lds_bytes += (tile_elems * es_a + 15) / 16 * 16;
-  if (p.stage_b) p.lds_bytes += (tile_elems * es_b + 15) / 16 * 16;
-  p.total_tiles = 1;
-  for (int d = 0; d < n; ++d) {
-    p.ntiles[d] = (p.size[d] + ((int64_t)1 << p.tile_log2[d]) - 1) >> p.tile_log2[d];
-    p.total_tiles *= p.ntiles[d];
-  }
-  // One tile per workgroup.  (Persistent workgroups looping over tiles, and handing each XCD
-  // a contiguous range of tiles, were both measured slower on MI355X.)
-  p.grid = p.total_tiles;
-  p.kernel = (p.stage_a || p.stage_b) ? OCN_KERNEL_EW_TILED : OCN_KERNEL_EW_GENERIC;
-  // The unclipped all-vector form of the tiled kernel: no tile is clipped, every enumeration
-  // order moves whole vectors over at least one full pass, inputs that are not staged are
-  // contiguous along the output's fastest dim, and inside a tile every stride is non-negative
-  // with offsets that fit 31 bits.
-  if (p.kernel == OCN_KERNEL_EW_TILED && p.vecw_o > 0) {
-    bool ok = true;
-    const int d0 = p.ord_o[0];
-    if (p.stage_a ? p.vecw_a == 0 : p.a.stride[d0] != es_a) ok = false;
-    if (nin == 2 && (p.stage_b ? p.vecw_b == 0 : p.b.stride[d0] != es_b)) ok = false;
-    const int vmax = std::max(p.vecw_o, std::max(p.stage_a ? p.vecw_a : 0, p.stage_b ? p.vecw_b : 0));
-    if (p.tile_bits - vmax < 8) ok = false;  // fewer vectors than lanes in some order
-    int64_t span_o = 0, span_a = 0, span_b = 0;
-    for (int d = 0; d < n && ok; ++d) {
-      const int64_t ext = (int64_t)1 << p.tile_log2[d];
-      if (p.size[d] % ext != 0) ok = false;
-      if (ext > 1 && (p.a.stride[d] < 0 || p.b.stride[d] < 0)) ok = false;
-      span_o += (ext - 1) * p.out.stride[d];
-      span_a += (ext - 1) * iabs64(p.a.stride[d]);
-      span_b += (ext - 1) * iabs64(p.b.stride[d]);
+    auto log2i = [](int v) { int l = 0; while ((1 << l) < v) ++l; return l; };
+    p.vecw_o = p.vecw_a = p.vecw_b = 0;
+    if (p.nord > 0) {
+      const int d0 = p.ord_o[0];
+      // compute phase: V consecutive elements along the output's fastest dim per lane
+      bool ok = p.out.stride[d0] == es_o && p.tile_log2[d0] >= log2i(V) && V > 1 &&
+                aligned(p.out, (int64_t)V * es_o, d0);
+      auto direct_ok = [&](const Operand &x, int es, bool staged) {
+        if (staged) return true;
+        if (x.stride[d0] != es) return true;  // broadcast or strided: element loads, no constraint
+        return aligned(x, (int64_t)V * es, d0);
+      };
+      ok = ok && direct_ok(p.a, es_a, p.stage_a) && (nin == 1 || direct_ok(p.b, es_b, p.stage_b));
+      if (ok) p.vecw_o = log2i(V);
+      auto stage_vec = [&](const Operand &x, int es, const int8_t *ord) {
+        const int v = 16 / es;
+        if (v <= 1) return 0;
+        const int f = ord[0];
+        if (x.stride[f] != es || p.tile_log2[f] < log2i(v) || !aligned(x, 16, f)) return 0;
+        return log2i(v);
+      };
+      if (p.stage_a) p.vecw_a = stage_vec(p.a, es_a, p.ord_a);
+      if (p.stage_b) p.vecw_b = stage_vec(p.b, es_b, p.ord_b);
     }
-    const int64_t lim = ((int64_t)1 << 31) - 64;
-    p.fast_tiled = ok && span_o < lim && span_a < lim && span_b < lim;
-  }
-  if (p.fast_tiled) {
-    // An input whose contiguous run inside a tile is a fraction of a 128-byte line shares its
-    // lines with the neighbouring tiles along the dim that continues the run.  Such tiles are
-    // handed to workgroups that land on the same XCD one after the other (see the kernel), so
-    // that the line is fetched into that L2 once instead of once per tile.
-    p.pair_dim = -1;
-    p.pair_log2 = 0;
-    const Operand *ins[2] = {&p.a, &p.b};
-    const int es_in[2] = {es_a, es_b};
-    for (int x = 0; x < nin && p.pair_dim < 0; ++x) {
-      int64_t run = es_in[x];
-      int cont = -1;
-      for (bool more = true; more;) {
-        more = false;
-        for (int d = 0; d < n; ++d) {
-          if (iabs64(ins[x]->stride[d]) != run || p.size[d] == 1) continue;
-          const int64_t ext = (int64_t)1 << p.tile_log2[d];
-          if (ext >= p.size[d]) { run *= p.size[d]; more = true; }   // fully covered: the run goes on
-          else if (ext > 1) run *= ext;                              // partly covered: it ends here
-          else cont = d;                                             // not in the tile: the neighbours continue it
-          break;
-        }
+    const int64_t tile_elems = (int64_t)1 << p.tile_bits;
+    p.lds_bytes = 0;
+    if (p.stage_a) p.lds_bytes += (tile_elems * es_a + 15) / 16 * 16;
+    if (p.stage_b) p.lds_bytes += (tile_elems * es_b + 15) / 16 * 16;
+    p.total_tiles = 1;
+    for (int d = 0; d < n; ++d) {
+      p.ntiles[d] = (p.size[d] + ((int64_t)1 << p.tile_log2[d]) - 1) >> p.tile_log2[d];
+      p.total_tiles *= p.ntiles[d];
+    }
+    // One tile per workgroup.  (Persistent workgroups looping over tiles, and handing each XCD
+    // a contiguous range of tiles, were both measured slower on MI355X.)
+    p.grid = p.total_tiles;
+    p.kernel = (p.stage_a || p.stage_b) ? OCN_KERNEL_EW_TILED : OCN_KERNEL_EW_GENERIC;
+    // The unclipped all-vector form of the tiled kernel: no tile is clipped, every enumeration
+    // order moves whole vectors over at least one full pass, inputs that are not staged are
+    // contiguous along the output's fastest dim, and inside a tile every stride is non-negative
+    // with offsets that fit 31 bits.
+    if (p.kernel == OCN_KERNEL_EW_TILED && p.vecw_o > 0) {
+      bool ok = true;
+      const int d0 = p.ord_o[0];
+      if (p.stage_a ? p.vecw_a == 0 : p.a.stride[d0] != es_a) ok = false;
+      if (nin == 2 && (p.stage_b ? p.vecw_b == 0 : p.b.stride[d0] != es_b)) ok = false;
+      const int vmax = std::max(p.vecw_o, std::max(p.stage_a ? p.vecw_a : 0, p.stage_b ? p.vecw_b : 0));
+      if (p.tile_bits - vmax < 8) ok = false;  // fewer vectors than lanes in some order
+      int64_t span_o = 0, span_a = 0, span_b = 0;
+      for (int d = 0; d < n && ok; ++d) {
+        const int64_t ext = (int64_t)1 << p.tile_log2[d];
+        if (p.size[d] % ext != 0) ok = false;
+        if (ext > 1 && (p.a.stride[d] < 0 || p.b.stride[d] < 0)) ok = false;
+        span_o += (ext - 1) * p.out.stride[d];
+        span_a += (ext - 1) * iabs64(p.a.stride[d]);
+        span_b += (ext - 1) * iabs64(p.b.stride[d]);
       }
-      if (cont < 0 || run >= 128 || 128 % run != 0 || ins[x]->stride[cont] < 0) continue;
-      const int lg = run == 64 ? 1 : run == 32 ? 2 : 0;
-      if (lg == 0 || p.ntiles[cont] % (1 << lg) != 0 || p.total_tiles % (8 << lg) != 0) continue;
-      p.pair_dim = cont;
-      p.pair_log2 = lg;
+      const int64_t lim = ((int64_t)1 << 31) - 64;
+      p.fast_tiled = ok && span_o < lim && span_a < lim && span_b < lim;
     }
-    break;
-  }
+    if (p.fast_tiled) {
+      // An input whose contiguous run inside a tile is a fraction of a 128-byte line shares its
+      // lines with the neighbouring tiles along the dim that continues the run.  Such tiles are
+      // handed to workgroups that land on the same XCD one after the other (see the kernel), so
+      // that the line is fetched into that L2 once instead of once per tile.
+      p.pair_dim = -1;
+      p.pair_log2 = 0;
+      const Operand *ins[2] = {&p.a, &p.b};
+      const int es_in[2] = {es_a, es_b};
+      for (int x = 0; x < nin && p.pair_dim < 0; ++x) {
+        int64_t run = es_in[x];
+        int cont = -1;
+        for (bool more = true; more;) {
+          more = false;
+          for (int d = 0; d < n; ++d) {
+            if (iabs64(ins[x]->stride[d]) != run || p.size[d] == 1) continue;
+            const int64_t ext = (int64_t)1 << p.tile_log2[d];
+            if (ext >= p.size[d]) {  // fully covered: the run goes on along another dim
+              run *= p.size[d];
+              more = true;
+            } else {                 // the neighbouring tiles along d continue the run
+              run *= ext;
+              cont = d;
+            }
+            break;
+          }
+        }
+        if (cont < 0 || run >= 128 || 128 % run != 0 || ins[x]->stride[cont] < 0) continue;
+        const int lg = run == 64 ? 1 : run == 32 ? 2 : 0;
+        if (lg == 0 || p.ntiles[cont] % (1 << lg) != 0 || p.total_tiles % (8 << lg) != 0) continue;
+        p.pair_dim = cont;
+        p.pair_log2 = lg;
+      }
+      break;
+    }
   }  // attempts
   p.vec = 1 << p.vecw_o;
   if (p.total_tiles >= ((int64_t)1 << 31)) {  // tile coordinates are 32-bit: use the 64-bit generic kernel
