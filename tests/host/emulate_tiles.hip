@@ -58,7 +58,7 @@ static HostTensor make_view(int dt, int ndim, const int64_t *sizes, char *base, 
   return h;
 }
 
-static int g_stats[7];  // tiled-or-generic, staged a, staged b, vector compute, vector staging, edge tiles, fast form
+static int g_stats[8];  // tiled-or-generic, staged a, staged b, vector compute, vector staging, edge tiles, fast form, paired tiles
 
 // Replay of ew_tiled_fast_kernel: returns 0 when every output element is written once, from the
 // right input elements, with every access in range and aligned.
@@ -323,6 +323,7 @@ static int check_case(int dt, int ndim, const int64_t *sizes, int case_no) {
   if (count != numel) { std::printf("case %d: %ld of %ld output elements written\n", case_no, (long)count, (long)numel); return 1; }
   if (p.fast_tiled) {
     g_stats[6]++;
+    if (p.pair_dim >= 0) g_stats[7]++;
     return check_fast(p, a, b, o, es, case_no);
   }
   return 0;
@@ -333,13 +334,15 @@ int main(int argc, char **argv) {
   const int dts[5] = {DT_U8, DT_I16, DT_F32, DT_F64, DT_C64};
   int tiled = 0;
   for (int c = 0; c < ncases; ++c) {
-    const int ndim = rnd_in(1, 5);
+    // every sixth case: three to five small power-of-two extents (short runs of every operand:
+    // the shapes whose neighbouring tiles share cache lines)
+    const int ndim = c % 6 == 0 ? rnd_in(3, 5) : rnd_in(1, 5);
     int64_t sizes[8];
     int64_t total = 1;
     for (int i = 0; i < ndim; ++i) {
       const int kind = rnd_in(0, 3);
       sizes[i] = kind == 0 ? rnd_in(1, 4) : kind == 1 ? rnd_in(5, 20) : kind == 2 ? (1 << rnd_in(2, 6)) : rnd_in(21, 70);
-      if (c % 3 == 0) sizes[i] = 1 << rnd_in(1, 6);  // every third case: power-of-two extents (no clipped tiles)
+      if (c % 3 == 0) sizes[i] = 1 << rnd_in(1, c % 6 == 0 ? 4 : 6);  // every third case: power-of-two extents (no clipped tiles)
       if (total * sizes[i] > 300000) sizes[i] = 2;
       total *= sizes[i];
     }
@@ -353,7 +356,7 @@ int main(int argc, char **argv) {
     ++tiled;
   }
   std::printf("ok: %d cases; %d used the tiled kernel (staged a %d, staged b %d, vector compute %d, "
-              "vector staging %d, clipped tile dims %d, all-vector form %d)\n", tiled, g_stats[0], g_stats[1], g_stats[2],
-              g_stats[3], g_stats[4], g_stats[5], g_stats[6]);
+              "vector staging %d, clipped tile dims %d, all-vector form %d, with grouped tiles %d)\n", tiled, g_stats[0],
+              g_stats[1], g_stats[2], g_stats[3], g_stats[4], g_stats[5], g_stats[6], g_stats[7]);
   return 0;
 }

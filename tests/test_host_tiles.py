@@ -18,6 +18,6 @@ def test_tiled_kernel_index_emulation(tmp_path):
            os.path.join(ROOT, "tests", "host", "emulate_tiles.hip"), os.path.join(csrc, "planner.cpp"),
            os.path.join(csrc, "ew_launch.cpp")]
     subprocess.run(cmd, check=True, capture_output=True)
-    r = subprocess.run([str(exe), "700"], capture_output=True, text=True, timeout=300)
+    r = subprocess.run([str(exe), "6000"], capture_output=True, text=True, timeout=300)
     assert r.returncode == 0, r.stdout[-2000:]
     assert r.stdout.startswith("ok:")
