@@ -1142,6 +1142,7 @@ void plan_second_pass(const RedPlan &first, char *workspace, RedPlan *second) {
     q.kernel = OCN_KERNEL_RED_ROWS;
     q.group = 1;                       // lanes per output: the partials of one output are adjacent
     while (q.group < first.split && q.group < kWave) q.group <<= 1;
+    if (first.split >= 4 * kBlock) q.group = kBlock;   // as in the first pass: four partials per lane and more
     q.chunk = first.split;  // vectors (vec = 1) per output
     q.grid = (q.nout * q.group + kBlock - 1) / kBlock;
   } else if (!rows_layout && first.nkept >= 1 && q.nout < ((int64_t)1 << 31)) {
