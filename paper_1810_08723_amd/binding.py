@@ -138,6 +138,11 @@ class Tensor:
         return Tensor(storage.data_ptr(), dtype, tuple(sizes), tuple(strides), offset, dev, storage)
 
     def desc(self) -> OcnTensor:
+        # the C struct is rebuilt only when a field has changed (the library never writes to it)
+        key = (self.base, self.dtype, self.sizes, self.strides, self.offset, self.device)
+        cached = self.__dict__.get("_desc_cache")
+        if cached is not None and cached[0] == key:
+            return cached[1]
         t = OcnTensor()
         t.base = self.base
         t.offset = self.offset
@@ -147,6 +152,7 @@ class Tensor:
             t.size[d] = self.sizes[d]
             t.stride[d] = self.strides[d]
         t.device = self.device
+        self.__dict__["_desc_cache"] = (key, t)
         return t
 
 
