@@ -60,7 +60,11 @@ def test_fuzz_reduce(seed):
         if len(shape) == 0:
             continue
         dt = ("int8", "uint8", "int16", "int32", "int64", "uint32", "bool")[int(rng.integers(0, 7))]
-        a = random_strided_view(rng, dt, shape, allow_broadcast=False)
+        a = random_strided_view(rng, dt, shape, allow_broadcast=bool(it % 2))   # every other case may have zero strides
+        if tuple(a.sizes) != tuple(shape):  # axes left to be broadcast: a reduction wants them spelled out (zero strides)
+            while a.ndim < len(shape):
+                a = a.unsqueeze(0)
+            a = a.broadcast_to(shape)
         naxes = int(rng.integers(0, len(shape) + 1))
         axes = [int(x) for x in rng.permutation(len(shape))[:naxes]]
         kept = [s for d, s in enumerate(shape) if d not in axes]

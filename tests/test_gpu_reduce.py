@@ -299,3 +299,22 @@ def test_few_columns_share_a_wavefront(ncol):
     _check("sum", b, [1])
     c = random_view(rng, "int16", (70000, ncol))
     _check("sum", c, [0])
+
+
+def test_broadcast_inputs():
+    # zero strides along reduced and kept axes (views made by broadcasting): every layout branch
+    rng = rng_for(10370)
+    row = random_view(rng, "int32", (1, 70))
+    col = random_view(rng, "int32", (300, 1))
+    one = random_view(rng, "float", (1, 1), specials=False)
+    for v in (row.broadcast_to((300, 70)), col.broadcast_to((300, 70)), one.broadcast_to((300, 70))):
+        for axes in ([0], [1], [0, 1]):
+            _check("sum", v, axes)
+            _check("max", v, axes)
+    cube = random_view(rng, "double", (20, 1, 33), specials=False).broadcast_to((20, 500, 33))
+    for axes in ([1], [0, 1], [1, 2], [2], [0, 2], [0, 1, 2]):
+        _check("sum", cube, axes)
+    wide = random_view(rng, "int8", (1, 5000)).broadcast_to((4000, 5000))     # long reductions of a broadcast axis
+    _check("sum", wide, [0])
+    _check("sum", wide, [1])
+    _check("sum", wide, [0, 1])
