@@ -315,14 +315,14 @@ struct VecFold<DT_F16, OP, V, std::enable_if_t<(OP == R_MIN || OP == R_MAX) && V
     for (int k = 0; k < 4; ++k) add_word(w[k]);
   }
   OCN_DEV void add_partial(const Pk &pk, int n) {
-    const uint16_t *h = reinterpret_cast<const uint16_t *>(&pk);
-    // pad the missing slots by repeating the first element (n >= 1 here)
+    // pad the missing slots by repeating the first element (n >= 1 here).  The bits are taken
+    // element by element from the values that were stored (no access through another type: the
+    // elements were written as halves, and only the first n of them).
+    uint32_t h[V];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      const uint32_t lo = 2 * k < n ? h[2 * k] : h[0];
-      const uint32_t hi = 2 * k + 1 < n ? h[2 * k + 1] : h[0];
-      add_word(lo | (hi << 16));
-    }
+    for (int i = 0; i < V; ++i) h[i] = __builtin_bit_cast(uint16_t, pk.v[i < n ? i : 0]);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) add_word(h[2 * k] | (h[2 * k + 1] << 16));
   }
   OCN_DEV A result() {
     const unsigned short m = mag.x > mag.y ? mag.x : mag.y;

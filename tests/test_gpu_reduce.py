@@ -318,3 +318,43 @@ def test_broadcast_inputs():
     _check("sum", wide, [0])
     _check("sum", wide, [1])
     _check("sum", wide, [0, 1])
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_fuzz_float_reductions(seed):
+    # random shapes, strides (steps, flips, permuted storage, zero strides) and axes with
+    # floating types: sums within the tolerance of their type, min/max bit for bit
+    from workloads.fuzz import random_shape, random_strided_view
+    rng = rng_for(10400 + seed)
+    for it in range(8):
+        shape = random_shape(rng, max_ndim=5, max_elems=30000)
+        if len(shape) == 0 or 0 in shape:
+            continue
+        dt = ("half", "float", "double", "cfloat")[int(rng.integers(0, 4))]
+        a = random_strided_view(rng, dt, shape, specials=False, allow_broadcast=bool(it % 2))
+        if tuple(a.sizes) != tuple(shape):
+            while a.ndim < len(shape):
+                a = a.unsqueeze(0)
+            a = a.broadcast_to(shape)
+        naxes = int(rng.integers(1, len(shape) + 1))
+        axes = sorted(int(x) for x in rng.permutation(len(shape))[:naxes])
+        print("fuzz-float-reduce", seed, it, shape, axes, dt, a.strides, flush=True)
+        _check("sum", a, axes)
+        if dt != "cfloat":
+            _check("max", a, axes)
+
+
+@pytest.mark.parametrize("n", (1, 2, 3, 5, 7, 8, 9, 11, 15, 16, 19))
+def test_half_min_max_with_a_partial_last_vector(n):
+    # rows whose length is not a multiple of the eight halves of a vector, starting on a
+    # 16-byte boundary (the vector path), with subnormals, infinities and signed zeros among
+    # the values: the elements of the partial vector must all take part, and only they
+    bits = np.array([0xFC00, 0x0008, 0xF442, 0x8000, 0x0000, 0x8001, 0x7BFF, 0x0001, 0x7C00, 0x3C00, 0xBC00],
+                    dtype=np.uint16)
+    rng = rng_for(10500 + n)
+    for trial in range(6):
+        row = bits[rng.integers(0, len(bits) - (3 if trial < 3 else 0), size=(4, n))]   # first trials: nothing above 1.0
+        x = View.from_numpy(row.view(np.float16))
+        for op in ("max", "min"):
+            _check(op, x, [1])
+            _check(op, x, [0, 1])
