@@ -394,17 +394,44 @@ template <class F> OCN_DEV F cosh_any(F x) { if constexpr (sizeof(F) == 4) retur
 template <class F> OCN_DEV F abs_any(F x) { if constexpr (sizeof(F) == 4) return __builtin_fabsf(x); else return __builtin_fabs(x); }
 template <class F> OCN_DEV F copysign_any(F x, F y) { if constexpr (sizeof(F) == 4) return __builtin_copysignf(x, y); else return __builtin_copysign(x, y); }
 
+// a * b where an exact zero wins: 0 * Inf = 0 and 0 * NaN = 0 (sign as for finite factors).
+// In sin, cos and exp of a complex number a factor is an exact zero only when a component of
+// the argument is a zero (or the exponential underflowed); the other factor may have overflowed
+// to infinity, and the product is then the zero that C's complex functions return, not NaN.
+template <class F> OCN_DEV F times_zero_wins(F a, F b) {
+  if (a == 0 || b == 0) {
+    const bool neg = (a == a && __builtin_signbit(a)) != (b == b && __builtin_signbit(b));
+    return neg ? -(F)0 : (F)0;
+  }
+  return a * b;
+}
+
 template <int OP, class F> OCN_DEV void elementary_complex(F x, F y, F &re, F &im) {
+  // Beyond this argument exp, cosh and sinh overflow although their product with a small sine
+  // or cosine may not: the exponential is then applied in two halves, (t * e^(u/2)) * e^(u/2).
+  const F half_range = sizeof(F) == 4 ? (F)88 : (F)709;
   if constexpr (OP == U_SIN) {          // sin x cosh y + i cos x sinh y
     F s, c;
     sincos_any(x, s, c);
-    re = s * cosh_any(y);
-    im = c * sinh_any(y);
+    if (abs_any(y) > half_range) {       // cosh y = |sinh y| = e^|y| / 2 to the last bit
+      const F h = exp_any(abs_any(y) * (F)0.5);
+      re = times_zero_wins(times_zero_wins(s, h), h * (F)0.5);
+      im = times_zero_wins(times_zero_wins(c, h), copysign_any(h * (F)0.5, y));
+    } else {
+      re = times_zero_wins(s, cosh_any(y));
+      im = times_zero_wins(c, sinh_any(y));
+    }
   } else if constexpr (OP == U_COS) {   // cos x cosh y - i sin x sinh y
     F s, c;
     sincos_any(x, s, c);
-    re = c * cosh_any(y);
-    im = -(s * sinh_any(y));
+    if (abs_any(y) > half_range) {
+      const F h = exp_any(abs_any(y) * (F)0.5);
+      re = times_zero_wins(times_zero_wins(c, h), h * (F)0.5);
+      im = -times_zero_wins(times_zero_wins(s, h), copysign_any(h * (F)0.5, y));
+    } else {
+      re = c * cosh_any(y);
+      im = -times_zero_wins(s, sinh_any(y));
+    }
   } else if constexpr (OP == U_TAN) {   // (sin x cos x + i sinh y cosh y) / (cos^2 x + sinh^2 y)
     const F big = sizeof(F) == 4 ? (F)20 : (F)40;
     F s, c;
@@ -421,9 +448,15 @@ template <int OP, class F> OCN_DEV void elementary_complex(F x, F y, F &re, F &i
   } else if constexpr (OP == U_EXP) {   // e^x (cos y + i sin y)
     F s, c;
     sincos_any(y, s, c);
-    const F e = exp_any(x);
-    re = e * c;
-    im = e * s;
+    if (x > half_range) {
+      const F h = exp_any(x * (F)0.5);
+      re = times_zero_wins(times_zero_wins(h, c), h);
+      im = times_zero_wins(times_zero_wins(h, s), h);
+    } else {
+      const F e = exp_any(x);
+      re = times_zero_wins(e, c);
+      im = times_zero_wins(e, s);
+    }
   } else if constexpr (OP == U_LOG) {   // log |z| + i arg z
     const F h = hypot_any(x, y);
     if (h > (F)0.5 && h < (F)2) {        // near the unit circle: log |z| = log1p(|z|^2 - 1) / 2 without cancellation
@@ -434,9 +467,19 @@ template <int OP, class F> OCN_DEV void elementary_complex(F x, F y, F &re, F &i
     }
     im = atan2_any(y, x);
   } else {                              // U_SQRT, principal branch, signed zeros as in C
+    const F inf = (F)__builtin_inff();
     if (x == 0 && y == 0) {
       re = 0;
       im = y;
+    } else if (abs_any(y) == inf) {      // an infinite imaginary part wins over everything (as in C)
+      re = inf;
+      im = y;
+    } else if (x == inf) {               // sqrt(+Inf + iy) = +Inf + i0 for finite y
+      re = inf;
+      im = y == y ? copysign_any((F)0, y) : y;
+    } else if (x == -inf) {              // sqrt(-Inf + iy) = 0 + i Inf for finite y
+      re = y == y ? (F)0 : y;
+      im = copysign_any(inf, y);
     } else {
       const F t = sqrt_any((abs_any(x) + hypot_any(x, y)) * (F)0.5);
       if (x >= 0) { re = t; im = y / (2 * t); }

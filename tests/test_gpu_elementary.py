@@ -1,7 +1,12 @@
 """GPU parity of the elementary functions (sin, cos, tan, exp, log, complex sqrt) against the
 oracle, in the tolerance class these operations have: a few units in the last place of the
 output type (real: |gpu - oracle| <= K ulp of the oracle value; complex: each component within
-K ulp of the magnitude of the oracle value), special values exactly."""
+K ulp of the magnitude of the oracle value).  Results of finite arguments agree with the
+oracle in kind (NaN, signed infinity, signed zero), and so does the complex square root for
+infinite parts.  Not compared: sin, cos, tan and exp of complex arguments with an infinite or
+NaN part, where the kernels evaluate the plain formulas (e.g. exp(Inf + i Inf) gives NaN + i NaN,
+C gives Inf + i NaN; cos(Inf + i0) gives NaN - i0, C gives NaN + i0; tan(Inf + i Inf) gives
+NaN + i, C gives 0 + i)."""
 import numpy as np
 import pytest
 
@@ -116,6 +121,41 @@ def test_special_values_and_branch_cuts():
     assert np.allclose(got, want, rtol=1e-6, atol=0) and np.array_equal(np.signbit(got.imag), np.signbit(want.imag))
     got, want = _run("log", z.slice(0, 0, 3, 1), View.empty("cfloat", (3,)))
     assert np.allclose(got, want, rtol=1e-6, atol=1e-7) and np.array_equal(np.signbit(got.imag), np.signbit(want.imag))
+
+
+def _same_class(g, w, rtol):
+    """Equal in kind (NaN, infinity with its sign, zero with its sign), else close."""
+    if np.isnan(w):
+        return bool(np.isnan(g))
+    if np.isinf(w) or w == 0:
+        return bool(g == w and np.signbit(g) == np.signbit(w))
+    return bool(abs(g - w) <= rtol * abs(w))
+
+
+@pytest.mark.parametrize("dt", ("cfloat", "cdouble"))
+def test_complex_functions_of_finite_arguments_with_zero_and_huge_parts(dt):
+    # A component that is exactly zero, next to one that makes a factor overflow: the products
+    # in sin, cos and exp must give the zero (0 * Inf), not NaN; tiny and huge magnitudes
+    # elsewhere.  Every finite argument must agree with the oracle in kind, part by part.
+    big = 1e30 if dt == "cfloat" else 1e300
+    parts = [0.0, -0.0, 1.0, -1.0, 0.5, big, -big, 1e-40 if dt == "cfloat" else 1e-310, 700.0, -700.0, 89.0, -104.0]
+    z = np.array([complex(a, b) for a in parts for b in parts])
+    for op in ("sqrt", "exp", "log", "sin", "cos"):
+        a = _complex_view(z, dt)
+        got, want = _run(op, a, View.empty(dt, a.sizes))
+        for i in range(len(z)):
+            ok = _same_class(got[i].real, want[i].real, 1e-5) and _same_class(got[i].imag, want[i].imag, 1e-5)
+            assert ok, (op, dt, z[i], got[i], want[i])
+
+
+def test_complex_square_root_of_infinite_arguments():
+    inf, nan = np.inf, np.nan
+    z = np.array([complex(a, b) for a in (0.0, -0.0, 1.0, -1.0, inf, -inf, nan) for b in (inf, -inf)] +
+                 [complex(a, b) for a in (inf, -inf) for b in (0.0, -0.0, 2.0, -2.0)], dtype=np.complex64)
+    a = View.from_numpy(z)
+    got, want = _run("sqrt", a, View.empty("cfloat", a.sizes))
+    for i in range(len(z)):
+        assert _same_class(got[i].real, want[i].real, 1e-6) and _same_class(got[i].imag, want[i].imag, 1e-6), (z[i], got[i], want[i])
 
 
 def test_mixed_types_and_errors():
