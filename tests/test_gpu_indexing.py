@@ -253,3 +253,47 @@ def test_gather_scatter_row_lengths_and_alignments(dt, inner_len):
     got3 = dv.download(inner).copy()
     OI.scatter(src, poffs, inner, 0, (nrows - 1) * a.strides[0])
     assert np.array_equal(got3, a.storage)
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_fuzz_gather_scatter(seed):
+    # random element types, inner shapes (0 to 3 dims, permuted), strided row tensors and offsets
+    # (some outside the stated range): gather into a strided output, scatter of distinct rows
+    import torch
+    import paper_1810_08723_amd as ocn
+    from workloads.fuzz import random_strided_view
+    rng = rng_for(17500 + seed)
+    types = ("int8", "int16", "half", "float", "double", "cfloat", "cdouble", "int64", "bool")
+    for it in range(6):
+        dt = types[int(rng.integers(0, len(types)))]
+        es = itemsize(dt)
+        nin = int(rng.integers(0, 4))
+        inner_shape = tuple(int(rng.choice([1, 2, 3, 4, 5, 8, 16, 17, 33, 64])) for _ in range(nin))
+        nrows = int(rng.integers(1, 60))
+        full = random_view(rng, dt, (nrows,) + inner_shape)
+        perm = [int(p) for p in rng.permutation(nin)] if nin else []
+        inner = View(full.storage, dt, tuple(inner_shape[p] for p in perm), tuple(full.strides[1 + p] for p in perm),
+                     full.offset)
+        pick = int(rng.integers(0, 200))
+        offs = rng.integers(0, nrows, size=(pick,)).astype(np.int64) * full.strides[0]
+        if pick and rng.random() < 0.5:
+            bad = rng.integers(0, pick, size=(max(1, pick // 7),))
+            offs[bad] = rng.choice([-es, 10 ** 9, nrows * full.strides[0]], size=bad.shape)
+        lo, hi = 0, (nrows - 1) * full.strides[0]
+        out = random_strided_view(rng, dt, (pick,) + inner.sizes, writable=True)
+        print("fuzz-gather", seed, it, dt, inner_shape, perm, pick, flush=True)
+        dv = H.DeviceViews()
+        ocn.gather(dv.tensor(inner), _dev_i64(offs), lo, hi, dv.tensor(out))
+        torch.cuda.synchronize()
+        got = dv.download(out).copy()
+        OI.gather(inner, offs, out, lo, hi)
+        assert np.array_equal(got, out.storage)
+        k = int(rng.integers(0, nrows + 1))
+        soffs = rng.permutation(nrows)[:k].astype(np.int64) * full.strides[0]
+        src = random_strided_view(rng, dt, (k,) + inner.sizes, allow_broadcast=False)
+        dv = H.DeviceViews()
+        ocn.scatter(dv.tensor(src), _dev_i64(soffs), lo, hi, dv.tensor(inner))
+        torch.cuda.synchronize()
+        got = dv.download(inner).copy()
+        OI.scatter(src, soffs, inner, lo, hi)
+        assert np.array_equal(got, full.storage)
