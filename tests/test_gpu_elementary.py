@@ -159,6 +159,24 @@ def test_complex_square_root_of_infinite_arguments():
         assert _same_class(got[i].real, want[i].real, 1e-6) and _same_class(got[i].imag, want[i].imag, 1e-6), (z[i], got[i], want[i])
 
 
+@pytest.mark.parametrize("dt", tuple(REAL))
+def test_real_functions_at_special_and_extreme_arguments(dt):
+    # zeros, infinities, NaN, the largest and smallest magnitudes, arguments around the overflow
+    # and underflow of exp, outside the domain of asin, acos and log: same kind of result
+    # (NaN, signed infinity, signed zero) as the oracle, close where finite
+    ft = REAL[dt]
+    fi = np.finfo(ft)
+    vals = np.array([0.0, -0.0, 1.0, -1.0, 0.5, -0.5, 2.0, -2.0, np.inf, -np.inf, np.nan, fi.max, -fi.max, fi.tiny,
+                     -fi.tiny, fi.tiny / 4, 1e-3, 11.0, -11.0, 89.0, -89.0, 104.0, -104.0, 709.0, 710.0, -745.0,
+                     -746.0, 1e4, -1e4, 1.0000001, -1.0000001], dtype=ft)
+    rtol = {"half": 2e-3, "float": 1e-5, "double": 1e-12}[dt]
+    for op in ("sin", "cos", "tan", "exp", "log", "asin", "acos", "atan", "sinh", "cosh", "tanh", "sqrt"):
+        a = View.from_numpy(vals.copy())
+        got, want = _run(op, a, View.empty(dt, a.sizes))
+        for i in range(len(vals)):
+            assert _same_class(float(got[i]), float(want[i]), rtol), (op, dt, float(vals[i]), float(got[i]), float(want[i]))
+
+
 def test_mixed_types_and_errors():
     import paper_1810_08723_amd as ocn
     rng = rng_for(16200)
