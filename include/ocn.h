@@ -224,6 +224,10 @@ int ocn_mask_offsets(const ocn_tensor *mask, const int64_t *target_strides, void
  * old contents (pass the smallest and largest offset that stays inside the storage).
  * ocn_scatter: the reverse copy, src[j, i...] into the indexed tensor; offsets that repeat
  * leave one of the written values, which one is not defined.
+ * A lane moves one item (an element, or 16 bytes where the rows' fastest dimension is
+ * contiguous and 16-byte aligned on both sides); rows of up to 256 items share a workgroup.
+ * OCN_ERR_SHAPE if the copy needs 2^32 lanes or more (n times the items of a row, rounded up
+ * to a power of two for short rows): split the offsets into several calls.
  */
 int ocn_gather(const ocn_tensor *a_inner, const void *offsets, int64_t n, int64_t lo, int64_t hi,
                const ocn_tensor *out, void *stream);
