@@ -263,7 +263,10 @@ int ocn_dtype_size(int dtype);
 /* Static description of a status code. */
 const char *ocn_error_string(int code);
 
-/* The hipError_t (as int) behind the most recent OCN_ERR_LAUNCH on this host thread. */
+/* The hipError_t (as int) behind the most recent OCN_ERR_LAUNCH on this host thread.  A launch
+ * that would need 2^32 lanes or more (e.g. 2^32 elements through the generic-dtype kernel, or
+ * 2^26 reduction outputs of a wavefront each) is refused by the runtime and reported this way;
+ * nothing has run then. */
 int ocn_last_hip_error(void);
 
 /* ---- plan inspection (host only; launches nothing, touches no device memory) -------- */
