@@ -190,6 +190,58 @@ template <class G, int OP> __global__ __launch_bounds__(kBlock) void fred_rows_k
   }
 }
 
+// Rows of at most one vector per lane of their group, a single reduced dim, no split: the same
+// groups, loads and fold order as fred_rows_kernel without its loops and 64-bit bookkeeping.
+template <class G, int OP, int V>
+OCN_DEV typename FusedFold<G, OP>::A fred_short_row(const RedArgs &p, const char *pa, const char *pb, uint32_t lane) {
+  using F = FusedFold<G, OP>;
+  using A = typename F::A;
+  using SAt = typename G::SAt;
+  using SBt = typename G::SBt;
+  A acc = F::R::identity();
+  if (lane < (uint32_t)p.nvec) {
+    const bool abc = p.a_bcast, bbc = p.b_bcast;
+    const uint32_t e0 = lane * V;
+    const char *qa = pa + (abc ? 0 : (int64_t)e0 * (int64_t)sizeof(SAt));
+    const char *qb = pb + (bbc ? 0 : (int64_t)e0 * (int64_t)sizeof(SBt));
+    const uint32_t left = (uint32_t)p.n0 - e0;
+    if (left >= (uint32_t)V) {
+      Pack<SAt, V> va;
+      Pack<SBt, V> vb;
+      fused_load<SAt, V>(qa, abc, va);
+      fused_load<SBt, V>(qb, bbc, vb);
+#pragma unroll
+      for (int i = 0; i < V; ++i) acc = F::add(acc, va.v[i], vb.v[i]);
+    } else {
+#pragma unroll
+      for (int i = 0; i < V; ++i)
+        if (i < (int)left)
+          acc = F::add(acc, reinterpret_cast<const SAt *>(qa)[abc ? 0 : i], reinterpret_cast<const SBt *>(qb)[bbc ? 0 : i]);
+    }
+  }
+  return acc;
+}
+
+template <class G, int OP> __global__ __launch_bounds__(kBlock) void fred_rows_short_kernel(const RedArgs p) {
+  using F = FusedFold<G, OP>;
+  using R = typename F::R;
+  using A = typename F::A;
+  const uint32_t width = (uint32_t)p.group;
+  const uint32_t gl = blockIdx.x * kBlock + threadIdx.x;
+  const uint32_t o = gl >> (__ffs(p.group) - 1), lane = gl & (width - 1);
+  const bool active = o < (uint32_t)p.nout;
+  A acc = R::identity();
+  int64_t off_o = 0;
+  if (active) {
+    int64_t off_a, off_b;
+    kept_offsets2(p, o, off_a, off_b, off_o);
+    if (p.vec > 1) acc = fred_short_row<G, OP, G::V>(p, p.a + off_a, p.b + off_b, lane);
+    else acc = fred_short_row<G, OP, 1>(p, p.a + off_a, p.b + off_b, lane);
+  }
+  acc = group_fold<R>(acc, (int)width);
+  if (active && lane == 0) store_result<A>(p.out + off_o, p.out_dtype, acc);
+}
+
 // ---------------------------------------------------------------------------------------
 // cols: a kept axis is the fastest of the inputs; lanes own output columns
 // ---------------------------------------------------------------------------------------

@@ -918,6 +918,8 @@ void choose_fused_launch(RedPlan &p) {
     p.chunk = (nvec + p.split - 1) / p.split;
     p.split = (nvec + p.chunk - 1) / p.chunk;
     p.grid = (p.nout * p.split + groups_per_block - 1) / groups_per_block;
+    p.short_rows = p.group <= kWave && nvec <= p.group && p.nred == 1 && p.split == 1 &&
+                   p.nout * p.group < ((int64_t)1 << 32) && n0 < ((int64_t)1 << 31);
   } else if (k_fast_dim >= 0 && k_fast_dim == p.nkept - 1 && p.nred >= 1 && idx32 &&
              fast_ok(p.kstride_a[k_fast_dim], p.kstride_b[k_fast_dim]) && (r_fast == 0 || r_fast > k_fast)) {
     p.kernel = OCN_KERNEL_RED_COLS;
