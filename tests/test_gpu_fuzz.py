@@ -164,3 +164,28 @@ def test_unclipped_form_on_known_shapes(case):
         plan = ocn.plan_binary(op, dv.tensor(a), dv.tensor(b), dv.tensor(out))
         assert plan["kernel"] == "ew_tiled" and plan["unclipped"], plan
         H.check_binary(op, a, b, out)
+
+
+MIXED_PAIRS = [("int32", "float", "float"), ("float", "int32", "float"), ("half", "float", "float"),
+               ("float", "half", "float"), ("float", "double", "double"), ("double", "float", "double"),
+               ("int32", "double", "double"), ("double", "int32", "double"), ("int64", "double", "double"),
+               ("double", "int64", "double"), ("float", "cfloat", "cfloat"), ("cfloat", "float", "cfloat"),
+               ("double", "cdouble", "cdouble"), ("cdouble", "double", "cdouble")]
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_fuzz_mixed_types_converted_on_load(seed):
+    """+, -, *, / on the mixed input type pairs that have kernels of their own, over random
+    shapes (every third one with power-of-two extents) and random strided views."""
+    rng = rng_for(11800 + seed)
+    for it in range(10):
+        da, db, dout = MIXED_PAIRS[int(rng.integers(0, len(MIXED_PAIRS)))]
+        op = ("add", "sub", "mul", "div")[int(rng.integers(0, 4))]
+        shape = random_shape(rng, max_ndim=5, max_elems=20000)
+        if it % 3 == 0:
+            shape = tuple(1 << int(rng.integers(1, 6)) for _ in range(int(rng.integers(2, 5))))
+        a = random_strided_view(rng, da, shape)
+        b = random_strided_view(rng, db, shape)
+        out = random_strided_view(rng, dout, shape, writable=True)
+        print("fuzz-mixed", seed, it, op, da, db, shape, a.strides, b.strides, out.strides, flush=True)
+        H.check_binary(op, a, b, out)
