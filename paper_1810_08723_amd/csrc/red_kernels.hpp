@@ -609,7 +609,58 @@ OCN_DEV void cols_body(const RedArgs &p, typename Reducer<S, OP>::A (*lds)[kWave
   struct alignas(sizeof(St) * V >= 16 ? 16 : sizeof(St) * V) Pk { St v[V]; };
   const int RS = NW * RPW;           // rows between two rows of the same lane
   int64_t r = r0 + wave * RPW + lr;
-  if (ncol == V) {  // whole vectors of columns: no per-element conditions
+  // Sums of 8-bit integers: the sixteen columns of a vector are added two at a time, as 16-bit
+  // halves of 32-bit words (signed bytes biased by 128 to make them unsigned), and spilled into
+  // the 64-bit accumulators every 256 rows, before a half can overflow (256 * 255 < 2^16).
+  constexpr bool PACKED8 = (S == DT_I8 || S == DT_U8) && OP == R_SUM && V == 16;
+  bool packed_done = false;
+  if constexpr (PACKED8) {
+    if (ncol == V) {
+      packed_done = true;
+      uint32_t even[4] = {0, 0, 0, 0}, odd[4] = {0, 0, 0, 0};  // bytes 0 and 2 / 1 and 3 of each word
+      uint32_t pending = 0;                                    // rows added since the last spill
+      auto spill = [&]() {
+        const A bias = S == DT_I8 ? (A)128 * (A)pending : (A)0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          acc[4 * k + 0] += (A)(even[k] & 0xffffu) - bias;
+          acc[4 * k + 1] += (A)(odd[k] & 0xffffu) - bias;
+          acc[4 * k + 2] += (A)(even[k] >> 16) - bias;
+          acc[4 * k + 3] += (A)(odd[k] >> 16) - bias;
+          even[k] = odd[k] = 0;
+        }
+        pending = 0;
+      };
+      auto add_row = [&](const Pk &pk) {
+        uint32_t w[4];
+        __builtin_memcpy(w, &pk, 16);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const uint32_t x = S == DT_I8 ? w[k] ^ 0x80808080u : w[k];
+          even[k] += x & 0x00ff00ffu;
+          odd[k] += (x >> 8) & 0x00ff00ffu;
+        }
+        if (++pending == 256) spill();
+      };
+      for (; r + (int64_t)(U - 1) * RS < r1; r += RS * U) {
+        Pk pk[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+          load_vec<St, V>(p.a + off_a + reduced_offset(p, (uint32_t)(r + (int64_t)u * RS), 0), pk[u]);
+#pragma unroll
+        for (int u = 0; u < U; ++u) add_row(pk[u]);
+      }
+      for (; r < r1; r += RS) {
+        Pk pk;
+        load_vec<St, V>(p.a + off_a + reduced_offset(p, (uint32_t)r, 0), pk);
+        add_row(pk);
+      }
+      spill();
+    }
+  }
+  if (packed_done) {
+    // (nothing left to add)
+  } else if (ncol == V) {  // whole vectors of columns: no per-element conditions
     for (; r + (int64_t)(U - 1) * RS < r1; r += RS * U) {
       Pk pk[U];
 #pragma unroll

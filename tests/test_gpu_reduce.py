@@ -358,3 +358,20 @@ def test_half_min_max_with_a_partial_last_vector(n):
         for op in ("max", "min"):
             _check(op, x, [1])
             _check(op, x, [0, 1])
+
+
+@pytest.mark.parametrize("dt", ("int8", "uint8"))
+def test_column_sums_of_8_bit_integers_spill_before_overflow(dt):
+    # extreme values in every row for more rows than a 16-bit half can hold (the packed
+    # accumulation spills every 256 rows), a ragged last column block, and several kept dims
+    info = np.iinfo(np.int8 if dt == "int8" else np.uint8)
+    rng = rng_for(10600 + (dt == "int8"))
+    for fill in (info.min, info.max):
+        x = np.full((3000, 80), fill, dtype=info.dtype)
+        x[rng.integers(0, 3000, 200), rng.integers(0, 80, 200)] = info.max if fill == info.min else info.min
+        _check("sum", View.from_numpy(x), [0])
+    y = rng.integers(info.min, info.max, size=(5, 1200, 3, 48), endpoint=True).astype(info.dtype)
+    _check("sum", View.from_numpy(y), [1])
+    _check("sum", View.from_numpy(y), [0, 1])
+    z = rng.integers(info.min, info.max, size=(70001, 16), endpoint=True).astype(info.dtype)
+    _check("sum", View.from_numpy(z), [0])
