@@ -168,6 +168,19 @@ def _check(rc: int) -> None:
         raise OcnError(rc)
 
 
+def _scratch(nbytes: int, device: int, stream):
+    """A workspace this wrapper allocates on the caller's behalf.  torch's caching allocator ties
+    a block to the stream that was current when it was allocated and may hand it out again as
+    soon as the last reference is dropped; the kernels that use the block run on `stream`, so
+    when that is another stream the block is recorded as in use there and is not reused before
+    the enqueued work has finished."""
+    import torch
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=f"cuda:{device}")
+    if stream is not None and int(stream) != int(torch.cuda.current_stream(device).cuda_stream):
+        ws.record_stream(torch.cuda.ExternalStream(int(stream), device=f"cuda:{device}"))
+    return ws
+
+
 def _axes(axes: Sequence[int]):
     return (C.c_int32 * max(len(axes), 1))(*axes), len(axes)
 
@@ -200,8 +213,7 @@ def reduce(op: str, a: Tensor, axes: Sequence[int], out: Tensor, workspace=None,
     if workspace is None:
         need = reduce_workspace_bytes(op, a, axes, out)
         if need:
-            import torch
-            workspace = torch.empty(need, dtype=torch.uint8, device=f"cuda:{a.device}")
+            workspace = _scratch(need, a.device, stream)
     if workspace is not None:
         ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel()
     _check(lib().ocn_reduce(REDUCE_CODE[op], C.byref(a.desc()), ax, n, C.byref(out.desc()),
@@ -224,8 +236,7 @@ def binary_reduce(ew_op: str, red_op: str, a: Tensor, b: Tensor, axes: Sequence[
     if workspace is None:
         need = binary_reduce_workspace_bytes(ew_op, red_op, a, b, axes, out, mid_dtype)
         if need:
-            import torch
-            workspace = torch.empty(need, dtype=torch.uint8, device=f"cuda:{a.device}")
+            workspace = _scratch(need, a.device, stream)
     if workspace is not None:
         ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel()
     _check(lib().ocn_binary_reduce(BINARY_CODE[ew_op], REDUCE_CODE[red_op], C.byref(a.desc()), C.byref(b.desc()),
@@ -244,8 +255,7 @@ def mask_offsets(mask: Tensor, target_strides: Sequence[int], offsets, count, wo
     int64 torch tensor; `workspace`: uint8 torch tensor or None to allocate one through torch."""
     need = int(lib().ocn_mask_offsets_workspace_bytes(C.byref(mask.desc())))
     if workspace is None:
-        import torch
-        workspace = torch.empty(max(need, 8), dtype=torch.uint8, device=f"cuda:{mask.device}")
+        workspace = _scratch(max(need, 8), mask.device, stream)
     ts = (C.c_int64 * max(len(target_strides), 1))(*target_strides)
     _check(lib().ocn_mask_offsets(C.byref(mask.desc()), ts, offsets.data_ptr() if offsets.numel() else None,
                                   offsets.numel(), count.data_ptr(), workspace.data_ptr(), workspace.numel(),
@@ -272,7 +282,7 @@ def domain_check(op: str, a: Tensor, flag=None, workspace=None, stream=None):
     tf = Tensor(flag.data_ptr(), "bool", (), (), 0, a.device, flag)
     if workspace is None:
         need = int(lib().ocn_domain_check_workspace_bytes(UNARY_CODE[op], C.byref(a.desc())))
-        workspace = torch.empty(need, dtype=torch.uint8, device=f"cuda:{a.device}")
+        workspace = _scratch(need, a.device, stream)
     _check(lib().ocn_domain_check(UNARY_CODE[op], C.byref(a.desc()), C.byref(tf.desc()), workspace.data_ptr(),
                                   workspace.numel(), _stream(stream)))
     return flag

@@ -11,8 +11,10 @@ from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
-OBJ = os.path.join(HERE, "_build")
-LIB = os.path.join(HERE, "libocn.so")
+# OCN_BUILD_TAG builds an experimental variant beside the library (with OCN_EXTRA_FLAGS)
+_TAG = os.environ.get("OCN_BUILD_TAG", "")
+OBJ = os.path.join(HERE, "_build" + ("_" + _TAG if _TAG else ""))
+LIB = os.path.join(HERE, "libocn" + ("_" + _TAG if _TAG else "") + ".so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 # Floating-point contraction stays off: a*b+c must round twice, as in the definition of each
@@ -26,8 +28,30 @@ SOURCES = (["api.cpp", "planner.cpp", "ew_launch.cpp", "red_launch.cpp", "ew_int
            + [f"fred_slice_{i}.hip" for i in range(4)])
 
 
-def _compile(src: str) -> str:
+def _stamp(src: str) -> str:
+    """Fingerprint of everything an object depends on: its source, the files it includes and the
+    flags."""
+    import hashlib
+    h = hashlib.sha256(" ".join(COMMON).encode())
+    import re
+    seen, todo = [], [os.path.join(CSRC, src)]
+    while todo:                      # the files it includes with quotes, transitively
+        path = os.path.normpath(todo.pop())
+        if path in seen or not os.path.exists(path):
+            continue
+        seen.append(path)
+        text = open(path, "rb").read()
+        h.update(path.encode() + text)
+        for inc in re.findall(rb'^\s*#\s*include\s+"([^"]+)"', text, flags=re.M):
+            todo.append(os.path.join(os.path.dirname(path), inc.decode()))
+    return h.hexdigest()
+
+
+def _compile(src: str, force: bool = True) -> str:
     obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
+    stamp_file, stamp = obj + ".stamp", _stamp(src)
+    if not force and os.path.exists(obj) and os.path.exists(stamp_file) and open(stamp_file).read() == stamp:
+        return obj
     cmd = [HIPCC, *COMMON, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in r.stderr.splitlines() if "is not a recognized feature" not in l)
@@ -35,18 +59,21 @@ def _compile(src: str) -> str:
         raise RuntimeError(f"hipcc failed on {src}:\n{err}")
     if err.strip():
         sys.stderr.write(err + "\n")
+    open(stamp_file, "w").write(stamp)
     return obj
 
 
-def build(jobs: int | None = None) -> str:
+def build(jobs: int | None = None, force: bool = True) -> str:
+    """Compiles every source and links the library.  force=False recompiles only the objects
+    whose source, headers or flags changed since they were last built."""
     os.makedirs(OBJ, exist_ok=True)
     jobs = jobs or min(16, os.cpu_count() or 4)
     with ThreadPoolExecutor(max_workers=jobs) as ex:
-        objs = list(ex.map(_compile, SOURCES))
+        objs = list(ex.map(lambda src: _compile(src, force), SOURCES))
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     subprocess.run(cmd, check=True)
     return LIB
 
 
 if __name__ == "__main__":
-    print(build())
+    print(build(force="--changed" not in sys.argv))

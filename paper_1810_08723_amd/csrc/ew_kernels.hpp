@@ -33,6 +33,8 @@ struct RowsArgs {
   int64_t nvec;      // vectors in total
   int32_t a_bcast, b_bcast;
   int32_t nt_store;  // stream the output past the caches
+  int32_t nt_a, nt_b; // read that input with streaming (non-temporal) loads
+  int32_t simple;     // at most one outer dim, rows of whole vectors, fewer than 2^31 vectors
 };
 
 constexpr int kMaxTilePasses = 16;  // a tile holds at most 4096 elements = 16 passes of 256 lanes
@@ -134,19 +136,41 @@ template <class S, int V> struct alignas(sizeof(S) * V >= 16 ? 16 : sizeof(S) * 
   S v[V];
 };
 
-template <class S, int V> OCN_DEV void load_pack(const char *p, Pack<S, V> &dst) {
+#define OCN_KEEP_BRANCH() asm volatile("")
+// `nt`: a streaming (non-temporal) load, for inputs too large to be found in a cache again
+// (the hint is only ever set for a single piece of at most 16 bytes per lane).  The empty asm
+// statements keep the two branches apart; merged, the hint would be dropped.
+template <class S, int V> OCN_DEV void load_pack(const char *p, Pack<S, V> &dst, bool nt = false) {
   constexpr int B = sizeof(S) * V;
   if constexpr (B >= 16) {
     using Q = uint32_t __attribute__((ext_vector_type(4)));
+    if (B == 16 && nt) {
+      OCN_KEEP_BRANCH();
+      reinterpret_cast<Q *>(&dst)[0] = __builtin_nontemporal_load(reinterpret_cast<const Q *>(p));
+      OCN_KEEP_BRANCH();
+    } else {
 #pragma unroll
-    for (int i = 0; i < B / 16; ++i) {
-      reinterpret_cast<Q *>(&dst)[i] = reinterpret_cast<const Q *>(p)[i];
+      for (int i = 0; i < B / 16; ++i) {
+        reinterpret_cast<Q *>(&dst)[i] = reinterpret_cast<const Q *>(p)[i];
+      }
     }
   } else if constexpr (B == 8) {
     using D = uint32_t __attribute__((ext_vector_type(2)));
-    *reinterpret_cast<D *>(&dst) = *reinterpret_cast<const D *>(p);
+    if (nt) {
+      OCN_KEEP_BRANCH();
+      *reinterpret_cast<D *>(&dst) = __builtin_nontemporal_load(reinterpret_cast<const D *>(p));
+      OCN_KEEP_BRANCH();
+    } else {
+      *reinterpret_cast<D *>(&dst) = *reinterpret_cast<const D *>(p);
+    }
   } else if constexpr (B == 4) {
-    *reinterpret_cast<uint32_t *>(&dst) = *reinterpret_cast<const uint32_t *>(p);
+    if (nt) {
+      OCN_KEEP_BRANCH();
+      *reinterpret_cast<uint32_t *>(&dst) = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(p));
+      OCN_KEEP_BRANCH();
+    } else {
+      *reinterpret_cast<uint32_t *>(&dst) = *reinterpret_cast<const uint32_t *>(p);
+    }
   } else if constexpr (B == 2) {
     *reinterpret_cast<uint16_t *>(&dst) = *reinterpret_cast<const uint16_t *>(p);
   } else {
@@ -159,7 +183,6 @@ template <class S, int V> OCN_DEV void load_pack(const char *p, Pack<S, V> &dst)
 // kernel then pays for writing them back while it reads (measured: up to a third of its time).
 // (The empty asm statements fence the streaming branch: without them the compiler merges the
 // two stores of an if/else into one and drops the hint.)
-#define OCN_KEEP_BRANCH() asm volatile("")
 template <class S, int V> OCN_DEV void store_pack(char *p, const Pack<S, V> &src, bool nt = false) {
   constexpr int B = sizeof(S) * V;
   if constexpr (B >= 16) {
@@ -215,6 +238,8 @@ template <int OP, int SA, int SB, int SO, int NIN> struct Sig {
   static constexpr int SA_DT = SA, SB_DT = SB, SO_DT = SO;
   static constexpr int V = rows_vec((int)sizeof(SOt), ES_MAX);
   static constexpr int U = rows_unroll(V, ES_MAX);
+  static constexpr int VR = rows_stream_vec((int)sizeof(SOt), ES_MIN, ES_MAX);  // the rows kernel's vector
+  static constexpr int UR = rows_stream_unroll(VR, ES_MAX);
 
   OCN_DEV static SOt eval(SAt a, SBt b) {
     reg_t<T> ra = convert<T>(from_storage<SA>(a));
@@ -233,8 +258,8 @@ template <int OP, int SA, int SB, int SO, int NIN> struct Sig {
 // rows kernel
 // ---------------------------------------------------------------------------------------
 
-template <class G> __global__ __launch_bounds__(kBlock) void ew_rows_kernel(const RowsArgs p) {
-  constexpr int V = G::V, U = G::U;
+template <class G> OCN_DEV void rows_general(const RowsArgs &p) {
+  constexpr int V = G::VR, U = G::UR;
   using SAt = typename G::SAt;
   using SBt = typename G::SBt;
   using SOt = typename G::SOt;
@@ -284,7 +309,7 @@ template <class G> __global__ __launch_bounds__(kBlock) void ew_rows_kernel(cons
 #pragma unroll
           for (int i = 0; i < V; ++i) va[u].v[i] = s;
         } else {
-          load_pack<SAt, V>(pa, va[u]);
+          load_pack<SAt, V>(pa, va[u], p.nt_a != 0);
         }
         if constexpr (BIN) {
           if (p.b_bcast) {
@@ -292,7 +317,7 @@ template <class G> __global__ __launch_bounds__(kBlock) void ew_rows_kernel(cons
 #pragma unroll
             for (int i = 0; i < V; ++i) vb[u].v[i] = s;
           } else {
-            load_pack<SBt, V>(pb, vb[u]);
+            load_pack<SBt, V>(pb, vb[u], p.nt_b != 0);
           }
         }
       } else {
@@ -326,6 +351,67 @@ template <class G> __global__ __launch_bounds__(kBlock) void ew_rows_kernel(cons
         if (i < n) reinterpret_cast<SOt *>(po)[i] = r.v[i];
     }
   }
+}
+
+// The common shapes - at most one outer dim, rows of whole vectors, fewer than 2^31 vectors -
+// need one division per vector and no per-element conditions.
+template <class G> OCN_DEV void rows_simple(const RowsArgs &p) {
+  constexpr int V = G::VR, U = G::UR;
+  using SAt = typename G::SAt;
+  using SBt = typename G::SBt;
+  using SOt = typename G::SOt;
+  constexpr bool BIN = G::NIN2;
+  const uint32_t g0 = blockIdx.x * (uint32_t)(kBlock * U) + threadIdx.x;
+  const uint32_t nvec = (uint32_t)p.nvec;
+  const bool two_d = p.nouter != 0;
+  Pack<SAt, V> va[U];
+  Pack<SBt, V> vb[U];
+  int64_t oo[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const uint32_t g = g0 + (uint32_t)u * kBlock;
+    oo[u] = 0;
+    if (g < nvec) {
+      const uint32_t row = two_d ? fastdiv(g, p.vpr_div) : 0u;
+      const int64_t e0 = (int64_t)(g - row * p.vpr_div.d) * V;
+      oo[u] = (int64_t)row * p.so[0] + e0 * (int64_t)sizeof(SOt);
+      const char *pa = p.a + (int64_t)row * p.sa[0];
+      if (p.a_bcast) {
+        const SAt s = *reinterpret_cast<const SAt *>(pa);
+#pragma unroll
+        for (int i = 0; i < V; ++i) va[u].v[i] = s;
+      } else {
+        load_pack<SAt, V>(pa + e0 * (int64_t)sizeof(SAt), va[u], p.nt_a != 0);
+      }
+      if constexpr (BIN) {
+        const char *pb = p.b + (int64_t)row * p.sb[0];
+        if (p.b_bcast) {
+          const SBt s = *reinterpret_cast<const SBt *>(pb);
+#pragma unroll
+          for (int i = 0; i < V; ++i) vb[u].v[i] = s;
+        } else {
+          load_pack<SBt, V>(pb + e0 * (int64_t)sizeof(SBt), vb[u], p.nt_b != 0);
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    if (g0 + (uint32_t)u * kBlock < nvec) {
+      Pack<SOt, V> r;
+#pragma unroll
+      for (int i = 0; i < V; ++i) {
+        if constexpr (BIN) r.v[i] = G::eval(va[u].v[i], vb[u].v[i]);
+        else r.v[i] = G::eval(va[u].v[i], SBt{});
+      }
+      store_pack<SOt, V>(p.out + oo[u], r, p.nt_store != 0);
+    }
+  }
+}
+
+template <class G> __global__ __launch_bounds__(kBlock) void ew_rows_kernel(const RowsArgs p) {
+  if (p.simple) rows_simple<G>(p);
+  else rows_general<G>(p);
 }
 
 // ---------------------------------------------------------------------------------------

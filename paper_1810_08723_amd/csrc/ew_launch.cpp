@@ -31,6 +31,11 @@ RowsArgs make_rows_args(const EwPlan &p) {
   r.a_bcast = p.a_inner_bcast;
   r.b_bcast = p.b_inner_bcast;
   r.nt_store = p.nt_store;
+  r.nt_a = p.nt_a;
+  r.nt_b = p.nt_b;
+  // with no outer dim the "row" is the whole tensor: so[0], sa[0], sb[0] stay zero and unused
+  r.simple = inner <= 1 && r.inner % p.vec == 0 && r.nvec < ((int64_t)1 << 31) &&
+             (int64_t)p.grid * kBlock * p.unroll < ((int64_t)1 << 32);
   return r;
 }
 

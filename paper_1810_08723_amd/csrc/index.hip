@@ -404,14 +404,15 @@ int ocn_index_offsets(const ocn_tensor *index, int64_t dim_size, int64_t stride_
   a.dim_size = dim_size;
   a.stride = stride_bytes;
   a.invalid = (unsigned long long *)invalid_count;
-  hipStream_t s = (hipStream_t)stream;
-  hipLaunchKernelGGL(fill_u64_kernel, dim3(1), dim3(1), 0, s, a.invalid, 0ull);
+  // every check comes before the first launch: on error nothing has been enqueued or written
+  const int64_t grid = (a.n + kBlock - 1) / kBlock;
   if (a.n > 0) {
     if (!index->base || !offsets->base) return OCN_ERR_NULLPTR;
-    const int64_t grid = (a.n + kBlock - 1) / kBlock;
     if (grid >= ((int64_t)1 << 31)) return OCN_ERR_SHAPE;
-    hipLaunchKernelGGL(index_offsets_kernel, dim3((unsigned)grid), dim3(kBlock), 0, s, a);
   }
+  hipStream_t s = (hipStream_t)stream;
+  hipLaunchKernelGGL(fill_u64_kernel, dim3(1), dim3(1), 0, s, a.invalid, 0ull);
+  if (a.n > 0) hipLaunchKernelGGL(index_offsets_kernel, dim3((unsigned)grid), dim3(kBlock), 0, s, a);
   return done(hipGetLastError());
 }
 

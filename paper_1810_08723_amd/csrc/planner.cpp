@@ -394,10 +394,12 @@ int plan_elementwise(int nin, int op, const ocn_tensor *a, const ocn_tensor *b,
   // An output of 32 MiB or more will not be found in the caches by whoever reads it next
   // (4 MB of L2 per XCD, 256 MB of Infinity Cache shared with the inputs): write it with
   // streaming stores, so that its dirty lines do not burden the next kernel.
-  p.nt_store = numel * es_o >= ((int64_t)32 << 20);
+  p.nt_store = numel * es_o >= kStreamBytes;
   const int inner = n - 1;
   const int es_max = std::max({es_o, es_a, nin == 2 ? es_b : es_a});
-  const int V = rows_vec(es_o, es_max);
+  const int es_min = std::min({es_o, es_a, nin == 2 ? es_b : es_a});
+  const int VT = rows_vec(es_o, es_max);                    // the tiled kernel's compute vector (Sig::V)
+  const int V = rows_stream_vec(es_o, es_min, es_max);      // the rows kernel's vector (Sig::VR)
   auto inner_ok = [&](int64_t stride, int es) { return stride == es || stride == 0; };
   bool rows = p.specialised && p.out.stride[inner] == es_o && inner_ok(p.a.stride[inner], es_a) &&
               (nin == 1 || inner_ok(p.b.stride[inner], es_b));
@@ -419,9 +421,23 @@ int plan_elementwise(int nin, int op, const ocn_tensor *a, const ocn_tensor *b,
     if (rows) {
       p.kernel = OCN_KERNEL_EW_ROWS;
       p.vec = V;
-      p.unroll = rows_unroll(V, es_max);
+      p.unroll = rows_stream_unroll(V, es_max);
       p.a_inner_bcast = p.a.stride[inner] == 0;
       p.b_inner_bcast = nin == 2 && p.b.stride[inner] == 0;
+      // Inputs too large to be found in a cache again are read with streaming loads: those
+      // that move one piece per lane and are not broadcast along any dim (a broadcast operand
+      // is re-read from the caches by every row).
+      auto streamed = [&](const Operand &x, int es) {
+        if (V * es > 16) return false;
+        int64_t distinct = es;
+        for (int d = 0; d < n; ++d) {
+          if (x.stride[d] == 0) return false;
+          distinct *= p.size[d];
+        }
+        return distinct >= kStreamBytes;
+      };
+      p.nt_a = streamed(p.a, es_a);
+      p.nt_b = nin == 2 && streamed(p.b, es_b);
       const int64_t nvec = vpr * nrows;
       p.grid = (nvec + (int64_t)kBlock * p.unroll - 1) / ((int64_t)kBlock * p.unroll);
       p.lds_bytes = 0;
@@ -484,15 +500,15 @@ int plan_elementwise(int nin, int op, const ocn_tensor *a, const ocn_tensor *b,
     if (p.nord > 0) {
       const int d0 = p.ord_o[0];
       // compute phase: V consecutive elements along the output's fastest dim per lane
-      bool ok = p.out.stride[d0] == es_o && p.tile_log2[d0] >= log2i(V) && V > 1 &&
-                aligned(p.out, (int64_t)V * es_o, d0);
+      bool ok = p.out.stride[d0] == es_o && p.tile_log2[d0] >= log2i(VT) && VT > 1 &&
+                aligned(p.out, (int64_t)VT * es_o, d0);
       auto direct_ok = [&](const Operand &x, int es, bool staged) {
         if (staged) return true;
         if (x.stride[d0] != es) return true;  // broadcast or strided: element loads, no constraint
-        return aligned(x, (int64_t)V * es, d0);
+        return aligned(x, (int64_t)VT * es, d0);
       };
       ok = ok && direct_ok(p.a, es_a, p.stage_a) && (nin == 1 || direct_ok(p.b, es_b, p.stage_b));
-      if (ok) p.vecw_o = log2i(V);
+      if (ok) p.vecw_o = log2i(VT);
       auto stage_vec = [&](const Operand &x, int es, const int8_t *ord) {
         const int v = 16 / es;
         if (v <= 1) return 0;
@@ -714,6 +730,11 @@ void choose_reduce_launch(RedPlan &p) {
     p.grid = (p.nout * p.split + groups_per_block - 1) / groups_per_block;
     p.short_rows = p.group <= kWave && nvec <= p.group && p.nred == 1 && p.split == 1 &&
                    p.nout * p.group < ((int64_t)1 << 32) && n0 < ((int64_t)1 << 31);
+    // the common 2-D shape: one reduced dim of whole vectors, at most one kept dim, a wavefront or
+    // a workgroup per output (or per split of it), everything below 2^31
+    p.lean = !p.short_rows && p.nred == 1 && p.nkept <= 1 && p.vec > 1 && es < 16 && n0 % p.vec == 0 &&
+             p.group >= kWave && nvec < ((int64_t)1 << 31) && p.nout * p.split < ((int64_t)1 << 31) &&
+             p.chunk < ((int64_t)1 << 31);
   } else if (cols_ok) {
     // ---- cols: a kept axis is the input's fastest; lanes own output columns -------------
     // (requires that axis to be the last canonical kept dim, i.e. also the output's fastest)
@@ -752,6 +773,9 @@ void choose_reduce_launch(RedPlan &p) {
   }
   p.passes = p.split > 1 ? 2 : 1;
   p.workspace_bytes = p.split > 1 ? (size_t)(p.nout * p.split * acc_es) : 0;
+  // an input that cannot stay in the caches anyway is read with streaming loads (whole
+  // 16-byte vectors only: neighbouring lanes then cover whole lines)
+  p.nt_load = p.vec > 1 && p.kernel != OCN_KERNEL_RED_GENERIC && p.nout * p.nredtot * es >= kStreamBytes;
 }
 
 }  // namespace
@@ -920,6 +944,7 @@ void choose_fused_launch(RedPlan &p) {
     p.grid = (p.nout * p.split + groups_per_block - 1) / groups_per_block;
     p.short_rows = p.group <= kWave && nvec <= p.group && p.nred == 1 && p.split == 1 &&
                    p.nout * p.group < ((int64_t)1 << 32) && n0 < ((int64_t)1 << 31);
+
   } else if (k_fast_dim >= 0 && k_fast_dim == p.nkept - 1 && p.nred >= 1 && idx32 &&
              fast_ok(p.kstride_a[k_fast_dim], p.kstride_b[k_fast_dim]) && (r_fast == 0 || r_fast > k_fast)) {
     p.kernel = OCN_KERNEL_RED_COLS;

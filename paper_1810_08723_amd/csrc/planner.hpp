@@ -21,6 +21,10 @@ constexpr int kWave = 64;
 constexpr int64_t kNumCUs = 256;          // MI355X: 8 XCDs x 32 compute units
 constexpr uint32_t kXcds = 8;
 constexpr int64_t kLdsPerCu = 160 * 1024;  // bytes of LDS per compute unit
+// Operands of this many bytes or more are streamed: stores bypass the caches (an ordinary store
+// leaves the lines dirty in the 256 MB Infinity Cache and the next kernel pays for the
+// write-back), loads carry the non-temporal hint.
+constexpr int64_t kStreamBytes = (int64_t)32 << 20;
 #ifndef OCN_MAX_BLOCKS_PER_CU
 #define OCN_MAX_BLOCKS_PER_CU 8
 #endif
@@ -67,6 +71,7 @@ struct EwPlan {
   bool specialised = false;     // a dtype-specialised kernel exists for this signature
   bool fast_tiled = false;      // tiled kernel: the unclipped all-vector form applies
   bool nt_store = false;        // the output is too large to stay cached: stream it past the caches
+  bool nt_a = false, nt_b = false;  // rows kernel: that input is read with streaming loads
   int64_t grid = 0;
   int64_t lds_bytes = 0;
   int pair_dim = -1;            // all-vector tiled form: tiles that are neighbours along this dim share
@@ -88,6 +93,8 @@ struct RedPlan {
   int block = kBlock;           // threads per workgroup (the cols kernel may use 1024)
   bool short_rows = false;      // rows kernel: every row fits one vector per lane of its group (loop-free kernel)
   int cpw = kWave;              // cols kernel: lanes per row of columns (power of two, at most a wavefront)
+  bool nt_load = false;         // the input is far larger than the caches: stream it (non-temporal vector loads)
+  bool lean = false;            // rows kernel: the common 2-D shape, run by the lean form of the kernel
   int64_t split = 1;            // partial results per output
   int64_t chunk = 0;            // reduction elements (rows: vectors) per split
   int64_t grid = 0;

@@ -41,6 +41,7 @@ RedArgs make_red_args(const RedPlan &p, char *partial) {
   r.nredtot = p.nredtot;
   r.split = p.split;
   r.chunk = p.chunk;
+  r.nt_load = p.nt_load ? 1 : 0;
   if (p.kernel == OCN_KERNEL_RED_ROWS) {
     r.n0 = p.rsize[p.nred - 1];
     const int64_t vpr = (r.n0 + p.vec - 1) / p.vec;
@@ -52,6 +53,24 @@ RedArgs make_red_args(const RedPlan &p, char *partial) {
     const int64_t colblocks = (r.nc + (int64_t)p.cpw * p.vec - 1) / ((int64_t)p.cpw * p.vec);
     r.colblocks_div = make_fastdiv((uint32_t)colblocks);
   }
+  return r;
+}
+
+RedLeanArgs make_red_lean_args(const RedPlan &p, char *partial) {
+  RedLeanArgs r;
+  std::memset(&r, 0, sizeof r);
+  r.a = p.a_ptr;
+  r.out = p.out_ptr;
+  r.partial = partial;
+  r.ksa = p.nkept ? p.kstride_a[0] : 0;
+  r.kso = p.nkept ? p.kstride_o[0] : 0;
+  r.nout = (uint32_t)p.nout;
+  r.split = (uint32_t)p.split;
+  r.nvec = (uint32_t)(p.nredtot / p.vec);
+  r.chunk = (uint32_t)p.chunk;
+  r.out_dtype = p.out_dtype;
+  r.group = p.group;
+  r.nt_load = p.nt_load ? 1 : 0;
   return r;
 }
 

@@ -13,12 +13,18 @@ extern RedLauncher g_reduce_launchers[R_COUNT][DT_COUNT];
 extern RedLauncher g_fused_launchers[B_COUNT][DT_COUNT][R_COUNT];
 
 RedArgs make_red_args(const RedPlan &p, char *partial);
+RedLeanArgs make_red_lean_args(const RedPlan &p, char *partial);
 
 #if defined(__HIPCC__)
 template <int S, int OP> hipError_t launch_red(const RedPlan &p, char *partial, hipStream_t stream) {
   const RedArgs args = make_red_args(p, partial);
   switch (p.kernel) {
     case OCN_KERNEL_RED_ROWS:
+      if (p.lean) {
+        hipLaunchKernelGGL((red_rows_lean_kernel<S, OP>), dim3((unsigned)p.grid), dim3(kBlock), 0, stream,
+                           make_red_lean_args(p, partial));
+        break;
+      }
       if (p.short_rows) {
         hipLaunchKernelGGL((red_rows_short_kernel<S, OP>), dim3((unsigned)p.grid), dim3(kBlock), 0, stream, args);
         break;

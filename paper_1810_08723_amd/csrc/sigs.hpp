@@ -93,4 +93,22 @@ OCN_HD constexpr int rows_unroll(int vec, int es_max) {
   return imax(1, imin(OCN_ROWS_MAXU, 64 / (vec * es_max)));
 }
 
+// The rows kernel's own choice.  Every operand moves ONE piece of at most 16 bytes per lane
+// and vector, the widest exactly 16, so that the lanes of a wavefront cover whole cache lines
+// of every operand with a single instruction each - the access shape that streaming
+// (non-temporal) loads and stores need (a double -> int16 cast of 16 Mi elements: 28.8 us with
+// 64-byte inputs and 16-byte outputs per lane, 27.1 us with 16-byte inputs and 4-byte outputs).
+// A narrow operand still moves at least 4 bytes where the output's 16-byte limit allows it;
+// the wide one then takes several pieces and is read without the hint.
+OCN_HD constexpr int rows_stream_vec(int es_out, int es_min, int es_max) {
+  return imax(1, imin(16 / es_out, imax(16 / es_max, 4 / es_min)));
+}
+#ifndef OCN_ROWS_STREAM_BYTES
+#define OCN_ROWS_STREAM_BYTES 32
+#endif
+// vectors per lane: about 32 bytes of the widest operand in flight per lane
+OCN_HD constexpr int rows_stream_unroll(int vec, int es_max) {
+  return imax(1, imin(4, OCN_ROWS_STREAM_BYTES / (vec * es_max)));
+}
+
 }  // namespace ocn

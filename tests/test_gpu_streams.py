@@ -111,6 +111,39 @@ def test_two_streams_at_once():
         assert np.all(np.abs(got[2].view(np.float64) - s.storage.view(np.float64)) <= 1e-13 * np.abs(x).sum(axis=1) + 1e-300)
 
 
+def test_split_reductions_on_side_streams_with_wrapper_allocated_workspaces():
+    # Two chains of two-launch (split) reductions on two side streams, each call letting the
+    # wrapper allocate its workspace.  The workspace of one call is dropped by the wrapper while
+    # its second launch may still be pending; unless the block is recorded as in use on the side
+    # stream, the allocator hands it to the other chain's next call and the partial results mix.
+    import torch
+    import paper_1810_08723_amd as ocn
+    from oracle import binding as O
+    rng = rng_for(14003)
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    jobs = []
+    for k in range(2):
+        n = (1 << 22) + 4099 * (k + 1)
+        x = View.from_numpy(rng.integers(-128, 127, size=n, endpoint=True, dtype=np.int8))
+        outs = [View.empty("int64", ()) for _ in range(6)]
+        dv = H.DeviceViews()
+        tx = dv.tensor(x)
+        touts = [dv.tensor(o) for o in outs]
+        plan = ocn.plan_reduce("sum", tx, [0], touts[0])
+        assert plan["split"] > 1 and plan["passes"] == 2
+        jobs.append((dv, x, outs, tx, touts))
+    torch.cuda.synchronize()
+    for rep in range(6):
+        for k, (dv, x, outs, tx, touts) in enumerate(jobs):
+            ocn.reduce("sum", tx, [0], touts[rep], stream=streams[k].cuda_stream)
+    torch.cuda.synchronize()
+    for dv, x, outs, tx, touts in jobs:
+        want = View.empty("int64", ())
+        O.reduce("sum", x, [0], want)
+        for o in outs:
+            assert np.array_equal(dv.download(o), want.storage)
+
+
 def test_graph_of_fused_reduce_mask_compaction_gather_and_domain_check():
     # the later entry points under capture: every buffer (outputs, workspaces, the count) is
     # allocated before the capture, the calls only launch kernels.  Each replay is compared

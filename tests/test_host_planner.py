@@ -80,7 +80,8 @@ def test_worked_plan_config2_keeps_the_flipped_rows():
     assert plan["size"] == (64, 48)
     assert plan["stride_a"] == (-48 * 8, 8) and plan["stride_out"] == (96, 2)
     assert plan["offset_a"] == 63 * 48 * 8
-    assert plan["kernel"] == "ew_rows" and plan["vec"] == 8
+    # the widest operand (the double input) moves 16 bytes per lane: two elements
+    assert plan["kernel"] == "ew_rows" and plan["vec"] == 2
 
 
 def test_worked_plan_config3_broadcast_row_blocks_the_merge():
@@ -211,14 +212,15 @@ def test_reduce_plan_preserves_addend_sets(seed):
     assert {k: sorted(v) for k, v in raw.items()} == {k: sorted(v) for k, v in got.items()}
 
 
-def test_vector_length_follows_the_output_width():
-    # a lane stores 16 bytes per vector whatever the inputs' widths: widening operations read
-    # narrower pieces, narrowing ones several 16-byte pieces (at most 64 bytes)
+def test_vector_length_gives_the_widest_operand_sixteen_bytes():
+    # per lane and vector the widest operand moves one 16-byte piece and the others one narrower
+    # piece each, but no operand less than 4 bytes where the output's 16-byte limit allows it
     def vec(din, dout):
         return ocn.plan_unary("ident", fake(View.empty(din, (1 << 16,)), 0), fake(View.empty(dout, (1 << 16,)), 2))["vec"]
     assert vec("int8", "int32") == 4 and vec("half", "float") == 4 and vec("float", "double") == 2
-    assert vec("double", "int16") == 8 and vec("double", "float") == 4 and vec("cdouble", "bool") == 4
+    assert vec("double", "int16") == 2 and vec("double", "float") == 2 and vec("cdouble", "bool") == 4
     assert vec("float", "float") == 4 and vec("int8", "int8") == 16 and vec("cdouble", "cdouble") == 1
+    assert vec("double", "int8") == 4 and vec("float", "int8") == 4 and vec("int8", "double") == 2
 
 
 def test_general_form_layout_and_short_fastest_axes():
