@@ -167,6 +167,23 @@ int ocn_reduce(int op, const ocn_tensor *a, const int32_t *axes, int32_t naxes,
                const ocn_tensor *out, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * ocn_reduce for callers that cannot allocate device memory and have no workspace to pass:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, kernels, results (bit for bit) and errors as ocn_reduce, except that the partial
+ * results of a split reduction live in a fixed array of OCN_REDUCE_SCRATCH_BYTES bytes inside
+ * the library's device image (every GPU the library runs on holds its own copy until the
+ * process ends).  The call allocates and frees nothing.  OCN_ERR_WORKSPACE if the reduction
+ * would need more than that (ocn_reduce_workspace_bytes tells; ocn_reduce takes any size);
+ * OCN_ERR_DEVICE unless a->device is the calling thread's current HIP device.  All calls on
+ * one GPU share the one array: two calls whose enqueued work may overlap in time (different
+ * streams) race on it; calls on one stream are ordered and safe.  Nothing is carried from one
+ * call to the next: every partial result that is read was written by the same call.
+ */
+#define OCN_REDUCE_SCRATCH_BYTES (1u << 20)
+int ocn_reduce_scratch(int op, const ocn_tensor *a, const int32_t *axes, int32_t naxes,
+                       const ocn_tensor *out, void *stream);
+
+/*
  * Reduction of an elementwise result (sections 3.2 and 5: elementwise functions followed by a
  * reduction along axes, as in inner products and norms): what
  *     ocn_binary(ew_op, a, b, t);  ocn_reduce(red_op, t, axes, naxes, out, ...)

@@ -40,7 +40,7 @@ EXPORTS = ("ocn_unary", "ocn_binary", "ocn_cast_copy", "ocn_reduce", "ocn_reduce
            "ocn_plan_unary", "ocn_plan_binary", "ocn_plan_reduce",
            "ocn_binary_reduce", "ocn_binary_reduce_workspace_bytes", "ocn_plan_binary_reduce",
            "ocn_index_offsets", "ocn_mask_offsets", "ocn_mask_offsets_workspace_bytes", "ocn_gather",
-           "ocn_scatter", "ocn_domain_check", "ocn_domain_check_workspace_bytes")
+           "ocn_scatter", "ocn_domain_check", "ocn_domain_check_workspace_bytes", "ocn_reduce_scratch")
 
 
 class OcnTensor(C.Structure):
@@ -90,6 +90,7 @@ def lib() -> C.CDLL:
         L.ocn_reduce.argtypes = [C.c_int, T, C.POINTER(C.c_int32), C.c_int32, T, C.c_void_p,
                                  C.c_size_t, C.c_void_p]
         L.ocn_reduce_workspace_bytes.argtypes = [C.c_int, T, C.POINTER(C.c_int32), C.c_int32, T]
+        L.ocn_reduce_scratch.argtypes = [C.c_int, T, C.POINTER(C.c_int32), C.c_int32, T, C.c_void_p]
         L.ocn_reduce_workspace_bytes.restype = C.c_size_t
         L.ocn_promote.argtypes = [C.c_int, C.c_int]
         L.ocn_dtype_size.argtypes = [C.c_int]
@@ -218,6 +219,17 @@ def reduce(op: str, a: Tensor, axes: Sequence[int], out: Tensor, workspace=None,
         ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel()
     _check(lib().ocn_reduce(REDUCE_CODE[op], C.byref(a.desc()), ax, n, C.byref(out.desc()),
                             ws_ptr, ws_bytes, _stream(stream)))
+
+
+REDUCE_SCRATCH_BYTES = 1 << 20
+
+
+def reduce_scratch(op: str, a: Tensor, axes: Sequence[int], out: Tensor, stream=None) -> None:
+    """ocn_reduce without a workspace: partial results go to the library's fixed device array
+    (at most REDUCE_SCRATCH_BYTES); nothing is allocated, here or in the library."""
+    ax, n = _axes(axes)
+    _check(lib().ocn_reduce_scratch(REDUCE_CODE[op], C.byref(a.desc()), ax, n, C.byref(out.desc()),
+                                    _stream(stream)))
 
 
 def binary_reduce_workspace_bytes(ew_op: str, red_op: str, a: Tensor, b: Tensor, axes: Sequence[int],

@@ -133,6 +133,54 @@ int ocn_binary_reduce(int ew_op, int red_op, const ocn_tensor *a, const ocn_tens
                     (hipStream_t)stream);
 }
 
+// ---- reduction without a workspace argument ----------------------------------------------
+// Partial results of a split reduction go to a fixed array in device memory instead of a
+// caller-provided workspace.  In host code the array's name is only a handle: its device
+// address is looked up once per device (with that device current) and the kernels are given
+// that address.
+static __device__ __align__(256) unsigned char scratch[OCN_REDUCE_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+static char *g_scratch_ptr[kMaxDevices];   // device address of `scratch` on each device, once known
+static std::mutex g_scratch_mutex;
+
+// device address of `scratch` on the CURRENT device (which must be `device`)
+static int scratch_address(int device, char **ptr) {
+  if (device < 0 || device >= kMaxDevices) return OCN_ERR_DEVICE;
+  int current = -1;
+  hipError_t e = hipGetDevice(&current);
+  if (e != hipSuccess) return finish(e);
+  if (current != device) return OCN_ERR_DEVICE;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[device]) {
+    void *p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return finish(e);
+    if (!p) return OCN_ERR_LAUNCH;
+    g_scratch_ptr[device] = (char *)p;
+  }
+  *ptr = g_scratch_ptr[device];
+  return OCN_OK;
+}
+
+int ocn_reduce_scratch(int op, const ocn_tensor *a, const int32_t *axes, int32_t naxes,
+                       const ocn_tensor *out, void *stream) {
+  RedPlan p;
+  const int rc = plan_reduce(op, a, axes, naxes, out, &p);
+  if (rc != OCN_OK) return rc;
+  if (p.kernel == OCN_KERNEL_NONE) return OCN_OK;
+  if (p.workspace_bytes > (size_t)OCN_REDUCE_SCRATCH_BYTES) return OCN_ERR_WORKSPACE;
+  char *ws = nullptr;
+  if (p.workspace_bytes > 0) {
+    // every partial result the second launch reads is written by the first one: nothing in
+    // the array has to be cleared between calls
+    const int st = scratch_address(a->device, &ws);
+    if (st != OCN_OK) return st;
+  }
+  ensure_registered();
+  return run_reduce(p, g_reduce_launchers[p.op][p.a_dtype], ws, (hipStream_t)stream);
+}
+
 size_t ocn_binary_reduce_workspace_bytes(int ew_op, int red_op, const ocn_tensor *a, const ocn_tensor *b,
                                          const int32_t *axes, int32_t naxes, const ocn_tensor *out,
                                          int32_t mid_dtype) {
