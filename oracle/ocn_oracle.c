@@ -511,14 +511,14 @@ static int unary_supported(int op, int T) {
   switch (op) {
     case ORC_U_IDENT: case ORC_U_CONJ: case ORC_U_LNOT: return 1;
     case ORC_U_NEG: return k != K_BOOL;
-    case ORC_U_ABS: return k != K_BOOL && k != K_CPLX; /* complex modulus is not an exact op */
+    case ORC_U_ABS: return k != K_BOOL; /* complex: the modulus, a real value (tolerance class) */
     case ORC_U_BNOT: return k == K_BOOL || k == K_SINT || k == K_UINT;
     case ORC_U_BSWAP: return k == K_BOOL || k == K_SINT || k == K_UINT;
     case ORC_U_SQRT: return k == K_REAL || k == K_CPLX;
     case ORC_U_SIN: case ORC_U_COS: case ORC_U_TAN: case ORC_U_EXP: case ORC_U_LOG:
       return k == K_REAL || k == K_CPLX;
     case ORC_U_ASIN: case ORC_U_ACOS: case ORC_U_ATAN: case ORC_U_SINH: case ORC_U_COSH: case ORC_U_TANH:
-      return k == K_REAL; /* the inverse and hyperbolic functions are built for real types only */
+      return k == K_REAL || k == K_CPLX;
     default: return 0;
   }
 }
@@ -559,6 +559,12 @@ static val_t apply_elementary(int op, int T, val_t a) {
       case ORC_U_EXP: w = cexp(z); break;
       case ORC_U_LOG: w = clog(z); break;
       case ORC_U_SQRT: w = csqrt(z); break;
+      case ORC_U_ASIN: w = casin(z); break;
+      case ORC_U_ACOS: w = cacos(z); break;
+      case ORC_U_ATAN: w = catan(z); break;
+      case ORC_U_SINH: w = csinh(z); break;
+      case ORC_U_COSH: w = ccosh(z); break;
+      case ORC_U_TANH: w = ctanh(z); break;
     }
     r.re = round_arith(t, creal(w));
     r.im = round_arith(t, cimag(w));
@@ -580,6 +586,12 @@ static val_t apply_unary(int op, int T, val_t a) {
     case ORC_U_ABS:
       if (k == K_SINT) r.i = a.i < 0 ? wrap_s((uint64_t)0 - (uint64_t)a.i, bits) : a.i;
       else if (k == K_REAL) r.re = fabs(a.re);
+      else if (k == K_CPLX) { /* the modulus: a real value of the same precision, without undue
+                                 overflow or underflow (the C library's cabs), rounded once */
+        r.k = K_REAL;
+        r.re = round_arith(arith_of(T), cabs(CMPLX(a.re, a.im)));
+        r.im = 0;
+      }
       break;
     case ORC_U_CONJ:
       if (k == K_CPLX) r.im = -a.im;
@@ -701,8 +713,13 @@ int orc_unary(int op, const orc_tensor *a, const orc_tensor *out, uint32_t flags
   if ((rc = check_tensor(a)) || (rc = check_tensor(out))) return rc;
   if (op < 0 || op >= ORC_NUM_UNARY) return ORC_ERR_OP;
   if ((rc = check_broadcast(a, out))) return rc;
+  /* compute type: the output's; bool for the logical not; the modulus of a complex tensor is
+   * evaluated in that tensor's own type (its result is the real type of the same precision) */
   int T = op == ORC_U_LNOT ? ORC_BOOL : out->dtype;
-  if ((flags & ORC_STRICT_TYPES) && op != ORC_U_LNOT && a->dtype != out->dtype) return ORC_ERR_DTYPE;
+  if (op == ORC_U_ABS && kind_of(a->dtype) == K_CPLX) T = a->dtype;
+  if ((flags & ORC_STRICT_TYPES) && op != ORC_U_LNOT && a->dtype != out->dtype &&
+      !(op == ORC_U_ABS && kind_of(a->dtype) == K_CPLX && out->dtype == real_part_type(a->dtype)))
+    return ORC_ERR_DTYPE;
   if (!unary_supported(op, T)) return ORC_ERR_DTYPE;
   int64_t n = numel(out);
 #pragma omp parallel for schedule(static)

@@ -1,4 +1,5 @@
-"""Pins for the oracle's elementary functions (sin, cos, tan, exp, log, complex sqrt): values
+"""Pins for the oracle's elementary functions (sin, cos, tan, exp, log, the inverse and
+hyperbolic functions, complex sqrt and the complex modulus): values
 computed independently of the C library with Python's arbitrary-precision `decimal` arithmetic
 (Taylor series after argument reduction; exp and ln are decimal's own), closed forms and
 identities.  The oracle must sit within one unit in the last place of the true value in double
@@ -100,6 +101,17 @@ def d_complex(op: str, x: Decimal, y: Decimal):
         return (x.exp() * c, x.exp() * s)
     if op == "log":
         return ((x * x + y * y).ln() / 2, d_atan2(y, x))
+    if op in ("sinh", "cosh", "tanh"):
+        s, c = d_sin_cos(y)
+        ch, sh = (x.exp() + (-x).exp()) / 2, (x.exp() - (-x).exp()) / 2
+        snh = (sh * c, ch * s)
+        csh = (ch * c, sh * s)
+        if op == "sinh":
+            return snh
+        if op == "cosh":
+            return csh
+        den = csh[0] ** 2 + csh[1] ** 2
+        return ((snh[0] * csh[0] + snh[1] * csh[1]) / den, (snh[1] * csh[0] - snh[0] * csh[1]) / den)
     m = (x * x + y * y).sqrt()       # sqrt, principal branch
     t = ((abs(x) + m) / 2).sqrt()
     if x >= 0:
@@ -207,11 +219,148 @@ def test_identities():
     assert np.all(np.abs(r * r - z) <= 1e-15 * np.abs(z)) and np.all(r.real >= 0)
 
 
-def test_inverse_and_hyperbolic_functions_are_real_only():
-    z = View.from_numpy(np.zeros(3, dtype=np.complex64))
-    for op in ("asin", "acos", "atan", "sinh", "cosh", "tanh"):
-        with pytest.raises(O.OracleError):
-            O.unary(op, z, z.fresh_copy())
+@pytest.mark.parametrize("op", ("sinh", "cosh", "tanh"))
+def test_complex_hyperbolic_functions_in_double(op):
+    rng = rng_for(9004)
+    z = rng.uniform(-6, 6, 120) + 1j * rng.uniform(-6, 6, 120)
+    got = _oracle(op, z.astype(np.complex128), "cdouble")
+    for zi, gi in zip(z, got):
+        er, ei = d_complex(op, Decimal(float(zi.real)), Decimal(float(zi.imag)))
+        mag = (er * er + ei * ei).sqrt()
+        tol = mag * Decimal(2) ** -50
+        assert abs(Decimal(float(gi.real)) - er) <= tol and abs(Decimal(float(gi.imag)) - ei) <= tol, (op, zi, gi)
+
+
+FORWARD = {"asin": "sin", "acos": "cos", "atan": "tan"}
+
+
+@pytest.mark.parametrize("op", ("asin", "acos", "atan"))
+def test_complex_inverse_functions_invert_the_forward_function(op):
+    # w = f^-1(z) is pinned through the forward function in arbitrary precision: f(w) must give z
+    # back as closely as a few units in the last place of w allow (an error dw in w moves f(w) by
+    # f'(w) dw), and w must lie in the principal range of the function.
+    rng = rng_for(9005)
+    z = np.concatenate([rng.uniform(-4, 4, 100) + 1j * rng.uniform(-4, 4, 100),
+                        rng.uniform(-0.9, 0.9, 40) + 1j * rng.uniform(-0.3, 0.3, 40)])
+    got = _oracle(op, z.astype(np.complex128), "cdouble")
+    for zi, wi in zip(z, got):
+        wr, wim = Decimal(float(wi.real)), Decimal(float(wi.imag))
+        fr, fi = d_complex(FORWARD[op], wr, wim)
+        # |f'(w)|: cos w for asin, sin w for acos, 1 + tan^2 w for atan
+        if op == "asin":
+            dr, di = d_complex("cos", wr, wim)
+        elif op == "acos":
+            dr, di = d_complex("sin", wr, wim)
+        else:
+            dr, di = 1 + fr * fr - fi * fi, 2 * fr * fi
+        slope = (dr * dr + di * di).sqrt()
+        wmag = (wr * wr + wim * wim).sqrt()
+        tol = slope * wmag * Decimal(2) ** -50 + Decimal(10) ** -300
+        err = ((fr - Decimal(float(zi.real))) ** 2 + (fi - Decimal(float(zi.imag))) ** 2).sqrt()
+        assert err <= tol, (op, zi, wi, err, tol)
+        if op == "acos":
+            assert 0 <= wi.real <= np.pi
+        else:
+            assert -np.pi / 2 <= wi.real <= np.pi / 2
+    if op in ("asin", "acos"):       # acos z + asin z = pi / 2
+        other = _oracle("acos" if op == "asin" else "asin", z.astype(np.complex128), "cdouble")
+        assert np.all(np.abs(got + other - np.pi / 2) <= 1e-15 * (1 + np.abs(got)))
+
+
+def test_complex_inverse_and_hyperbolic_closed_forms_and_branch_cuts():
+    def one(op, v):
+        return _oracle(op, np.array([v], dtype=np.complex128), "cdouble")[0]
+    assert one("asin", 0j) == 0 and one("acos", 0j).real == np.pi / 2 and one("atan", 1 + 0j).real == np.pi / 4
+    w = one("asin", 1j)                                   # asin(i) = i asinh(1)
+    assert w.real == 0 and abs(w.imag - 0.881373587019543) < 2e-16
+    # the cuts of asin and acos run along the real axis beyond +-1; the sign of the zero
+    # imaginary part selects the side (conjugate symmetry): asin(2 +- 0i) = pi/2 +- i ln(2 + sqrt 3)
+    up, dn = one("asin", complex(2, 0.0)), one("asin", complex(2, -0.0))
+    assert up.real == dn.real == np.pi / 2 and abs(up.imag - np.log(2 + np.sqrt(3))) < 4e-16 and dn.imag == -up.imag
+    up, dn = one("acos", complex(2, 0.0)), one("acos", complex(2, -0.0))
+    assert up.real == 0 and dn.real == 0 and up.imag == -dn.imag and up.imag < 0
+    # atan: cuts along the imaginary axis beyond +-i; the sign of the zero real part selects the side
+    rt, lf = one("atan", complex(0.0, 2)), one("atan", complex(-0.0, 2))
+    assert rt.real == np.pi / 2 and lf.real == -np.pi / 2 and abs(rt.imag - np.arctanh(0.5)) < 2e-16 and lf.imag == rt.imag
+    assert one("sinh", 0j) == 0 and one("cosh", 0j) == 1 and one("tanh", 0j) == 0
+    w = one("sinh", 1j * np.pi / 2)
+    assert abs(w.real) < 1e-16 and w.imag == 1.0
+    w = one("cosh", 1j * np.pi)
+    assert w.real == -1.0 and abs(w.imag) < 2e-16
+    # sinh z = -i sin(iz), cosh z = cos(iz), tanh z = -i tan(iz), to the last bit (as C defines them)
+    rng = rng_for(9006)
+    z = (rng.uniform(-3, 3, 100) + 1j * rng.uniform(-3, 3, 100)).astype(np.complex128)
+    assert np.array_equal(_oracle("sinh", z, "cdouble"), -1j * _oracle("sin", 1j * z, "cdouble"))
+    assert np.array_equal(_oracle("cosh", z, "cdouble"), _oracle("cos", 1j * z, "cdouble"))
+
+
+def test_complex_functions_of_infinite_and_nan_arguments_follow_the_c_standard():
+    # the values C's Annex G prescribes for the exponential and the hyperbolic sine and cosine
+    # (the trigonometric ones follow through sin z = -i sinh(iz), cos z = cosh(iz))
+    inf, nan = np.inf, np.nan
+
+    def one(op, re, im):
+        return _oracle(op, np.array([complex(re, im)], dtype=np.complex128), "cdouble")[0]
+
+    def same(w, re, im):
+        def part(g, v):
+            if v is None:
+                return True
+            if np.isnan(v):
+                return bool(np.isnan(g))
+            return g == v and np.signbit(g) == np.signbit(v)
+        return part(w.real, re) and part(w.imag, im)
+    assert same(one("exp", 0.0, 0.0), 1.0, 0.0) and same(one("exp", -0.0, -0.0), 1.0, -0.0)
+    assert same(one("exp", 1.0, inf), nan, nan) and same(one("exp", 1.0, nan), nan, nan)
+    assert same(one("exp", inf, 0.0), inf, 0.0) and same(one("exp", -inf, 1.0), 0.0 * np.cos(1.0), 0.0)
+    assert same(one("exp", inf, 2.0), -inf, inf)                     # +inf cis(2): cos 2 < 0 < sin 2
+    w = one("exp", -inf, inf)
+    assert w.real == 0 and w.imag == 0                               # signs unspecified
+    w = one("exp", inf, inf)
+    assert np.isinf(w.real) and np.isnan(w.imag)
+    assert same(one("exp", nan, 0.0), nan, 0.0) and same(one("exp", nan, 1.0), nan, nan)
+    assert same(one("sinh", 0.0, inf), None, nan) and one("sinh", 0.0, inf).real == 0
+    assert same(one("sinh", inf, 0.0), inf, 0.0) and same(one("sinh", inf, 2.0), -inf, inf)
+    assert same(one("sinh", 1.0, inf), nan, nan) and same(one("sinh", nan, 0.0), nan, 0.0)
+    assert same(one("cosh", 0.0, inf), nan, None) and one("cosh", 0.0, inf).imag == 0
+    assert same(one("cosh", inf, 0.0), inf, 0.0) and same(one("cosh", inf, 2.0), -inf, inf)
+    assert same(one("cosh", 1.0, inf), nan, nan)
+    assert same(one("tanh", inf, 1.0), 1.0, 0.0) and same(one("tanh", inf, 2.0), 1.0, -0.0)   # 1 + i0 sin(2y)
+    assert same(one("tanh", 0.0, inf), None, nan)
+    assert same(one("cos", inf, 0.0), nan, None) and one("cos", inf, 0.0).imag == 0
+    assert same(one("tan", 1.0, inf), 0.0, 1.0)                      # sin 2 > 0
+    assert same(one("sin", 0.0, inf), 0.0, inf)
+
+
+def test_complex_modulus():
+    # |x + iy| = sqrt(x^2 + y^2), a real value of the input's precision, without undue overflow
+    rng = rng_for(9007)
+    z = (rng.uniform(-6, 6, 300) + 1j * rng.uniform(-6, 6, 300)) * np.exp(rng.uniform(-40, 40, 300))
+    got = _oracle("abs", z.astype(np.complex128), "double")
+    for zi, gi in zip(z, got):
+        exact = (Decimal(float(zi.real)) ** 2 + Decimal(float(zi.imag)) ** 2).sqrt()
+        assert abs(Decimal(float(gi)) - exact) <= Decimal(float(np.spacing(gi))), (zi, gi)
+    def one(re, im, dt_in=np.complex128, dt_out="double"):
+        return _oracle("abs", np.array([complex(re, im)], dtype=dt_in), dt_out)[0]
+    assert one(3, 4) == 5 and one(-3, -4) == 5 and one(0.0, -0.0) == 0 and not np.signbit(one(-0.0, -0.0))
+    assert one(1e200, 1e200) == np.hypot(1e200, 1e200) and np.isfinite(one(1e300, 1e300))
+    assert one(3e-320, 4e-320) == 5e-320
+    assert one(np.inf, np.nan) == np.inf and one(np.nan, -np.inf) == np.inf and np.isnan(one(np.nan, 1.0))
+    # single-precision input: evaluated in single precision whatever the output type is
+    zs = (rng.uniform(-6, 6, 200) + 1j * rng.uniform(-6, 6, 200)).astype(np.complex64)
+    g32 = _oracle("abs", zs, "float")
+    g64 = _oracle("abs", zs, "double")
+    assert g32.dtype == np.float32 and np.array_equal(g32.astype(np.float64), g64)
+    exact = np.hypot(zs.real.astype(np.float64), zs.imag.astype(np.float64))
+    assert np.all(np.abs(g32.astype(np.float64) - exact) <= np.spacing(g32).astype(np.float64) * 0.5000001)
+    # complex output: the modulus with a zero imaginary part
+    gc = _oracle("abs", zs, "cfloat")
+    assert np.array_equal(gc.real, g32) and np.all(gc.imag == 0)
+    # strict types accept the real type of the same precision only
+    a = View.from_numpy(zs)
+    O.unary("abs", a, View.empty("float", zs.shape), O.STRICT_TYPES)
+    with pytest.raises(O.OracleError):
+        O.unary("abs", a, View.empty("double", zs.shape), O.STRICT_TYPES)
 
 
 def test_not_defined_for_integers():

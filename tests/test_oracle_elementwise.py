@@ -235,7 +235,9 @@ def test_unsupported_combinations_are_rejected():
             O.binary(op, x, y, o.fresh_copy())
         assert e.value.code == O.ERR_DTYPE
     with pytest.raises(O.OracleError):
-        O.unary("abs", c, c.fresh_copy())
+        O.unary("abs", b, b.fresh_copy())       # no modulus in bool arithmetic
+    with pytest.raises(O.OracleError):
+        O.unary("bnot", c, c.fresh_copy())
     i = View.from_numpy(np.zeros(3, dtype=np.int32))
     with pytest.raises(O.OracleError):
         O.unary("sqrt", i, i.fresh_copy())
