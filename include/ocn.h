@@ -60,7 +60,8 @@ typedef struct {
 typedef enum { /* section 3.2: basic arithmetic; complex types add conjugation (section 4) */
   OCN_U_IDENT = 0, /* out = a (a cast when the types differ)                   */
   OCN_U_NEG,       /* -a; integers wrap                                        */
-  OCN_U_ABS,       /* |a| for real types; integers wrap; not defined for complex */
+  OCN_U_ABS,       /* |a|; integers wrap; for a complex input the modulus, evaluated in
+                      the input's type: a real value of that precision (a few ulp)  */
   OCN_U_CONJ,      /* complex conjugate; identity on real types                */
   OCN_U_LNOT,      /* !(a != 0)                                                */
   OCN_U_BNOT,      /* ~a for integers, ! for bool                              */
@@ -74,8 +75,8 @@ typedef enum { /* section 3.2: basic arithmetic; complex types add conjugation (
   OCN_U_BSWAP,     /* integer types: the element with its bytes reversed (section
                       3.1.3: data in the other byte order; view floating data as
                       unsigned integers of the scalar size to bring it to native order) */
-  OCN_U_ASIN, OCN_U_ACOS, OCN_U_ATAN,   /* inverse trigonometric and hyperbolic functions,  */
-  OCN_U_SINH, OCN_U_COSH, OCN_U_TANH,   /* real floating types only, same accuracy class    */
+  OCN_U_ASIN, OCN_U_ACOS, OCN_U_ATAN,   /* inverse trigonometric and hyperbolic functions on */
+  OCN_U_SINH, OCN_U_COSH, OCN_U_TANH,   /* real and complex floating types, same accuracy    */
   OCN_NUM_UNARY
 } ocn_unary_op;
 
@@ -117,7 +118,8 @@ typedef enum {
 /*
  * Elementwise unary operation (sections 3.2 and 3.2.1): for every index i of out,
  *     out[i] = convert_out( f( convert_T( a[i] ) ) ).
- * T is out's dtype (bool for OCN_U_LNOT).  `a` broadcasts against out as in ocn_binary.
+ * T is out's dtype (bool for OCN_U_LNOT; a's dtype for OCN_U_ABS of a complex a, whose result
+ * is real).  `a` broadcasts against out as in ocn_binary.
  * a may be the identical view as out (in place); any other sharing of bytes between a and
  * out is OCN_ERR_ALIAS (section 4: overlap between tensors must not corrupt results; the
  * paper resolves it with an intermediate tensor, which is the caller's to provide here).

@@ -406,46 +406,246 @@ template <class F> OCN_DEV F times_zero_wins(F a, F b) {
   return a * b;
 }
 
-template <int OP, class F> OCN_DEV void elementary_complex(F x, F y, F &re, F &im) {
-  // Beyond this argument exp, cosh and sinh overflow although their product with a small sine
-  // or cosine may not: the exponential is then applied in two halves, (t * e^(u/2)) * e^(u/2).
+template <class F> OCN_DEV F asin_any(F x) { if constexpr (sizeof(F) == 4) return asinf(x); else return asin(x); }
+template <class F> OCN_DEV F acos_any(F x) { if constexpr (sizeof(F) == 4) return acosf(x); else return acos(x); }
+template <class F> OCN_DEV F atan_any(F x) { if constexpr (sizeof(F) == 4) return atanf(x); else return atan(x); }
+template <class F> OCN_DEV bool finite_any(F x) { return abs_any(x) < (F)__builtin_inff(); }   // false for NaN too
+template <class F> struct FloatLimits;
+template <> struct FloatLimits<float> {
+  static constexpr float eps = 1.1920929e-7f, max = 3.4028235e38f, min = 1.1754944e-38f;
+  static constexpr float safe_max = 2.3e18f;    // about sqrt(max) / 8
+  static constexpr float safe_min = 4.4e-19f;   // about sqrt(min) * 4
+};
+template <> struct FloatLimits<double> {
+  static constexpr double eps = 2.220446049250313e-16, max = 1.7976931348623157e308, min = 2.2250738585072014e-308;
+  static constexpr double safe_max = 1.6e153;
+  static constexpr double safe_min = 6.0e-154;
+};
+
+// The hyperbolic core: sinh, cosh and tanh of x + iy.  The trigonometric functions go through
+// it as C defines them - sin z = -i sinh(iz), cos z = cosh(iz), tan z = -i tanh(iz) - so that
+// both families share one set of conventions for infinite and NaN parts (C's Annex G: an
+// infinite part of the result keeps its direction where the other part of the argument fixes
+// one, and an exact zero times anything is that zero).
+template <class F> OCN_DEV void sinh_cosh_complex(F x, F y, bool want_sinh, F &re, F &im) {
   const F half_range = sizeof(F) == 4 ? (F)88 : (F)709;
-  if constexpr (OP == U_SIN) {          // sin x cosh y + i cos x sinh y
-    F s, c;
-    sincos_any(x, s, c);
-    if (abs_any(y) > half_range) {       // cosh y = |sinh y| = e^|y| / 2 to the last bit
-      const F h = exp_any(abs_any(y) * (F)0.5);
-      re = times_zero_wins(times_zero_wins(s, h), h * (F)0.5);
-      im = times_zero_wins(times_zero_wins(c, h), copysign_any(h * (F)0.5, y));
+  const F inf = (F)__builtin_inff();
+  if (abs_any(x) == inf && !finite_any(y)) {   // direction unknown: an infinity and a NaN
+    re = inf;
+    im = y - y;
+    return;
+  }
+  F s, c;
+  sincos_any(y, s, c);
+  // sinh: sinh x cos y + i cosh x sin y;  cosh: cosh x cos y + i sinh x sin y
+  if (abs_any(x) > half_range) {   // cosh x = |sinh x| = e^|x| / 2 to the last bit; applied in two halves
+    const F h = exp_any(abs_any(x) * (F)0.5);
+    const F ch = h * (F)0.5, sh = copysign_any(h * (F)0.5, x);
+    re = times_zero_wins(times_zero_wins(c, h), want_sinh ? sh : ch);
+    im = times_zero_wins(times_zero_wins(s, h), want_sinh ? ch : sh);
+  } else {
+    const F sh = sinh_any(x), ch = cosh_any(x);
+    re = times_zero_wins(want_sinh ? sh : ch, c);
+    im = times_zero_wins(want_sinh ? ch : sh, s);
+  }
+}
+
+template <class F> OCN_DEV void tanh_complex(F x, F y, F &re, F &im) {
+  const F inf = (F)__builtin_inff();
+  const F big = sizeof(F) == 4 ? (F)20 : (F)40;
+  if (abs_any(x) == inf) {                       // +-1, and a zero that leans the way sin(2y) does
+    re = copysign_any((F)1, x);
+    if (finite_any(y)) {
+      F s, c;
+      sincos_any(y, s, c);
+      im = copysign_any((F)0, s * c);
     } else {
-      re = times_zero_wins(s, cosh_any(y));
-      im = times_zero_wins(c, sinh_any(y));
+      im = copysign_any((F)0, y);
     }
-  } else if constexpr (OP == U_COS) {   // cos x cosh y - i sin x sinh y
-    F s, c;
-    sincos_any(x, s, c);
-    if (abs_any(y) > half_range) {
-      const F h = exp_any(abs_any(y) * (F)0.5);
-      re = times_zero_wins(times_zero_wins(c, h), h * (F)0.5);
-      im = -times_zero_wins(times_zero_wins(s, h), copysign_any(h * (F)0.5, y));
+    return;
+  }
+  if (!finite_any(y)) {                          // no direction at all
+    re = x == 0 ? x : y - y;
+    im = y - y;
+    return;
+  }
+  if (x != x) {                                  // NaN + i0 keeps the zero
+    re = x;
+    im = y == 0 ? y : x;
+    return;
+  }
+  F s, c;
+  sincos_any(y, s, c);
+  if (abs_any(x) > big) {                        // sinh^2 x swamps cos^2 y (and would overflow)
+    re = copysign_any((F)1, x);
+    im = 4 * s * c * exp_any(-2 * abs_any(x));
+  } else {                                       // (sinh x cosh x + i sin y cos y) / (cos^2 y + sinh^2 x)
+    const F sh = sinh_any(x), ch = cosh_any(x);
+    const F den = c * c + sh * sh;               // a sum of squares: no cancellation
+    re = sh * ch / den;
+    im = s * c / den;
+  }
+}
+
+// Inverse sine and cosine of x + iy after Hull, Fairgrieve and Tang (ACM TOMS 23, 1997): with
+// r, s the distances of |z| from -1 and +1, a = (r + s) / 2 and b = x / a, the real part is
+// asin(b) or acos(b) and the imaginary part log(a + sqrt(a^2 - 1)), each rewritten where it
+// would cancel (b near 1, a near 1) and replaced by asymptotic forms where squares would
+// overflow or underflow.  Computed for the first quadrant, signs restored at the end.
+template <class F> OCN_DEV void asin_acos_complex(F zx, F zy, bool want_acos, F &re, F &im) {
+  using L = FloatLimits<F>;
+  const F inf = (F)__builtin_inff();
+  const F pi = (F)3.14159265358979323846, half_pi = (F)1.57079632679489661923, ln2 = (F)0.69314718055994530942;
+  const F x = abs_any(zx), y = abs_any(zy);
+  F real, imag;   // of asin (or acos) in the first quadrant
+  if (zx != zx || zy != zy) {                    // a NaN part (C, Annex G)
+    const F nan = zx + zy;
+    if (y == inf) { re = nan; im = want_acos ? -zy : zy; }              // NaN + i Inf: the infinity survives
+    else if (x == inf) { re = nan; im = want_acos ? -inf : inf; }       // Inf + i NaN: an infinity of unspecified sign
+    else if (zx == 0) { re = want_acos ? half_pi : zx; im = nan; }      // +-0 + i NaN
+    else { re = nan; im = nan; }
+    return;
+  }
+  if (x == inf || y == inf) {
+    if (x == inf && y == inf) real = (F)0.78539816339744830962;         // pi/4
+    else if (x == inf) real = want_acos ? (F)0 : half_pi;
+    else real = want_acos ? half_pi : (F)0;
+    imag = inf;
+  } else if (x < L::safe_max && x > L::safe_min && y < L::safe_max && y > L::safe_min) {
+    const F xp1 = x + 1, xm1 = x - 1, yy = y * y;
+    const F r = sqrt_any(xp1 * xp1 + yy), s = sqrt_any(xm1 * xm1 + yy);
+    const F a = (r + s) * (F)0.5, b = x / a;
+    if (b <= (F)0.6417) {
+      real = want_acos ? acos_any(b) : asin_any(b);
+    } else {                                     // b near 1: through sqrt(a^2 - x^2) without cancellation
+      const F apx = a + x;
+      F root;                                    // sqrt(a^2 - x^2) (x <= 1), or that over y (x > 1)
+      if (x <= 1) root = sqrt_any((F)0.5 * apx * (yy / (r + xp1) + (s - xm1)));
+      else root = y * sqrt_any((F)0.5 * (apx / (r + xp1) + apx / (s + xm1)));
+      real = want_acos ? atan_any(root / x) : atan_any(x / root);
+    }
+    if (a <= (F)1.5) {                           // a near 1: a - 1 without cancellation
+      F am1;
+      if (x < 1) am1 = (F)0.5 * (yy / (r + xp1) + yy / (s - xm1));
+      else am1 = (F)0.5 * (yy / (r + xp1) + (s + xm1));
+      imag = log1p_any(am1 + sqrt_any(am1 * (a + 1)));
     } else {
-      re = c * cosh_any(y);
-      im = -times_zero_wins(s, sinh_any(y));
+      imag = log_any(a + sqrt_any(a * a - 1));
     }
-  } else if constexpr (OP == U_TAN) {   // (sin x cos x + i sinh y cosh y) / (cos^2 x + sinh^2 y)
-    const F big = sizeof(F) == 4 ? (F)20 : (F)40;
-    F s, c;
-    sincos_any(x, s, c);
-    if (abs_any(y) > big) {              // sinh^2 y swamps cos^2 x (and would overflow): tan -> +-i
-      re = 4 * s * c * exp_any(-2 * abs_any(y));
-      im = copysign_any((F)1, y);
-    } else {
-      const F sh = sinh_any(y), ch = cosh_any(y);
-      const F den = c * c + sh * sh;     // a sum of squares: no cancellation
-      re = s * c / den;
-      im = sh * ch / den;
+  } else {                                       // a part so large or small that a square would overflow or vanish
+    const F xm1 = x - 1, xp1 = x + 1;
+    if (y <= L::eps * abs_any(xm1)) {            // y does not reach x - 1
+      if (x < 1) {
+        real = want_acos ? acos_any(x) : asin_any(x);
+        imag = y / sqrt_any(xp1 * (1 - x));
+      } else {
+        if (L::max / xp1 > xm1) {
+          imag = log1p_any(xm1 + sqrt_any(xp1 * xm1));
+          real = want_acos ? (y == 0 ? (F)0 : y / sqrt_any(xm1 * xp1)) : half_pi;
+        } else {
+          imag = ln2 + log_any(x);
+          real = want_acos ? y / x : half_pi;
+        }
+      }
+    } else if (y <= L::safe_min) {               // x within y of 1, both differences tiny
+      const F t = sqrt_any(y);
+      real = want_acos ? t : half_pi - t;
+      imag = t;
+    } else if (L::eps * y - 1 >= x) {            // x does not reach y
+      real = want_acos ? half_pi : x / y;
+      imag = ln2 + log_any(y);
+    } else if (x > 1) {                          // both large
+      real = want_acos ? atan_any(y / x) : atan_any(x / y);
+      const F xoy = x / y;
+      imag = ln2 + log_any(y) + (F)0.5 * log1p_any(xoy * xoy);
+    } else {                                     // x at most 1 (possibly tiny), y beyond the safe range or x below it
+      const F a = sqrt_any(1 + y * y);
+      real = want_acos ? half_pi : x / a;
+      imag = (F)0.5 * log1p_any(2 * y * (y + a));
     }
+  }
+  if (want_acos) {
+    re = __builtin_signbit(zx) ? pi - real : real;
+    im = __builtin_signbit(zy) ? imag : -imag;
+  } else {
+    re = copysign_any(real, zx);
+    im = copysign_any(imag, zy);
+  }
+}
+
+// Inverse hyperbolic tangent of x + iy (the inverse tangent goes through it: atan z =
+// -i atanh(iz)): re = log1p(4x / ((1 - x)^2 + y^2)) / 4, im = atan2(2y, (1 - x)(1 + x) - y^2) / 2,
+// with the asymptotic forms where a part is so large that the squares would overflow.
+template <class F> OCN_DEV void atanh_complex(F x, F y, F &re, F &im) {
+  using L = FloatLimits<F>;
+  const F inf = (F)__builtin_inff();
+  const F half_pi = (F)1.57079632679489661923, ln2 = (F)0.69314718055994530942;
+  const F ax = abs_any(x), ay = abs_any(y);
+  if (x != x || y != y) {
+    if (ay == inf) { re = copysign_any((F)0, x); im = copysign_any(half_pi, y); }   // NaN + i Inf
+    else if (ax == inf) { re = copysign_any((F)0, x); im = y; }                     // Inf + i NaN
+    else if (x == 0) { re = x; im = y; }                                            // +-0 + i NaN
+    else { re = x + y; im = x + y; }
+    return;
+  }
+  if (ax == inf || ay == inf) {
+    re = copysign_any((F)0, x);
+    im = copysign_any(half_pi, y);
+    return;
+  }
+  const F huge = 16 / L::eps;
+  if (ax >= huge || ay >= huge) {                // 1/z to the last bit; the angle has reached +-pi/2
+    im = copysign_any(half_pi, y);
+    if (ay <= 1) re = 1 / x;
+    else if (ax <= 1) re = x / y / y;
+    else { const F h = hypot_any(x * (F)0.5, y * (F)0.5); re = x / h / h * (F)0.25; }
+    return;
+  }
+  if (ax == 1 && ay < L::safe_min) {             // next to the poles at +-1: y^2 would vanish
+    re = copysign_any((F)0.5, x) * (ln2 - log_any(ay));
+  } else {
+    const F yy = y * y, d = (1 - ax) * (1 - ax) + yy;
+    re = copysign_any((F)0.25 * log1p_any(4 * ax / d), x);
+  }
+  im = (F)0.5 * atan2_any(2 * y, (1 - ax) * (1 + ax) - y * y);
+}
+
+template <int OP, class F> OCN_DEV void elementary_complex(F x, F y, F &re, F &im) {
+  if constexpr (OP == U_SINH) {
+    sinh_cosh_complex<F>(x, y, true, re, im);
+  } else if constexpr (OP == U_COSH) {
+    sinh_cosh_complex<F>(x, y, false, re, im);
+  } else if constexpr (OP == U_TANH) {
+    tanh_complex<F>(x, y, re, im);
+  } else if constexpr (OP == U_SIN) {          // -i sinh(iz), iz = -y + ix
+    F a, b;
+    sinh_cosh_complex<F>(-y, x, true, a, b);
+    re = b;
+    im = -a;
+  } else if constexpr (OP == U_COS) {          // cosh(iz)
+    sinh_cosh_complex<F>(-y, x, false, re, im);
+  } else if constexpr (OP == U_TAN) {          // -i tanh(iz)
+    F a, b;
+    tanh_complex<F>(-y, x, a, b);
+    re = b;
+    im = -a;
+  } else if constexpr (OP == U_ASIN) {
+    asin_acos_complex<F>(x, y, false, re, im);
+  } else if constexpr (OP == U_ACOS) {
+    asin_acos_complex<F>(x, y, true, re, im);
+  } else if constexpr (OP == U_ATAN) {         // -i atanh(iz)
+    F a, b;
+    atanh_complex<F>(-y, x, a, b);
+    re = b;
+    im = -a;
   } else if constexpr (OP == U_EXP) {   // e^x (cos y + i sin y)
+    const F half_range = sizeof(F) == 4 ? (F)88 : (F)709;
+    const F inf = (F)__builtin_inff();
+    if (x == inf && !finite_any(y)) {            // an infinity of unknown direction
+      re = inf;
+      im = y - y;
+      return;
+    }
     F s, c;
     sincos_any(y, s, c);
     if (x > half_range) {
@@ -481,9 +681,23 @@ template <int OP, class F> OCN_DEV void elementary_complex(F x, F y, F &re, F &i
       re = y == y ? (F)0 : y;
       im = copysign_any(inf, y);
     } else {
+      // parts in the subnormal range are scaled up first (by an even power of two, taken out of
+      // the root again), so that the sum below keeps all its bits; parts near the largest
+      // number are scaled down, so that it does not overflow
+      const F m = abs_any(x) > abs_any(y) ? abs_any(x) : abs_any(y);
+      F up = 1, down = 1;
+      if (m < (sizeof(F) == 4 ? (F)0x1p-100f : (F)0x1p-900)) {
+        up = sizeof(F) == 4 ? (F)0x1p48f : (F)0x1p108;
+        down = sizeof(F) == 4 ? (F)0x1p-24f : (F)0x1p-54;
+      } else if (m > (sizeof(F) == 4 ? (F)0x1p125f : (F)0x1p1021)) {
+        up = (F)0.0625;
+        down = 4;
+      }
+      x *= up;
+      y *= up;
       const F t = sqrt_any((abs_any(x) + hypot_any(x, y)) * (F)0.5);
-      if (x >= 0) { re = t; im = y / (2 * t); }
-      else { re = abs_any(y) / (2 * t); im = copysign_any(t, y); }
+      if (x >= 0) { re = t * down; im = y / (2 * t) * down; }
+      else { re = abs_any(y) / (2 * t) * down; im = copysign_any(t, y) * down; }
     }
   }
 }
@@ -503,7 +717,12 @@ template <int OP, int T> OCN_DEV reg_t<unary_result_dtype(OP, T)> apply_unary(re
     else if constexpr (k == K_UINT) return a;
     else if constexpr (T == DT_F16) return hreg{__builtin_fabsf(a.v)};
     else if constexpr (T == DT_F32) return __builtin_fabsf(a);
-    else return __builtin_fabs(a);
+    else if constexpr (T == DT_F64) return __builtin_fabs(a);
+    // the modulus of a complex number: a real value of the same precision, scaled so that it
+    // neither overflows nor underflows before the result does
+    else if constexpr (T == DT_C16) return hreg{hypotf(a.re, a.im)};
+    else if constexpr (T == DT_C32) return hypotf(a.re, a.im);
+    else return hypot(a.re, a.im);
   } else if constexpr (OP == U_CONJ) {
     if constexpr (k == K_CPLX) return R{a.re, -a.im};
     else return a;

@@ -60,17 +60,19 @@ OCN_HD constexpr bool unary_supported(int op, int T) {
   switch (op) {
     case U_IDENT: case U_CONJ: case U_LNOT: return true;
     case U_NEG: return k != K_BOOL;
-    case U_ABS: return k != K_BOOL && k != K_CPLX;
+    case U_ABS: return k != K_BOOL;   // complex: the modulus, a real value
     case U_BNOT: case U_BSWAP: return k == K_BOOL || k == K_SINT || k == K_UINT;
     case U_SQRT: return k == K_REAL || k == K_CPLX;
     case U_SIN: case U_COS: case U_TAN: case U_EXP: case U_LOG: return k == K_REAL || k == K_CPLX;
-    case U_ASIN: case U_ACOS: case U_ATAN: case U_SINH: case U_COSH: case U_TANH: return k == K_REAL;
+    case U_ASIN: case U_ACOS: case U_ATAN: case U_SINH: case U_COSH: case U_TANH: return k == K_REAL || k == K_CPLX;
     default: return false;
   }
 }
 // result dtype of the operation itself (before conversion to the output type)
 OCN_HD constexpr int binary_result_dtype(int op, int T) { return (is_arith(op) || is_bitwise(op)) ? T : DT_BOOL; }
-OCN_HD constexpr int unary_result_dtype(int op, int T) { return op == U_LNOT ? DT_BOOL : T; }
+OCN_HD constexpr int unary_result_dtype(int op, int T) {
+  return op == U_LNOT ? (int)DT_BOOL : (op == U_ABS && dt_kind(T) == K_CPLX) ? dt_real_of(T) : T;
+}
 
 
 }  // namespace ocn

@@ -47,7 +47,10 @@ template <int T, int OP> OCN_DEV void binary_one(const InterpArgs &p, reg_t<T> a
 template <int T, int OP> OCN_DEV void unary_one(const InterpArgs &p, reg_t<T> a, char *po) {
   if constexpr (unary_supported(OP, T) && (OP != U_LNOT || T == DT_BOOL)) {
     auto r = apply_unary<OP, T>(a);
-    if constexpr (OP == U_LNOT) store_as<bool>(po, p.dt_o, r);
+    // the result has the output type already, except for the logical not (bool) and the
+    // modulus of a complex value (the real type of T), which are converted on store
+    if constexpr (OP == U_LNOT || unary_result_dtype(OP, T) != T)
+      store_as<reg_t<unary_result_dtype(OP, T)>>(po, p.dt_o, r);
     else *reinterpret_cast<storage_t<T> *>(po) = to_storage<T>(r);
   }
 }

@@ -228,7 +228,7 @@ template <class S, int V> OCN_DEV void store_pack(char *p, const Pack<S, V> &src
 template <int OP, int SA, int SB, int SO, int NIN> struct Sig {
   // compute type: inputs of a specialised comparison have equal types, so T is that type
   static constexpr int T = NIN == 2 ? (is_logical(OP) ? (int)DT_BOOL : is_compare(OP) ? SA : SO)
-                                    : unary_compute_dtype(OP, SO);
+                                    : unary_compute_dtype(OP, SA, SO);
   using SAt = storage_t<SA>;
   using SBt = storage_t<SB>;
   using SOt = storage_t<SO>;

@@ -320,8 +320,10 @@ int plan_elementwise(int nin, int op, const ocn_tensor *a, const ocn_tensor *b,
     if (!binary_supported(op, p.T)) return OCN_ERR_DTYPE;
     p.specialised = binary_specialised(op, sa, sb, so);
   } else {
-    if ((flags & OCN_STRICT_TYPES) && op != U_LNOT && sa != so) return OCN_ERR_DTYPE;
-    p.T = unary_compute_dtype(op, so);
+    const bool modulus = op == U_ABS && dt_kind(sa) == K_CPLX;   // complex -> real of the same precision
+    if ((flags & OCN_STRICT_TYPES) && op != U_LNOT && sa != so && !(modulus && so == dt_real_of(sa)))
+      return OCN_ERR_DTYPE;
+    p.T = unary_compute_dtype(op, sa, so);
     if (!unary_supported(op, p.T)) return OCN_ERR_DTYPE;
     p.specialised = unary_specialised(op, sa, so);
   }

@@ -47,12 +47,17 @@ OCN_HD constexpr bool binary_specialised(int op, int sa, int sb, int so) {
   return sa == sb && so == DT_BOOL && binary_supported(op, sa);
 }
 
-OCN_HD constexpr int unary_compute_dtype(int op, int so) { return op == U_LNOT ? (int)DT_BOOL : so; }
+// compute type of a unary operation: the output's type; bool for the logical not; the modulus
+// of a complex tensor is evaluated in that tensor's own type (and is a real value)
+OCN_HD constexpr int unary_compute_dtype(int op, int sa, int so) {
+  return op == U_LNOT ? (int)DT_BOOL : (op == U_ABS && dt_kind(sa) == K_CPLX) ? sa : so;
+}
 
 OCN_HD constexpr bool unary_specialised(int op, int sa, int so) {
   if (op < 0 || op >= U_COUNT) return false;
   if (op == U_IDENT) return true;  // the full cast matrix
   if (op == U_LNOT) return sa == DT_BOOL && so == DT_BOOL;
+  if (op == U_ABS && dt_kind(sa) == K_CPLX) return so == dt_real_of(sa);  // complex -> its real type
   return sa == so && unary_supported(op, so);
 }
 

@@ -1,12 +1,11 @@
-"""GPU parity of the elementary functions (sin, cos, tan, exp, log, complex sqrt) against the
-oracle, in the tolerance class these operations have: a few units in the last place of the
-output type (real: |gpu - oracle| <= K ulp of the oracle value; complex: each component within
-K ulp of the magnitude of the oracle value).  Results of finite arguments agree with the
-oracle in kind (NaN, signed infinity, signed zero), and so does the complex square root for
-infinite parts.  Not compared: sin, cos, tan and exp of complex arguments with an infinite or
-NaN part, where the kernels evaluate the plain formulas (e.g. exp(Inf + i Inf) gives NaN + i NaN,
-C gives Inf + i NaN; cos(Inf + i0) gives NaN - i0, C gives NaN + i0; tan(Inf + i Inf) gives
-NaN + i, C gives 0 + i)."""
+"""GPU parity of the elementary functions (sin, cos, tan, exp, log, asin, acos, atan, sinh,
+cosh, tanh, complex sqrt, complex modulus) against the oracle, in the tolerance class these
+operations have: a few units in the last place of the output type (real: |gpu - oracle| <= K ulp
+of the oracle value; complex: each component within K ulp of the magnitude of the oracle value;
+at hand-picked arguments with zero, tiny and huge parts: each component within K ulp of itself).
+Every result agrees with the oracle in kind (NaN, signed infinity, signed zero), also for
+arguments with infinite and NaN parts; only where C leaves a sign unspecified - a zero or an
+infinity next to a NaN part, the two zeros of exp(-Inf + i Inf) - is the sign not compared."""
 import numpy as np
 import pytest
 
@@ -94,17 +93,73 @@ def _complex_view(z, dt):
     return View.from_numpy(z.astype({"cfloat": np.complex64, "cdouble": np.complex128}[dt]))
 
 
+COMPLEX_OPS = ("sin", "cos", "tan", "exp", "log", "sqrt", "asin", "acos", "atan", "sinh", "cosh", "tanh")
+
+
 @pytest.mark.parametrize("dt", ("cfloat", "cdouble"))
-@pytest.mark.parametrize("op", ("sin", "cos", "tan", "exp", "log", "sqrt"))
+@pytest.mark.parametrize("op", COMPLEX_OPS)
 def test_complex_elementary_functions(op, dt):
     rng = rng_for(16100)
     n = 30000
     z = rng.uniform(-5, 5, n) + 1j * rng.uniform(-5, 5, n)
     if op == "tan":      # away from the poles on the real axis, where the value is ill-conditioned
         z = z[np.abs(np.cos(z)) > 0.1]
+    if op == "tanh":     # the same poles, on the imaginary axis
+        z = z[np.abs(np.cosh(z)) > 0.1]
+    if op in ("asin", "acos", "atan"):   # also small arguments and arguments next to the cuts and the poles
+        z = np.concatenate([z, rng.uniform(-1.2, 1.2, n // 3) + 1j * rng.uniform(-1e-3, 1e-3, n // 3),
+                            rng.uniform(-1e-3, 1e-3, n // 3) + 1j * rng.uniform(-1.2, 1.2, n // 3),
+                            (rng.uniform(-1, 1, n // 3) + 1j * rng.uniform(-1, 1, n // 3)) * 1e-4])
     a = _complex_view(z, dt)
     got, want = _run(op, a, View.empty(dt, a.sizes))
     _check_complex(got, want, dt)
+    # a transposed view goes through the tiled kernel: same values
+    m = View.from_numpy(z[: 96 * 64].reshape(96, 64).astype(a.to_numpy().dtype)).permute(1, 0) if dt != "chalf" else None
+    if m is not None:
+        got, want = _run(op, m, View.empty(dt, m.sizes))
+        _check_complex(got, want, dt)
+
+
+def test_complex_half_functions_go_through_single():
+    rng = rng_for(16101)
+    z = rng.uniform(-2, 2, 4000) + 1j * rng.uniform(-2, 2, 4000)
+    for op in ("sinh", "asin", "atan", "exp"):
+        a = _complex_view(z, "chalf")
+        got, want = _run(op, a, View.empty("chalf", a.sizes))
+        _check_complex(got, want, "chalf")
+
+
+@pytest.mark.parametrize("dt", ("chalf", "cfloat", "cdouble"))
+def test_complex_modulus(dt):
+    rng = rng_for(16102)
+    n = 20000
+    scale = np.exp(rng.uniform(-3, 3, n)) if dt == "chalf" else np.exp(rng.uniform(-30, 30, n))
+    z = (rng.uniform(-2, 2, n) + 1j * rng.uniform(-2, 2, n)) * scale
+    real_dt = {"chalf": "half", "cfloat": "float", "cdouble": "double"}[dt]
+    a = _complex_view(z, dt)
+    got, want = _run("abs", a, View.empty(real_dt, a.sizes))
+    _check_real(got, want, real_dt)
+    assert np.all(got >= 0)
+    if dt == "chalf":
+        return
+    # wider and complex outputs (the generic-dtype kernel): the same value, converted on store
+    got, want = _run("abs", a, View.empty("double", a.sizes))
+    _check_real(got.astype(REAL[real_dt]), want.astype(REAL[real_dt]), real_dt)
+    got, want = _run("abs", a, View.empty(dt, a.sizes))
+    assert np.all(got.imag == 0) and not np.any(np.signbit(got.imag))
+    _check_real(got.real, want.real, real_dt)
+    # a transposed view (tiled kernel)
+    m = View.from_numpy(z[: 96 * 64].reshape(96, 64).astype(a.to_numpy().dtype)).permute(1, 0)
+    got, want = _run("abs", m, View.empty(real_dt, m.sizes))
+    _check_real(got, want, real_dt)
+    # special values: no undue overflow or underflow, an infinite part wins over a NaN
+    fi = np.finfo(REAL[real_dt])
+    parts = [0.0, -0.0, 3.0, -4.0, fi.max, -fi.max, fi.max / 2, fi.tiny, fi.tiny / 8, np.inf, -np.inf, np.nan]
+    zs = np.array([complex(p, q) for p in parts for q in parts])
+    a = _complex_view(zs, dt)
+    got, want = _run("abs", a, View.empty(real_dt, a.sizes))
+    for i in range(len(zs)):
+        assert _same_class(got[i], want[i], 4 * float(fi.eps)), (dt, zs[i], got[i], want[i])
 
 
 def test_special_values_and_branch_cuts():
@@ -113,40 +168,75 @@ def test_special_values_and_branch_cuts():
         got, want = _run(op, x, View.empty("float", x.sizes))
         assert np.array_equal(np.isnan(got), np.isnan(want)), op
         fin = ~np.isnan(want)
-        assert np.allclose(got[fin], want[fin], rtol=1e-6, atol=0), (op, got, want)
+        assert np.allclose(got[fin], want[fin], rtol=4 * 1.2e-7, atol=0), (op, got, want)
         assert np.array_equal(np.signbit(got[fin]), np.signbit(want[fin])), op
     z = View.from_numpy(np.array([complex(-1, 0.0), complex(-1, -0.0), complex(-4, 0.0), 0j, complex(0.0, -0.0),
                                   1j, -1j, complex(3, 4)], dtype=np.complex64))
     got, want = _run("sqrt", z, View.empty("cfloat", z.sizes))
-    assert np.allclose(got, want, rtol=1e-6, atol=0) and np.array_equal(np.signbit(got.imag), np.signbit(want.imag))
+    assert np.allclose(got, want, rtol=8 * 1.2e-7, atol=0) and np.array_equal(np.signbit(got.imag), np.signbit(want.imag))
     got, want = _run("log", z.slice(0, 0, 3, 1), View.empty("cfloat", (3,)))
-    assert np.allclose(got, want, rtol=1e-6, atol=1e-7) and np.array_equal(np.signbit(got.imag), np.signbit(want.imag))
+    assert np.allclose(got, want, rtol=8 * 1.2e-7, atol=1e-7) and np.array_equal(np.signbit(got.imag), np.signbit(want.imag))
 
 
-def _same_class(g, w, rtol):
-    """Equal in kind (NaN, infinity with its sign, zero with its sign), else close."""
+SPECIAL_ULP = 8      # units in the last place allowed per part at the hand-picked arguments
+
+
+def _same_class(g, w, rtol, sign=True):
+    """Equal in kind (NaN, infinity with its sign, zero with its sign), else within rtol of the
+    oracle value (or, for a subnormal value, within as many of its fixed-size steps)."""
     if np.isnan(w):
         return bool(np.isnan(g))
     if np.isinf(w) or w == 0:
+        if not sign:
+            return bool(abs(g) == abs(w))
         return bool(g == w and np.signbit(g) == np.signbit(w))
-    return bool(abs(g - w) <= rtol * abs(w))
+    with np.errstate(over="ignore"):
+        step = float(np.spacing(np.abs(w)))      # one unit in the last place of w in its own type
+    return bool(abs(float(g) - float(w)) <= max(rtol * abs(float(w)), SPECIAL_ULP * step))
 
 
 @pytest.mark.parametrize("dt", ("cfloat", "cdouble"))
 def test_complex_functions_of_finite_arguments_with_zero_and_huge_parts(dt):
     # A component that is exactly zero, next to one that makes a factor overflow: the products
     # in sin, cos and exp must give the zero (0 * Inf), not NaN; tiny and huge magnitudes
-    # elsewhere.  Every finite argument must agree with the oracle in kind, part by part.
+    # elsewhere.  Every finite argument must agree with the oracle in kind, part by part, and
+    # each finite non-zero part within the ulp class of that part itself.
     big = 1e30 if dt == "cfloat" else 1e300
     parts = [0.0, -0.0, 1.0, -1.0, 0.5, big, -big, 1e-40 if dt == "cfloat" else 1e-310, 700.0, -700.0, 89.0, -104.0]
     z = np.array([complex(a, b) for a in parts for b in parts])
-    for op in ("sqrt", "exp", "log", "sin", "cos", "tan"):
+    rtol = SPECIAL_ULP * float(np.finfo(CPLX[dt]).eps)
+    bad = []
+    for op in COMPLEX_OPS:
         a = _complex_view(z, dt)
         got, want = _run(op, a, View.empty(dt, a.sizes))
-        rtol = 1e-5 if dt == "cfloat" else 1e-12
         for i in range(len(z)):
             ok = _same_class(got[i].real, want[i].real, rtol) and _same_class(got[i].imag, want[i].imag, rtol)
-            assert ok, (op, dt, z[i], got[i], want[i])
+            if not ok:
+                bad.append((op, z[i], got[i], want[i]))
+    for b in bad:
+        print("differs:", dt, *b)
+    assert not bad, len(bad)
+
+
+@pytest.mark.parametrize("dt", ("cfloat", "cdouble"))
+def test_complex_functions_of_infinite_and_nan_arguments(dt):
+    # every combination of an infinite or NaN part with zero, finite, infinite and NaN parts:
+    # the same kind of result as the oracle (C's Annex G), part by part
+    inf, nan = np.inf, np.nan
+    parts = [0.0, -0.0, 1.0, -2.0, 0.5, 40.0, inf, -inf, nan]
+    z = np.array([complex(a, b) for a in parts for b in parts if not (np.isfinite(a) and np.isfinite(b))])
+    rtol = SPECIAL_ULP * float(np.finfo(CPLX[dt]).eps)
+    for op in COMPLEX_OPS:
+        a = _complex_view(z, dt)
+        got, want = _run(op, a, View.empty(dt, a.sizes))
+        for i in range(len(z)):
+            g, w = got[i], want[i]
+            # C leaves the sign of a zero or an infinity unspecified where the other part is NaN,
+            # and both signs of exp(-Inf + i Inf) and exp(-Inf + i NaN)
+            free = (op == "exp" and z[i].real == -inf and not np.isfinite(z[i].imag))
+            ok = (_same_class(g.real, w.real, rtol, sign=not (np.isnan(w.imag) or free)) and
+                  _same_class(g.imag, w.imag, rtol, sign=not (np.isnan(w.real) or free)))
+            assert ok, (op, dt, z[i], g, w)
 
 
 def test_complex_square_root_of_infinite_arguments():
@@ -169,12 +259,12 @@ def test_real_functions_at_special_and_extreme_arguments(dt):
     vals = np.array([0.0, -0.0, 1.0, -1.0, 0.5, -0.5, 2.0, -2.0, np.inf, -np.inf, np.nan, fi.max, -fi.max, fi.tiny,
                      -fi.tiny, fi.tiny / 4, 1e-3, 11.0, -11.0, 89.0, -89.0, 104.0, -104.0, 709.0, 710.0, -745.0,
                      -746.0, 1e4, -1e4, 1.0000001, -1.0000001], dtype=ft)
-    rtol = {"half": 2e-3, "float": 1e-5, "double": 1e-12}[dt]
+    rtol = K_ULP[dt] * float(fi.eps)        # the ulp class of the random tests
     for op in ("sin", "cos", "tan", "exp", "log", "asin", "acos", "atan", "sinh", "cosh", "tanh", "sqrt"):
         a = View.from_numpy(vals.copy())
         got, want = _run(op, a, View.empty(dt, a.sizes))
         for i in range(len(vals)):
-            assert _same_class(float(got[i]), float(want[i]), rtol), (op, dt, float(vals[i]), float(got[i]), float(want[i]))
+            assert _same_class(got[i], want[i], rtol), (op, dt, float(vals[i]), float(got[i]), float(want[i]))
 
 
 def test_mixed_types_and_errors():

@@ -64,7 +64,14 @@ def test_operation_not_defined_for_type():
     assert code(ocn.plan_binary, "lt", f("cfloat", A), f("cfloat", Bb), f("bool", O_)) == E["DTYPE"]
     assert code(ocn.plan_binary, "max", f("cfloat", A), f("cfloat", Bb), f("cfloat", O_)) == E["DTYPE"]
     assert code(ocn.plan_binary, "add", f("bool", A), f("bool", Bb), f("bool", O_)) == E["DTYPE"]
-    assert code(ocn.plan_unary, "abs", f("cdouble", A), f("cdouble", O_)) == E["DTYPE"]
+    assert code(ocn.plan_unary, "abs", f("bool", A), f("bool", O_)) == E["DTYPE"]
+    assert code(ocn.plan_unary, "bnot", f("cdouble", A), f("cdouble", O_)) == E["DTYPE"]
+    # the modulus of a complex tensor is defined: computed in the input's type, a real result
+    p = ocn.plan_unary("abs", f("cdouble", A), f("double", O_))
+    assert p["compute_dtype"] == "cdouble" and p["specialised"]
+    assert ocn.plan_unary("abs", f("cfloat", A), f("double", O_))["compute_dtype"] == "cfloat"
+    ocn.plan_unary("abs", f("cfloat", A), f("float", O_), ocn.STRICT_TYPES)      # accepted
+    assert code(ocn.plan_unary, "abs", f("cfloat", A), f("double", O_), ocn.STRICT_TYPES) == E["DTYPE"]
     assert code(ocn.plan_unary, "sqrt", f("int32", A), f("int32", O_)) == E["DTYPE"]
     assert code(ocn.plan_reduce, "max", f("cfloat", A), [0], T("cfloat", (), base=O_)) == E["DTYPE"]
 
