@@ -35,7 +35,7 @@ STRICT_TYPES = 1
 class OrcTensor(C.Structure):
     _fields_ = [("base", C.c_void_p), ("offset", C.c_int64), ("dtype", C.c_int32),
                 ("ndim", C.c_int32), ("size", C.c_int64 * MAX_DIMS),
-                ("stride", C.c_int64 * MAX_DIMS), ("device", C.c_int32)]
+                ("stride", C.c_int64 * MAX_DIMS), ("device", C.c_int32), ("byteswapped", C.c_int32)]
 
 
 _lib = None
@@ -76,6 +76,7 @@ def _desc(view) -> OrcTensor:
         t.size[d] = view.sizes[d]
         t.stride[d] = view.strides[d]
     t.device = -1
+    t.byteswapped = 1 if getattr(view, "byteswapped", False) else 0
     return t
 
 
@@ -138,6 +139,37 @@ def domain_check(op: str, a) -> bool:
     else:
         return False
     return bool(out.to_numpy())
+
+
+MODES = ("standard", "warning", "error", "complex")
+
+
+class DomainError(ValueError):
+    """Error mode: some element lies outside the operator's domain."""
+
+
+def unary_mode(op: str, mode: str, a, out, out_complex=None) -> dict:
+    """A unary operation in one of the paper's compute modes (section 3.2.1), written as its
+    definition on top of the domain check and the plain operation:
+      standard  no check; NaN where an element is outside the domain;
+      warning   check, then compute as in standard mode; the caller is told (`outside`);
+      error     check; outside the domain nothing is computed and DomainError is raised;
+      complex   check; outside the domain the result is computed in the complex type of
+                `out_complex` (the real input converts with a zero imaginary part) and written
+                there, otherwise in `out` as usual.
+    Returns {"outside": None (not checked) | bool, "wrote": "out" | "out_complex"}."""
+    assert mode in MODES
+    if mode == "standard":
+        unary(op, a, out)
+        return {"outside": None, "wrote": "out"}
+    outside = domain_check(op, a)
+    if mode == "error" and outside:
+        raise DomainError(op)
+    if mode == "complex" and outside:
+        unary(op, a, out_complex)
+        return {"outside": True, "wrote": "out_complex"}
+    unary(op, a, out)
+    return {"outside": outside, "wrote": "out"}
 
 
 def promote(a: str, b: str) -> str:

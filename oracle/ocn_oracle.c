@@ -172,6 +172,35 @@ static void store_elem(int dt, unsigned char *p, val_t v) {
   }
 }
 
+/* Elements of a tensor stored in the other byte order (section 3.1.3): the bytes of every
+ * scalar - of each component of a complex element - are reversed in memory.  Loading
+ * un-reverses them first, storing reverses them last; the value in between is the same. */
+static int scalar_bytes(int dt) {
+  switch (dt) {
+    case ORC_BOOL: case ORC_INT8: case ORC_UINT8: return 1;
+    case ORC_INT16: case ORC_UINT16: case ORC_HALF: case ORC_CHALF: return 2;
+    case ORC_INT32: case ORC_UINT32: case ORC_FLOAT: case ORC_CFLOAT: return 4;
+    default: return 8;
+  }
+}
+static void reverse_scalars(int dt, const unsigned char *src, unsigned char *dst) {
+  int sb = scalar_bytes(dt), n = orc_dtype_size(dt);
+  for (int s0 = 0; s0 < n; s0 += sb)
+    for (int b = 0; b < sb; ++b) dst[s0 + b] = src[s0 + sb - 1 - b];
+}
+static val_t load_tensor_elem(const orc_tensor *t, const unsigned char *p) {
+  if (!t->byteswapped) return load_elem(t->dtype, p);
+  unsigned char tmp[16];
+  reverse_scalars(t->dtype, p, tmp);
+  return load_elem(t->dtype, tmp);
+}
+static void store_tensor_elem(const orc_tensor *t, unsigned char *p, val_t v) {
+  if (!t->byteswapped) { store_elem(t->dtype, p, v); return; }
+  unsigned char tmp[16];
+  store_elem(t->dtype, tmp, v);
+  reverse_scalars(t->dtype, tmp, p);
+}
+
 /* ------------------------------------------------------------------------------------ */
 /* conversion rules (explicit and implicit type casting, section 3.2.1)                 */
 /* ------------------------------------------------------------------------------------ */
@@ -700,10 +729,10 @@ int orc_binary(int op, const orc_tensor *a, const orc_tensor *b, const orc_tenso
   for (int64_t lin = 0; lin < n; ++lin) {
     int64_t idx[ORC_MAX_DIMS];
     decode(lin, out, idx);
-    val_t va = convert(load_elem(a->dtype, addr_in(a, out, idx)), T);
-    val_t vb = convert(load_elem(b->dtype, addr_in(b, out, idx)), T);
+    val_t va = convert(load_tensor_elem(a, addr_in(a, out, idx)), T);
+    val_t vb = convert(load_tensor_elem(b, addr_in(b, out, idx)), T);
     val_t r = apply_binary(op, T, va, vb);
-    store_elem(out->dtype, addr_out(out, idx), convert(r, out->dtype));
+    store_tensor_elem(out, addr_out(out, idx), convert(r, out->dtype));
   }
   return ORC_OK;
 }
@@ -726,9 +755,9 @@ int orc_unary(int op, const orc_tensor *a, const orc_tensor *out, uint32_t flags
   for (int64_t lin = 0; lin < n; ++lin) {
     int64_t idx[ORC_MAX_DIMS];
     decode(lin, out, idx);
-    val_t va = convert(load_elem(a->dtype, addr_in(a, out, idx)), T);
+    val_t va = convert(load_tensor_elem(a, addr_in(a, out, idx)), T);
     val_t r = apply_unary(op, T, va);
-    store_elem(out->dtype, addr_out(out, idx), convert(r, out->dtype));
+    store_tensor_elem(out, addr_out(out, idx), convert(r, out->dtype));
   }
   return ORC_OK;
 }
@@ -814,7 +843,7 @@ int orc_reduce(int op, const orc_tensor *a, const int32_t *axes, int32_t naxes,
       }
       int64_t off = a->offset;
       for (int d = 0; d < a->ndim; ++d) off += aidx[d] * a->stride[d];
-      val_t v = load_elem(a->dtype, (const unsigned char *)a->base + off);
+      val_t v = load_tensor_elem(a, (const unsigned char *)a->base + off);
       switch (op) {
         case ORC_R_SUM:
           if (ka == K_BOOL || ka == K_SINT) acc_i += (uint64_t)v.i;
@@ -859,7 +888,7 @@ int orc_reduce(int op, const orc_tensor *a, const int32_t *axes, int32_t naxes,
       case ORC_R_MIN: case ORC_R_MAX: res = best; break;
       default: res.k = K_BOOL; res.i = acc_b; break;
     }
-    store_elem(out->dtype, addr_out(out, oidx), convert(res, out->dtype));
+    store_tensor_elem(out, addr_out(out, oidx), convert(res, out->dtype));
   }
   return ORC_OK;
 }

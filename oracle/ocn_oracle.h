@@ -50,6 +50,9 @@ typedef struct {
   int64_t size[ORC_MAX_DIMS];
   int64_t stride[ORC_MAX_DIMS];
   int32_t device; /* ignored by the oracle */
+  int32_t byteswapped; /* non-zero: the elements are stored in the other byte order (section
+                          3.1.3: operations can be applied in either byte order): every scalar -
+                          each component of a complex element - has its bytes reversed in memory */
 } orc_tensor;
 
 enum { /* unary operations */

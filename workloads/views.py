@@ -57,6 +57,7 @@ class View:
     sizes: Tuple[int, ...]
     strides: Tuple[int, ...]  # bytes; may be zero or negative
     offset: int = 0  # bytes from storage start to element (0,...,0)
+    byteswapped: bool = False  # the storage holds every scalar in the other byte order (section 3.1.3)
 
     # ---- construction -------------------------------------------------------------
     @staticmethod
@@ -205,7 +206,28 @@ class View:
         if self.numel == 0:
             return np.zeros(shape, dtype=nd)
         v = np.ndarray(shape, dtype=nd, buffer=self.storage, offset=self.offset, strides=strides)
-        return np.array(v, order="C")
+        out = np.array(v, order="C")
+        return out.byteswap() if self.byteswapped else out     # numpy reverses each scalar's bytes
+
+    def in_other_byte_order(self) -> "View":
+        """A copy of the viewed storage with the bytes of every scalar reversed, described by the
+        same sizes, strides and offset and flagged as stored in the other byte order: it holds
+        the same values as ``self``."""
+        _, nd = DTYPES[self.dtype]
+        sb = nd.itemsize if self.dtype not in ("cfloat", "cdouble") else nd.itemsize // 2
+        storage = self.storage.copy()
+        if sb > 1:
+            # reverse, in place, the scalars this view addresses (other bytes of the storage stay)
+            shape, strides = self.sizes, self.strides
+            comp = np.dtype(f"V{sb}")
+            ncomp = itemsize(self.dtype) // sb
+            if ncomp > 1:
+                shape, strides = shape + (ncomp,), strides + (sb,)
+            if self.numel:
+                v = np.ndarray(shape, dtype=comp, buffer=storage, offset=self.offset, strides=strides)
+                raw = np.array(v, order="C").view(np.uint8).reshape(shape + (sb,))[..., ::-1]
+                v[...] = np.ascontiguousarray(raw).view(comp).reshape(shape)
+        return replace(self, storage=storage, byteswapped=not self.byteswapped)
 
 
 def contiguous_strides(sizes: Sequence[int], es: int, order: str = "C") -> Tuple[int, ...]:
