@@ -55,6 +55,14 @@ typedef struct {
   int64_t size[OCN_MAX_DIMS];    /* extents, >= 0                                         */
   int64_t stride[OCN_MAX_DIMS];  /* bytes; may be 0 or negative                           */
   int32_t device;                /* HIP device ordinal; all operands of a call must agree */
+  int32_t byteswapped;           /* non-zero: the elements are stored in the other byte order
+                                    (section 3.1.3): every scalar - each component of a complex
+                                    element - has its bytes reversed in memory.  The kernels
+                                    reverse on load and on store; no extra pass is made.
+                                    Honoured by ocn_unary, ocn_binary, ocn_cast_copy and
+                                    ocn_reduce (and their variants); the other entry points
+                                    return OCN_ERR_BYTEORDER for such an operand.  The field
+                                    takes the place of what used to be padding: zero it */
 } ocn_tensor;
 
 typedef enum { /* section 3.2: basic arithmetic; complex types add conjugation (section 4) */
@@ -108,7 +116,9 @@ typedef enum {
   OCN_ERR_WORKSPACE = -9,   /* reduction workspace missing or too small                          */
   OCN_ERR_EMPTY = -10,      /* min/max over zero elements                                        */
   OCN_ERR_LAUNCH = -11,     /* the HIP runtime reported an error; see ocn_last_hip_error         */
-  OCN_ERR_OP = -12          /* unknown operation code                                            */
+  OCN_ERR_OP = -12,         /* unknown operation code                                            */
+  OCN_ERR_BYTEORDER = -13,  /* an operand in the other byte order, in a call that takes native order only */
+  OCN_ERR_DOMAIN = -14      /* error mode: an element lies outside the operation's domain         */
 } ocn_status;
 
 /* flags */

@@ -31,7 +31,8 @@ STRICT_TYPES = 1
 
 OK = 0
 ERR = {"NULLPTR": -1, "DTYPE": -2, "NDIM": -3, "SHAPE": -4, "DEVICE": -5, "ALIGN": -6,
-       "OVERLAP_OUT": -7, "ALIAS": -8, "WORKSPACE": -9, "EMPTY": -10, "LAUNCH": -11, "OP": -12}
+       "OVERLAP_OUT": -7, "ALIAS": -8, "WORKSPACE": -9, "EMPTY": -10, "LAUNCH": -11, "OP": -12,
+       "BYTEORDER": -13, "DOMAIN": -14}
 
 KERNELS = ("none", "ew_rows", "ew_tiled", "ew_generic", "red_rows", "red_cols", "red_generic")
 
@@ -46,7 +47,7 @@ EXPORTS = ("ocn_unary", "ocn_binary", "ocn_cast_copy", "ocn_reduce", "ocn_reduce
 class OcnTensor(C.Structure):
     _fields_ = [("base", C.c_void_p), ("offset", C.c_int64), ("dtype", C.c_int32),
                 ("ndim", C.c_int32), ("size", C.c_int64 * MAX_DIMS),
-                ("stride", C.c_int64 * MAX_DIMS), ("device", C.c_int32)]
+                ("stride", C.c_int64 * MAX_DIMS), ("device", C.c_int32), ("byteswapped", C.c_int32)]
 
 
 class OcnPlanInfo(C.Structure):
@@ -130,17 +131,18 @@ class Tensor:
     offset: int = 0                # bytes
     device: int = 0
     keepalive: Any = field(default=None, repr=False, compare=False)
+    byteswapped: bool = False      # the storage holds every scalar in the other byte order
 
     @staticmethod
     def on_storage(storage, dtype: str, sizes: Sequence[int], strides: Sequence[int],
-                   offset: int = 0) -> "Tensor":
+                   offset: int = 0, byteswapped: bool = False) -> "Tensor":
         """View over a 1-D uint8 torch tensor living on a GPU."""
         dev = storage.device.index if storage.device.index is not None else 0
-        return Tensor(storage.data_ptr(), dtype, tuple(sizes), tuple(strides), offset, dev, storage)
+        return Tensor(storage.data_ptr(), dtype, tuple(sizes), tuple(strides), offset, dev, storage, byteswapped)
 
     def desc(self) -> OcnTensor:
         # the C struct is rebuilt only when a field has changed (the library never writes to it)
-        key = (self.base, self.dtype, self.sizes, self.strides, self.offset, self.device)
+        key = (self.base, self.dtype, self.sizes, self.strides, self.offset, self.device, self.byteswapped)
         cached = self.__dict__.get("_desc_cache")
         if cached is not None and cached[0] == key:
             return cached[1]
@@ -153,6 +155,7 @@ class Tensor:
             t.size[d] = self.sizes[d]
             t.stride[d] = self.strides[d]
         t.device = self.device
+        t.byteswapped = 1 if self.byteswapped else 0
         self.__dict__["_desc_cache"] = (key, t)
         return t
 

@@ -215,6 +215,8 @@ const char *ocn_error_string(int code) {
     case OCN_ERR_EMPTY: return "min/max over zero elements";
     case OCN_ERR_LAUNCH: return "HIP runtime error";
     case OCN_ERR_OP: return "unknown operation";
+    case OCN_ERR_BYTEORDER: return "an operand is stored in the other byte order, which this call does not take";
+    case OCN_ERR_DOMAIN: return "an element lies outside the domain of the operation";
     default: return "unknown status code";
   }
 }

@@ -80,6 +80,44 @@ template <int DT> OCN_DEV storage_t<DT> to_storage(reg_t<DT> r) {
   else return r;
 }
 
+// ---- tensors stored in the other byte order (section 3.1.3) -------------------------------
+// Every scalar - each component of a complex element - has its bytes reversed in memory.
+// The kernels reverse them back right after a load and reverse results right before a store,
+// on whole register packs: a handful of byte permutes next to a memory access, so that a
+// foreign-endian operand needs no pass of its own.
+template <int SCALAR_BYTES, class P> OCN_DEV void reverse_scalars(P &pk) {
+  static_assert(sizeof(P) % SCALAR_BYTES == 0, "a pack holds whole scalars");
+  if constexpr (SCALAR_BYTES == 2) {
+    if constexpr (sizeof(P) % 4 == 0) {   // two scalars per 32-bit word: one byte permute
+      uint32_t w[sizeof(P) / 4];
+      __builtin_memcpy(w, &pk, sizeof(P));
+#pragma unroll
+      for (int i = 0; i < (int)(sizeof(P) / 4); ++i) w[i] = __builtin_amdgcn_perm(0u, w[i], 0x02030001u);
+      __builtin_memcpy(&pk, w, sizeof(P));
+    } else {
+      uint16_t w[sizeof(P) / 2];
+      __builtin_memcpy(w, &pk, sizeof(P));
+#pragma unroll
+      for (int i = 0; i < (int)(sizeof(P) / 2); ++i) w[i] = __builtin_bswap16(w[i]);
+      __builtin_memcpy(&pk, w, sizeof(P));
+    }
+  } else if constexpr (SCALAR_BYTES == 4) {
+    uint32_t w[sizeof(P) / 4];
+    __builtin_memcpy(w, &pk, sizeof(P));
+#pragma unroll
+    for (int i = 0; i < (int)(sizeof(P) / 4); ++i) w[i] = __builtin_bswap32(w[i]);
+    __builtin_memcpy(&pk, w, sizeof(P));
+  } else if constexpr (SCALAR_BYTES == 8) {
+    uint64_t w[sizeof(P) / 8];
+    __builtin_memcpy(w, &pk, sizeof(P));
+#pragma unroll
+    for (int i = 0; i < (int)(sizeof(P) / 8); ++i) w[i] = __builtin_bswap64(w[i]);
+    __builtin_memcpy(&pk, w, sizeof(P));
+  }
+}
+// bytes of one scalar of an element type
+constexpr int scalar_bytes(int dt) { return dt_size(dt_real_of(dt)); }
+
 // ---- conversions ----------------------------------------------------------------------
 
 // double -> half, nearest even in ONE step: round to odd into single precision first (the

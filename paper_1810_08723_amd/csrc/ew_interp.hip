@@ -7,10 +7,16 @@
 namespace ocn {
 
 // load an element of runtime dtype `dt` and convert it to compile-time type T
-template <int T> __device__ __noinline__ reg_t<T> load_as(const char *p, int dt) {
+// (`swapped`: the tensor is stored in the other byte order, its scalars are reversed after
+// the load / before the store)
+template <int T> __device__ __noinline__ reg_t<T> load_as(const char *p, int dt, bool swapped) {
   switch (dt) {
-#define OCN_CASE(D) \
-  case D: return convert<T>(from_storage<D>(*reinterpret_cast<const storage_t<D> *>(p)));
+#define OCN_CASE(D)                                                  \
+  case D: {                                                          \
+    storage_t<D> s = *reinterpret_cast<const storage_t<D> *>(p);     \
+    if (swapped) reverse_scalars<scalar_bytes(D)>(s);                \
+    return convert<T>(from_storage<D>(s));                           \
+  }
     OCN_CASE(DT_BOOL) OCN_CASE(DT_I8) OCN_CASE(DT_I16) OCN_CASE(DT_I32) OCN_CASE(DT_I64)
     OCN_CASE(DT_U8) OCN_CASE(DT_U16) OCN_CASE(DT_U32) OCN_CASE(DT_U64)
     OCN_CASE(DT_F16) OCN_CASE(DT_F32) OCN_CASE(DT_F64)
@@ -21,10 +27,14 @@ template <int T> __device__ __noinline__ reg_t<T> load_as(const char *p, int dt)
 }
 
 // convert a register value to runtime dtype `dt` and store it
-template <class R> __device__ __noinline__ void store_as(char *p, int dt, R r) {
+template <class R> __device__ __noinline__ void store_as(char *p, int dt, R r, bool swapped) {
   switch (dt) {
-#define OCN_CASE(D) \
-  case D: *reinterpret_cast<storage_t<D> *>(p) = to_storage<D>(convert<D>(r)); break;
+#define OCN_CASE(D)                                      \
+  case D: {                                              \
+    storage_t<D> s = to_storage<D>(convert<D>(r));       \
+    if (swapped) reverse_scalars<scalar_bytes(D)>(s);    \
+    *reinterpret_cast<storage_t<D> *>(p) = s;            \
+  } break;
     OCN_CASE(DT_BOOL) OCN_CASE(DT_I8) OCN_CASE(DT_I16) OCN_CASE(DT_I32) OCN_CASE(DT_I64)
     OCN_CASE(DT_U8) OCN_CASE(DT_U16) OCN_CASE(DT_U32) OCN_CASE(DT_U64)
     OCN_CASE(DT_F16) OCN_CASE(DT_F32) OCN_CASE(DT_F64)
@@ -34,13 +44,20 @@ template <class R> __device__ __noinline__ void store_as(char *p, int dt, R r) {
   }
 }
 
+// the value already has the output's type T
+template <int T> OCN_DEV void store_same(char *p, reg_t<T> r, bool swapped) {
+  storage_t<T> s = to_storage<T>(r);
+  if (swapped) reverse_scalars<scalar_bytes(T)>(s);
+  *reinterpret_cast<storage_t<T> *>(p) = s;
+}
+
 template <int T, int OP> OCN_DEV void binary_one(const InterpArgs &p, reg_t<T> a, reg_t<T> b, char *po) {
   // logical operations always compute in bool
   if constexpr (binary_supported(OP, T) && (!is_logical(OP) || T == DT_BOOL)) {
     auto r = apply_binary<OP, T>(a, b);
     // arithmetic and bitwise results already have the output type (T is out's dtype)
-    if constexpr (is_arith(OP) || is_bitwise(OP)) *reinterpret_cast<storage_t<T> *>(po) = to_storage<T>(r);
-    else store_as<bool>(po, p.dt_o, r);
+    if constexpr (is_arith(OP) || is_bitwise(OP)) store_same<T>(po, r, (p.swap & 4) != 0);
+    else store_as<bool>(po, p.dt_o, r, (p.swap & 4) != 0);
   }
 }
 
@@ -50,15 +67,15 @@ template <int T, int OP> OCN_DEV void unary_one(const InterpArgs &p, reg_t<T> a,
     // the result has the output type already, except for the logical not (bool) and the
     // modulus of a complex value (the real type of T), which are converted on store
     if constexpr (OP == U_LNOT || unary_result_dtype(OP, T) != T)
-      store_as<reg_t<unary_result_dtype(OP, T)>>(po, p.dt_o, r);
-    else *reinterpret_cast<storage_t<T> *>(po) = to_storage<T>(r);
+      store_as<reg_t<unary_result_dtype(OP, T)>>(po, p.dt_o, r, (p.swap & 4) != 0);
+    else store_same<T>(po, r, (p.swap & 4) != 0);
   }
 }
 
 template <int T> OCN_DEV void interp_body(const InterpArgs &p, const char *pa, const char *pb, char *po) {
-  const reg_t<T> a = load_as<T>(pa, p.dt_a);
+  const reg_t<T> a = load_as<T>(pa, p.dt_a, (p.swap & 1) != 0);
   if (p.nin == 2) {
-    const reg_t<T> b = load_as<T>(pb, p.dt_b);
+    const reg_t<T> b = load_as<T>(pb, p.dt_b, (p.swap & 2) != 0);
     switch (p.op) {
 #define OCN_CASE(O) case O: binary_one<T, O>(p, a, b, po); break;
       OCN_CASE(B_ADD) OCN_CASE(B_SUB) OCN_CASE(B_MUL) OCN_CASE(B_DIV) OCN_CASE(B_MIN) OCN_CASE(B_MAX)

@@ -35,6 +35,7 @@ struct RowsArgs {
   int32_t nt_store;  // stream the output past the caches
   int32_t nt_a, nt_b; // read that input with streaming (non-temporal) loads
   int32_t simple;     // at most one outer dim, rows of whole vectors, fewer than 2^31 vectors
+  int32_t swap;       // operands stored in the other byte order: bit 0 a, bit 1 b, bit 2 out
 };
 
 constexpr int kMaxTilePasses = 16;  // a tile holds at most 4096 elements = 16 passes of 256 lanes
@@ -68,6 +69,7 @@ struct TiledArgs {
   FastDiv ntdiv[kMaxDims];
   int32_t stage_a, stage_b;
   int32_t nt_store;                // stream the output past the caches
+  int32_t swap;                    // operands stored in the other byte order: bit 0 a, bit 1 b, bit 2 out
   uint32_t lds_off_b;              // byte offset of b's staging area in dynamic LDS
   TileSwizzle swz[2];              // for a, b
   TileOrder ord[3];                // enumeration orders: out's, a's, b's
@@ -96,6 +98,7 @@ struct FastTiledArgs {
   int32_t ntd;                              // entries of the tile-number decomposition, fastest first
   int32_t stage_a, stage_b;
   int32_t nt_store;                         // stream the output past the caches
+  int32_t swap;                             // operands stored in the other byte order: bit 0 a, bit 1 b, bit 2 out
   int32_t pair_log2;                        // groups of 1 << pair_log2 consecutive tiles share input lines
   uint32_t lds_base[2];                     // byte offset of a's / b's staging area
   FastDiv ntdiv[kMaxDims + 1];              // (one more than dims: a dim's tile index may be split in two)
@@ -117,6 +120,7 @@ struct InterpArgs {
   int64_t size[kMaxDims], so[kMaxDims], sa[kMaxDims], sb[kMaxDims];
   int64_t numel;
   int32_t idx32;              // fewer than 2^31 elements: 32-bit multiply-shift index arithmetic
+  int32_t swap;               // operands stored in the other byte order: bit 0 a, bit 1 b, bit 2 out
   FastDiv div[kMaxDims];
 };
 
@@ -241,6 +245,18 @@ template <int OP, int SA, int SB, int SO, int NIN> struct Sig {
   static constexpr int VR = rows_stream_vec((int)sizeof(SOt), ES_MIN, ES_MAX);  // the rows kernel's vector
   static constexpr int UR = rows_stream_unroll(VR, ES_MAX);
 
+  // operands stored in the other byte order: un-reverse inputs after the load, reverse the
+  // result before the store (sw: bit 0 a, bit 1 b, bit 2 out; uniform over the launch)
+  template <class PA, class PB> OCN_DEV static void order_inputs(int sw, PA &a, PB &b) {
+    if (sw & 1) reverse_scalars<scalar_bytes(SA)>(a);
+    if constexpr (NIN == 2) {
+      if (sw & 2) reverse_scalars<scalar_bytes(SB)>(b);
+    }
+  }
+  template <class PO> OCN_DEV static void order_output(int sw, PO &r) {
+    if (sw & 4) reverse_scalars<scalar_bytes(SO)>(r);
+  }
+
   OCN_DEV static SOt eval(SAt a, SBt b) {
     reg_t<T> ra = convert<T>(from_storage<SA>(a));
     if constexpr (NIN == 2) {
@@ -337,11 +353,13 @@ template <class G> OCN_DEV void rows_general(const RowsArgs &p) {
     const int n = nvalid[u];
     if (n == 0) continue;
     Pack<SOt, V> r;
+    if (p.swap) G::order_inputs(p.swap, va[u], vb[u]);
 #pragma unroll
     for (int i = 0; i < V; ++i) {
       if constexpr (BIN) r.v[i] = G::eval(va[u].v[i], vb[u].v[i]);
       else r.v[i] = G::eval(va[u].v[i], SBt{});
     }
+    if (p.swap) G::order_output(p.swap, r);
     char *po = p.out + oo[u];
     if (n == V) {
       store_pack<SOt, V>(po, r, p.nt_store != 0);
@@ -399,11 +417,13 @@ template <class G> OCN_DEV void rows_simple(const RowsArgs &p) {
   for (int u = 0; u < U; ++u) {
     if (g0 + (uint32_t)u * kBlock < nvec) {
       Pack<SOt, V> r;
+      if (p.swap) G::order_inputs(p.swap, va[u], vb[u]);
 #pragma unroll
       for (int i = 0; i < V; ++i) {
         if constexpr (BIN) r.v[i] = G::eval(va[u].v[i], vb[u].v[i]);
         else r.v[i] = G::eval(va[u].v[i], SBt{});
       }
+      if (p.swap) G::order_output(p.swap, r);
       store_pack<SOt, V>(p.out + oo[u], r, p.nt_store != 0);
     }
   }
@@ -619,11 +639,13 @@ OCN_DEV void tiled_compute(KTiledArgs &p, char *out, const char *pa, const char 
       const int n = nv[j];
       if (!FULL && n == 0) continue;
       Pack<SOt, V> r;
+      if (p.swap) G::order_inputs(p.swap, av[j], bv[j]);
 #pragma unroll
       for (int i = 0; i < V; ++i) {
         if constexpr (BIN) r.v[i] = G::eval(av[j].v[i], bv[j].v[i]);
         else r.v[i] = G::eval(av[j].v[i], SBt{});
       }
+      if (p.swap) G::order_output(p.swap, r);
       char *po = out + offo[j];
       if (FULL || n == V) {
         store_pack<SOt, V>(po, r, p.nt_store != 0);
@@ -879,11 +901,13 @@ template <class G> __global__ __launch_bounds__(kBlock) void ew_tiled_fast_kerne
       const int jj = j0 + j;
       if (jj >= no) break;  // uniform: the last batch of passes may be short
       Pack<SOt, VC> r;
+      if (p.swap) G::order_inputs(p.swap, av[j], bv[j]);
 #pragma unroll
       for (int i = 0; i < VC; ++i) {
         if constexpr (BIN) r.v[i] = G::eval(av[j].v[i], bv[j].v[i]);
         else r.v[i] = G::eval(av[j].v[i], SBt{});
       }
+      if (p.swap) G::order_output(p.swap, r);
       store_pack<SOt, VC>(out + p.ord[0].hi_off[0][jj] + off[0], r, p.nt_store != 0);
     }
   }

@@ -31,6 +31,7 @@ RowsArgs make_rows_args(const EwPlan &p) {
   r.a_bcast = p.a_inner_bcast;
   r.b_bcast = p.b_inner_bcast;
   r.nt_store = p.nt_store;
+  r.swap = p.swap;
   r.nt_a = p.nt_a;
   r.nt_b = p.nt_b;
   // with no outer dim the "row" is the whole tensor: so[0], sa[0], sb[0] stay zero and unused
@@ -59,6 +60,7 @@ TiledArgs make_tiled_args(const EwPlan &p, int es_a) {
   t.stage_a = p.stage_a;
   t.stage_b = p.stage_b;
   t.nt_store = p.nt_store;
+  t.swap = p.swap;
   const int64_t tile_elems = (int64_t)1 << p.tile_bits;
   t.lds_off_b = p.stage_a ? (uint32_t)((tile_elems * es_a + 15) / 16 * 16) : 0u;
   // bit position of each tiled dim in the output's enumeration order = its LDS slot shift
@@ -130,6 +132,7 @@ FastTiledArgs make_fast_tiled_args(const EwPlan &p, int es_a) {
   f.stage_a = t.stage_a;
   f.stage_b = t.stage_b;
   f.nt_store = t.nt_store;
+  f.swap = t.swap;
   // tile grid: only dims with more than one tile, fastest (last canonical dim) first.  Where
   // neighbouring tiles along one dim share input lines, that dim's tile index is split: its low
   // part (the group of tiles sharing a line) varies fastest of all, its high part stays in place.
@@ -220,6 +223,7 @@ InterpArgs make_interp_args(const EwPlan &p) {
     a.sb[d] = p.b.stride[d];
   }
   a.numel = p.numel;
+  a.swap = p.swap;
   a.idx32 = p.numel < ((int64_t)1 << 31);
   if (a.idx32)
     for (int d = 0; d < p.ndim; ++d) a.div[d] = make_fastdiv((uint32_t)p.size[d]);

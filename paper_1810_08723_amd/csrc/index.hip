@@ -327,6 +327,11 @@ int done(hipError_t e) {
   return OCN_ERR_LAUNCH;
 }
 
+// the indexing kernels take tensors in native byte order only (one-byte scalars have no order)
+bool other_byte_order(const ocn_tensor *t) {
+  return t && t->byteswapped && t->dtype >= 0 && t->dtype < DT_COUNT && dt_size(dt_real_of(t->dtype)) > 1;
+}
+
 bool bad_tensor(const ocn_tensor *t) {
   if (!t || t->ndim < 0 || t->ndim > kMaxDims || t->dtype < 0 || t->dtype >= DT_COUNT) return true;
   for (int d = 0; d < t->ndim; ++d)
@@ -381,6 +386,7 @@ extern "C" {
 int ocn_index_offsets(const ocn_tensor *index, int64_t dim_size, int64_t stride_bytes, const ocn_tensor *offsets,
                       void *invalid_count, void *stream) {
   if (bad_tensor(index) || bad_tensor(offsets)) return (!index || !offsets) ? OCN_ERR_NULLPTR : OCN_ERR_SHAPE;
+  if (other_byte_order(index) || other_byte_order(offsets)) return OCN_ERR_BYTEORDER;
   if (!invalid_count) return OCN_ERR_NULLPTR;
   if (index->dtype != DT_I64 || offsets->dtype != DT_I64) return OCN_ERR_DTYPE;
   if (index->ndim != offsets->ndim || dim_size < 0) return OCN_ERR_SHAPE;
@@ -454,6 +460,8 @@ static int run_gather(bool scatter, const ocn_tensor *inner, const void *offsets
                       const ocn_tensor *rows, void *stream) {
   if (bad_tensor(inner) || bad_tensor(rows)) return (!inner || !rows) ? OCN_ERR_NULLPTR : OCN_ERR_SHAPE;
   if (inner->dtype != rows->dtype) return OCN_ERR_DTYPE;
+  // a copy of elements between two tensors of the same byte order needs no reversal
+  if (other_byte_order(inner) != other_byte_order(rows)) return OCN_ERR_BYTEORDER;
   if (inner->device != rows->device) return OCN_ERR_DEVICE;
   if (n < 0 || rows->ndim != inner->ndim + 1 || rows->size[0] != n) return OCN_ERR_SHAPE;
   for (int d = 0; d < inner->ndim; ++d)

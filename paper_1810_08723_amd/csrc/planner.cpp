@@ -311,6 +311,11 @@ int plan_elementwise(int nin, int op, const ocn_tensor *a, const ocn_tensor *b,
   if ((rc = check_broadcast(a, out)) != OCN_OK) return rc;
   if (nin == 2 && (rc = check_broadcast(b, out)) != OCN_OK) return rc;
 
+  // operands stored in the other byte order (section 3.1.3); one-byte scalars have no order
+  p.swap = (a->byteswapped && scalar_size(a->dtype) > 1 ? 1 : 0) |
+           (nin == 2 && b->byteswapped && scalar_size(b->dtype) > 1 ? 2 : 0) |
+           (out->byteswapped && scalar_size(out->dtype) > 1 ? 4 : 0);
+
   // compute type and strict-mode checks (section 3.2.1)
   const int sa = a->dtype, sb = nin == 2 ? b->dtype : a->dtype, so = out->dtype;
   if (nin == 2) {
@@ -819,6 +824,8 @@ int plan_reduce(int op, const ocn_tensor *a, const int32_t *axes, int32_t naxes,
   p.a_dtype = a->dtype;
   p.out_dtype = out->dtype;
   p.acc_dtype = reduce_acc_dtype(op, a->dtype);
+  p.swap_a = a->byteswapped && scalar_size(a->dtype) > 1;     // stored in the other byte order (section 3.1.3)
+  p.swap_o = out->byteswapped && scalar_size(out->dtype) > 1;
   if (nout == 0) { *plan = p; return OCN_OK; }
   if ((op == R_MIN || op == R_MAX) && nred == 0) return OCN_ERR_EMPTY;
   if (nred > 0 && (rc = check_alignment(a)) != OCN_OK) return rc;
@@ -995,6 +1002,9 @@ int plan_binary_reduce(int ew_op, int red_op, const ocn_tensor *a, const ocn_ten
   if (ew_op < 0 || ew_op >= B_COUNT || red_op < 0 || red_op >= R_COUNT) return OCN_ERR_OP;
   if (!valid_dtype(mid_dtype)) return OCN_ERR_DTYPE;
   if (a->device != out->device || b->device != out->device) return OCN_ERR_DEVICE;
+  // the fused kernels take operands in native byte order only (one-byte scalars have no order)
+  for (const ocn_tensor *t : {a, b, out})
+    if (t->byteswapped && scalar_size(t->dtype) > 1) return OCN_ERR_BYTEORDER;
   // broadcast shape of the two inputs (missing leading dims count as size 1)
   const int nd = std::max(a->ndim, b->ndim);
   int64_t shape[kMaxDims], sa[kMaxDims], sb[kMaxDims];
@@ -1163,6 +1173,7 @@ void plan_second_pass(const RedPlan &first, char *workspace, RedPlan *second) {
   q.rsize[0] = first.split;
   q.rstride_a[0] = rows_layout ? es : first.nout * es;
   q.split = 1;
+  q.swap_o = first.swap_o;   // the partial results are in native order, the output as the caller declared it
   q.chunk = first.split;
   q.passes = 1;
   q.workspace_bytes = 0;

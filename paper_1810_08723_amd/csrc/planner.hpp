@@ -72,6 +72,7 @@ struct EwPlan {
   bool fast_tiled = false;      // tiled kernel: the unclipped all-vector form applies
   bool nt_store = false;        // the output is too large to stay cached: stream it past the caches
   bool nt_a = false, nt_b = false;  // rows kernel: that input is read with streaming loads
+  int swap = 0;                 // operands stored in the other byte order: bit 0 a, bit 1 b, bit 2 out
   int64_t grid = 0;
   int64_t lds_bytes = 0;
   int pair_dim = -1;            // all-vector tiled form: tiles that are neighbours along this dim share
@@ -95,6 +96,7 @@ struct RedPlan {
   int cpw = kWave;              // cols kernel: lanes per row of columns (power of two, at most a wavefront)
   bool nt_load = false;         // the input is far larger than the caches: stream it (non-temporal vector loads)
   bool lean = false;            // rows kernel: the common 2-D shape, run by the lean form of the kernel
+  bool swap_a = false, swap_o = false;  // the input / the output is stored in the other byte order
   int64_t split = 1;            // partial results per output
   int64_t chunk = 0;            // reduction elements (rows: vectors) per split
   int64_t grid = 0;

@@ -46,6 +46,7 @@ struct RedArgs {
   int32_t a_bcast, b_bcast;                // broadcast along the vectorised dim
   int32_t cpw;                             // cols: lanes per row of columns (power of two <= 64)
   int32_t nt_load;                         // vector loads carry the streaming (non-temporal) hint
+  int32_t swap_a, swap_o;                  // the input / the output is stored in the other byte order
 };
 
 // arguments of the lean rows kernel: one reduced dim read in whole 16-byte vectors, at most one
@@ -57,6 +58,7 @@ struct RedLeanArgs {
   uint32_t nout, split;    // outputs; partial results per output
   uint32_t nvec, chunk;    // vectors per output; vectors per split
   int32_t out_dtype, group, nt_load;
+  int32_t swap_a, swap_o;  // the input / the output is stored in the other byte order
 };
 
 #if defined(__HIPCC__)
@@ -187,10 +189,14 @@ template <class R> OCN_DEV typename R::A group_fold(typename R::A v, int width) 
 }
 
 // convert an accumulator to the runtime output dtype and store it (once per output)
-template <class A> __device__ __noinline__ void store_result(char *p, int dt, A r) {
+template <class A> __device__ __noinline__ void store_result(char *p, int dt, A r, bool swapped = false) {
   switch (dt) {
-#define OCN_CASE(D) \
-  case D: *reinterpret_cast<storage_t<D> *>(p) = to_storage<D>(convert<D>(r)); break;
+#define OCN_CASE(D)                                      \
+  case D: {                                              \
+    storage_t<D> s = to_storage<D>(convert<D>(r));       \
+    if (swapped) reverse_scalars<scalar_bytes(D)>(s);    \
+    *reinterpret_cast<storage_t<D> *>(p) = s;            \
+  } break;
     OCN_CASE(DT_BOOL) OCN_CASE(DT_I8) OCN_CASE(DT_I16) OCN_CASE(DT_I32) OCN_CASE(DT_I64)
     OCN_CASE(DT_U8) OCN_CASE(DT_U16) OCN_CASE(DT_U32) OCN_CASE(DT_U64)
     OCN_CASE(DT_F16) OCN_CASE(DT_F32) OCN_CASE(DT_F64)
@@ -350,6 +356,18 @@ struct VecFold<DT_F16, OP, V, std::enable_if_t<(OP == R_MIN || OP == R_MAX) && V
 // is read once and never again; read this way a wavefront's whole-line requests stream about
 // 7 % faster from HBM (fp32 row sums over 256 MiB: 43.9 -> 40.4 us).  Only for 16-byte pieces
 // that neighbouring lanes read side by side: with partial lines the hint costs time.
+// A pack whose tensor is stored in the other byte order is put right as soon as it is loaded.
+template <int S, class Pk> OCN_DEV void order_pack(bool swapped, Pk &pk) {
+  if constexpr (scalar_bytes(S) > 1) {
+    if (swapped) reverse_scalars<scalar_bytes(S)>(pk);
+  }
+}
+template <int S> OCN_DEV storage_t<S> load_one(bool swapped, const char *src) {
+  storage_t<S> v = *reinterpret_cast<const storage_t<S> *>(src);
+  order_pack<S>(swapped, v);
+  return v;
+}
+
 template <class St, int V, bool NT = false, class Pk> OCN_DEV void load_vec(const char *src, Pk &pk) {
   if constexpr (sizeof(St) * V >= 16) {
     using Q = uint32_t __attribute__((ext_vector_type(4)));
@@ -398,12 +416,12 @@ OCN_DEV typename Reducer<S, OP>::A rows_accumulate_impl(const RedArgs &p, const 
       const int64_t left = p.n0 - e0;
       if (left >= V) {
         load_vec<St, V, NT>(src, pk);
-        one.add_full(pk);
+        order_pack<S>(p.swap_a != 0, pk); one.add_full(pk);
       } else {
 #pragma unroll
         for (int i = 0; i < V; ++i)
           if (i < (int)left) pk.v[i] = reinterpret_cast<const St *>(src)[i];
-        one.add_partial(pk, (int)left);
+        order_pack<S>(p.swap_a != 0, pk); one.add_partial(pk, (int)left);
       }
     }
     return one.result();
@@ -428,13 +446,16 @@ OCN_DEV typename Reducer<S, OP>::A rows_accumulate_impl(const RedArgs &p, const 
       load_vec<St, V, NT>(address(t + (int64_t)u * lanes + lane, e0), pk[u]);
     }
 #pragma unroll
-    for (int u = 0; u < U; ++u) fold[u].add_full(pk[u]);
+    for (int u = 0; u < U; ++u) {
+      order_pack<S>(p.swap_a != 0, pk[u]);
+      fold[u].add_full(pk[u]);
+    }
   }
   for (; t + lanes <= t_full; t += lanes) {  // whole vectors, one per lane and trip
     Pk pk;
     int64_t e0;
     load_vec<St, V, NT>(address(t + lane, e0), pk);
-    fold[0].add_full(pk);
+    order_pack<S>(p.swap_a != 0, pk); fold[0].add_full(pk);
   }
   for (int64_t tt = t + lane; tt < t1; tt += lanes) {
     Pk pk;
@@ -443,12 +464,12 @@ OCN_DEV typename Reducer<S, OP>::A rows_accumulate_impl(const RedArgs &p, const 
     const int64_t left = p.n0 - e0;
     if (left >= V) {
       load_vec<St, V, NT>(src, pk);
-      fold[0].add_full(pk);
+      order_pack<S>(p.swap_a != 0, pk); fold[0].add_full(pk);
     } else {
 #pragma unroll
       for (int i = 0; i < V; ++i)
         if (i < (int)left) pk.v[i] = reinterpret_cast<const St *>(src)[i];
-      fold[0].add_partial(pk, (int)left);
+      order_pack<S>(p.swap_a != 0, pk); fold[0].add_partial(pk, (int)left);
     }
   }
   typename R::A acc = fold[0].result();
@@ -522,7 +543,7 @@ template <int S, int OP> __global__ __launch_bounds__(kBlock) OCN_ROWS_OCC void 
   }
   if (active && lane == 0) {
     if (p.split == 1) {
-      store_result<A>(p.out + off_o, p.out_dtype, acc);
+      store_result<A>(p.out + off_o, p.out_dtype, acc, p.swap_o != 0);
     } else {
       reinterpret_cast<typename R::P *>(p.partial)[o * p.split + s] = to_storage<R::ACC>(acc);
     }
@@ -536,7 +557,7 @@ template <int S, int OP> __global__ __launch_bounds__(kBlock) OCN_ROWS_OCC void 
 // after its last one is time during which it has nothing in flight (half-precision maxima
 // over rows of 8 KiB: 24.6 us in the general kernel).  Same fold order as the general kernel.
 template <int S, int OP, bool NT>
-OCN_DEV typename Reducer<S, OP>::A lean_fold(const char *base, uint32_t t0, uint32_t t1, uint32_t lane, uint32_t lanes) {
+OCN_DEV typename Reducer<S, OP>::A lean_fold(const char *base, uint32_t t0, uint32_t t1, uint32_t lane, uint32_t lanes, bool sw) {
   using R = Reducer<S, OP>;
   using St = storage_t<S>;
   constexpr int V = 16 / (int)sizeof(St);
@@ -552,12 +573,15 @@ OCN_DEV typename Reducer<S, OP>::A lean_fold(const char *base, uint32_t t0, uint
 #pragma unroll
     for (int u = 0; u < U; ++u) load_vec<St, V, NT>(base + (uint64_t)(t + u * lanes) * 16u, pk[u]);
 #pragma unroll
-    for (int u = 0; u < U; ++u) fold[u].add_full(pk[u]);
+    for (int u = 0; u < U; ++u) {
+      order_pack<S>(sw, pk[u]);
+      fold[u].add_full(pk[u]);
+    }
   }
   for (; t < t1; t += lanes) {
     Pk pk;
     load_vec<St, V, NT>(base + (uint64_t)t * 16u, pk);
-    fold[0].add_full(pk);
+    order_pack<S>(sw, pk); fold[0].add_full(pk);
   }
   typename R::A acc = fold[0].result();
 #pragma unroll
@@ -586,8 +610,8 @@ template <int S, int OP> __global__ __launch_bounds__(kBlock) OCN_ROWS_OCC void 
       }
       const char *base = p.a + (int64_t)o * p.ksa;
       const uint32_t lanes = per_block ? kBlock : kWave;
-      if (p.nt_load) acc = lean_fold<S, OP, true>(base, t0, t1, lane, lanes);
-      else acc = lean_fold<S, OP, false>(base, t0, t1, lane, lanes);
+      if (p.nt_load) acc = lean_fold<S, OP, true>(base, t0, t1, lane, lanes, p.swap_a != 0);
+      else acc = lean_fold<S, OP, false>(base, t0, t1, lane, lanes, p.swap_a != 0);
     }
     acc = group_fold<R>(acc, kWave);
     if (per_block) {
@@ -599,7 +623,7 @@ template <int S, int OP> __global__ __launch_bounds__(kBlock) OCN_ROWS_OCC void 
       }
     }
     if (active && lane == 0) {
-      if (p.split == 1) store_result<A>(p.out + (int64_t)o * p.kso, p.out_dtype, acc);
+      if (p.split == 1) store_result<A>(p.out + (int64_t)o * p.kso, p.out_dtype, acc, p.swap_o != 0);
       else reinterpret_cast<typename R::P *>(p.partial)[(uint64_t)o * p.split + sp] = to_storage<R::ACC>(acc);
     }
   }
@@ -622,12 +646,12 @@ OCN_DEV typename Reducer<S, OP>::A short_row_fold(const RedArgs &p, const char *
     const uint32_t left = (uint32_t)p.n0 - e0;
     if (left >= (uint32_t)V) {
       load_vec<St, V, NT>(src, pk);
-      one.add_full(pk);
+      order_pack<S>(p.swap_a != 0, pk); one.add_full(pk);
     } else {
 #pragma unroll
       for (int i = 0; i < V; ++i)
         if (i < (int)left) pk.v[i] = reinterpret_cast<const St *>(src)[i];
-      one.add_partial(pk, (int)left);
+      order_pack<S>(p.swap_a != 0, pk); one.add_partial(pk, (int)left);
     }
   }
   return one.result();
@@ -654,7 +678,7 @@ template <int S, int OP> __global__ __launch_bounds__(kBlock) void red_rows_shor
     }
   }
   acc = group_fold<R>(acc, (int)width);
-  if (active && lane == 0) store_result<A>(p.out + off_o, p.out_dtype, acc);
+  if (active && lane == 0) store_result<A>(p.out + off_o, p.out_dtype, acc, p.swap_o != 0);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -784,13 +808,16 @@ OCN_DEV void cols_body(const RedArgs &p, typename Reducer<S, OP>::A (*lds)[kWave
       for (int u = 0; u < U; ++u)
         load_vec<St, V, NT>(p.a + off_a + row_offset(r + (int64_t)u * RS), pk[u]);
 #pragma unroll
-      for (int u = 0; u < U; ++u)
+      for (int u = 0; u < U; ++u) {
+        order_pack<S>(p.swap_a != 0, pk[u]);
 #pragma unroll
         for (int i = 0; i < V; ++i) acc[i] = R::combine(acc[i], R::lift(from_storage<S>(pk[u].v[i])));
+      }
     }
     for (; r < r1; r += RS) {
       Pk pk;
       load_vec<St, V, NT>(p.a + off_a + row_offset(r), pk);
+      order_pack<S>(p.swap_a != 0, pk);
 #pragma unroll
       for (int i = 0; i < V; ++i) acc[i] = R::combine(acc[i], R::lift(from_storage<S>(pk.v[i])));
     }
@@ -799,7 +826,7 @@ OCN_DEV void cols_body(const RedArgs &p, typename Reducer<S, OP>::A (*lds)[kWave
       const char *src = p.a + off_a + row_offset(r);
 #pragma unroll
       for (int i = 0; i < V; ++i)
-        if (i < ncol) acc[i] = R::combine(acc[i], R::lift(from_storage<S>(reinterpret_cast<const St *>(src)[i])));
+        if (i < ncol) acc[i] = R::combine(acc[i], R::lift(from_storage<S>(load_one<S>(p.swap_a != 0, src + (int64_t)i * (int64_t)sizeof(St)))));
     }
   }
   // lanes of a wavefront that hold the same columns of different rows: fold onto the first
@@ -819,7 +846,7 @@ OCN_DEV void cols_body(const RedArgs &p, typename Reducer<S, OP>::A (*lds)[kWave
       A v = lds[0][lane];
       for (int w = 1; w < NW; ++w) v = R::combine(v, lds[w][lane]);
       if (p.split == 1) {
-        store_result<A>(p.out + off_o + (int64_t)i * p.kso[0], p.out_dtype, v);
+        store_result<A>(p.out + off_o + (int64_t)i * p.kso[0], p.out_dtype, v, p.swap_o != 0);
       } else {
         const int64_t olin = (int64_t)other * p.nc + col0 + i;
         reinterpret_cast<typename R::P *>(p.partial)[(int64_t)s * p.nout + olin] = to_storage<R::ACC>(v);
@@ -878,9 +905,9 @@ template <int S, int OP> __global__ __launch_bounds__(kBlock) void red_generic_k
         q = qq;
       }
     }
-    acc = R::combine(acc, R::lift(from_storage<S>(*reinterpret_cast<const St *>(p.a + off_a + off))));
+    acc = R::combine(acc, R::lift(from_storage<S>(load_one<S>(p.swap_a != 0, p.a + off_a + off))));
   }
-  store_result<A>(p.out + off_o, p.out_dtype, acc);
+  store_result<A>(p.out + off_o, p.out_dtype, acc, p.swap_o != 0);
 }
 
 #endif  // __HIPCC__

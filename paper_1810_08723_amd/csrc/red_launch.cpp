@@ -42,6 +42,8 @@ RedArgs make_red_args(const RedPlan &p, char *partial) {
   r.split = p.split;
   r.chunk = p.chunk;
   r.nt_load = p.nt_load ? 1 : 0;
+  r.swap_a = p.swap_a ? 1 : 0;
+  r.swap_o = p.swap_o ? 1 : 0;
   if (p.kernel == OCN_KERNEL_RED_ROWS) {
     r.n0 = p.rsize[p.nred - 1];
     const int64_t vpr = (r.n0 + p.vec - 1) / p.vec;
@@ -71,6 +73,8 @@ RedLeanArgs make_red_lean_args(const RedPlan &p, char *partial) {
   r.out_dtype = p.out_dtype;
   r.group = p.group;
   r.nt_load = p.nt_load ? 1 : 0;
+  r.swap_a = p.swap_a ? 1 : 0;
+  r.swap_o = p.swap_o ? 1 : 0;
   return r;
 }
 

@@ -30,17 +30,35 @@ class DeviceViews:
             self._by_id[key] = (view.storage, self.torch.from_numpy(host.copy()).to(f"cuda:{self.device}"))
         assert self._by_id[key][0] is view.storage
         assert view.in_bounds()
-        return ocn.Tensor.on_storage(self._by_id[key][1], view.dtype, view.sizes, view.strides, view.offset)
+        return ocn.Tensor.on_storage(self._by_id[key][1], view.dtype, view.sizes, view.strides, view.offset,
+                                     getattr(view, "byteswapped", False))
 
     def download(self, view: View) -> np.ndarray:
         got = self._by_id[id(view.storage)][1].cpu().numpy()
         return got[:view.storage.size]
 
 
-def storages_equal(dtype: str, got: np.ndarray, want: np.ndarray) -> bool:
-    """Byte equality; where the bytes differ, both sides must hold NaN in the same float slot."""
+_SCALAR_BYTES = {"int16": 2, "uint16": 2, "half": 2, "chalf": 2, "int32": 4, "uint32": 4, "float": 4, "cfloat": 4,
+                 "int64": 8, "uint64": 8, "double": 8, "cdouble": 8}
+
+
+def native_order(dtype: str, storage: np.ndarray) -> np.ndarray:
+    """The bytes of a storage that holds scalars of `dtype` in the other byte order, every scalar
+    reversed back (the storage must consist of such scalars from its first byte on)."""
+    sb = _SCALAR_BYTES.get(dtype, 1)
+    n = storage.size // sb * sb
+    if sb == 1:
+        return storage
+    return np.concatenate([storage[:n].reshape(-1, sb)[:, ::-1].reshape(-1), storage[n:]])
+
+
+def storages_equal(dtype: str, got: np.ndarray, want: np.ndarray, swapped: bool = False) -> bool:
+    """Byte equality; where the bytes differ, both sides must hold NaN in the same float slot.
+    `swapped`: both storages hold their scalars in the other byte order."""
     if np.array_equal(got, want):
         return True
+    if swapped:
+        got, want = native_order(dtype, got), native_order(dtype, want)
     if dtype not in _FLOAT_COMPONENT:
         return False
     comp = np.dtype(_FLOAT_COMPONENT[dtype])
@@ -76,7 +94,7 @@ def check_binary(op: str, a: View, b: View, out: View, flags: int = 0) -> None:
     dv.torch.cuda.synchronize()
     got = dv.download(out)
     O.binary(op, a, b, out, flags)          # oracle writes into the host storage
-    assert storages_equal(out.dtype, got, out.storage), first_mismatch(out.dtype, got, out.storage)
+    assert storages_equal(out.dtype, got, out.storage, out.byteswapped), first_mismatch(out.dtype, got, out.storage)
 
 
 def check_unary(op: str, a: View, out: View, flags: int = 0) -> None:
@@ -88,7 +106,7 @@ def check_unary(op: str, a: View, out: View, flags: int = 0) -> None:
     dv.torch.cuda.synchronize()
     got = dv.download(out)
     O.unary(op, a, out, flags)
-    assert storages_equal(out.dtype, got, out.storage), first_mismatch(out.dtype, got, out.storage)
+    assert storages_equal(out.dtype, got, out.storage, out.byteswapped), first_mismatch(out.dtype, got, out.storage)
 
 
 def run_reduce(op: str, a: View, axes: Sequence[int], out: View):
