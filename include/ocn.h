@@ -276,6 +276,30 @@ size_t ocn_domain_check_workspace_bytes(int op, const ocn_tensor *a);
 int ocn_domain_check(int op, const ocn_tensor *a, const ocn_tensor *flag, void *workspace,
                      size_t workspace_bytes, void *stream);
 
+/*
+ * A unary operation in one of the compute modes of section 3.2.1 (parameters added to operators
+ * such as the square root and the arccosine, whose domain a real tensor may leave):
+ *   OCN_MODE_STANDARD  no check on the elements; NaN where an element is outside the domain.
+ *                      Exactly ocn_unary(op, a, out, 0, stream); *outside is set to -1.
+ *   OCN_MODE_WARNING   the domain check runs ahead of the operation on the same stream, then
+ *                      the operation as in standard mode; *outside tells the caller what to warn about.
+ *   OCN_MODE_ERROR     the check runs first; if an element is outside the domain nothing else
+ *                      is launched, out is untouched and the call returns OCN_ERR_DOMAIN.
+ *   OCN_MODE_COMPLEX   the check decides the result type: outside the domain the operation is
+ *                      computed into out_complex (a complex tensor of out's shape; the real
+ *                      input converts with a zero imaginary part), otherwise into out.
+ * *outside (HOST int, may be NULL): -1 not checked, 0 all elements inside, 1 some outside; in
+ * complex mode 1 also means that out_complex was written instead of out.  The domain is that
+ * of ocn_domain_check.  Every mode but the standard one reads the check's answer on the host:
+ * the call waits for the stream, and cannot be part of a graph capture.  Both result plans
+ * are validated before anything is launched.  workspace: DEVICE scratch of
+ * ocn_unary_mode_workspace_bytes(op, mode, a) bytes, 256-byte aligned (0 in standard mode).
+ */
+typedef enum { OCN_MODE_STANDARD = 0, OCN_MODE_WARNING, OCN_MODE_ERROR, OCN_MODE_COMPLEX } ocn_compute_mode;
+size_t ocn_unary_mode_workspace_bytes(int op, int mode, const ocn_tensor *a);
+int ocn_unary_mode(int op, int mode, const ocn_tensor *a, const ocn_tensor *out, const ocn_tensor *out_complex,
+                   void *workspace, size_t workspace_bytes, int *outside, void *stream);
+
 /* Bytes of workspace ocn_reduce needs for these arguments (0 when it runs in one pass).
  * Returns 0 as well when the arguments are invalid; ocn_reduce then reports the error. */
 size_t ocn_reduce_workspace_bytes(int op, const ocn_tensor *a, const int32_t *axes,

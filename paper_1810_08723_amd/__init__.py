@@ -9,10 +9,10 @@ from .binding import (BINARY_OPS, DTYPES, REDUCE_OPS, STRICT_TYPES, UNARY_OPS, O
                       binary, binary_reduce, binary_reduce_workspace_bytes, cast_copy, domain_check, dtype_size,
                       gather, index_offsets, mask_offsets, scatter,
                       plan_binary, plan_binary_reduce, plan_reduce, plan_unary, promote, reduce,
-                      reduce_scratch, reduce_workspace_bytes, unary)
+                      reduce_scratch, reduce_workspace_bytes, unary, unary_mode)
 
 __all__ = ["BINARY_OPS", "DTYPES", "REDUCE_OPS", "STRICT_TYPES", "UNARY_OPS", "OcnError", "Tensor",
            "binary", "binary_reduce", "binary_reduce_workspace_bytes", "cast_copy", "domain_check", "dtype_size",
            "gather", "index_offsets", "mask_offsets", "scatter",
            "plan_binary", "plan_binary_reduce", "plan_reduce", "plan_unary", "promote", "reduce",
-           "reduce_scratch", "reduce_workspace_bytes", "unary"]
+           "reduce_scratch", "reduce_workspace_bytes", "unary", "unary_mode"]

@@ -41,7 +41,8 @@ EXPORTS = ("ocn_unary", "ocn_binary", "ocn_cast_copy", "ocn_reduce", "ocn_reduce
            "ocn_plan_unary", "ocn_plan_binary", "ocn_plan_reduce",
            "ocn_binary_reduce", "ocn_binary_reduce_workspace_bytes", "ocn_plan_binary_reduce",
            "ocn_index_offsets", "ocn_mask_offsets", "ocn_mask_offsets_workspace_bytes", "ocn_gather",
-           "ocn_scatter", "ocn_domain_check", "ocn_domain_check_workspace_bytes", "ocn_reduce_scratch")
+           "ocn_scatter", "ocn_domain_check", "ocn_domain_check_workspace_bytes", "ocn_reduce_scratch",
+           "ocn_unary_mode", "ocn_unary_mode_workspace_bytes")
 
 
 class OcnTensor(C.Structure):
@@ -110,6 +111,9 @@ def lib() -> C.CDLL:
         L.ocn_domain_check_workspace_bytes.argtypes = [C.c_int, T]
         L.ocn_domain_check_workspace_bytes.restype = C.c_size_t
         L.ocn_domain_check.argtypes = [C.c_int, T, T, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.ocn_unary_mode_workspace_bytes.argtypes = [C.c_int, C.c_int, T]
+        L.ocn_unary_mode_workspace_bytes.restype = C.c_size_t
+        L.ocn_unary_mode.argtypes = [C.c_int, C.c_int, T, T, T, C.c_void_p, C.c_size_t, C.POINTER(C.c_int), C.c_void_p]
         L.ocn_index_offsets.argtypes = [T, C.c_int64, C.c_int64, T, C.c_void_p, C.c_void_p]
         L.ocn_mask_offsets_workspace_bytes.argtypes = [T]
         L.ocn_mask_offsets_workspace_bytes.restype = C.c_size_t
@@ -301,6 +305,30 @@ def domain_check(op: str, a: Tensor, flag=None, workspace=None, stream=None):
     _check(lib().ocn_domain_check(UNARY_CODE[op], C.byref(a.desc()), C.byref(tf.desc()), workspace.data_ptr(),
                                   workspace.numel(), _stream(stream)))
     return flag
+
+
+MODES = ("standard", "warning", "error", "complex")
+
+
+def unary_mode(op: str, mode: str, a: Tensor, out: Tensor, out_complex: Optional[Tensor] = None, workspace=None,
+               stream=None) -> dict:
+    """A unary operation in a compute mode (standard, warning, error, complex).  Returns
+    {"outside": None (not checked) | bool, "wrote": "out" | "out_complex"}; error mode raises
+    OcnError with code ERR["DOMAIN"] when an element is outside the domain.  `workspace` as for
+    reduce()."""
+    m = MODES.index(mode)
+    need = int(lib().ocn_unary_mode_workspace_bytes(UNARY_CODE[op], m, C.byref(a.desc())))
+    ws_ptr, ws_bytes = None, 0
+    if workspace is None and need:
+        workspace = _scratch(need, a.device, stream)
+    if workspace is not None:
+        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel()
+    outside = C.c_int(-1)
+    oc = C.byref(out_complex.desc()) if out_complex is not None else None
+    _check(lib().ocn_unary_mode(UNARY_CODE[op], m, C.byref(a.desc()), C.byref(out.desc()), oc, ws_ptr, ws_bytes,
+                                C.byref(outside), _stream(stream)))
+    flag = None if outside.value < 0 else bool(outside.value)
+    return {"outside": flag, "wrote": "out_complex" if (flag and mode == "complex") else "out"}
 
 
 def promote(a: str, b: str) -> str:

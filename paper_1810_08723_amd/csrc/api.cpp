@@ -336,6 +336,47 @@ int ocn_domain_check(int op, const ocn_tensor *a, const ocn_tensor *flag, void *
                     (hipStream_t)stream);
 }
 
+// ---- compute modes (section 3.2.1) ---------------------------------------------------------
+// The first 256 bytes of the workspace hold the flag the domain check writes; the check's own
+// workspace follows.
+size_t ocn_unary_mode_workspace_bytes(int op, int mode, const ocn_tensor *a) {
+  if (mode == OCN_MODE_STANDARD) return 0;
+  return 256 + ocn_domain_check_workspace_bytes(op, a);
+}
+
+int ocn_unary_mode(int op, int mode, const ocn_tensor *a, const ocn_tensor *out, const ocn_tensor *out_complex,
+                   void *workspace, size_t workspace_bytes, int *outside, void *stream) {
+  if (mode < OCN_MODE_STANDARD || mode > OCN_MODE_COMPLEX) return OCN_ERR_OP;
+  if (outside) *outside = -1;
+  if (mode == OCN_MODE_STANDARD) return ocn_unary(op, a, out, 0, stream);
+  // everything that can be refused is refused before the first launch
+  EwPlan real_plan, complex_plan;
+  int rc = plan_elementwise(1, op, a, nullptr, out, 0, &real_plan);
+  if (rc != OCN_OK) return rc;
+  if (mode == OCN_MODE_COMPLEX) {
+    if (!out_complex) return OCN_ERR_NULLPTR;
+    if (out_complex->dtype < 0 || out_complex->dtype >= DT_COUNT || dt_kind(out_complex->dtype) != K_CPLX)
+      return OCN_ERR_DTYPE;
+    if ((rc = plan_elementwise(1, op, a, nullptr, out_complex, 0, &complex_plan)) != OCN_OK) return rc;
+  }
+  if (!workspace || workspace_bytes < ocn_unary_mode_workspace_bytes(op, mode, a)) return OCN_ERR_WORKSPACE;
+  if ((uintptr_t)workspace % 256 != 0) return OCN_ERR_ALIGN;
+  ocn_tensor flag;
+  std::memset(&flag, 0, sizeof flag);
+  flag.base = workspace;
+  flag.dtype = DT_BOOL;
+  flag.device = a->device;
+  rc = ocn_domain_check(op, a, &flag, (char *)workspace + 256, workspace_bytes - 256, stream);
+  if (rc != OCN_OK) return rc;
+  unsigned char answer = 0;
+  hipError_t e = hipMemcpyAsync(&answer, workspace, 1, hipMemcpyDeviceToHost, (hipStream_t)stream);
+  if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
+  if (e != hipSuccess) return finish(e);
+  if (outside) *outside = answer ? 1 : 0;
+  if (answer && mode == OCN_MODE_ERROR) return OCN_ERR_DOMAIN;
+  return run_elementwise(answer && mode == OCN_MODE_COMPLEX ? complex_plan : real_plan, (hipStream_t)stream);
+}
+
 int ocn_plan_binary_reduce(int ew_op, int red_op, const ocn_tensor *a, const ocn_tensor *b, const int32_t *axes,
                            int32_t naxes, const ocn_tensor *out, int32_t mid_dtype, ocn_plan_info *info) {
   if (!info) return OCN_ERR_NULLPTR;

@@ -243,7 +243,7 @@ template <int OP, int SA, int SB, int SO, int NIN> struct Sig {
   static constexpr int V = rows_vec((int)sizeof(SOt), ES_MAX);
   static constexpr int U = rows_unroll(V, ES_MAX);
   static constexpr int VR = rows_stream_vec((int)sizeof(SOt), ES_MIN, ES_MAX);  // the rows kernel's vector
-  static constexpr int UR = rows_stream_unroll(VR, ES_MAX);
+  static constexpr int UR = rows_stream_unroll(VR, ES_MIN);
 
   // operands stored in the other byte order: un-reverse inputs after the load, reverse the
   // result before the store (sw: bit 0 a, bit 1 b, bit 2 out; uniform over the launch)

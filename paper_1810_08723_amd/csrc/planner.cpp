@@ -428,7 +428,7 @@ int plan_elementwise(int nin, int op, const ocn_tensor *a, const ocn_tensor *b,
     if (rows) {
       p.kernel = OCN_KERNEL_EW_ROWS;
       p.vec = V;
-      p.unroll = rows_stream_unroll(V, es_max);
+      p.unroll = rows_stream_unroll(V, es_min);
       p.a_inner_bcast = p.a.stride[inner] == 0;
       p.b_inner_bcast = nin == 2 && p.b.stride[inner] == 0;
       // Inputs too large to be found in a cache again are read with streaming loads: those

@@ -1,4 +1,5 @@
-"""GPU parity of the byte-swap operation and of the domain check behind the compute modes."""
+"""GPU parity of the byte-swap operation, of the domain check behind the compute modes, and of
+the compute modes themselves (standard, warning, error, complex)."""
 import numpy as np
 import pytest
 
@@ -79,3 +80,74 @@ def test_domain_check_on_complex_is_always_clear():
     z = View.from_numpy(np.array([-1 + 0j, -2 - 3j], dtype=np.complex64))
     flag = ocn.domain_check("sqrt", H.DeviceViews().tensor(z))
     assert not bool(flag.cpu()[0])
+
+
+def _mode_case(op, x, cdt="cdouble"):
+    a = View.from_numpy(np.asarray(x, dtype=np.float64))
+    return a, View.empty("double", a.sizes), View.empty(cdt, a.sizes)
+
+
+@pytest.mark.parametrize("op", ("sqrt", "log", "acos", "asin", "sin"))
+def test_compute_modes_follow_the_oracle(op):
+    # standard / warning / error / complex (section 3.2.1) on inputs inside and outside the
+    # operator's domain: the same answer to "outside?", the same output written, the same
+    # values (ulp class), and an untouched output where error mode refuses
+    import paper_1810_08723_amd as ocn
+    from oracle import binding as O
+    rng = rng_for(15100)
+    inside = {"sqrt": rng.uniform(0, 9, 5000), "log": rng.uniform(0.01, 9, 5000), "acos": rng.uniform(-1, 1, 5000),
+              "asin": rng.uniform(-1, 1, 5000), "sin": rng.uniform(-9, 9, 5000)}[op]
+    outside = inside.copy()
+    outside[1234] = -2.5
+    for x in (inside, outside):
+        for mode in O.MODES:
+            a, out, outc = _mode_case(op, x)
+            dv = H.DeviceViews()
+            ta, to, tc = dv.tensor(a), dv.tensor(out), dv.tensor(outc)
+            print(op, mode, "outside" if x is outside else "inside", flush=True)
+            try:
+                got = ocn.unary_mode(op, mode, ta, to, tc)
+            except ocn.OcnError as e:
+                assert e.code == ocn.binding.ERR["DOMAIN"]
+                got = "refused"
+            dv.torch.cuda.synchronize()
+            g_out, g_outc = dv.download(out).copy(), dv.download(outc).copy()
+            try:
+                want = O.unary_mode(op, mode, a, out, outc)
+            except O.DomainError:
+                want = "refused"
+            assert got == want, (op, mode, got, want)
+            if want == "refused":
+                assert np.all(g_out == 0xA5) and np.all(g_outc == 0xA5)       # nothing was written
+                continue
+            if want["wrote"] == "out":
+                g, w = g_out.view(np.float64), out.to_numpy()
+                assert np.all(g_outc == 0xA5)
+                assert np.array_equal(np.isnan(g), np.isnan(w))
+                ok = ~np.isnan(w)
+                assert np.all(np.abs(g[ok] - w[ok]) <= 4 * np.spacing(np.abs(w[ok])))
+            else:
+                g, w = g_outc.view(np.complex128), outc.to_numpy()
+                assert np.all(g_out == 0xA5)
+                mag = np.abs(w)
+                for part in (np.real, np.imag):
+                    assert np.all(np.abs(part(g) - part(w)) <= 8 * np.spacing(mag))
+
+
+def test_compute_mode_errors_come_before_any_launch():
+    import paper_1810_08723_amd as ocn
+    a, out, outc = _mode_case("sqrt", [1.0, -1.0, 4.0])
+    dv = H.DeviceViews()
+    ta, to, tc = dv.tensor(a), dv.tensor(out), dv.tensor(outc)
+    with pytest.raises(ocn.OcnError) as e:        # complex mode needs a complex second output
+        ocn.unary_mode("sqrt", "complex", ta, to, to)
+    assert e.value.code == ocn.binding.ERR["DTYPE"]
+    with pytest.raises(ocn.OcnError) as e:
+        ocn.unary_mode("sqrt", "complex", ta, to, None)
+    assert e.value.code == ocn.binding.ERR["NULLPTR"]
+    bad = ocn.Tensor(to.base, "double", (4,), (8,), 0, 0, to.keepalive)       # shape mismatch
+    with pytest.raises(ocn.OcnError) as e:
+        ocn.unary_mode("sqrt", "warning", ta, bad, tc)
+    assert e.value.code == ocn.binding.ERR["SHAPE"]
+    dv.torch.cuda.synchronize()
+    assert np.all(dv.download(out) == 0xA5) and np.all(dv.download(outc) == 0xA5)
