@@ -255,8 +255,7 @@ int ocn_mask_offsets(const ocn_tensor *mask, const int64_t *target_strides, void
  * leave one of the written values, which one is not defined.
  * A lane moves one item (an element, or 16 bytes where the rows' fastest dimension is
  * contiguous and 16-byte aligned on both sides); rows of up to 256 items share a workgroup.
- * OCN_ERR_SHAPE if the copy needs 2^32 lanes or more (n times the items of a row, rounded up
- * to a power of two for short rows): split the offsets into several calls.
+ * A copy of 2^32 lanes or more goes out in several launches.
  */
 int ocn_gather(const ocn_tensor *a_inner, const void *offsets, int64_t n, int64_t lo, int64_t hi,
                const ocn_tensor *out, void *stream);
@@ -313,13 +312,17 @@ int ocn_promote(int dtype_a, int dtype_b);
 /* Element size in bytes of a dtype, 0 if invalid. */
 int ocn_dtype_size(int dtype);
 
+/* Upper bound on the workgroups (of 256 lanes) in one launch: 2^24 - 1 by default and at most,
+ * which keeps a launch below 2^32 lanes; 0 restores the default.  Work that needs more runs as
+ * a loop inside the kernel (generic-dtype elementwise kernel, generic reductions, index
+ * binding) or goes out in several launches (gather, scatter).  Lowering the bound moves that
+ * point; results never depend on it.  Process-wide. */
+void ocn_set_max_launch_blocks(int64_t blocks);
+
 /* Static description of a status code. */
 const char *ocn_error_string(int code);
 
-/* The hipError_t (as int) behind the most recent OCN_ERR_LAUNCH on this host thread.  A launch
- * that would need 2^32 lanes or more (e.g. 2^32 elements through the generic-dtype kernel, or
- * 2^26 reduction outputs of a wavefront each) is refused by the runtime and reported this way;
- * nothing has run then. */
+/* The hipError_t (as int) behind the most recent OCN_ERR_LAUNCH on this host thread. */
 int ocn_last_hip_error(void);
 
 /* ---- plan inspection (host only; launches nothing, touches no device memory) -------- */

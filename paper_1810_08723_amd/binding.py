@@ -42,7 +42,7 @@ EXPORTS = ("ocn_unary", "ocn_binary", "ocn_cast_copy", "ocn_reduce", "ocn_reduce
            "ocn_binary_reduce", "ocn_binary_reduce_workspace_bytes", "ocn_plan_binary_reduce",
            "ocn_index_offsets", "ocn_mask_offsets", "ocn_mask_offsets_workspace_bytes", "ocn_gather",
            "ocn_scatter", "ocn_domain_check", "ocn_domain_check_workspace_bytes", "ocn_reduce_scratch",
-           "ocn_unary_mode", "ocn_unary_mode_workspace_bytes")
+           "ocn_unary_mode", "ocn_unary_mode_workspace_bytes", "ocn_set_max_launch_blocks")
 
 
 class OcnTensor(C.Structure):
@@ -84,6 +84,10 @@ def lib() -> C.CDLL:
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is missing: build it with "
                               "`python -m paper_1810_08723_amd.build` (no fallback exists)")
+        # PyTorch owns the device memory and the streams the library is handed, so both must run
+        # on one HIP runtime: torch is loaded first, and the library then binds to the runtime
+        # torch brought (loaded the other way round, the process ends up with two).
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         T, I = C.POINTER(OcnTensor), C.POINTER(OcnPlanInfo)
         L.ocn_unary.argtypes = [C.c_int, T, T, C.c_uint32, C.c_void_p]
@@ -114,6 +118,8 @@ def lib() -> C.CDLL:
         L.ocn_unary_mode_workspace_bytes.argtypes = [C.c_int, C.c_int, T]
         L.ocn_unary_mode_workspace_bytes.restype = C.c_size_t
         L.ocn_unary_mode.argtypes = [C.c_int, C.c_int, T, T, T, C.c_void_p, C.c_size_t, C.POINTER(C.c_int), C.c_void_p]
+        L.ocn_set_max_launch_blocks.argtypes = [C.c_int64]
+        L.ocn_set_max_launch_blocks.restype = None
         L.ocn_index_offsets.argtypes = [T, C.c_int64, C.c_int64, T, C.c_void_p, C.c_void_p]
         L.ocn_mask_offsets_workspace_bytes.argtypes = [T]
         L.ocn_mask_offsets_workspace_bytes.restype = C.c_size_t
@@ -329,6 +335,11 @@ def unary_mode(op: str, mode: str, a: Tensor, out: Tensor, out_complex: Optional
                                 C.byref(outside), _stream(stream)))
     flag = None if outside.value < 0 else bool(outside.value)
     return {"outside": flag, "wrote": "out_complex" if (flag and mode == "complex") else "out"}
+
+
+def set_max_launch_blocks(blocks: int) -> None:
+    """Upper bound on the workgroups of one launch (0: the default, 2^24 - 1)."""
+    lib().ocn_set_max_launch_blocks(blocks)
 
 
 def promote(a: str, b: str) -> str:

@@ -223,6 +223,8 @@ const char *ocn_error_string(int code) {
 
 int ocn_last_hip_error(void) { return g_last_hip_error; }
 
+void ocn_set_max_launch_blocks(int64_t blocks) { set_max_launch_blocks(blocks); }
+
 int ocn_plan_unary(int op, const ocn_tensor *a, const ocn_tensor *out, uint32_t flags, ocn_plan_info *info) {
   if (!info) return OCN_ERR_NULLPTR;
   EwPlan p;

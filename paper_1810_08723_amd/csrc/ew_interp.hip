@@ -2,6 +2,8 @@
 // conversions picked by (wavefront-uniform) runtime switches.  It serves the combinations for
 // which no dtype-specialised kernel is instantiated; one element per lane; 32-bit multiply-shift
 // index arithmetic below 2^31 elements, 64-bit division above.
+#include <algorithm>
+
 #include "ew_launch.hpp"
 
 namespace ocn {
@@ -98,13 +100,16 @@ template <int T> OCN_DEV void interp_body(const InterpArgs &p, const char *pa, c
   }
 }
 
-constexpr int kInterpPerLane = 1;  // elements per lane (more were measured three times slower: the element chains of a lane run one after the other)
+// (one element per lane and trip: more were measured three times slower, the element chains of
+// a lane then run one after the other)
 
+// Workgroup b takes elements b * 256 .. b * 256 + 255, then those gridDim.x * 256 further on, and
+// so on: the grid is capped (a launch cannot have 2^32 lanes), larger tensors loop.
 __global__ __launch_bounds__(kBlock) void ew_interp_kernel(const InterpArgs p) {
-  const int64_t lin0 = (int64_t)blockIdx.x * (kBlock * kInterpPerLane) + threadIdx.x;
-  for (int k = 0; k < kInterpPerLane; ++k) {
-    int64_t lin = lin0 + (int64_t)k * kBlock;
-    if (lin >= p.numel) return;
+  const int64_t lin0 = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  const int64_t step = (int64_t)gridDim.x * kBlock;
+  for (int64_t lin_k = lin0; lin_k < p.numel; lin_k += step) {
+    int64_t lin = lin_k;
     int64_t off_o = 0, off_a = 0, off_b = 0;
     if (p.idx32) {
       uint32_t l = (uint32_t)lin;
@@ -149,8 +154,8 @@ __global__ __launch_bounds__(kBlock) void ew_interp_kernel(const InterpArgs p) {
 
 hipError_t launch_interp(const EwPlan &p, hipStream_t stream) {
   const InterpArgs args = make_interp_args(p);
-  const int64_t per_block = (int64_t)kBlock * kInterpPerLane;
-  hipLaunchKernelGGL(ew_interp_kernel, dim3((unsigned)((p.numel + per_block - 1) / per_block)), dim3(kBlock), 0, stream, args);
+  const int64_t blocks = std::min<int64_t>((p.numel + kBlock - 1) / kBlock, max_launch_blocks());
+  hipLaunchKernelGGL(ew_interp_kernel, dim3((unsigned)blocks), dim3(kBlock), 0, stream, args);
   return hipGetLastError();
 }
 

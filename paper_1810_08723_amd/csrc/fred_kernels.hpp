@@ -370,8 +370,8 @@ template <class G, int OP> __global__ __launch_bounds__(kBlock) void fred_generi
   using A = typename F::A;
   using SAt = typename G::SAt;
   using SBt = typename G::SBt;
-  const int64_t o = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (o >= p.nout) return;
+  // the grid is capped (a launch cannot have 2^32 lanes): more outputs than lanes loop
+  for (int64_t o = (int64_t)blockIdx.x * kBlock + threadIdx.x; o < p.nout; o += (int64_t)gridDim.x * kBlock) {
   int64_t off_a = 0, off_b = 0, off_o = 0, t = o;
 #pragma unroll
   for (int k = 0; k < kMaxDims; ++k) {
@@ -401,6 +401,7 @@ template <class G, int OP> __global__ __launch_bounds__(kBlock) void fred_generi
     acc = F::add(acc, *reinterpret_cast<const SAt *>(p.a + off_a + oa), *reinterpret_cast<const SBt *>(p.b + off_b + ob));
   }
   store_result<A>(p.out + off_o, p.out_dtype, acc);
+  }
 }
 
 #endif  // __HIPCC__

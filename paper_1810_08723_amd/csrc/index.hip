@@ -48,7 +48,11 @@ struct IndexArgs {
 __global__ void fill_u64_kernel(unsigned long long *p, unsigned long long v) { *p = v; }
 
 __global__ __launch_bounds__(kBlock) void index_offsets_kernel(const IndexArgs p) {
-  const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  // the grid is capped (a launch cannot have 2^32 lanes): longer index arrays loop; every lane
+  // of a wavefront makes the same number of trips, so that the vote below stays whole
+  const int64_t step = (int64_t)gridDim.x * kBlock;
+  for (int64_t e0 = (int64_t)blockIdx.x * kBlock; e0 < p.n; e0 += step) {
+  const int64_t e = e0 + threadIdx.x;
   bool bad = false;
   if (e < p.n) {
     int64_t rem = e, oi = 0, oo = 0;
@@ -69,6 +73,7 @@ __global__ __launch_bounds__(kBlock) void index_offsets_kernel(const IndexArgs p
   }
   const unsigned long long votes = __ballot(bad);
   if (votes != 0 && (threadIdx.x & (kWave - 1)) == 0) atomicAdd(p.invalid, (unsigned long long)__popcll(votes));
+  }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -411,11 +416,8 @@ int ocn_index_offsets(const ocn_tensor *index, int64_t dim_size, int64_t stride_
   a.stride = stride_bytes;
   a.invalid = (unsigned long long *)invalid_count;
   // every check comes before the first launch: on error nothing has been enqueued or written
-  const int64_t grid = (a.n + kBlock - 1) / kBlock;
-  if (a.n > 0) {
-    if (!index->base || !offsets->base) return OCN_ERR_NULLPTR;
-    if (grid >= ((int64_t)1 << 31)) return OCN_ERR_SHAPE;
-  }
+  const int64_t grid = std::min<int64_t>((a.n + kBlock - 1) / kBlock, max_launch_blocks());   // the kernel loops beyond that
+  if (a.n > 0 && (!index->base || !offsets->base)) return OCN_ERR_NULLPTR;
   hipStream_t s = (hipStream_t)stream;
   hipLaunchKernelGGL(fill_u64_kernel, dim3(1), dim3(1), 0, s, a.invalid, 0ull);
   if (a.n > 0) hipLaunchKernelGGL(index_offsets_kernel, dim3((unsigned)grid), dim3(kBlock), 0, s, a);
@@ -535,18 +537,33 @@ static int run_gather(bool scatter, const ocn_tensor *inner, const void *offsets
     g.chunks_div = make_fastdiv((uint32_t)chunks);
     grid = n * chunks;
   }
-  // the launch may not exceed 2^32 lanes
-  if (grid >= ((int64_t)1 << 32) / kBlock) return OCN_ERR_SHAPE;
+  // A launch may not exceed 2^32 lanes: longer lists of offsets go out in several launches,
+  // each over a contiguous run of rows (the kernels are independent of one another).
+  const int64_t max_blocks = max_launch_blocks();
+  const int64_t blocks_per_row_num = g.items_log2 >= 0 ? 1 : (int64_t)g.chunks_div.d;      // blocks per row ...
+  const int64_t rows_per_block = g.items_log2 >= 0 ? (kBlock >> g.items_log2) : 1;          // ... or rows per block
+  if (blocks_per_row_num > max_blocks) return OCN_ERR_SHAPE;   // a single row of 2^40 items: not a gather any more
+  const int64_t rows_per_launch = g.items_log2 >= 0 ? max_blocks * rows_per_block : max_blocks / blocks_per_row_num;
+  (void)grid;
   hipStream_t s = (hipStream_t)stream;
-#define OCN_LAUNCH(ES)                                                                                        \
-  if (scatter) hipLaunchKernelGGL((gather_kernel<ES, true>), dim3((unsigned)grid), dim3(kBlock), 0, s, g);   \
-  else hipLaunchKernelGGL((gather_kernel<ES, false>), dim3((unsigned)grid), dim3(kBlock), 0, s, g);
-  switch (es) {
-    case 1: OCN_LAUNCH(1) break;
-    case 2: OCN_LAUNCH(2) break;
-    case 4: OCN_LAUNCH(4) break;
-    case 8: OCN_LAUNCH(8) break;
-    default: OCN_LAUNCH(16) break;
+  const GatherArgs all = g;
+  for (int64_t j0 = 0; j0 < n; j0 += rows_per_launch) {
+    g = all;
+    g.n = std::min<int64_t>(rows_per_launch, n - j0);
+    g.offsets = all.offsets + j0;
+    if (scatter) g.src = all.src + j0 * all.row_stride;
+    else g.dst = all.dst + j0 * all.row_stride;
+    const int64_t launch_grid = g.items_log2 >= 0 ? (g.n + rows_per_block - 1) / rows_per_block : g.n * blocks_per_row_num;
+#define OCN_LAUNCH(ES)                                                                                               \
+  if (scatter) hipLaunchKernelGGL((gather_kernel<ES, true>), dim3((unsigned)launch_grid), dim3(kBlock), 0, s, g);   \
+  else hipLaunchKernelGGL((gather_kernel<ES, false>), dim3((unsigned)launch_grid), dim3(kBlock), 0, s, g);
+    switch (es) {
+      case 1: OCN_LAUNCH(1) break;
+      case 2: OCN_LAUNCH(2) break;
+      case 4: OCN_LAUNCH(4) break;
+      case 8: OCN_LAUNCH(8) break;
+      default: OCN_LAUNCH(16) break;
+    }
   }
 #undef OCN_LAUNCH
   return done(hipGetLastError());

@@ -2,6 +2,7 @@
 #include "planner.hpp"
 
 #include <algorithm>
+#include <atomic>
 #include <cstdlib>
 #include <cstring>
 
@@ -12,6 +13,15 @@ namespace ocn {
 // ---------------------------------------------------------------------------------------
 // small helpers
 // ---------------------------------------------------------------------------------------
+
+namespace {
+std::atomic<int64_t> g_max_launch_blocks{((int64_t)1 << 24) - 1};
+}
+int64_t max_launch_blocks() { return g_max_launch_blocks.load(std::memory_order_relaxed); }
+void set_max_launch_blocks(int64_t blocks) {
+  const int64_t hard = ((int64_t)1 << 24) - 1;
+  g_max_launch_blocks.store(blocks <= 0 || blocks > hard ? hard : blocks, std::memory_order_relaxed);
+}
 
 FastDiv make_fastdiv(uint32_t d) {
   // q = (mulhi(n, m) + n) >> s with s = ceil(log2 d), m = floor(2^32 (2^s - d) / d) + 1;
@@ -425,6 +435,12 @@ int plan_elementwise(int nin, int op, const ocn_tensor *a, const ocn_tensor *b,
     const int64_t vpr = (p.size[inner] + V - 1) / V;
     const int64_t nrows = numel / p.size[inner];
     if (n > 1 && (vpr * nrows >= ((int64_t)1 << 31))) rows = false;
+    // more workgroups than one launch may have: the generic kernel, which loops, takes it
+    if ((vpr * nrows + (int64_t)kBlock * rows_stream_unroll(V, es_min) - 1) /
+            ((int64_t)kBlock * rows_stream_unroll(V, es_min)) > max_launch_blocks()) {
+      rows = false;
+      p.specialised = false;
+    }
     if (rows) {
       p.kernel = OCN_KERNEL_EW_ROWS;
       p.vec = V;
@@ -457,7 +473,7 @@ int plan_elementwise(int nin, int op, const ocn_tensor *a, const ocn_tensor *b,
     // generic-dtype kernel: one element per lane, conversions through runtime switches
     p.kernel = OCN_KERNEL_EW_GENERIC;
     p.vec = 1;
-    p.grid = (numel + kBlock - 1) / kBlock;
+    p.grid = std::min<int64_t>((numel + kBlock - 1) / kBlock, max_launch_blocks());   // the kernel loops beyond that
     *plan = p;
     return OCN_OK;
   }
@@ -776,7 +792,17 @@ void choose_reduce_launch(RedPlan &p) {
     p.vec = 1;
     p.split = 1;
     p.chunk = p.nredtot;
-    p.grid = (p.nout + kBlock - 1) / kBlock;
+    p.grid = std::min<int64_t>((p.nout + kBlock - 1) / kBlock, max_launch_blocks());   // the kernel loops beyond that
+  }
+  if (p.grid > max_launch_blocks()) {
+    // more workgroups than one launch may have: the generic kernel, which loops over its outputs
+    p.kernel = OCN_KERNEL_RED_GENERIC;
+    p.vec = 1;
+    p.split = 1;
+    p.short_rows = p.lean = false;
+    p.block = kBlock;
+    p.chunk = p.nredtot;
+    p.grid = std::min<int64_t>((p.nout + kBlock - 1) / kBlock, max_launch_blocks());
   }
   p.passes = p.split > 1 ? 2 : 1;
   p.workspace_bytes = p.split > 1 ? (size_t)(p.nout * p.split * acc_es) : 0;
@@ -982,7 +1008,7 @@ void choose_fused_launch(RedPlan &p) {
     p.kernel = OCN_KERNEL_RED_GENERIC;
     p.vec = 1;
     p.chunk = p.nredtot;
-    p.grid = (p.nout + kBlock - 1) / kBlock;
+    p.grid = std::min<int64_t>((p.nout + kBlock - 1) / kBlock, max_launch_blocks());
   }
   p.passes = p.split > 1 ? 2 : 1;
   p.workspace_bytes = p.split > 1 ? (size_t)(p.nout * p.split * acc_es) : 0;
@@ -1194,7 +1220,7 @@ void plan_second_pass(const RedPlan &first, char *workspace, RedPlan *second) {
     if (first.split >= 64) q.block = 16 * kWave;   // many partials per column: more wavefronts share them
   } else {
     q.kernel = OCN_KERNEL_RED_GENERIC;
-    q.grid = (q.nout + kBlock - 1) / kBlock;
+    q.grid = std::min<int64_t>((q.nout + kBlock - 1) / kBlock, max_launch_blocks());
   }
   *second = q;
 }

@@ -140,6 +140,12 @@ int promote(int a, int b);
 int reduce_acc_dtype(int op, int in_dtype);
 bool reduce_supported(int op, int in_dtype);
 
+// Most workgroups one launch may have (2^24 - 1 of 256 lanes keeps a launch below 2^32 lanes;
+// ocn_set_max_launch_blocks lowers it).  Kernels whose grid would be larger loop over their
+// work with the capped grid, or their work goes out in several launches.
+int64_t max_launch_blocks();
+void set_max_launch_blocks(int64_t blocks);
+
 // remembers a failed HIP call for ocn_last_hip_error (per host thread)
 void record_hip_error(int code);
 

@@ -878,8 +878,8 @@ template <int S, int OP> __global__ __launch_bounds__(kBlock) void red_generic_k
   using R = Reducer<S, OP>;
   using A = typename R::A;
   using St = storage_t<S>;
-  const int64_t o = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (o >= p.nout) return;
+  // the grid is capped (a launch cannot have 2^32 lanes): more outputs than lanes loop
+  for (int64_t o = (int64_t)blockIdx.x * kBlock + threadIdx.x; o < p.nout; o += (int64_t)gridDim.x * kBlock) {
   // 64-bit decomposition over the kept dims (fastest first)
   int64_t off_a = 0, off_o = 0, t = o;
 #pragma unroll
@@ -908,6 +908,7 @@ template <int S, int OP> __global__ __launch_bounds__(kBlock) void red_generic_k
     acc = R::combine(acc, R::lift(from_storage<S>(load_one<S>(p.swap_a != 0, p.a + off_a + off))));
   }
   store_result<A>(p.out + off_o, p.out_dtype, acc, p.swap_o != 0);
+  }
 }
 
 #endif  // __HIPCC__
