@@ -4,11 +4,14 @@ One "step" runs every benchmark operation once, through the C ABI, on synthetic 
 already resident in HBM: the five configurations (C1, C1x8, C2, C3, C4a-d, C5, C5m, and C5b,
 C5bm: the second reading of configuration 5's layout).  The operations touch about 3.5 GB of
 distinct memory per step, so each one starts with a cold 256 MB Infinity Cache.  The timed
-region runs the step K times with HIP events around the dominant operation only (`roofline`);
-`per_op` comes from an untimed pass of the same step with events around every call (`avg_us`,
-cold), plus `warm_us` (same buffers back to back), `host_us` (host time to plan and enqueue one
-call) and `plan_us` (the planner alone, through the binding).  `next_ops` times the operations
-built beyond the five configurations.  Prints ONE JSON line.
+region runs the step K times with HIP events around the dominant operation only (`roofline`).
+`per_op`: `avg_us` is the cold time per launch (the call on four sets of buffers in rotation,
+one pair of events around the whole run - what a kernel trace shows too), `step_event_us` the
+one-call event bracket in an untimed pass of the step (2-6 us more: event records and the
+gaps they cause), `warm_us` the same buffers back to back, `host_us` the host time to plan and
+enqueue one call, `plan_us` the planner alone through the binding.  `roofline_worst` is the
+operation furthest below its own bar.  `next_ops` times what is built beyond the five
+configurations, each call with cold caches.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--profile]
 
@@ -75,7 +78,8 @@ def _device_cases(cases):
         key = id(view.storage)
         if key not in uploaded:
             uploaded[key] = torch.from_numpy(view.storage).to("cuda:0")
-        return ocn.Tensor.on_storage(uploaded[key], view.dtype, view.sizes, view.strides, view.offset)
+        return ocn.Tensor.on_storage(uploaded[key], view.dtype, view.sizes, view.strides, view.offset,
+                                     view.byteswapped)
 
     runs = []
     for c in cases:
@@ -102,7 +106,7 @@ def _plan_kernel(c):
     import paper_1810_08723_amd as ocn
 
     def fake(view, base):
-        return ocn.Tensor(base, view.dtype, view.sizes, view.strides, view.offset, 0)
+        return ocn.Tensor(base, view.dtype, view.sizes, view.strides, view.offset, 0, None, view.byteswapped)
     ins = [fake(v, 0x100000000 * (i + 1)) for i, v in enumerate(c.inputs)]
     out = fake(c.out, 0x700000000)
     if c.kind == "binary":
@@ -197,6 +201,8 @@ def main() -> int:
         want = args.only.split(",")
         if any(w.startswith("F") for w in want):
             cases = cases + configs.fused_cases()
+        if any(w[0] in "LS" for w in want):
+            cases = cases + configs.layout_cases()
         cases = [c for c in cases if c.name in want]
         if "copy" in want:
             from workloads.views import View
@@ -246,6 +252,32 @@ def main() -> int:
     op_ms = [sorted(ev[s][i][0].elapsed_time(ev[s][i][1]) for s in range(args.steps)) for i in range(len(runs))]
     dom_i = max(range(len(runs)), key=lambda i: sum(op_ms[i]))
 
+    # Cold, steady-state time per launch of every operation: the same call on four distinct sets
+    # of buffers used in rotation (well over 256 MB between two uses of a buffer, so nothing is
+    # found in the Infinity Cache again), one pair of events around the whole run of launches.
+    # This is what the kernel durations of a rocprofv3 trace of the step show as well; the
+    # one-call brackets above read 2-6 us more (event records and the launch gaps they cause).
+    NB = 4
+    sets = [runs] + [_device_cases(cases)[0] for _ in range(NB - 1)]
+    torch.cuda.synchronize()
+    cold_us = []
+    for i in range(len(runs)):
+        fns = [sets[k][i][1] for k in range(NB)]
+        for f in fns:
+            f()
+        torch.cuda.synchronize()
+        rounds = 6
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(rounds):
+            for f in fns:
+                f()
+        e1.record()
+        torch.cuda.synchronize()
+        cold_us.append(e0.elapsed_time(e1) * 1e3 / (rounds * NB))
+    del sets
+    torch.cuda.empty_cache()
+
     # timed region: exactly `steps` passes of the whole step, events around the dominant call only
     dev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     torch.cuda.synchronize()
@@ -269,9 +301,10 @@ def main() -> int:
         avg = sum(ms) / len(ms)
         plan = _plan_kernel(c)
         per_op.append({"case": c.name, "op": c.op, "kernel": plan["kernel"], "passes": plan["passes"],
-                       "logical_bytes": c.logical_bytes, "avg_us": avg * 1e3, "min_us": ms[0] * 1e3,
-                       "gbs": c.logical_bytes / (avg * 1e-3) / 1e9,
-                       "frac_of_peak": c.logical_bytes / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS})
+                       "logical_bytes": c.logical_bytes, "avg_us": cold_us[i],
+                       "step_event_us": avg * 1e3, "step_event_min_us": ms[0] * 1e3,
+                       "gbs": c.logical_bytes / (cold_us[i] * 1e-6) / 1e9,
+                       "frac_of_peak": c.logical_bytes / (cold_us[i] * 1e-6) / 1e9 / HBM_PEAK_GBS})
     # outside the timed region: steady-state (cache-warm) device time, and host-side cost
     for i, (c, fn, _) in enumerate(runs):
         reps = 12
@@ -296,12 +329,18 @@ def main() -> int:
     if not args.only:
         del runs, _keep
         torch.cuda.empty_cache()
-        fcases = configs.fused_cases() + configs.elementary_cases()
+        fcases = configs.fused_cases() + configs.elementary_cases() + configs.layout_cases()
         fruns, _fkeep = _device_cases(fcases)
+
+        # every timed call starts with cold caches: 1 GiB of other memory is read in between
+        # (by torch, outside the event bracket), which pushes the operands out of the
+        # 256 MB Infinity Cache without leaving dirty lines behind
+        filler = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
 
         def timed(f, reps=12):
             evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
             for a, b in evs:
+                filler.sum()
                 a.record(); f(); b.record()
             torch.cuda.synchronize()
             t = sorted(a.elapsed_time(b) for a, b in evs[2:])
@@ -311,7 +350,7 @@ def main() -> int:
             if c.kind != "binary_reduce":
                 us = timed(fn)
                 plan = _plan_kernel(c)
-                next_ops.append({"case": c.name, "op": c.op, "kernel": plan["kernel"], "fused": False,
+                next_ops.append({"case": c.name, "op": c.op, "note": c.note, "kernel": plan["kernel"], "fused": False,
                                  "passes": plan["passes"], "logical_bytes": c.logical_bytes, "us": us,
                                  "gbs": c.logical_bytes / (us * 1e-6) / 1e9,
                                  "frac_of_peak": c.logical_bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS,
@@ -369,7 +408,7 @@ def main() -> int:
                              "frac_of_peak": lb / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, "two_calls_us": None})
     device_ms = sum(p["avg_us"] for p in per_op) / 1e3
     dom = dict(per_op[dom_i])
-    dom["avg_us"] = sum(dom_ms) / len(dom_ms) * 1e3          # measured inside the timed region
+    dom["avg_us"] = sum(dom_ms) / len(dom_ms) * 1e3          # one-call brackets inside the timed region
     dom["gbs"] = dom["logical_bytes"] / (dom["avg_us"] * 1e-6) / 1e9
     traffic = _measured_traffic()
     for p in per_op:

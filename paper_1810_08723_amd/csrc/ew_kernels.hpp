@@ -121,6 +121,9 @@ struct InterpArgs {
   int64_t numel;
   int32_t idx32;              // fewer than 2^31 elements: 32-bit multiply-shift index arithmetic
   int32_t swap;               // operands stored in the other byte order: bit 0 a, bit 1 b, bit 2 out
+  int32_t vec;                // 4: a lane takes four consecutive elements of the innermost dim (sizes, strides and
+                              // numel then count groups of four); 1: one element
+  int32_t inner_a, inner_b;   // vec == 4: the input is contiguous along the innermost dim (else broadcast there)
   FastDiv div[kMaxDims];
 };
 

@@ -224,9 +224,35 @@ InterpArgs make_interp_args(const EwPlan &p) {
   }
   a.numel = p.numel;
   a.swap = p.swap;
-  a.idx32 = p.numel < ((int64_t)1 << 31);
+  a.vec = 1;
+  // Four elements per lane where the innermost dim allows it: a multiple of four long,
+  // contiguous in the output, contiguous or broadcast in the inputs, and every group of four
+  // aligned as one access (at most 16 bytes).  The elementary functions stay at one.
+  const bool elementary = p.nin == 1 && ((p.op >= U_SIN && p.op <= U_LOG) || (p.op >= U_ASIN && p.op <= U_TANH));
+  if (p.ndim >= 1 && !elementary) {
+    const int last = p.ndim - 1;
+    auto fits = [&](const Operand &x, bool may_broadcast) {
+      const int64_t es = dt_size(x.dtype), al = std::min<int64_t>(16, 4 * es);
+      if (x.stride[last] == 0) return may_broadcast;
+      if (x.stride[last] != es || (intptr_t)x.ptr % al) return false;
+      for (int d = 0; d < last; ++d)
+        if (x.stride[d] % al) return false;
+      return true;
+    };
+    if (p.size[last] % 4 == 0 && fits(p.out, false) && fits(p.a, true) && (p.nin == 1 || fits(p.b, true))) {
+      a.vec = 4;
+      a.inner_a = p.a.stride[last] != 0;
+      a.inner_b = p.nin == 2 && p.b.stride[last] != 0;
+      a.size[last] /= 4;
+      a.so[last] *= 4;
+      a.sa[last] *= 4;
+      a.sb[last] *= 4;
+      a.numel /= 4;
+    }
+  }
+  a.idx32 = a.numel < ((int64_t)1 << 31);
   if (a.idx32)
-    for (int d = 0; d < p.ndim; ++d) a.div[d] = make_fastdiv((uint32_t)p.size[d]);
+    for (int d = 0; d < p.ndim; ++d) a.div[d] = make_fastdiv((uint32_t)a.size[d]);
   return a;
 }
 

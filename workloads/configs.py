@@ -203,6 +203,47 @@ def elementary_cases(n_flat: int = 1 << 26, n_cplx: int = 1 << 24) -> List[Case]
     ]
 
 
+def layout_cases(scale: int = 1) -> List[Case]:
+    """Shapes and types outside the five configurations, measured beside them: a transpose with
+    extents that are not powers of two, a channel-first to channel-last copy with three channels
+    (an output whose fastest axis is 12 bytes long), an operation on a combination of types that
+    has no kernel of its own, the full sum of an every-other-element view, and the contiguous
+    cast and the row sums of configurations 2 and 4 on operands stored in the other byte order.
+    `scale` > 1 shrinks every case for tests."""
+    def sz(n):
+        return max(n // scale, 8)
+    n0, n1 = sz(6000), sz(5000)
+    a = View.from_numpy(_uniform_pm1(_seed(7, 0), (n0, n1)))
+    b = View.from_numpy(_uniform_pm1(_seed(7, 1), (n1, n0))).permute(1, 0)
+    nb, hw = sz(64), sz(512)
+    img = View.from_numpy(_uniform_pm1(_seed(7, 2), (nb, 3, hw, hw)))
+    ne = sz(1 << 25)
+    i16 = View.from_numpy(rng_for(_seed(7, 3)).integers(-30000, 30000, size=ne).astype(np.int16))
+    f32 = View.from_numpy(_uniform_pm1(_seed(7, 4), (ne,)))
+    ns = sz(1 << 27)
+    strided = View.from_numpy(_normal(_seed(7, 5), (ns,), np.float32)).slice(0, 0, ns, 2)
+    rows2, cols2 = sz(4096), sz(4096)
+    x64 = rng_for(_seed(7, 6)).standard_normal((rows2, cols2))
+    x64 *= 2e4
+    swapped64 = View.from_numpy(x64).in_other_byte_order().flip(0)
+    r4, c4 = sz(16384), sz(4096)
+    swapped32 = View.from_numpy(_normal(_seed(7, 7), (r4, c4), np.float32)).in_other_byte_order()
+    return [
+        Case("L1", "binary", "add", [a, b], View.empty("float", (n0, n1)), logical_bytes=12 * n0 * n1,
+             note="transpose, extents not powers of two (general tiled form)"),
+        Case("L2", "unary", "ident", [img.permute(0, 2, 3, 1)], View.empty("float", (nb, hw, hw, 3)),
+             logical_bytes=8 * nb * 3 * hw * hw, note="channel-first to channel-last, 3 channels"),
+        Case("L3", "binary", "add", [i16, f32], View.empty("double", (ne,)), logical_bytes=14 * ne,
+             note="int16 + float -> double: no kernel of its own (generic-dtype kernel)"),
+        Case("L4", "reduce", "sum", [strided], View.empty("float", ()), axes=(0,), logical_bytes=4 * (ns // 2) + 4,
+             compare="sum", rel_bound=1e-6, note="full sum of an every-other-element view"),
+        Case("S2", "unary", "ident", [swapped64], View.empty("int16", (rows2, cols2)), logical_bytes=10 * rows2 * cols2,
+             note="configuration 2 with the input in the other byte order"),
+        Case("S4", "reduce", "sum", [swapped32], View.empty("float", (r4,)), axes=(1,), logical_bytes=4 * r4 * c4 + 4 * r4,
+             compare="sum", rel_bound=1e-6, note="configuration 4 (sum over axis 1) with the input in the other byte order"),
+    ]
+
+
 def all_cases_full() -> List[Case]:
     """Every benchmark case at full size (about 3.2 GB of host memory)."""
     return [config1(1), config1(8), config2(), config3(), *config4(), *config5(),
