@@ -335,7 +335,8 @@ typedef enum {
   OCN_KERNEL_EW_GENERIC,   /* one element per lane, arbitrary strides                       */
   OCN_KERNEL_RED_ROWS,     /* reduced axis is the input's fastest                           */
   OCN_KERNEL_RED_COLS,     /* a kept axis is the input's fastest                            */
-  OCN_KERNEL_RED_GENERIC   /* one output per lane, arbitrary strides                        */
+  OCN_KERNEL_RED_GENERIC,  /* one output per lane, arbitrary strides                        */
+  OCN_KERNEL_EW_INTERLEAVE /* copy from planes into an output whose fastest axis is 2..8 long */
 } ocn_kernel_kind;
 
 /* What the host planner decided for a call: the canonical dimension list after dropping

@@ -34,7 +34,7 @@ ERR = {"NULLPTR": -1, "DTYPE": -2, "NDIM": -3, "SHAPE": -4, "DEVICE": -5, "ALIGN
        "OVERLAP_OUT": -7, "ALIAS": -8, "WORKSPACE": -9, "EMPTY": -10, "LAUNCH": -11, "OP": -12,
        "BYTEORDER": -13, "DOMAIN": -14}
 
-KERNELS = ("none", "ew_rows", "ew_tiled", "ew_generic", "red_rows", "red_cols", "red_generic")
+KERNELS = ("none", "ew_rows", "ew_tiled", "ew_generic", "red_rows", "red_cols", "red_generic", "ew_interleave")
 
 EXPORTS = ("ocn_unary", "ocn_binary", "ocn_cast_copy", "ocn_reduce", "ocn_reduce_workspace_bytes",
            "ocn_promote", "ocn_dtype_size", "ocn_error_string", "ocn_last_hip_error",

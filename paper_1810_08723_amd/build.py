@@ -23,7 +23,7 @@ COMMON = ["--offload-arch=gfx950", *os.environ.get("OCN_EXTRA_FLAGS", "").split(
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
           "-Wno-unused-command-line-argument"]
 
-SOURCES = (["api.cpp", "planner.cpp", "ew_launch.cpp", "red_launch.cpp", "ew_interp.hip", "index.hip"]
+SOURCES = (["api.cpp", "planner.cpp", "ew_launch.cpp", "red_launch.cpp", "ew_interp.hip", "ew_interleave.hip", "index.hip"]
            + [f"ew_slice_{i}.hip" for i in range(8)] + [f"red_slice_{i}.hip" for i in range(4)]
            + [f"fred_slice_{i}.hip" for i in range(4)])
 

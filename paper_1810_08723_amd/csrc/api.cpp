@@ -53,6 +53,7 @@ static int finish(hipError_t e) {
 static int run_elementwise(const EwPlan &p, hipStream_t stream) {
   if (p.kernel == OCN_KERNEL_NONE) return OCN_OK;
   ensure_registered();
+  if (p.kernel == OCN_KERNEL_EW_INTERLEAVE) return finish(launch_interleave(p, stream));
   if (!p.specialised) return finish(launch_interp(p, stream));
   EwLauncher f = p.nin == 2 ? g_binary_launchers[p.op][p.a.dtype][p.b.dtype][p.out.dtype]
                             : g_unary_launchers[p.op][p.a.dtype][p.out.dtype];

@@ -18,6 +18,7 @@ TiledArgs make_tiled_args(const EwPlan &p, int es_a);
 FastTiledArgs make_fast_tiled_args(const EwPlan &p, int es_a);
 InterpArgs make_interp_args(const EwPlan &p);
 hipError_t launch_interp(const EwPlan &p, hipStream_t stream);
+hipError_t launch_interleave(const EwPlan &p, hipStream_t stream);
 
 #if defined(__HIPCC__)
 template <int OP, int SA, int SB, int SO, int NIN>

@@ -469,6 +469,28 @@ int plan_elementwise(int nin, int op, const ocn_tensor *a, const ocn_tensor *b,
     }
   }
 
+  // A plain copy from planes into an output whose fastest axis is 2..8 elements long, the
+  // next output axis being the input's fastest (channel-first to channel-last): lanes take
+  // 16-byte vectors along that long axis and deal them out in registers.
+  if (nin == 1 && op == U_IDENT && sa == so && es_o <= 8 && n >= 2 && (p.swap == 0 || p.swap == 5)) {
+    const int64_t c = p.size[n - 1], mlen = p.size[n - 2], vv = 16 / es_o;
+    bool ok = c >= 2 && c <= 8 && p.out.stride[n - 1] == es_o && p.out.stride[n - 2] == c * es_o &&
+              p.a.stride[n - 2] == es_o && p.a.stride[n - 1] % 16 == 0 && mlen % vv == 0 &&
+              (intptr_t)p.out.ptr % 16 == 0 && (intptr_t)p.a.ptr % 16 == 0;
+    for (int d = 0; d < n - 2 && ok; ++d) ok = p.out.stride[d] % 16 == 0 && p.a.stride[d] % 16 == 0;
+    const int64_t nvec = numel / (c * vv);
+    const int64_t grid = (nvec + kBlock - 1) / kBlock;
+    if (ok && nvec < ((int64_t)1 << 31) && grid <= max_launch_blocks()) {
+      p.kernel = OCN_KERNEL_EW_INTERLEAVE;
+      p.vec = (int)vv;
+      p.grid = grid;
+      p.nt_a = numel * es_o >= kStreamBytes;
+      p.lds_bytes = (int64_t)kBlock * c * 16;
+      *plan = p;
+      return OCN_OK;
+    }
+  }
+
   if (!p.specialised) {
     // generic-dtype kernel: one element per lane, conversions through runtime switches
     p.kernel = OCN_KERNEL_EW_GENERIC;
