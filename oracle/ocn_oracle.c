@@ -719,7 +719,17 @@ int orc_binary(int op, const orc_tensor *a, const orc_tensor *b, const orc_tenso
   int T;
   if (is_logical_binary(op)) T = ORC_BOOL;
   else if (is_compare_binary(op)) T = orc_promote(a->dtype, b->dtype);
-  else T = out->dtype;
+  else {
+    /* Section 3.2.1: the operation's type comes from the operands (the smallest type that
+       holds both).  A destination that is one of the operands' types (the A += B case) or
+       that holds the promoted type takes the operands into its own type; any other
+       destination receives the promoted-type result, converted once on store. */
+    int P = orc_promote(a->dtype, b->dtype);
+    if (out->dtype == a->dtype || out->dtype == b->dtype || orc_promote(P, out->dtype) == out->dtype)
+      T = out->dtype;
+    else
+      T = P;
+  }
   if ((flags & ORC_STRICT_TYPES) && !is_compare_binary(op) && !is_logical_binary(op) &&
       a->dtype != out->dtype)
     return ORC_ERR_DTYPE;

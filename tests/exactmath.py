@@ -311,7 +311,10 @@ def compute_type(op: str, da: str, db: str, dout: str) -> str:
         return "bool"
     if op in COMPARE:
         return promote(da, db)
-    return dout
+    P = promote(da, db)
+    if dout in (da, db) or promote(P, dout) == dout:
+        return dout
+    return P
 
 
 def binary_supported(op: str, T: str) -> bool:

@@ -38,7 +38,15 @@ def _cases_binary():
         cases += [(op, "int32", "float", "float"), (op, "double", "int8", "int16"),
                   (op, "half", "uint8", "half"), (op, "int64", "double", "float"),
                   (op, "cfloat", "half", "chalf"), (op, "bool", "int16", "double")]
-    cases = [c for c in cases if X.binary_supported(c[0], c[3])]
+    # destinations that are neither an operand's type nor able to hold the promoted type: the
+    # operation runs in the promoted type and its result is converted once
+    for op in ("add", "sub", "mul", "div", "min"):
+        cases += [(op, "int32", "int32", "int8"), (op, "double", "double", "float"),
+                  (op, "int16", "uint8", "int8"), (op, "float", "int32", "half"),
+                  (op, "uint64", "int8", "uint16"), (op, "cdouble", "float", "cfloat")]
+    for op in X.BITWISE:
+        cases += [(op, "int32", "uint8", "int8"), (op, "uint16", "bool", "uint8")]
+    cases = [c for c in cases if X.binary_supported(c[0], X.compute_type(*c))]
     for op in X.COMPARE + X.LOGICAL:
         for da, db in [("int8", "uint8"), ("int64", "uint64"), ("int64", "float"), ("half", "int16"),
                        ("float", "double"), ("bool", "half"), ("cfloat", "cdouble"), ("chalf", "int32"),
@@ -205,6 +213,37 @@ def test_integer_division_rules():
         out = View.empty(dt, (4,))
         O.binary("div", View.from_numpy(a), View.from_numpy(b), out)
         assert [int(t) for t in out.to_numpy()] == [lo, -(lo + 1), -11, lo // 2]
+
+
+def test_operand_types_set_the_compute_type_when_the_destination_is_narrower():
+    """Section 3.2.1: the operation's type is the smallest one holding both operands' types.  A
+    destination of another, narrower type receives that result converted once; it does not
+    narrow the operands first.  Values worked by hand."""
+    i32 = lambda *v: View.from_numpy(np.array(v, dtype=np.int32))
+    out = View.empty("int8", (3,))
+    O.binary("add", i32(1000, -1000, 100), i32(-900, 900, 100), out)
+    assert list(out.to_numpy()) == [100, -100, 127]          # sat(1000) + sat(-900) would be -1
+    O.binary("bxor", i32(0x1FF, 0x7FFFFFFF, 3), i32(0x180, 0x7FFFFF00, 1), out)
+    assert list(out.to_numpy()) == [0x7F, 127, 2]            # 127 ^ 127 would be 0
+    O.binary("mul", i32(100, 16, -16), i32(100, 8, 8), out)
+    assert list(out.to_numpy()) == [127, 127, -128]
+    # one rounding: (1 + 2^-24 + 2^-30) + (-2^-30) = 1 + 2^-24 exactly, a tie that rounds to 1;
+    # narrowing the first operand to single precision before adding would give 1 + 2^-23
+    a = View.from_numpy(np.array([1 + 2.0 ** -24 + 2.0 ** -30], dtype=np.float64))
+    b = View.from_numpy(np.array([-(2.0 ** -30)], dtype=np.float64))
+    o = View.empty("float", (1,))
+    O.binary("add", a, b, o)
+    assert o.to_numpy()[0] == np.float32(1.0)
+    assert np.float32(a.to_numpy()[0]) + np.float32(b.to_numpy()[0]) == np.float32(1 + 2.0 ** -23)
+    # the destination's type still rules when it is an operand's type (A += B) ...
+    acc = View.from_numpy(np.array([100, -100], dtype=np.int8))
+    O.binary("add", acc, i32(1000, -1000), acc)
+    assert list(acc.to_numpy()) == [-29, 28]                 # 100 + sat(1000) = 227 wraps; -100 - 128 wraps
+    # ... and when it holds the promoted type (int8 and uint8 promote to int16, held by int64)
+    wide = View.empty("int64", (1,))
+    O.binary("mul", View.from_numpy(np.array([-128], dtype=np.int8)),
+             View.from_numpy(np.array([255], dtype=np.uint8)), wide)
+    assert int(wide.to_numpy()[0]) == -32640
 
 
 def test_config3_both_compute_type_readings_agree():
