@@ -144,9 +144,12 @@ int ocn_unary(int op, const ocn_tensor *a, const ocn_tensor *out, uint32_t flags
  * Shapes: out fixes the result shape.  Inputs are right-aligned against it; an input
  * dimension must equal out's or be 1, and a size-1 dimension is read at index 0 whatever
  * its stride says (section 4: broadcasting along dimensions).
- * Compute type T: out's dtype for arithmetic and bitwise operations (as in "A += B", where
- * B is coerced to A); ocn_promote(a.dtype, b.dtype) for comparisons and OCN_B_ABSGT; bool
- * for the logical operations.  Half-precision types are evaluated in single precision and
+ * Compute type T, with P = ocn_promote(a.dtype, b.dtype): for arithmetic and bitwise
+ * operations out's dtype when that is a.dtype or b.dtype (as in "A += B", where B is coerced
+ * to A) or holds P (ocn_promote(P, out.dtype) == out.dtype), otherwise P, and the result is
+ * converted to out's dtype once, on store (a narrower destination does not narrow the
+ * operands first); P for comparisons and OCN_B_ABSGT; bool for the logical operations.
+ * Half-precision types are evaluated in single precision and
  * rounded once when stored.  With OCN_STRICT_TYPES, a.dtype != b.dtype (and, for arithmetic
  * and bitwise operations, a.dtype != out.dtype) is OCN_ERR_DTYPE.
  * Either input may be the identical view as out.

@@ -79,9 +79,14 @@ OCN_DEV void binary_one(const InterpArgs &p, const Vals<reg_t<T>, N> &a, const V
     Vals<reg_t<binary_result_dtype(OP, T)>, N> r;
 #pragma unroll
     for (int i = 0; i < N; ++i) r.v[i] = apply_binary<OP, T>(a.v[i], b.v[i]);
-    // arithmetic and bitwise results already have the output type (T is out's dtype)
-    if constexpr (is_arith(OP) || is_bitwise(OP)) store_same<T, N>(po, r, (p.swap & 4) != 0);
-    else store_as<bool, N>(po, p.dt_o, r, (p.swap & 4) != 0);
+    // arithmetic and bitwise results have type T: the output's own, or the operands' promoted
+    // type, then converted on store; predicates give a bool
+    if constexpr (is_arith(OP) || is_bitwise(OP)) {
+      if (p.dt_o == T) store_same<T, N>(po, r, (p.swap & 4) != 0);
+      else store_as<reg_t<T>, N>(po, p.dt_o, r, (p.swap & 4) != 0);
+    } else {
+      store_as<bool, N>(po, p.dt_o, r, (p.swap & 4) != 0);
+    }
   }
 }
 

@@ -331,7 +331,8 @@ int plan_elementwise(int nin, int op, const ocn_tensor *a, const ocn_tensor *b,
   if (nin == 2) {
     if ((flags & OCN_STRICT_TYPES) && sa != sb) return OCN_ERR_DTYPE;
     if ((flags & OCN_STRICT_TYPES) && !is_compare(op) && !is_logical(op) && sa != so) return OCN_ERR_DTYPE;
-    p.T = binary_compute_dtype(op, sa, sb, so, promote(sa, sb));
+    const int promoted = promote(sa, sb);
+    p.T = binary_compute_dtype(op, sa, sb, so, promoted, promote(promoted, so));
     if (!binary_supported(op, p.T)) return OCN_ERR_DTYPE;
     p.specialised = binary_specialised(op, sa, sb, so);
   } else {
@@ -1072,7 +1073,8 @@ int plan_binary_reduce(int ew_op, int red_op, const ocn_tensor *a, const ocn_ten
     reduced[axes[i]] = true;
   }
   if (out->ndim != nd - naxes) return OCN_ERR_SHAPE;
-  const int T = binary_compute_dtype(ew_op, a->dtype, b->dtype, mid_dtype, promote(a->dtype, b->dtype));
+  const int promoted = promote(a->dtype, b->dtype);
+  const int T = binary_compute_dtype(ew_op, a->dtype, b->dtype, mid_dtype, promoted, promote(promoted, mid_dtype));
   if (!binary_supported(ew_op, T) || !reduce_supported(red_op, mid_dtype)) return OCN_ERR_DTYPE;
 
   RDim kd[kMaxDims], rd[kMaxDims];

@@ -10,8 +10,14 @@ namespace ocn {
 
 
 // compute type of a binary operation (section 3.2.1 of the paper and include/ocn.h)
-OCN_HD constexpr int binary_compute_dtype(int op, int sa, int sb, int so, int promoted) {
-  return is_logical(op) ? (int)DT_BOOL : is_compare(op) ? promoted : so;
+// Logical operations run in bool, comparisons in the operands' promoted type.  Arithmetic and
+// bitwise operations run in the destination's type when that is one of the operands' types
+// (the A += B case) or holds the promoted type (`widened` = promote(promoted, so)); any other
+// destination receives the promoted-type result, converted once on store.
+OCN_HD constexpr int binary_compute_dtype(int op, int sa, int sb, int so, int promoted, int widened) {
+  if (is_logical(op)) return (int)DT_BOOL;
+  if (is_compare(op)) return promoted;
+  return (so == sa || so == sb || widened == so) ? so : promoted;
 }
 
 // Mixed input types whose +, -, *, / get kernels that convert on load (section 3.2.1: operands

@@ -72,7 +72,14 @@ MIXED = [("add", "int32", "float", "float"), ("sub", "double", "int8", "int16"),
          ("add", "uint64", "int64", "double"), ("mul", "float", "cdouble", "cfloat"), ("bxor", "uint8", "int64", "int32"),
          ("lt", "int8", "uint8", "bool"), ("ge", "int64", "float", "bool"), ("eq", "cfloat", "cdouble", "bool"),
          ("absgt", "chalf", "int32", "bool"), ("ne", "uint64", "int64", "uint8"), ("land", "float", "int8", "bool"),
-         ("lor", "cdouble", "bool", "float"), ("le", "half", "int16", "int64"), ("absgt", "int8", "uint64", "bool")]
+         ("lor", "cdouble", "bool", "float"), ("le", "half", "int16", "int64"), ("absgt", "int8", "uint64", "bool"),
+         # destinations that are neither an operand's type nor hold the promoted type: the operation
+         # runs in the promoted type, the result is converted on store
+         ("add", "int32", "int32", "int8"), ("mul", "int32", "int32", "int8"), ("add", "double", "double", "float"),
+         ("sub", "int16", "uint8", "int8"), ("div", "float", "int32", "half"), ("mul", "uint64", "int8", "uint16"),
+         ("mul", "cdouble", "float", "cfloat"), ("add", "half", "half", "int16"), ("mul", "chalf", "half", "half"),
+         ("sub", "half", "uint8", "int32"), ("bxor", "int32", "uint8", "int8"), ("band", "uint16", "bool", "uint8"),
+         ("min", "int64", "int64", "int16"), ("max", "float", "float", "half")]
 
 
 @pytest.mark.parametrize("op,da,db,dout", MIXED)

@@ -86,6 +86,30 @@ def test_strict_types_flag():
     assert code(ocn.plan_unary, "ident", a, o, ocn.STRICT_TYPES) == E["DTYPE"]
 
 
+def test_binary_compute_type_follows_the_operands_unless_the_destination_is_one_of_them():
+    """The planner's compute type against the rule of section 3.2.1, for every triple of types:
+    the destination's type when it is an operand's or holds the promoted type, else the
+    promoted type; kernels specialised by type only ever run in the destination's type."""
+    import exactmath as X
+    for da in X.ALL:
+        for db in X.ALL:
+            for do in X.ALL:
+                want = X.compute_type("add", da, db, do)
+                if not X.binary_supported("add", want):
+                    assert code(ocn.plan_binary, "add", T(da, (4,), base=A), T(db, (4,), base=Bb), T(do, (4,), base=O_)) == E["DTYPE"]
+                    continue
+                p = ocn.plan_binary("add", T(da, (4,), base=A), T(db, (4,), base=Bb), T(do, (4,), base=O_))
+                assert p["compute_dtype"] == want, (da, db, do)
+                assert not p["specialised"] or want == do
+    f = lambda dt, base: T(dt, (4,), base=base)
+    assert ocn.plan_binary("add", f("int32", A), f("int32", Bb), f("int8", O_))["compute_dtype"] == "int32"
+    assert ocn.plan_binary("add", f("int8", A), f("int32", Bb), f("int8", O_))["compute_dtype"] == "int8"
+    assert ocn.plan_binary("add", f("int8", A), f("uint8", Bb), f("int64", O_))["compute_dtype"] == "int64"
+    assert ocn.plan_binary("add", f("double", A), f("double", Bb), f("float", O_))["compute_dtype"] == "double"
+    # a bitwise operation on floating operands stays undefined whatever the destination
+    assert code(ocn.plan_binary, "bxor", f("float", A), f("double", Bb), f("int32", O_)) == E["DTYPE"]
+
+
 def test_device_mismatch():
     a, b = T("float", (4,), base=A, device=0), T("float", (4,), base=Bb, device=1)
     assert code(ocn.plan_binary, "add", a, b, T("float", (4,), base=O_)) == E["DEVICE"]

@@ -43,7 +43,8 @@ def _cases_binary():
     for op in ("add", "sub", "mul", "div", "min"):
         cases += [(op, "int32", "int32", "int8"), (op, "double", "double", "float"),
                   (op, "int16", "uint8", "int8"), (op, "float", "int32", "half"),
-                  (op, "uint64", "int8", "uint16"), (op, "cdouble", "float", "cfloat")]
+                  (op, "uint64", "int8", "uint16"), (op, "cdouble", "float", "cfloat"),
+                  (op, "half", "half", "int16"), (op, "chalf", "half", "half"), (op, "half", "uint8", "int32")]
     for op in X.BITWISE:
         cases += [(op, "int32", "uint8", "int8"), (op, "uint16", "bool", "uint8")]
     cases = [c for c in cases if X.binary_supported(c[0], X.compute_type(*c))]
