@@ -12,6 +12,11 @@ template <class G, int OP> hipError_t launch_fred(const RedPlan &p, char *partia
   const RedArgs args = make_red_args(p, partial);
   switch (p.kernel) {
     case OCN_KERNEL_RED_ROWS:
+      if (p.lean) {
+        hipLaunchKernelGGL((fred_rows_lean_kernel<G, OP>), dim3((unsigned)p.grid), dim3(kBlock), 0, stream,
+                           make_red_lean_args(p, partial));
+        break;
+      }
       if (p.short_rows) {
         hipLaunchKernelGGL((fred_rows_short_kernel<G, OP>), dim3((unsigned)p.grid), dim3(kBlock), 0, stream, args);
         break;

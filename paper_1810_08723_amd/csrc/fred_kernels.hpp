@@ -190,6 +190,94 @@ template <class G, int OP> __global__ __launch_bounds__(kBlock) void fred_rows_k
   }
 }
 
+// The common fused row reduction - one reduced dim along which both inputs are contiguous and
+// read in whole 16-byte vectors, at most one kept dim (along which either input may be
+// broadcast), a wavefront or a workgroup per output or per split of it, everything below 2^31 -
+// without the index decomposition and the 64-bit bookkeeping of the general kernel, and with
+// every load a single 16-byte piece per lane, so that a wavefront's instruction covers whole
+// lines of its input (the access shape streaming loads need; the general kernel reads 64 bytes
+// per lane and input when the intermediate type is bool).
+template <class G, int OP, bool NT>
+OCN_DEV typename FusedFold<G, OP>::A fred_lean_fold(const char *pa, const char *pb, uint32_t t0, uint32_t t1,
+                                                    uint32_t lane, uint32_t lanes) {
+  using F = FusedFold<G, OP>;
+  using A = typename F::A;
+  using SAt = typename G::SAt;
+  using SBt = typename G::SBt;
+  static_assert(sizeof(SAt) == sizeof(SBt) && sizeof(SAt) <= 16, "equal input widths of at most 16 bytes");
+  constexpr int V = 16 / (int)sizeof(SAt);
+  constexpr int U = 2;
+  A acc[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) acc[u] = F::R::identity();
+  uint32_t t = t0 + lane;
+  for (; t + (U - 1) * lanes < t1; t += U * lanes) {
+    Pack<SAt, V> va[U];
+    Pack<SBt, V> vb[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      load_vec<SAt, V, NT>(pa + (uint64_t)(t + u * lanes) * 16u, va[u]);
+      load_vec<SBt, V, NT>(pb + (uint64_t)(t + u * lanes) * 16u, vb[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int i = 0; i < V; ++i) acc[u] = F::add(acc[u], va[u].v[i], vb[u].v[i]);
+  }
+  for (; t < t1; t += lanes) {
+    Pack<SAt, V> va;
+    Pack<SBt, V> vb;
+    load_vec<SAt, V, NT>(pa + (uint64_t)t * 16u, va);
+    load_vec<SBt, V, NT>(pb + (uint64_t)t * 16u, vb);
+#pragma unroll
+    for (int i = 0; i < V; ++i) acc[0] = F::add(acc[0], va.v[i], vb.v[i]);
+  }
+  A r = acc[0];
+#pragma unroll
+  for (int u = 1; u < U; ++u) r = F::R::combine(r, acc[u]);
+  return r;
+}
+
+template <class G, int OP> __global__ __launch_bounds__(kBlock) OCN_ROWS_OCC void fred_rows_lean_kernel(const RedLeanArgs p) {
+  using F = FusedFold<G, OP>;
+  using R = typename F::R;
+  using A = typename F::A;
+  __shared__ A lds[kBlock / kWave];
+  const uint32_t tid = threadIdx.x, lane_in_wave = tid & (kWave - 1), wave = tid / kWave;
+  const bool per_block = p.group == kBlock;
+  const uint32_t gidx = per_block ? blockIdx.x : blockIdx.x * (kBlock / kWave) + wave;
+  const bool active = gidx < p.nout * p.split;
+  const uint32_t lane = per_block ? tid : lane_in_wave;
+  uint32_t o = gidx, sp = 0, t0 = 0, t1 = p.nvec;
+  A acc = R::identity();
+  if (active) {
+    if (p.split != 1) {
+      o = gidx / p.split;
+      sp = gidx - o * p.split;
+      t0 = sp * p.chunk;
+      t1 = t0 + p.chunk < p.nvec ? t0 + p.chunk : p.nvec;
+    }
+    const char *pa = p.a + (int64_t)o * p.ksa;
+    const char *pb = p.b + (int64_t)o * p.ksb;
+    const uint32_t lanes = per_block ? kBlock : kWave;
+    if (p.nt_load) acc = fred_lean_fold<G, OP, true>(pa, pb, t0, t1, lane, lanes);
+    else acc = fred_lean_fold<G, OP, false>(pa, pb, t0, t1, lane, lanes);
+  }
+  acc = group_fold<R>(acc, kWave);
+  if (per_block) {
+    if (lane_in_wave == 0) lds[wave] = acc;
+    __syncthreads();
+    if (tid == 0) {
+#pragma unroll
+      for (int w = 1; w < kBlock / kWave; ++w) acc = R::combine(acc, lds[w]);
+    }
+  }
+  if (active && lane == 0) {
+    if (p.split == 1) store_result<A>(p.out + (int64_t)o * p.kso, p.out_dtype, acc);
+    else reinterpret_cast<typename R::P *>(p.partial)[(uint64_t)o * p.split + sp] = to_storage<R::ACC>(acc);
+  }
+}
+
 // Rows of at most one vector per lane of their group, a single reduced dim, no split: the same
 // groups, loads and fold order as fred_rows_kernel without its loops and 64-bit bookkeeping.
 template <class G, int OP, int V>

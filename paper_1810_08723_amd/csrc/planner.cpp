@@ -1002,7 +1002,39 @@ void choose_fused_launch(RedPlan &p) {
     p.grid = (p.nout * p.split + groups_per_block - 1) / groups_per_block;
     p.short_rows = p.group <= kWave && nvec <= p.group && p.nred == 1 && p.split == 1 &&
                    p.nout * p.group < ((int64_t)1 << 32) && n0 < ((int64_t)1 << 31);
-
+    // The common 2-D shape takes the lean form of the kernel: one reduced dim along which both
+    // inputs are contiguous and made of whole, aligned 16-byte vectors, at most one kept dim,
+    // at least a wavefront per output, everything below 2^31.  Its vectors are 16 bytes of
+    // each input whatever the intermediate type is.
+    const int lv = es_a == es_b && es_a <= 16 ? 16 / es_a : 0;   // elements per vector
+    if (!p.short_rows && lv >= 1 && p.nred == 1 && p.nkept <= 1 && !p.a_fast_bcast && !p.b_fast_bcast &&
+        n0 % lv == 0 && n0 / lv >= kWave && n0 / lv < ((int64_t)1 << 31) && p.nout < ((int64_t)1 << 31) &&
+        (intptr_t)p.a_ptr % 16 == 0 && (intptr_t)p.b_ptr % 16 == 0 &&
+        (p.nkept == 0 || (p.kstride_a[0] % 16 == 0 && p.kstride_b[0] % 16 == 0))) {
+      const int64_t nv = n0 / lv;
+      const int group = nv * 32 <= 16 * 1024 ? kWave : kBlock;    // as above: rows of up to 16 KiB take a wavefront
+      const int64_t lwaves = (p.nout * group + kWave - 1) / kWave;
+      int64_t split = 1;
+      if (lwaves < kTargetWaves) {
+        const int64_t want = (kTargetWaves + lwaves - 1) / lwaves;
+        const int64_t most = std::max<int64_t>(1, nv / ((int64_t)group * 8));
+        split = std::max<int64_t>(1, std::min(want, most));
+      }
+      const int64_t chunk = (nv + split - 1) / split;
+      split = (nv + chunk - 1) / chunk;
+      if (p.nout * split < ((int64_t)1 << 31)) {
+        p.lean = true;
+        p.vec = lv;
+        p.group = group;
+        p.split = split;
+        p.chunk = chunk;
+        p.grid = (p.nout * split + kBlock / group - 1) / (kBlock / group);
+        // inputs far larger than the caches are streamed; one that is broadcast along the kept
+        // dim is re-read by every output and stays cacheable, and then so does the other (one flag)
+        const bool a_rows = p.nkept == 0 || p.kstride_a[0] != 0, b_rows = p.nkept == 0 || p.kstride_b[0] != 0;
+        p.nt_load = a_rows && b_rows && p.nout * n0 * es_a >= kStreamBytes;
+      }
+    }
   } else if (k_fast_dim >= 0 && k_fast_dim == p.nkept - 1 && p.nred >= 1 && idx32 &&
              fast_ok(p.kstride_a[k_fast_dim], p.kstride_b[k_fast_dim]) && (r_fast == 0 || r_fast > k_fast)) {
     p.kernel = OCN_KERNEL_RED_COLS;
@@ -1192,6 +1224,8 @@ int plan_binary_reduce(int ew_op, int red_op, const ocn_tensor *a, const ocn_ten
   // each output in a single lane: for long reductions the two-launch route, whose kernels
   // spread every layout over the device, is faster despite the temporary.
   if (p.kernel == OCN_KERNEL_RED_GENERIC && p.nredtot >= 1024) return plan_unfused();
+  // more workgroups than one launch may have: the two calls, whose kernels loop
+  if (p.grid > max_launch_blocks()) return plan_unfused();
   fp.workspace_bytes = p.workspace_bytes;
   *plan = fp;
   return OCN_OK;

@@ -53,8 +53,10 @@ struct RedArgs {
 // kept dim, everything below 2^31
 struct RedLeanArgs {
   const char *a;
+  const char *b;           // second input of a fused elementwise+reduce call
   char *out, *partial;
   int64_t ksa, kso;        // byte strides of the kept dim in the input and the output
+  int64_t ksb;             // ... in the second input
   uint32_t nout, split;    // outputs; partial results per output
   uint32_t nvec, chunk;    // vectors per output; vectors per split
   int32_t out_dtype, group, nt_load;

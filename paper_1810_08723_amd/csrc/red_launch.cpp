@@ -64,7 +64,9 @@ RedLeanArgs make_red_lean_args(const RedPlan &p, char *partial) {
   r.a = p.a_ptr;
   r.out = p.out_ptr;
   r.partial = partial;
+  r.b = p.b_ptr;
   r.ksa = p.nkept ? p.kstride_a[0] : 0;
+  r.ksb = p.nkept ? p.kstride_b[0] : 0;
   r.kso = p.nkept ? p.kstride_o[0] : 0;
   r.nout = (uint32_t)p.nout;
   r.split = (uint32_t)p.split;

@@ -136,6 +136,41 @@ def test_split_reductions_and_output_conversion():
     _check("absgt", "sum", z, w, (0, 1), "bool", expect_fused=True)
 
 
+@pytest.mark.parametrize("dt", ARITH_T)
+def test_rows_of_whole_aligned_vectors(dt):
+    """The form of the rows kernel for one contiguous reduced dim of whole 16-byte vectors: a
+    wavefront per row, a workgroup per row, a split full reduction, an operand broadcast along
+    the kept dim, and a row length that leaves the form (not a whole number of vectors)."""
+    rng = rng_for(15350 + X.ALL.index(dt))
+    sp = X.kind(dt) not in "fc"
+    cmp_ok = dt in ("int32", "float", "double", "cfloat")
+    for shape in ((9, 512), (5, 4096), (3, 8192 + 64)):
+        a = random_view(rng, dt, shape, specials=sp)
+        b = random_view(rng, dt, shape, specials=sp)
+        _check("mul", "sum", a, b, (1,), dt, expect_fused=True)
+        _check("sub", "sum", a, b, (0, 1), dt, expect_fused=True)
+        row = random_view(rng, dt, shape[1:], specials=sp)
+        _check("add", "sum", a, row, (1,), dt, expect_fused=True)
+        _check("mul", "sum", row, a, (1,), dt, expect_fused=True)
+        if cmp_ok:
+            b.storage[: b.storage.size // 2] = a.storage[: a.storage.size // 2]
+            for red in ("sum", "any", "all"):
+                _check("eq", red, a, b, (1,), "bool", expect_fused=True)
+            _check("absgt", "sum", a, row, (1,), "bool", expect_fused=True)
+    n = 1 << 20
+    x = random_view(rng, dt, (n,), specials=False)
+    y = random_view(rng, dt, (n,), specials=False)
+    _check("mul", "sum", x, y, (0,), dt, expect_fused=True)                          # split over workgroups
+    if cmp_ok:
+        _check("eq", "sum", x, y, (0,), "bool", expect_fused=True)
+    rag = random_view(rng, dt, (7, 1024 + 1), specials=sp)
+    rag2 = random_view(rng, dt, (7, 1024 + 1), specials=sp)
+    _check("mul", "sum", rag, rag2, (1,), dt, expect_fused=True)
+    # rows that start off a 16-byte boundary leave the form as well
+    off = random_view(rng, dt, (7, 1024 + 1), specials=sp).slice(1, 1, 1025, 1)
+    _check("mul", "sum", off, rag2.slice(1, 1, 1025, 1), (1,), dt, expect_fused=True)
+
+
 def test_unaligned_reversed_and_stepped_views():
     rng = rng_for(15400)
     big = random_view(rng, "float", (50, 131), specials=False)
