@@ -2,7 +2,8 @@
 
 One "step" runs every benchmark operation once, through the C ABI, on synthetic inputs that are
 already resident in HBM: the five configurations (C1, C1x8, C2, C3, C4a-d, C5, C5m, and C5b,
-C5bm: the second reading of configuration 5's layout).  The operations touch about 3.5 GB of
+C5bm: the second reading of configuration 5's layout; the masks run after both multiplies, so
+that no operation directly follows the one that read the same inputs).  The operations touch about 3.5 GB of
 distinct memory per step, so each one starts with a cold 256 MB Infinity Cache.  The timed
 region runs the step K times with HIP events around the dominant operation only (`roofline`).
 `per_op`: `avg_us` is the cold time per launch (the call on four sets of buffers in rotation,
@@ -203,6 +204,8 @@ def main() -> int:
             cases = cases + configs.fused_cases()
         if any(w[0] in "LS" for w in want):
             cases = cases + configs.layout_cases()
+        if any(w.startswith("E") for w in want):
+            cases = cases + configs.elementary_cases()
         cases = [c for c in cases if c.name in want]
         if "copy" in want:
             from workloads.views import View
@@ -263,11 +266,13 @@ def main() -> int:
     cold_us = []
     for i in range(len(runs)):
         fns = [sets[k][i][1] for k in range(NB)]
-        for f in fns:
-            f()
-        torch.cuda.synchronize()
-        rounds = 6
+        # a run of about 20 ms, entered without a pause after three untimed rounds (a shorter
+        # run that starts on an idle device reads up to 15 % more: clocks, first touches)
+        rounds = max(6, int(20e3 / (NB * max(op_ms[i][len(op_ms[i]) // 2] * 1e3, 1.0))))
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for _ in range(3):
+            for f in fns:
+                f()
         e0.record()
         for _ in range(rounds):
             for f in fns:
@@ -427,7 +432,7 @@ def main() -> int:
         "ms_per_step": wall / args.steps * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32/f64/i32/i8/f16/c64 (per case)", "data": "synthetic",
-        "config": {"workload": ("all five configurations in one step: C1, C1x8, C2, C3, C4a-d, C5, C5m, C5b, C5bm"
+        "config": {"workload": ("all five configurations in one step: C1, C1x8, C2, C3, C4a-d, C5, C5b, C5m, C5bm"
                                 if not args.only else "subset for profiling: " + args.only),
                    "logical_bytes_per_step": step_bytes, "device_ms_per_step": device_ms},
         "roofline": {"bound": "hbm", "achieved": dom["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
