@@ -34,7 +34,6 @@ struct RowsArgs {
   int32_t a_bcast, b_bcast;
   int32_t nt_store;  // stream the output past the caches
   int32_t nt_a, nt_b; // read that input with streaming (non-temporal) loads
-  int32_t simple;     // at most one outer dim, rows of whole vectors, fewer than 2^31 vectors
   int32_t swap;       // operands stored in the other byte order: bit 0 a, bit 1 b, bit 2 out
 };
 
@@ -375,66 +374,89 @@ template <class G> OCN_DEV void rows_general(const RowsArgs &p) {
 }
 
 // The common shapes - at most one outer dim, rows of whole vectors, fewer than 2^31 vectors -
-// need one division per vector and no per-element conditions.
-template <class G> OCN_DEV void rows_simple(const RowsArgs &p) {
+// get a kernel of their own.  With one vector per lane a wavefront lives for one memory round
+// trip, so what it executes before its first load is time during which it has nothing in
+// flight: this kernel reads 72 bytes of arguments with two scalar loads (the general kernel's
+// 340 bytes of strides and divisors arrive in eight loads that are all waited for), needs one
+// division per vector and no per-element conditions, and issues every load of a lane before it
+// waits for any (2^26 floats negated: 84.4 us in the general kernel's body for these shapes,
+// a plain copy of the same size written for the purpose 80.7 us).
+struct RowsSlimArgs {
+  char *out;
+  const char *a, *b;
+  int64_t so, sa, sb;   // byte strides of the outer dim (zero and unused without one)
+  uint32_t nvec;        // vectors in total
+  FastDiv vpr_div;      // vectors per row
+  uint32_t flags;       // kSlim* bits; operands in the other byte order in bits 8..10
+};
+enum : uint32_t { kSlimABcast = 1, kSlimBBcast = 2, kSlimNtA = 4, kSlimNtB = 8, kSlimNtStore = 16, kSlimSwapShift = 8 };
+#ifndef OCN_SLIM_BLOCK
+#define OCN_SLIM_BLOCK 64
+#endif
+constexpr int kSlimBlock = OCN_SLIM_BLOCK;
+
+template <class G> __global__ __launch_bounds__(kSlimBlock) void ew_rows_slim_kernel(const RowsSlimArgs p) {
   constexpr int V = G::VR, U = G::UR;
   using SAt = typename G::SAt;
   using SBt = typename G::SBt;
   using SOt = typename G::SOt;
   constexpr bool BIN = G::NIN2;
-  const uint32_t g0 = blockIdx.x * (uint32_t)(kBlock * U) + threadIdx.x;
-  const uint32_t nvec = (uint32_t)p.nvec;
-  const bool two_d = p.nouter != 0;
+  const uint32_t g0 = blockIdx.x * (uint32_t)(kSlimBlock * U) + threadIdx.x;
+  const uint32_t flags = p.flags;
   Pack<SAt, V> va[U];
   Pack<SBt, V> vb[U];
   int64_t oo[U];
+  // every load of the lane is issued before anything waits for one
 #pragma unroll
   for (int u = 0; u < U; ++u) {
-    const uint32_t g = g0 + (uint32_t)u * kBlock;
+    const uint32_t g = g0 + (uint32_t)u * kSlimBlock;
     oo[u] = 0;
-    if (g < nvec) {
-      const uint32_t row = two_d ? fastdiv(g, p.vpr_div) : 0u;
+    if (g < p.nvec) {
+      const uint32_t row = fastdiv(g, p.vpr_div);
       const int64_t e0 = (int64_t)(g - row * p.vpr_div.d) * V;
-      oo[u] = (int64_t)row * p.so[0] + e0 * (int64_t)sizeof(SOt);
-      const char *pa = p.a + (int64_t)row * p.sa[0];
-      if (p.a_bcast) {
-        const SAt s = *reinterpret_cast<const SAt *>(pa);
-#pragma unroll
-        for (int i = 0; i < V; ++i) va[u].v[i] = s;
-      } else {
-        load_pack<SAt, V>(pa + e0 * (int64_t)sizeof(SAt), va[u], p.nt_a != 0);
-      }
+      oo[u] = (int64_t)row * p.so + e0 * (int64_t)sizeof(SOt);
+      const char *pa = p.a + (int64_t)row * p.sa;
+      // (an operand broadcast along the row: its one element lands in the vector's first slot
+      // and is spread out after the loads; a register of its own would have to be cleared on
+      // the other path, which the compiler does behind a wait for the loads issued so far)
+      if (flags & kSlimABcast) va[u].v[0] = *reinterpret_cast<const SAt *>(pa);
+      else load_pack<SAt, V>(pa + e0 * (int64_t)sizeof(SAt), va[u], (flags & kSlimNtA) != 0);
       if constexpr (BIN) {
-        const char *pb = p.b + (int64_t)row * p.sb[0];
-        if (p.b_bcast) {
-          const SBt s = *reinterpret_cast<const SBt *>(pb);
-#pragma unroll
-          for (int i = 0; i < V; ++i) vb[u].v[i] = s;
-        } else {
-          load_pack<SBt, V>(pb + e0 * (int64_t)sizeof(SBt), vb[u], p.nt_b != 0);
-        }
+        const char *pb = p.b + (int64_t)row * p.sb;
+        if (flags & kSlimBBcast) vb[u].v[0] = *reinterpret_cast<const SBt *>(pb);
+        else load_pack<SBt, V>(pb + e0 * (int64_t)sizeof(SBt), vb[u], (flags & kSlimNtB) != 0);
       }
     }
   }
+  const int swap = (int)(flags >> kSlimSwapShift);
 #pragma unroll
   for (int u = 0; u < U; ++u) {
-    if (g0 + (uint32_t)u * kBlock < nvec) {
+    if (g0 + (uint32_t)u * kSlimBlock < p.nvec) {
+      if (flags & kSlimABcast) {
+#pragma unroll
+        for (int i = 1; i < V; ++i) va[u].v[i] = va[u].v[0];
+      }
+      if constexpr (BIN) {
+        if (flags & kSlimBBcast) {
+#pragma unroll
+          for (int i = 1; i < V; ++i) vb[u].v[i] = vb[u].v[0];
+        }
+      }
       Pack<SOt, V> r;
-      if (p.swap) G::order_inputs(p.swap, va[u], vb[u]);
+      if (swap) G::order_inputs(swap, va[u], vb[u]);
 #pragma unroll
       for (int i = 0; i < V; ++i) {
         if constexpr (BIN) r.v[i] = G::eval(va[u].v[i], vb[u].v[i]);
         else r.v[i] = G::eval(va[u].v[i], SBt{});
       }
-      if (p.swap) G::order_output(p.swap, r);
-      store_pack<SOt, V>(p.out + oo[u], r, p.nt_store != 0);
+      if (swap) G::order_output(swap, r);
+      store_pack<SOt, V>(p.out + oo[u], r, (flags & kSlimNtStore) != 0);
     }
   }
 }
 
 template <class G> __global__ __launch_bounds__(kBlock) void ew_rows_kernel(const RowsArgs p) {
-  if (p.simple) rows_simple<G>(p);
-  else rows_general<G>(p);
+  rows_general<G>(p);
 }
 
 // ---------------------------------------------------------------------------------------

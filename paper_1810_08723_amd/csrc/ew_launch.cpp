@@ -34,10 +34,37 @@ RowsArgs make_rows_args(const EwPlan &p) {
   r.swap = p.swap;
   r.nt_a = p.nt_a;
   r.nt_b = p.nt_b;
-  // with no outer dim the "row" is the whole tensor: so[0], sa[0], sb[0] stay zero and unused
-  r.simple = inner <= 1 && r.inner % p.vec == 0 && r.nvec < ((int64_t)1 << 31) &&
-             (int64_t)p.grid * kBlock * p.unroll < ((int64_t)1 << 32);
   return r;
+}
+
+bool make_rows_slim_args(const EwPlan &p, int block, RowsSlimArgs *args, int64_t *grid) {
+  const int inner = p.ndim - 1;
+  if (inner < 0 || inner > 1) return false;
+  const int64_t n0 = p.size[inner];
+  if (n0 % p.vec != 0) return false;
+  const int64_t vpr = n0 / p.vec;
+  const int64_t nvec = vpr * (inner == 1 ? p.size[0] : 1);
+  const int64_t g = (nvec + (int64_t)block * p.unroll - 1) / ((int64_t)block * p.unroll);
+  // 32-bit vector numbers (including those of the lanes past the end), one launch
+  if (nvec >= ((int64_t)1 << 31) || g * block * p.unroll >= ((int64_t)1 << 32) || g > max_launch_blocks() || g < 1)
+    return false;
+  RowsSlimArgs r;
+  std::memset(&r, 0, sizeof r);
+  r.out = p.out.ptr;
+  r.a = p.a.ptr;
+  r.b = p.b.ptr;
+  if (inner == 1) {
+    r.so = p.out.stride[0];
+    r.sa = p.a.stride[0];
+    r.sb = p.b.stride[0];
+  }
+  r.nvec = (uint32_t)nvec;
+  r.vpr_div = make_fastdiv((uint32_t)vpr);   // without an outer dim: row 0 for every vector
+  r.flags = (p.a_inner_bcast ? kSlimABcast : 0u) | (p.b_inner_bcast ? kSlimBBcast : 0u) | (p.nt_a ? kSlimNtA : 0u) |
+            (p.nt_b ? kSlimNtB : 0u) | (p.nt_store ? kSlimNtStore : 0u) | ((uint32_t)p.swap << kSlimSwapShift);
+  *args = r;
+  *grid = g;
+  return true;
 }
 
 TiledArgs make_tiled_args(const EwPlan &p, int es_a) {
