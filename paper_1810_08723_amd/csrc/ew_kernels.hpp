@@ -99,6 +99,7 @@ struct FastTiledArgs {
   int32_t nt_store;                         // stream the output past the caches
   int32_t swap;                             // operands stored in the other byte order: bit 0 a, bit 1 b, bit 2 out
   int32_t pair_log2;                        // groups of 1 << pair_log2 consecutive tiles share input lines
+  int32_t nt_a, nt_b;                       // read that input with streaming loads (its runs inside a tile are whole lines)
   uint32_t lds_base[2];                     // byte offset of a's / b's staging area
   FastDiv ntdiv[kMaxDims + 1];              // (one more than dims: a dim's tile index may be split in two)
   int64_t step[3][kMaxDims + 1];            // bytes from one tile to the next along that dim
@@ -853,11 +854,11 @@ template <class G> __global__ __launch_bounds__(kBlock) void ew_tiled_fast_kerne
       Pack<SBt, VB> vb[J];
 #pragma unroll
       for (int j = 0; j < J; ++j)
-        if (j0 + j < na) load_pack<SAt, VA>(pa + p.ord[1].hi_off[1][j0 + j] + offa[1], va[j]);
+        if (j0 + j < na) load_pack<SAt, VA>(pa + p.ord[1].hi_off[1][j0 + j] + offa[1], va[j], p.nt_a != 0);
       if constexpr (BIN) {
 #pragma unroll
         for (int j = 0; j < J; ++j)
-          if (j0 + j < nb) load_pack<SBt, VB>(pb + p.ord[2].hi_off[2][j0 + j] + offb[2], vb[j]);
+          if (j0 + j < nb) load_pack<SBt, VB>(pb + p.ord[2].hi_off[2][j0 + j] + offb[2], vb[j], p.nt_b != 0);
       }
 #pragma unroll
       for (int j = 0; j < J; ++j) {
@@ -906,7 +907,7 @@ template <class G> __global__ __launch_bounds__(kBlock) void ew_tiled_fast_kerne
             *reinterpret_cast<Pack<SAt, EPA> *>(&av[j].v[c * EPA]) =
                 *reinterpret_cast<const Pack<SAt, EPA> *>(lds + (ra ^ (h ^ p.rd_ch[0][c])));
         } else {
-          load_pack<SAt, VC>(pa + p.ord[0].hi_off[1][jj] + off[1], av[j]);
+          load_pack<SAt, VC>(pa + p.ord[0].hi_off[1][jj] + off[1], av[j], p.nt_a != 0);
         }
         if constexpr (BIN) {
           if (stage_b) {
@@ -916,7 +917,7 @@ template <class G> __global__ __launch_bounds__(kBlock) void ew_tiled_fast_kerne
               *reinterpret_cast<Pack<SBt, EPB> *>(&bv[j].v[c * EPB]) =
                   *reinterpret_cast<const Pack<SBt, EPB> *>(lds + (rb ^ (h ^ p.rd_ch[1][c])));
           } else {
-            load_pack<SBt, VC>(pb + p.ord[0].hi_off[2][jj] + off[2], bv[j]);
+            load_pack<SBt, VC>(pb + p.ord[0].hi_off[2][jj] + off[2], bv[j], p.nt_b != 0);
           }
         }
       }

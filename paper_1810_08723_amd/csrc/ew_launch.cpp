@@ -180,6 +180,25 @@ FastTiledArgs make_fast_tiled_args(const EwPlan &p, int es_a) {
     add_dim(d, count, paired ? group : 1);
   }
   const int es[2] = {es_a, p.nin == 2 ? dt_size(p.b.dtype) : 1};
+  // An input too large to be found in a cache again is read with streaming loads where every
+  // run of it inside a tile - along its own fastest axis if it is staged, along the output's
+  // if it is read in place - is a whole number of 128-byte lines starting on a line boundary
+  // (a streaming load of part of a line runs at a fraction of the rate of an ordinary one).
+  auto whole_lines = [&](const Operand &x, int esz, int run_dim) {
+    if (x.stride[run_dim] != esz || (((int64_t)esz << p.tile_log2[run_dim]) % 128) != 0) return false;
+    if (((intptr_t)x.ptr % 128) != 0) return false;
+    int64_t distinct = esz;
+    for (int d = 0; d < p.ndim; ++d) {
+      if (x.stride[d] == 0) return false;
+      if (d != run_dim && x.stride[d] % 128 != 0) return false;
+      distinct *= p.size[d];
+    }
+    return distinct >= kStreamBytes;
+  };
+  if (p.nord > 0) {
+    f.nt_a = whole_lines(p.a, es[0], p.stage_a ? p.ord_a[0] : p.ord_o[0]) ? 1 : 0;
+    f.nt_b = p.nin == 2 && whole_lines(p.b, es[1], p.stage_b ? p.ord_b[0] : p.ord_o[0]) ? 1 : 0;
+  }
   auto log2i = [](int64_t v) { int l = 0; while (((int64_t)1 << l) < v) ++l; return l; };
   const int64_t tile_elems = (int64_t)1 << p.tile_bits;
   // the larger staging area goes first, so that the smaller one starts at a multiple of its own
