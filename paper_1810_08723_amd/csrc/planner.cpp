@@ -1269,6 +1269,18 @@ void plan_second_pass(const RedPlan &first, char *workspace, RedPlan *second) {
     if (first.split >= 4 * kBlock) q.group = kBlock;   // as in the first pass: four partials per lane and more
     q.chunk = first.split;  // vectors (vec = 1) per output
     q.grid = (q.nout * q.group + kBlock - 1) / kBlock;
+    // Eight-byte partial results in whole, aligned 16-byte vectors, at most one kept dim: the
+    // lean form of the kernel, whose few arguments arrive with the first scalar loads (this
+    // launch is nothing but a chain of latencies)
+    const int64_t nv = first.split / 2;
+    if (es == 8 && first.split % 2 == 0 && nv >= kWave && nv < ((int64_t)1 << 31) && first.nkept <= 1 &&
+        q.nout < ((int64_t)1 << 31) && (intptr_t)workspace % 16 == 0) {
+      q.lean = true;
+      q.vec = 2;
+      q.chunk = nv;
+      q.group = nv < 4 * kBlock ? kWave : kBlock;
+      q.grid = (q.nout + kBlock / q.group - 1) / (kBlock / q.group);
+    }
   } else if (!rows_layout && first.nkept >= 1 && q.nout < ((int64_t)1 << 31)) {
     q.kernel = OCN_KERNEL_RED_COLS;
     const int64_t nc = q.ksize[q.nkept - 1];
@@ -1276,6 +1288,12 @@ void plan_second_pass(const RedPlan &first, char *workspace, RedPlan *second) {
     const int64_t colblocks = (nc + q.cpw - 1) / q.cpw;
     q.grid = colblocks * (q.nout / nc);
     if (first.split >= 64) q.block = 16 * kWave;   // many partials per column: more wavefronts share them
+    // eight-byte partial results of a single kept dim: the kernel made for this launch
+    if (es == 8 && first.nkept == 1 && first.split < ((int64_t)1 << 31) && max_launch_blocks() >= (q.nout + kWave - 1) / kWave) {
+      q.fold = true;
+      q.block = kWave;
+      q.grid = (q.nout + kWave - 1) / kWave;
+    }
   } else {
     q.kernel = OCN_KERNEL_RED_GENERIC;
     q.grid = std::min<int64_t>((q.nout + kBlock - 1) / kBlock, max_launch_blocks());

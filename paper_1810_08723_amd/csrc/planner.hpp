@@ -96,6 +96,7 @@ struct RedPlan {
   int cpw = kWave;              // cols kernel: lanes per row of columns (power of two, at most a wavefront)
   bool nt_load = false;         // the input is far larger than the caches: stream it (non-temporal vector loads)
   bool lean = false;            // rows kernel: the common 2-D shape, run by the lean form of the kernel
+  bool fold = false;            // second launch over [split][output] partial results: one output per lane
   bool swap_a = false, swap_o = false;  // the input / the output is stored in the other byte order
   int64_t split = 1;            // partial results per output
   int64_t chunk = 0;            // reduction elements (rows: vectors) per split

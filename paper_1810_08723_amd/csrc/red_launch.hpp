@@ -32,6 +32,18 @@ template <int S, int OP> hipError_t launch_red(const RedPlan &p, char *partial, 
       hipLaunchKernelGGL((red_rows_kernel<S, OP>), dim3((unsigned)p.grid), dim3(kBlock), 0, stream, args);
       break;
     case OCN_KERNEL_RED_COLS:
+      if (p.fold) {
+        RedFoldArgs f;
+        f.partial = p.a_ptr;
+        f.out = p.out_ptr;
+        f.kso = p.kstride_o[0];
+        f.nout = (uint32_t)p.nout;
+        f.split = (uint32_t)p.nredtot;
+        f.out_dtype = p.out_dtype;
+        f.swap_o = p.swap_o ? 1 : 0;
+        hipLaunchKernelGGL((red_fold_kernel<S, OP>), dim3((unsigned)p.grid), dim3(kWave), 0, stream, f);
+        break;
+      }
       hipLaunchKernelGGL((red_cols_kernel<S, OP>), dim3((unsigned)p.grid), dim3((unsigned)p.block), 0, stream, args);
       break;
     default:
