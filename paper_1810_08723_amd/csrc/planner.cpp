@@ -708,6 +708,12 @@ int sort_merge(RDim *d, int n, bool by_out) {
 #define OCN_RED_TARGET_WAVES (256 * 16)
 #endif
 constexpr int64_t kTargetWaves = OCN_RED_TARGET_WAVES;  // enough wavefronts to occupy every CU
+// A row reduction that runs in the lean form of the kernel and has to be split over workgroups
+// is split into half as many wavefronts, eight per CU: with four 16-byte loads per lane in
+// flight that measured fastest (int8 full sum of 2^28: 41.9 us, against 45.2, 44.7 and 43.6 with
+// 6, 12 and 16 per CU; the count of a > b over 2^26 pairs: 81.7 against 83.2 with 16).  The
+// general kernel's element loads want the sixteen (full sum of a stride-2 view: 96 against 104 us).
+constexpr int64_t kLeanSplitWaves = 256 * 8;
 
 void choose_reduce_launch(RedPlan &p) {
   const int es = dt_size(p.a_dtype);
@@ -765,9 +771,13 @@ void choose_reduce_launch(RedPlan &p) {
     const int64_t groups_per_block = kBlock / p.group;
     const int64_t waves = (p.nout * p.group + kWave - 1) / kWave;
     p.split = 1;
+    // the common 2-D shape: one reduced dim of whole vectors, at most one kept dim, a wavefront or
+    // a workgroup per output (or per split of it), everything below 2^31
+    const bool lean_shape = p.nred == 1 && p.nkept <= 1 && p.vec > 1 && es < 16 && n0 % p.vec == 0 &&
+                            p.group >= kWave && nvec < ((int64_t)1 << 31);
     if (p.group >= kWave && waves < kTargetWaves) {
       // split long reductions so the device fills; keep >= 16 vectors per lane per split
-      const int64_t want = (kTargetWaves + waves - 1) / waves;
+      const int64_t want = ((lean_shape ? kLeanSplitWaves : kTargetWaves) + waves - 1) / waves;
       const int64_t most = std::max<int64_t>(1, nvec / ((int64_t)p.group * 16));
       p.split = std::max<int64_t>(1, std::min(want, most));
     }
@@ -776,11 +786,7 @@ void choose_reduce_launch(RedPlan &p) {
     p.grid = (p.nout * p.split + groups_per_block - 1) / groups_per_block;
     p.short_rows = p.group <= kWave && nvec <= p.group && p.nred == 1 && p.split == 1 &&
                    p.nout * p.group < ((int64_t)1 << 32) && n0 < ((int64_t)1 << 31);
-    // the common 2-D shape: one reduced dim of whole vectors, at most one kept dim, a wavefront or
-    // a workgroup per output (or per split of it), everything below 2^31
-    p.lean = !p.short_rows && p.nred == 1 && p.nkept <= 1 && p.vec > 1 && es < 16 && n0 % p.vec == 0 &&
-             p.group >= kWave && nvec < ((int64_t)1 << 31) && p.nout * p.split < ((int64_t)1 << 31) &&
-             p.chunk < ((int64_t)1 << 31);
+    p.lean = !p.short_rows && lean_shape && p.nout * p.split < ((int64_t)1 << 31) && p.chunk < ((int64_t)1 << 31);
   } else if (cols_ok) {
     // ---- cols: a kept axis is the input's fastest; lanes own output columns -------------
     // (requires that axis to be the last canonical kept dim, i.e. also the output's fastest)
@@ -1016,7 +1022,7 @@ void choose_fused_launch(RedPlan &p) {
       const int64_t lwaves = (p.nout * group + kWave - 1) / kWave;
       int64_t split = 1;
       if (lwaves < kTargetWaves) {
-        const int64_t want = (kTargetWaves + lwaves - 1) / lwaves;
+        const int64_t want = (kLeanSplitWaves + lwaves - 1) / lwaves;
         const int64_t most = std::max<int64_t>(1, nv / ((int64_t)group * 8));
         split = std::max<int64_t>(1, std::min(want, most));
       }
