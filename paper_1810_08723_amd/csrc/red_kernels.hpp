@@ -589,6 +589,18 @@ OCN_DEV typename Reducer<S, OP>::A lean_fold(const char *base, uint32_t t0, uint
       fold[u].add_full(pk[u]);
     }
   }
+  // two vectors at a time while they last: a row of two or three vectors per lane takes one
+  // round trip less
+  for (; t + lanes < t1; t += 2 * lanes) {
+    Pk pk[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) load_vec<St, V, NT>(base + (uint64_t)(t + u * lanes) * 16u, pk[u]);
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      order_pack<S>(sw, pk[u]);
+      fold[u].add_full(pk[u]);
+    }
+  }
   for (; t < t1; t += lanes) {
     Pk pk;
     load_vec<St, V, NT>(base + (uint64_t)t * 16u, pk);
