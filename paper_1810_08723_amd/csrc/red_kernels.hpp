@@ -18,6 +18,8 @@
 // geometry, so results are reproducible bit for bit.
 #pragma once
 
+#include <type_traits>
+
 #include "dev_types.hpp"
 #include "planner.hpp"
 
@@ -737,10 +739,16 @@ template <int S, int OP> __global__ __launch_bounds__(kWave) void red_fold_kerne
 // ---------------------------------------------------------------------------------------
 
 constexpr int kColsMaxWaves = 16;  // the cols kernel runs with 4 or 16 wavefronts per workgroup
+// columns of a lane's vector that the wavefronts of a workgroup combine through LDS at a time
+// (32 KiB for sixteen wavefronts; the launcher sizes the dynamic LDS accordingly)
+template <class A> OCN_HD constexpr int cols_lds_columns() { return sizeof(A) <= 8 ? 4 : 2; }
+template <class A> OCN_HD constexpr size_t cols_lds_bytes(int block, int vec) {
+  return (size_t)(block / kWave) * kWave * sizeof(A) * (size_t)(cols_lds_columns<A>() < vec ? cols_lds_columns<A>() : vec);
+}
 
 // SINGLE: one reduced dim, so that row r lies r strides further on (no index decomposition)
 template <int S, int OP, int V, bool NT, bool SINGLE>
-OCN_DEV void cols_body(const RedArgs &p, typename Reducer<S, OP>::A (*lds)[kWave]) {
+OCN_DEV void cols_body(const RedArgs &p, typename Reducer<S, OP>::A *lds) {
   using R = Reducer<S, OP>;
   using A = typename R::A;
   using St = storage_t<S>;
@@ -853,25 +861,32 @@ OCN_DEV void cols_body(const RedArgs &p, typename Reducer<S, OP>::A (*lds)[kWave
   if (packed_done) {
     // (nothing left to add)
   } else if (ncol == V) {  // whole vectors of columns: no per-element conditions
-    for (; r + (int64_t)(U - 1) * RS < r1; r += RS * U) {
-      Pk pk[U];
+    // (one loop per byte order: decided per row inside the loop, the reversal is computed for
+    // every vector and selected away)
+    auto rows = [&](auto swapped) {
+      constexpr bool SW = decltype(swapped)::value;
+      for (; r + (int64_t)(U - 1) * RS < r1; r += RS * U) {
+        Pk pk[U];
 #pragma unroll
-      for (int u = 0; u < U; ++u)
-        load_vec<St, V, NT>(p.a + off_a + row_offset(r + (int64_t)u * RS), pk[u]);
+        for (int u = 0; u < U; ++u)
+          load_vec<St, V, NT>(p.a + off_a + row_offset(r + (int64_t)u * RS), pk[u]);
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        order_pack<S>(p.swap_a != 0, pk[u]);
+        for (int u = 0; u < U; ++u) {
+          order_pack<S>(SW, pk[u]);
 #pragma unroll
-        for (int i = 0; i < V; ++i) acc[i] = R::combine(acc[i], R::lift(from_storage<S>(pk[u].v[i])));
+          for (int i = 0; i < V; ++i) acc[i] = R::combine(acc[i], R::lift(from_storage<S>(pk[u].v[i])));
+        }
       }
-    }
-    for (; r < r1; r += RS) {
-      Pk pk;
-      load_vec<St, V, NT>(p.a + off_a + row_offset(r), pk);
-      order_pack<S>(p.swap_a != 0, pk);
+      for (; r < r1; r += RS) {
+        Pk pk;
+        load_vec<St, V, NT>(p.a + off_a + row_offset(r), pk);
+        order_pack<S>(SW, pk);
 #pragma unroll
-      for (int i = 0; i < V; ++i) acc[i] = R::combine(acc[i], R::lift(from_storage<S>(pk.v[i])));
-    }
+        for (int i = 0; i < V; ++i) acc[i] = R::combine(acc[i], R::lift(from_storage<S>(pk.v[i])));
+      }
+    };
+    if (p.swap_a) rows(std::true_type{});
+    else rows(std::false_type{});
   } else if (ncol > 0) {  // the ragged last column block
     for (; r < r1; r += RS) {
       const char *src = p.a + off_a + row_offset(r);
@@ -888,14 +903,21 @@ OCN_DEV void cols_body(const RedArgs &p, typename Reducer<S, OP>::A (*lds)[kWave
       for (int d = kWave / 2; d >= 1; d >>= 1)
         if (d >= p.cpw) acc[i] = R::combine(acc[i], shfl_down_any(acc[i], d));
   }
-  // combine the wavefronts (same columns, different rows), one column of the vector at a time
+  // Combine the wavefronts (same columns, different rows): CH columns of the vector go through
+  // LDS at a time, and wavefront c folds column c over all wavefronts, in wavefront order.  (One
+  // column at a time, folded by the first wavefront alone, was four rounds of a barrier and a
+  // chain of sixteen LDS reads and adds at the end of every workgroup - and the workgroups of
+  // a split reduction all end together.)
+  constexpr int CH = cols_lds_columns<A>() < V ? cols_lds_columns<A>() : V;
 #pragma unroll
-  for (int i = 0; i < V; ++i) {
-    lds[wave][lane] = acc[i];
+  for (int i0 = 0; i0 < V; i0 += CH) {
+#pragma unroll
+    for (int c = 0; c < CH; ++c) lds[((size_t)wave * CH + c) * kWave + lane] = acc[i0 + c];
     __syncthreads();
-    if (wave == 0 && lr == 0 && i < ncol) {
-      A v = lds[0][lane];
-      for (int w = 1; w < NW; ++w) v = R::combine(v, lds[w][lane]);
+    if (wave < CH && lr == 0 && i0 + wave < ncol) {
+      const int c = wave, i = i0 + wave;
+      A v = lds[(size_t)c * kWave + lane];
+      for (int w = 1; w < NW; ++w) v = R::combine(v, lds[((size_t)w * CH + c) * kWave + lane]);
       if (p.split == 1) {
         store_result<A>(p.out + off_o + (int64_t)i * p.kso[0], p.out_dtype, v, p.swap_o != 0);
       } else {
@@ -903,14 +925,15 @@ OCN_DEV void cols_body(const RedArgs &p, typename Reducer<S, OP>::A (*lds)[kWave
         reinterpret_cast<typename R::P *>(p.partial)[(int64_t)s * p.nout + olin] = to_storage<R::ACC>(v);
       }
     }
-    if (i + 1 < V) __syncthreads();
+    if (i0 + CH < V) __syncthreads();
   }
 }
 
 template <int S, int OP> __global__ __launch_bounds__(kColsMaxWaves * kWave) void red_cols_kernel(const RedArgs p) {
   using A = typename Reducer<S, OP>::A;
   constexpr int VF = 16 / (int)sizeof(storage_t<S>) > 0 ? 16 / (int)sizeof(storage_t<S>) : 1;
-  __shared__ A lds[kColsMaxWaves][kWave];
+  extern __shared__ __align__(16) unsigned char red_cols_lds_raw[];
+  A *lds = reinterpret_cast<A *>(red_cols_lds_raw);
   if (p.vec > 1 && p.nred == 1) {
     if (p.nt_load) cols_body<S, OP, VF, (VF > 1), true>(p, lds);
     else cols_body<S, OP, VF, false, true>(p, lds);

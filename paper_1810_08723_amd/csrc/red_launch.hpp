@@ -44,7 +44,12 @@ template <int S, int OP> hipError_t launch_red(const RedPlan &p, char *partial, 
         hipLaunchKernelGGL((red_fold_kernel<S, OP>), dim3((unsigned)p.grid), dim3(kWave), 0, stream, f);
         break;
       }
-      hipLaunchKernelGGL((red_cols_kernel<S, OP>), dim3((unsigned)p.grid), dim3((unsigned)p.block), 0, stream, args);
+      {
+        using A = typename Reducer<S, OP>::A;
+        constexpr int VF = 16 / (int)sizeof(storage_t<S>) > 0 ? 16 / (int)sizeof(storage_t<S>) : 1;
+        const size_t lds = cols_lds_bytes<A>((int)p.block, p.vec > 1 ? VF : 1);
+        hipLaunchKernelGGL((red_cols_kernel<S, OP>), dim3((unsigned)p.grid), dim3((unsigned)p.block), lds, stream, args);
+      }
       break;
     default:
       hipLaunchKernelGGL((red_generic_kernel<S, OP>), dim3((unsigned)p.grid), dim3(kBlock), 0, stream, args);
