@@ -310,6 +310,7 @@ struct GatherArgs {
   int32_t items_log2;                 // >= 0: rows of at most 256 items, padded to 1 << items_log2 lanes,
                                       // 256 >> items_log2 rows per workgroup; -1: workgroups per row below
   FastDiv chunks_div;                 // workgroups per row
+  int32_t nt_rows;                    // gather of single elements: stream the (large) result past the caches
 };
 
 template <int ES> struct Bytes { unsigned char b[ES]; };
@@ -362,6 +363,65 @@ template <int ES, bool SCATTER> __global__ __launch_bounds__(kBlock) void gather
     }
   } else {
     *reinterpret_cast<Bytes<ES> *>(p.dst + od) = *reinterpret_cast<const Bytes<ES> *>(p.src + os);
+  }
+}
+
+// Single elements per offset, the rows side contiguous (a[mask], a[index array] on a flat list):
+// a lane takes four consecutive offsets (two 16-byte loads), moves the four elements, and
+// handles the rows side as one piece of 4 * ES bytes - four times the bytes in flight per lane
+// of the kernel above, whose lanes each wait on one offset and then on one element.  An
+// offset outside [lo, hi] still skips its element alone.
+template <int ES, bool SCATTER> __global__ __launch_bounds__(kBlock) void gather_scalar4_kernel(const GatherArgs p) {
+  using E = Bytes<ES>;
+  struct alignas(4 * ES) E4 { E e[4]; };
+  using L2 = long long __attribute__((ext_vector_type(2)));
+  const int64_t j0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
+  if (j0 >= p.n) return;
+  char *dst = p.dst;
+  const char *src = p.src;
+  if (j0 + 4 <= p.n) {
+    const L2 o01 = *reinterpret_cast<const L2 *>(p.offsets + j0), o23 = *reinterpret_cast<const L2 *>(p.offsets + j0 + 2);
+    const int64_t off[4] = {o01.x, o01.y, o23.x, o23.y};
+    bool ok[4], all = true;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      ok[i] = off[i] >= p.lo && off[i] <= p.hi;
+      all = all && ok[i];
+    }
+    if (SCATTER) {
+      const E4 v = *reinterpret_cast<const E4 *>(src + j0 * ES);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (ok[i]) *reinterpret_cast<E *>(dst + off[i]) = v.e[i];
+    } else {
+      E4 v;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (ok[i]) v.e[i] = *reinterpret_cast<const E *>(src + off[i]);
+      if (all) {
+        if (ES == 4 && p.nt_rows) {   // (16 bytes per lane: a wavefront's store covers whole lines)
+          using Q = uint32_t __attribute__((ext_vector_type(4)));
+          Q q;
+          __builtin_memcpy(&q, &v, 16);
+          asm volatile("");
+          __builtin_nontemporal_store(q, reinterpret_cast<Q *>(dst + j0 * ES));
+          asm volatile("");
+        } else {
+          *reinterpret_cast<E4 *>(dst + j0 * ES) = v;
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (ok[i]) *reinterpret_cast<E *>(dst + (j0 + i) * ES) = v.e[i];
+      }
+    }
+  } else {
+    for (int64_t j = j0; j < p.n; ++j) {
+      const int64_t off = p.offsets[j];
+      if (off < p.lo || off > p.hi) continue;
+      if (SCATTER) *reinterpret_cast<E *>(dst + off) = *reinterpret_cast<const E *>(src + j * ES);
+      else *reinterpret_cast<E *>(dst + j * ES) = *reinterpret_cast<const E *>(src + off);
+    }
   }
 }
 
@@ -580,15 +640,40 @@ static int run_gather(bool scatter, const ocn_tensor *inner, const void *offsets
     g.chunks_div = make_fastdiv((uint32_t)chunks);
     grid = n * chunks;
   }
+  const int64_t max_blocks = max_launch_blocks();
+  hipStream_t s = (hipStream_t)stream;
+  // single elements, the rows side contiguous and aligned for pieces of four: four offsets per lane
+  if (inner_elems == 1 && es <= 8 && rows->stride[0] == es && (uintptr_t)offsets % 16 == 0 &&
+      ((intptr_t)rows->base + rows->offset) % (4 * es) == 0) {
+    const int64_t per_launch = max_blocks * kBlock * 4;   // a multiple of four offsets: later launches stay aligned
+    for (int64_t j0 = 0; j0 < n; j0 += per_launch) {
+      GatherArgs q = g;
+      q.nt_rows = !scatter && n * es >= ((int64_t)32 << 20);
+      q.n = std::min<int64_t>(per_launch, n - j0);
+      q.offsets = g.offsets + j0;
+      if (scatter) q.src = g.src + j0 * es;
+      else q.dst = g.dst + j0 * es;
+      const int64_t launch_grid = (q.n + 4 * kBlock - 1) / (4 * kBlock);
+#define OCN_LAUNCH4(ES)                                                                                                  \
+  if (scatter) hipLaunchKernelGGL((gather_scalar4_kernel<ES, true>), dim3((unsigned)launch_grid), dim3(kBlock), 0, s, q); \
+  else hipLaunchKernelGGL((gather_scalar4_kernel<ES, false>), dim3((unsigned)launch_grid), dim3(kBlock), 0, s, q);
+      switch (es) {
+        case 1: OCN_LAUNCH4(1) break;
+        case 2: OCN_LAUNCH4(2) break;
+        case 4: OCN_LAUNCH4(4) break;
+        default: OCN_LAUNCH4(8) break;
+      }
+#undef OCN_LAUNCH4
+    }
+    return done(hipGetLastError());
+  }
   // A launch may not exceed 2^32 lanes: longer lists of offsets go out in several launches,
   // each over a contiguous run of rows (the kernels are independent of one another).
-  const int64_t max_blocks = max_launch_blocks();
   const int64_t blocks_per_row_num = g.items_log2 >= 0 ? 1 : (int64_t)g.chunks_div.d;      // blocks per row ...
   const int64_t rows_per_block = g.items_log2 >= 0 ? (kBlock >> g.items_log2) : 1;          // ... or rows per block
   if (blocks_per_row_num > max_blocks) return OCN_ERR_SHAPE;   // a single row of 2^40 items: not a gather any more
   const int64_t rows_per_launch = g.items_log2 >= 0 ? max_blocks * rows_per_block : max_blocks / blocks_per_row_num;
   (void)grid;
-  hipStream_t s = (hipStream_t)stream;
   const GatherArgs all = g;
   for (int64_t j0 = 0; j0 < n; j0 += rows_per_launch) {
     g = all;
