@@ -150,6 +150,44 @@ def test_gather_scatter_elementwise_by_mask(dt):
     assert np.array_equal(got_a, a.storage)
 
 
+@pytest.mark.parametrize("dt", ("int8", "int16", "float", "double", "cdouble"))
+def test_single_elements_four_offsets_per_lane(dt):
+    """Single elements with a contiguous rows side: lanes take four offsets at a time.  Counts
+    that are not multiples of four, offsets outside the stated range inside a group of four
+    (only that element is skipped), a rows side that starts off the alignment of a piece of
+    four (the one-offset kernel), repeated offsets in a gather."""
+    import torch
+    import paper_1810_08723_amd as ocn
+    es = itemsize(dt)
+    rng = rng_for(17250 + es)
+    src = random_view(rng, dt, (5000,))
+    scalar = View(src.storage, dt, (), (), 0)
+    for n in (1, 3, 4, 5, 1021, 1024, 4099):
+        offs = rng.integers(0, 5000, size=n).astype(np.int64) * es
+        lo, hi = 1000 * es, 3999 * es                      # about two in five are outside
+        for skew in (0, 1):                                # rows side on / off a 4-element boundary
+            base = View.empty(dt, (n + skew,))
+            out = View(base.storage, dt, (n,), (es,), skew * es)
+            dv = H.DeviceViews()
+            ocn.gather(dv.tensor(scalar), _dev_i64(offs), lo, hi, dv.tensor(out))
+            torch.cuda.synchronize()
+            got = dv.download(out).copy()
+            OI.gather(scalar, offs, out, lo, hi)
+            assert np.array_equal(got, out.storage), (dt, n, skew)
+            # scatter: unique in-range targets, others skipped
+            perm = rng.permutation(5000)[:n].astype(np.int64) * es
+            vals_base = random_view(rng, dt, (n + skew,))
+            vals = View(vals_base.storage, dt, (n,), (es,), skew * es)
+            target = random_view(rng, dt, (5000,))
+            tscalar = View(target.storage, dt, (), (), 0)
+            dv = H.DeviceViews()
+            ocn.scatter(dv.tensor(vals), _dev_i64(perm), lo, hi, dv.tensor(tscalar))
+            torch.cuda.synchronize()
+            got_t = dv.download(tscalar).copy()
+            OI.scatter(vals, perm, tscalar, lo, hi)
+            assert np.array_equal(got_t, target.storage), (dt, n, skew)
+
+
 def test_gather_rows_by_index_array_and_skipped_offsets():
     import torch
     import paper_1810_08723_amd as ocn
