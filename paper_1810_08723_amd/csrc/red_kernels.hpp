@@ -314,31 +314,24 @@ struct VecFold<S, R_SUM, V, std::enable_if_t<(S == DT_I8 || S == DT_U8) && V == 
   OCN_DEV A result() { flush(); return total; }
 };
 
-// min / max of half precision, eight per vector
+// min / max of half precision, eight per vector: the packed IEEE 754-2019 maximum / minimum of
+// gfx950 (NaN-propagating, +0 above -0) folds two elements per instruction
 template <int OP, int V>
 struct VecFold<DT_F16, OP, V, std::enable_if_t<(OP == R_MIN || OP == R_MAX) && V == 8>> {
   using R = Reducer<DT_F16, OP>;
   using A = typename R::A;  // hreg
   using St = storage_t<DT_F16>;
   struct alignas(16) Pk { St v[V]; };
-  using s2 = short __attribute__((ext_vector_type(2)));
-  using u2 = unsigned short __attribute__((ext_vector_type(2)));
+  using h2 = _Float16 __attribute__((ext_vector_type(2)));
   static constexpr bool MX = OP == R_MAX;
-  // key(x) = x ^ ((x >> 15) & 0x7fff) orders every non-NaN half as a signed 16-bit integer,
-  // with -0 just below +0; it is its own inverse
-  s2 best;   // running max (min) of keys; starts at the value no finite-or-infinite half maps to
-  u2 mag;    // running max of |bits|: above 0x7c00 means a NaN was seen
+  h2 best;
   OCN_DEV void init() {
-    const short start = MX ? (short)-32768 : (short)32767;
-    best = s2{start, start};
-    mag = u2{0, 0};
+    const _Float16 start = MX ? (_Float16)-__builtin_inff() : (_Float16)__builtin_inff();
+    best = h2{start, start};
   }
   OCN_DEV void add_word(uint32_t w) {
-    const s2 x = __builtin_bit_cast(s2, w);
-    const s2 sign = x >> (short)15;
-    const s2 key = x ^ (sign & s2{0x7fff, 0x7fff});
-    best = MX ? __builtin_elementwise_max(best, key) : __builtin_elementwise_min(best, key);
-    mag = __builtin_elementwise_max(mag, __builtin_bit_cast(u2, w & 0x7fff7fffu));
+    const h2 x = __builtin_bit_cast(h2, w);
+    best = MX ? __builtin_elementwise_maximum(best, x) : __builtin_elementwise_minimum(best, x);
   }
   OCN_DEV void add_full(const Pk &pk) {
     const uint32_t *w = reinterpret_cast<const uint32_t *>(&pk);
@@ -356,12 +349,8 @@ struct VecFold<DT_F16, OP, V, std::enable_if_t<(OP == R_MIN || OP == R_MAX) && V
     for (int k = 0; k < 4; ++k) add_word(h[2 * k] | (h[2 * k + 1] << 16));
   }
   OCN_DEV A result() {
-    const unsigned short m = mag.x > mag.y ? mag.x : mag.y;
-    if (m > 0x7c00u) return hreg{__builtin_nanf("")};
-    const short k = MX ? (best.x > best.y ? best.x : best.y) : (best.x < best.y ? best.x : best.y);
-    if (k == (MX ? (short)-32768 : (short)32767)) return R::identity();  // this lane saw nothing
-    const unsigned short bits = (unsigned short)(k ^ ((k >> 15) & 0x7fff));
-    return hreg{(float)__builtin_bit_cast(_Float16, bits)};
+    const _Float16 r = MX ? __builtin_elementwise_maximum(best.x, best.y) : __builtin_elementwise_minimum(best.x, best.y);
+    return hreg{(float)r};
   }
 };
 
@@ -569,8 +558,12 @@ template <int S, int OP> __global__ __launch_bounds__(kBlock) OCN_ROWS_OCC void 
 // only a few loop trips on rows of some KiB, so what it executes before its first load and
 // after its last one is time during which it has nothing in flight (half-precision maxima
 // over rows of 8 KiB: 24.6 us in the general kernel).  Same fold order as the general kernel.
-template <int S, int OP, bool NT>
-OCN_DEV typename Reducer<S, OP>::A lean_fold(const char *base, uint32_t t0, uint32_t t1, uint32_t lane, uint32_t lanes, bool sw) {
+// (SW, the input's byte order, is a template parameter like NT: decided per vector inside the
+// loop, the reversal is computed for every vector and selected away - a quarter of the loop's
+// instructions for half-precision maxima)
+template <int S, int OP, bool NT, bool SW>
+OCN_DEV typename Reducer<S, OP>::A lean_fold(const char *base, uint32_t t0, uint32_t t1, uint32_t lane, uint32_t lanes) {
+  constexpr bool sw = SW;
   using R = Reducer<S, OP>;
   using St = storage_t<S>;
   constexpr int V = 16 / (int)sizeof(St);
@@ -614,10 +607,18 @@ OCN_DEV typename Reducer<S, OP>::A lean_fold(const char *base, uint32_t t0, uint
   return acc;
 }
 
-template <int S, int OP> __global__ __launch_bounds__(kBlock) OCN_ROWS_OCC void red_rows_lean_kernel(const RedLeanArgs p) {
+// All arguments in scalar registers at this point: left alone, the compiler fetches each field
+// just before its first use, in three or four batches of scalar loads that wait for one
+// another - each a round trip during which the wavefront has nothing in flight.
+#define OCN_ARGS_NOW(...) asm volatile("" ::__VA_ARGS__)
+
+template <int S, int OP> __global__ __launch_bounds__(kBlock) OCN_ROWS_OCC void red_rows_lean_kernel(const RedLeanArgs q) {
   using R = Reducer<S, OP>;
   using A = typename R::A;
   if constexpr (sizeof(storage_t<S>) < 16) {
+    RedLeanArgs p = q;
+    OCN_ARGS_NOW("s"(p.a), "s"(p.out), "s"(p.partial), "s"(p.ksa), "s"(p.kso), "s"(p.nout), "s"(p.split), "s"(p.nvec),
+                 "s"(p.chunk), "s"(p.out_dtype), "s"(p.group), "s"(p.nt_load), "s"(p.swap_a), "s"(p.swap_o));
     __shared__ A lds[kBlock / kWave];
     const uint32_t tid = threadIdx.x, lane_in_wave = tid & (kWave - 1), wave = tid / kWave;
     const bool per_block = p.group == kBlock;
@@ -626,17 +627,25 @@ template <int S, int OP> __global__ __launch_bounds__(kBlock) OCN_ROWS_OCC void 
     const uint32_t lane = per_block ? tid : lane_in_wave;
     uint32_t o = gidx, sp = 0, t0 = 0, t1 = p.nvec;
     A acc = R::identity();
+    // (the row's address is formed before the branch, for every wavefront: inside it, the
+    // compiler fetches the pointer with a scalar load of its own, one more round trip
+    // before the wavefront's first load)
+    if (p.split != 1) {
+      o = gidx / p.split;
+      sp = gidx - o * p.split;
+      t0 = sp * p.chunk;
+      t1 = t0 + p.chunk < p.nvec ? t0 + p.chunk : p.nvec;
+    }
+    const char *base = p.a + (int64_t)o * p.ksa;
     if (active) {
-      if (p.split != 1) {
-        o = gidx / p.split;
-        sp = gidx - o * p.split;
-        t0 = sp * p.chunk;
-        t1 = t0 + p.chunk < p.nvec ? t0 + p.chunk : p.nvec;
-      }
-      const char *base = p.a + (int64_t)o * p.ksa;
       const uint32_t lanes = per_block ? kBlock : kWave;
-      if (p.nt_load) acc = lean_fold<S, OP, true>(base, t0, t1, lane, lanes, p.swap_a != 0);
-      else acc = lean_fold<S, OP, false>(base, t0, t1, lane, lanes, p.swap_a != 0);
+      if (p.swap_a) {
+        if (p.nt_load) acc = lean_fold<S, OP, true, true>(base, t0, t1, lane, lanes);
+        else acc = lean_fold<S, OP, false, true>(base, t0, t1, lane, lanes);
+      } else {
+        if (p.nt_load) acc = lean_fold<S, OP, true, false>(base, t0, t1, lane, lanes);
+        else acc = lean_fold<S, OP, false, false>(base, t0, t1, lane, lanes);
+      }
     }
     acc = group_fold<R>(acc, kWave);
     if (per_block) {
