@@ -26,6 +26,11 @@ struct chreg { float re, im; };
 struct cf32 { float re, im; };
 struct cf64 { double re, im; };
 
+// All of a kernel's arguments in scalar registers at the point of use: left alone, the compiler
+// fetches each field just before its first use, in two to four batches of scalar loads that
+// wait for one another - each a round trip during which the wavefront has nothing in flight.
+#define OCN_ARGS_NOW(...) asm volatile("" ::__VA_ARGS__)
+
 // ---- storage representations ----------------------------------------------------------
 struct alignas(4) chalf_s { _Float16 re, im; };
 struct alignas(8) cfloat_s { float re, im; };

@@ -396,8 +396,11 @@ enum : uint32_t { kSlimABcast = 1, kSlimBBcast = 2, kSlimNtA = 4, kSlimNtB = 8, 
 #endif
 constexpr int kSlimBlock = OCN_SLIM_BLOCK;
 
-template <class G> __global__ __launch_bounds__(kSlimBlock) void ew_rows_slim_kernel(const RowsSlimArgs p) {
+template <class G> __global__ __launch_bounds__(kSlimBlock) void ew_rows_slim_kernel(const RowsSlimArgs q) {
   constexpr int V = G::VR, U = G::UR;
+  RowsSlimArgs p = q;
+  OCN_ARGS_NOW("s"(p.out), "s"(p.a), "s"(p.b), "s"(p.so), "s"(p.sa), "s"(p.sb), "s"(p.nvec), "s"(p.vpr_div.d),
+               "s"(p.vpr_div.m), "s"(p.vpr_div.s), "s"(p.flags));
   using SAt = typename G::SAt;
   using SBt = typename G::SBt;
   using SOt = typename G::SOt;

@@ -607,11 +607,6 @@ OCN_DEV typename Reducer<S, OP>::A lean_fold(const char *base, uint32_t t0, uint
   return acc;
 }
 
-// All arguments in scalar registers at this point: left alone, the compiler fetches each field
-// just before its first use, in three or four batches of scalar loads that wait for one
-// another - each a round trip during which the wavefront has nothing in flight.
-#define OCN_ARGS_NOW(...) asm volatile("" ::__VA_ARGS__)
-
 template <int S, int OP> __global__ __launch_bounds__(kBlock) OCN_ROWS_OCC void red_rows_lean_kernel(const RedLeanArgs q) {
   using R = Reducer<S, OP>;
   using A = typename R::A;
