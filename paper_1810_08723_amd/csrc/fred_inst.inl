@@ -24,7 +24,11 @@ template <class G, int OP> hipError_t launch_fred(const RedPlan &p, char *partia
       hipLaunchKernelGGL((fred_rows_kernel<G, OP>), dim3((unsigned)p.grid), dim3(kBlock), 0, stream, args);
       break;
     case OCN_KERNEL_RED_COLS:
-      hipLaunchKernelGGL((fred_cols_kernel<G, OP>), dim3((unsigned)p.grid), dim3(kBlock), 0, stream, args);
+      {
+        using A = typename FusedFold<G, OP>::A;
+        const size_t lds = cols_lds_bytes<A>((int)p.block, p.vec > 1 ? G::V : 1);
+        hipLaunchKernelGGL((fred_cols_kernel<G, OP>), dim3((unsigned)p.grid), dim3((unsigned)p.block), lds, stream, args);
+      }
       break;
     default:
       hipLaunchKernelGGL((fred_generic_kernel<G, OP>), dim3((unsigned)p.grid), dim3(kBlock), 0, stream, args);

@@ -49,13 +49,14 @@ OCN_DEV void kept_offsets2(const RedArgs &p, uint32_t o, int64_t &off_a, int64_t
 }
 
 // V consecutive elements of one input, or V copies of one element where it is broadcast
-template <class S, int V> OCN_DEV void fused_load(const char *src, bool bcast, Pack<S, V> &dst) {
+template <class S, int V, bool NT = false> OCN_DEV void fused_load(const char *src, bool bcast, Pack<S, V> &dst) {
   if (bcast) {
     const S s = *reinterpret_cast<const S *>(src);
 #pragma unroll
     for (int i = 0; i < V; ++i) dst.v[i] = s;
   } else {
-    load_pack<S, V>(src, dst);
+    if constexpr (NT) load_vec<S, V, true>(src, dst);
+    else load_pack<S, V>(src, dst);
   }
 }
 
@@ -334,8 +335,10 @@ template <class G, int OP> __global__ __launch_bounds__(kBlock) void fred_rows_s
 // cols: a kept axis is the fastest of the inputs; lanes own output columns
 // ---------------------------------------------------------------------------------------
 
-template <class G, int OP, int V>
-OCN_DEV void fred_cols_body(const RedArgs &p, typename FusedFold<G, OP>::A (*lds)[kWave]) {
+// NT: both inputs are read with streaming loads (one 16-byte piece per lane each).  SINGLE:
+// one reduced dim, so that row r lies r strides further on (no index decomposition).
+template <class G, int OP, int V, bool NT, bool SINGLE>
+OCN_DEV void fred_cols_body(const RedArgs &p, typename FusedFold<G, OP>::A *lds) {
   using F = FusedFold<G, OP>;
   using R = typename F::R;
   using A = typename F::A;
@@ -385,8 +388,21 @@ OCN_DEV void fred_cols_body(const RedArgs &p, typename FusedFold<G, OP>::A (*lds
   int64_t r1 = r0 + p.chunk;
   if (r1 > p.nredtot) r1 = p.nredtot;
   constexpr int U = 2;
-  const int RS = NW * RPW;           // rows between two rows of the same lane
-  int64_t r = r0 + wave * RPW + lr;
+  // each wavefront takes one contiguous run of the workgroup's rows, RPW rows at a time (as in
+  // red_cols_kernel: rows dealt out in turn measured 10 % slower there)
+  const int RS = RPW;
+  const int64_t per_wave = (((r1 - r0) + NW - 1) / NW + RPW - 1) / RPW * RPW;
+  const int64_t w0 = r0 + (int64_t)wave * per_wave;
+  if (w0 + per_wave < r1) r1 = w0 + per_wave;
+  int64_t r = w0 + lr;
+  auto row_offsets = [&](int64_t rr, int64_t &oa, int64_t &ob) {
+    if constexpr (SINGLE) {
+      oa = rr * p.rsa[0];
+      ob = rr * p.rsb[0];
+    } else {
+      reduced_offset2(p, (uint32_t)rr, 0, oa, ob);
+    }
+  };
   if (ncol == V) {
     for (; r + (int64_t)(U - 1) * RS < r1; r += RS * U) {
       Pack<SAt, V> va[U];
@@ -394,9 +410,9 @@ OCN_DEV void fred_cols_body(const RedArgs &p, typename FusedFold<G, OP>::A (*lds
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         int64_t oa, ob;
-        reduced_offset2(p, (uint32_t)(r + (int64_t)u * RS), 0, oa, ob);
-        fused_load<SAt, V>(p.a + off_a + oa, abc, va[u]);
-        fused_load<SBt, V>(p.b + off_b + ob, bbc, vb[u]);
+        row_offsets(r + (int64_t)u * RS, oa, ob);
+        fused_load<SAt, V, NT>(p.a + off_a + oa, abc, va[u]);
+        fused_load<SBt, V, NT>(p.b + off_b + ob, bbc, vb[u]);
       }
 #pragma unroll
       for (int u = 0; u < U; ++u)
@@ -407,7 +423,7 @@ OCN_DEV void fred_cols_body(const RedArgs &p, typename FusedFold<G, OP>::A (*lds
   if (ncol > 0) {  // remaining rows, and the ragged last column block
     for (; r < r1; r += RS) {
       int64_t oa, ob;
-      reduced_offset2(p, (uint32_t)r, 0, oa, ob);
+      row_offsets(r, oa, ob);
       const char *qa = p.a + off_a + oa, *qb = p.b + off_b + ob;
 #pragma unroll
       for (int i = 0; i < V; ++i)
@@ -424,13 +440,17 @@ OCN_DEV void fred_cols_body(const RedArgs &p, typename FusedFold<G, OP>::A (*lds
       for (int d = kWave / 2; d >= 1; d >>= 1)
         if (d >= p.cpw) acc[i] = R::combine(acc[i], shfl_down_any(acc[i], d));
   }
+  // combine the wavefronts: CH columns per barrier, wavefront c folds column c (as red_cols_kernel)
+  constexpr int CH = cols_lds_columns<A>() < V ? cols_lds_columns<A>() : V;
 #pragma unroll
-  for (int i = 0; i < V; ++i) {
-    lds[wave][lane] = acc[i];
+  for (int i0 = 0; i0 < V; i0 += CH) {
+#pragma unroll
+    for (int c = 0; c < CH; ++c) lds[((size_t)wave * CH + c) * kWave + lane] = acc[i0 + c];
     __syncthreads();
-    if (wave == 0 && lr == 0 && i < ncol) {
-      A v = lds[0][lane];
-      for (int w = 1; w < NW; ++w) v = R::combine(v, lds[w][lane]);
+    if (wave < CH && lr == 0 && i0 + wave < ncol) {
+      const int c = wave, i = i0 + wave;
+      A v = lds[(size_t)c * kWave + lane];
+      for (int w = 1; w < NW; ++w) v = R::combine(v, lds[((size_t)w * CH + c) * kWave + lane]);
       if (p.split == 1) {
         store_result<A>(p.out + off_o + (int64_t)i * p.kso[0], p.out_dtype, v);
       } else {
@@ -438,15 +458,22 @@ OCN_DEV void fred_cols_body(const RedArgs &p, typename FusedFold<G, OP>::A (*lds
         reinterpret_cast<typename R::P *>(p.partial)[(int64_t)s * p.nout + olin] = to_storage<R::ACC>(v);
       }
     }
-    if (i + 1 < V) __syncthreads();
+    if (i0 + CH < V) __syncthreads();
   }
 }
 
-template <class G, int OP> __global__ __launch_bounds__(kBlock) void fred_cols_kernel(const RedArgs p) {
+template <class G, int OP> __global__ __launch_bounds__(kColsMaxWaves * kWave) void fred_cols_kernel(const RedArgs p) {
   using A = typename FusedFold<G, OP>::A;
-  __shared__ A lds[kBlock / kWave][kWave];
-  if (p.vec > 1) fred_cols_body<G, OP, G::V>(p, lds);
-  else fred_cols_body<G, OP, 1>(p, lds);
+  extern __shared__ __align__(16) unsigned char fred_cols_lds_raw[];
+  A *lds = reinterpret_cast<A *>(fred_cols_lds_raw);
+  if (p.vec > 1 && p.nred == 1) {
+    if (p.nt_load) fred_cols_body<G, OP, G::V, true, true>(p, lds);
+    else fred_cols_body<G, OP, G::V, false, true>(p, lds);
+  } else if (p.vec > 1) {
+    fred_cols_body<G, OP, G::V, false, false>(p, lds);
+  } else {
+    fred_cols_body<G, OP, 1, false, false>(p, lds);
+  }
 }
 
 // ---------------------------------------------------------------------------------------

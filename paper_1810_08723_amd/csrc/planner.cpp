@@ -1055,13 +1055,22 @@ void choose_fused_launch(RedPlan &p) {
     const int rpw = kWave / p.cpw;
     const int64_t colblocks = (nc + (int64_t)p.cpw * p.vec - 1) / ((int64_t)p.cpw * p.vec);
     const int64_t blocks0 = colblocks * (p.nout / nc);
-    const int nw = 4;
+    int nw = 4;   // as in the plain column reduction: sixteen wavefronts keep the partial results small
     if (blocks0 * nw < kTargetWaves) {
+      if (p.nredtot >= 16 * 64 * rpw && blocks0 * 16 * 2 <= kTargetWaves) nw = 16;
       const int64_t want = (kTargetWaves + blocks0 * nw - 1) / (blocks0 * nw);
       const int64_t most = std::max<int64_t>(1, p.nredtot / ((int64_t)nw * rpw * 16));
       p.split = std::max<int64_t>(1, std::min(want, most));
     }
     p.block = nw * kWave;
+    // inputs far larger than the caches, each read as one 16-byte piece per lane and broadcast
+    // along no dim: streaming loads
+    {
+      bool plain = p.vec > 1 && (int64_t)p.vec * es_a == 16 && (int64_t)p.vec * es_b == 16;
+      for (int d = 0; d < p.nkept; ++d) plain = plain && p.kstride_a[d] != 0 && p.kstride_b[d] != 0;
+      for (int d = 0; d < p.nred; ++d) plain = plain && p.rstride_a[d] != 0 && p.rstride_b[d] != 0;
+      p.nt_load = plain && p.nout * p.nredtot * es_a >= kStreamBytes;
+    }
     p.chunk = (p.nredtot + p.split - 1) / p.split;
     p.split = (p.nredtot + p.chunk - 1) / p.chunk;
     p.grid = blocks0 * p.split;

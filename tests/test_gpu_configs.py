@@ -68,7 +68,7 @@ def _run_case(c):
         assert np.all(err <= 1e-7 * np.abs(x).sum(axis=c.axes).reshape(-1) + 1e-30)
 
 
-@pytest.mark.parametrize("idx", range(14))
+@pytest.mark.parametrize("idx", range(15))
 def test_small_cases(idx):
     c = (configs.all_cases_small() + configs.fused_cases(389, 1021, (1 << 20) + 77))[idx]
     print("case", c.name, c.op, [v.sizes for v in c.inputs], flush=True)

@@ -172,8 +172,8 @@ def config5(shape: Sequence[int] = (16, 32, 64, 64, 8), reading: str = "R1") -> 
 
 def fused_cases(rows: int = 16384, cols: int = 4096, n_flat: int = 1 << 26) -> List[Case]:
     """Reductions of an elementwise result (the step after the five configurations): row-wise
-    inner products of two fp32 [rows, cols] matrices N(0,1), and the count of a > b over two flat
-    fp32 vectors.  Logical bytes: both inputs once plus the output."""
+    and column-wise inner products of two fp32 [rows, cols] matrices N(0,1), and the count of
+    a > b over two flat fp32 vectors.  Logical bytes: both inputs once plus the output."""
     a = View.from_numpy(_normal(_seed(5, 0), (rows, cols), np.float32))
     b = View.from_numpy(_normal(_seed(5, 1), (rows, cols), np.float32))
     x = View.from_numpy(_normal(_seed(5, 2), (n_flat,), np.float32))
@@ -184,6 +184,9 @@ def fused_cases(rows: int = 16384, cols: int = 4096, n_flat: int = 1 << 26) -> L
              note="row-wise inner products", red_op="sum", mid_dtype="float"),
         Case("F2", "binary_reduce", "gt", [x, y], View.empty("int64", ()), axes=(0,),
              logical_bytes=8 * n_flat + 8, note="count of a > b", red_op="sum", mid_dtype="bool"),
+        Case("F3", "binary_reduce", "mul", [a, b], View.empty("float", (cols,)), axes=(0,),
+             logical_bytes=8 * rows * cols + 4 * cols, compare="sum", rel_bound=1e-6,
+             note="column-wise inner products", red_op="sum", mid_dtype="float"),
     ]
 
 
