@@ -59,9 +59,10 @@ typedef struct {
                                     (section 3.1.3): every scalar - each component of a complex
                                     element - has its bytes reversed in memory.  The kernels
                                     reverse on load and on store; no extra pass is made.
-                                    Honoured by ocn_unary, ocn_binary, ocn_cast_copy and
-                                    ocn_reduce (and their variants); the other entry points
-                                    return OCN_ERR_BYTEORDER for such an operand.  The field
+                                    Honoured by ocn_unary, ocn_binary, ocn_cast_copy,
+                                    ocn_reduce and ocn_binary_reduce (and their variants; the
+                                    last one then runs as its two calls); the indexing entry
+                                    points return OCN_ERR_BYTEORDER for such an operand.  The field
                                     takes the place of what used to be padding: zero it */
 } ocn_tensor;
 

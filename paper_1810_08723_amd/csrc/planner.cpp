@@ -1098,9 +1098,12 @@ int plan_binary_reduce(int ew_op, int red_op, const ocn_tensor *a, const ocn_ten
   if (ew_op < 0 || ew_op >= B_COUNT || red_op < 0 || red_op >= R_COUNT) return OCN_ERR_OP;
   if (!valid_dtype(mid_dtype)) return OCN_ERR_DTYPE;
   if (a->device != out->device || b->device != out->device) return OCN_ERR_DEVICE;
-  // the fused kernels take operands in native byte order only (one-byte scalars have no order)
+  // the fused kernels take operands in native byte order only (one-byte scalars have no order):
+  // with an operand in the other order the call runs as the two calls it abbreviates, whose
+  // kernels reverse on load and on store
+  bool other_order = false;
   for (const ocn_tensor *t : {a, b, out})
-    if (t->byteswapped && scalar_size(t->dtype) > 1) return OCN_ERR_BYTEORDER;
+    if (t->byteswapped && scalar_size(t->dtype) > 1) other_order = true;
   // broadcast shape of the two inputs (missing leading dims count as size 1)
   const int nd = std::max(a->ndim, b->ndim);
   int64_t shape[kMaxDims], sa[kMaxDims], sb[kMaxDims];
@@ -1185,7 +1188,7 @@ int plan_binary_reduce(int ew_op, int red_op, const ocn_tensor *a, const ocn_ten
     return OCN_OK;
   };
   // no fused kernel for these types
-  if (!fused_specialised(ew_op, a->dtype, b->dtype, mid_dtype, red_op) || nred == 0) return plan_unfused();
+  if (other_order || !fused_specialised(ew_op, a->dtype, b->dtype, mid_dtype, red_op) || nred == 0) return plan_unfused();
 
   const int es_a = dt_size(a->dtype), es_b = dt_size(b->dtype);
   int64_t off_a = a->offset, off_b = b->offset, off_o = out->offset;

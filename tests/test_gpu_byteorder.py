@@ -117,16 +117,43 @@ def test_reductions_in_either_byte_order(dtype):
         check("min", big.permute(1, 0), [0], _flagged_out(dtype, (300,)))
 
 
+def test_reduction_of_an_elementwise_result_in_either_byte_order():
+    """An operand in the other byte order makes the one-call form run as its two calls, whose
+    kernels reverse on load and on store: integer results bit for bit, floating sums within the
+    reduction bound."""
+    import paper_1810_08723_amd as ocn
+    rng = rng_for(18004)
+    ai = View.from_numpy(rng.integers(-3000, 3000, size=(70, 300)).astype(np.int32)).in_other_byte_order()
+    bi = View.from_numpy(rng.integers(-3000, 3000, size=(70, 300)).astype(np.int32))
+    for axes, kept in (([1], (70,)), ([0], (300,)), ([0, 1], ())):
+        out = _flagged_out("int64", kept)
+        dv = H.DeviceViews()
+        plan = ocn.plan_binary_reduce("mul", "sum", dv.tensor(ai), dv.tensor(bi), axes, dv.tensor(out), "int32")
+        assert not plan["fused"]
+        got, want = H.run_binary_reduce("mul", "sum", ai, bi, axes, out, "int32")
+        assert H.storages_equal("int64", got, want, out.byteswapped)
+        got, want = H.run_binary_reduce("gt", "sum", bi, ai, axes, View.empty("int64", kept), "bool")
+        assert H.storages_equal("int64", got, want)
+    af = View.from_numpy(rng.standard_normal((70, 300)).astype(np.float32)).in_other_byte_order()
+    bf = View.from_numpy(rng.standard_normal((70, 300)).astype(np.float32)).in_other_byte_order()
+    out = _flagged_out("float", (70,))
+    got, want = H.run_binary_reduce("mul", "sum", af, bf, [1], out, "float")
+    g = View(got.copy(), "float", out.sizes, out.strides, out.offset, out.byteswapped).to_numpy()
+    w = out.to_numpy()
+    mag = np.abs(af.to_numpy().astype(np.float64) * bf.to_numpy().astype(np.float64)).sum(axis=1)
+    assert np.all(np.abs(g - w) <= 1e-6 * mag + 1e-300)
+
+
 def test_calls_that_take_native_order_only_say_so():
     import paper_1810_08723_amd as ocn
     rng = rng_for(18003)
+    import torch
     a = random_view(rng, "float", (8, 8)).in_other_byte_order()
-    b = random_view(rng, "float", (8, 8))
     dv = H.DeviceViews()
-    ta, tb = dv.tensor(a), dv.tensor(b)
-    out = dv.tensor(View.empty("float", (8,)))
+    offs = torch.zeros(4, dtype=torch.int64, device="cuda:0")
     with pytest.raises(ocn.OcnError) as e:
-        ocn.binary_reduce("mul", "sum", ta, tb, [1], out, "float")
+        ocn.gather(dv.tensor(View(a.storage, "float", (), (), 0, byteswapped=True)), offs, 0, 0,
+                   dv.tensor(View.empty("float", (4,))))
     assert e.value.code == ocn.binding.ERR["BYTEORDER"]
     # one-byte scalars have no byte order: the flag is ignored
     m = random_view(rng, "int8", (8, 8)).in_other_byte_order()
