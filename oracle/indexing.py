@@ -46,6 +46,21 @@ def mask_offsets(mask: View, target_strides: Sequence[int]) -> np.ndarray:
     return np.array(offs, dtype=np.int64)
 
 
+def _scalar_size(dtype: str) -> int:
+    # a complex element is two scalars (section 3.1.3: each is stored in the tensor's byte order)
+    return itemsize(dtype) // 2 if dtype in ("chalf", "cfloat", "cdouble") else itemsize(dtype)
+
+
+def _move(dst_storage: np.ndarray, dst: int, src_storage: np.ndarray, src: int, dtype: str, reverse: bool) -> None:
+    """Copies one element; `reverse`: the two tensors are stored in different byte orders
+    (section 3.1.3), so every scalar of the element has its bytes reversed on the way."""
+    es, sc = itemsize(dtype), _scalar_size(dtype)
+    raw = src_storage[src:src + es].copy()
+    if reverse and sc > 1:
+        raw = raw.reshape(es // sc, sc)[:, ::-1].reshape(es)
+    dst_storage[dst:dst + es] = raw
+
+
 def _inner_offsets(view: View):
     for idx in itertools.product(*[range(s) for s in view.sizes]):
         yield idx, sum(i * s for i, s in zip(idx, view.strides))
@@ -54,7 +69,8 @@ def _inner_offsets(view: View):
 def gather(a_inner: View, offsets: np.ndarray, out: View, lo: int, hi: int) -> None:
     """out[j, i...] = element of a at byte offset offsets[j] + inner offset of i...; `a_inner`
     describes one indexed sub-tensor (its element (0,...,0) at offset 0).  Offsets outside
-    [lo, hi] are skipped (that output row is left untouched)."""
+    [lo, hi] are skipped (that output row is left untouched).  The two tensors may be stored in
+    different byte orders (section 3.1.3): values, not bytes, are what is copied."""
     es = itemsize(a_inner.dtype)
     assert out.dtype == a_inner.dtype and out.sizes == (len(offsets),) + tuple(a_inner.sizes)
     for j, off in enumerate(offsets):
@@ -64,7 +80,7 @@ def gather(a_inner: View, offsets: np.ndarray, out: View, lo: int, hi: int) -> N
         for idx, inner in _inner_offsets(a_inner):
             src = a_inner.offset + off + inner
             dst = out.offset + j * out.strides[0] + sum(i * s for i, s in zip(idx, out.strides[1:]))
-            out.storage[dst:dst + es] = a_inner.storage[src:src + es]
+            _move(out.storage, dst, a_inner.storage, src, a_inner.dtype, a_inner.byteswapped != out.byteswapped)
 
 
 def scatter(src: View, offsets: np.ndarray, out_inner: View, lo: int, hi: int) -> None:
@@ -80,4 +96,4 @@ def scatter(src: View, offsets: np.ndarray, out_inner: View, lo: int, hi: int) -
         for idx, inner in _inner_offsets(out_inner):
             dst = out_inner.offset + off + inner
             s = src.offset + j * src.strides[0] + sum(i * t for i, t in zip(idx, src.strides[1:]))
-            out_inner.storage[dst:dst + es] = src.storage[s:s + es]
+            _move(out_inner.storage, dst, src.storage, s, src.dtype, src.byteswapped != out_inner.byteswapped)

@@ -83,3 +83,43 @@ def test_out_of_range_offsets_are_skipped():
     got = out.to_numpy()
     assert got[0] == 0 and got[3] == 9
     assert np.array_equal(out.storage[2:6], before[2:6])      # rows 1 and 2 untouched
+
+
+def test_gather_and_scatter_between_byte_orders_move_values():
+    """Section 3.1.3: a tensor may hold its data in the other byte order.  Indexed copies move
+    values: bytes written by hand in big-endian order come out as the native numbers, complex
+    elements part by part, and a scatter into such a tensor writes big-endian bytes."""
+    be = np.array([1, 258, -2, 0x01020304], dtype=">i4")            # 00 00 00 01 | 00 00 01 02 | ff ff ff fe | 01 02 03 04
+    src = View(np.frombuffer(be.tobytes(), dtype=np.uint8).copy(), "int32", (), (), 0, True)
+    assert list(src.storage[:8]) == [0, 0, 0, 1, 0, 0, 1, 2]
+    out = View.empty("int32", (3,))
+    OI.gather(src, np.array([12, 0, 8], dtype=np.int64), out, 0, 12)
+    assert list(out.to_numpy()) == [0x01020304, 1, -2]
+    # the same order on both sides: bytes are copied as they are
+    same = View(np.zeros(12, dtype=np.uint8), "int32", (3,), (4,), 0, True)
+    OI.gather(src, np.array([4, 4, 0], dtype=np.int64), same, 0, 12)
+    assert list(same.storage) == [0, 0, 1, 2, 0, 0, 1, 2, 0, 0, 0, 1]
+    assert list(same.to_numpy()) == [258, 258, 1]
+    # complex: each part is a scalar of its own
+    z = np.array([1.5 - 2.25j, 3.0 + 0.5j], dtype=np.complex64)
+    zb = z.view(np.float32).astype(">f4").tobytes()
+    zsrc = View(np.frombuffer(zb, dtype=np.uint8).copy(), "cfloat", (), (), 0, True)
+    zout = View.empty("cfloat", (2,))
+    OI.gather(zsrc, np.array([8, 0], dtype=np.int64), zout, 0, 8)
+    assert list(zout.to_numpy()) == [z[1], z[0]]
+    # scatter native values into a big-endian tensor
+    vals = View.from_numpy(np.array([7, -1], dtype=np.int16))
+    tgt = View(np.zeros(8, dtype=np.uint8), "int16", (), (), 0, True)
+    OI.scatter(vals, np.array([6, 2], dtype=np.int64), tgt, 0, 6)
+    assert list(tgt.storage) == [0, 0, 0xff, 0xff, 0, 0, 0, 7]
+    # round trip through the other order gives the data back
+    rng = rng_for(16100)
+    a = random_view(rng, "double", (40,))
+    swapped = View.empty("double", (40,))
+    swapped = View(swapped.storage, "double", (40,), (8,), 0, True)
+    offs = (rng.permutation(40) * 8).astype(np.int64)
+    OI.gather(View(a.storage, "double", (), (), 0), offs, swapped, 0, 39 * 8)
+    back = View.empty("double", (40,))
+    OI.scatter(swapped, offs, View(back.storage, "double", (), (), 0), 0, 39 * 8)
+    assert np.array_equal(back.storage, a.storage)
+    assert np.array_equal(swapped.to_numpy().view(np.uint64), a.to_numpy()[offs // 8].view(np.uint64))
