@@ -61,8 +61,10 @@ typedef struct {
                                     reverse on load and on store; no extra pass is made.
                                     Honoured by ocn_unary, ocn_binary, ocn_cast_copy,
                                     ocn_reduce and ocn_binary_reduce (and their variants; the
-                                    last one then runs as its two calls); the indexing entry
-                                    points return OCN_ERR_BYTEORDER for such an operand.  The field
+                                    last one then runs as its two calls), and by ocn_gather and
+                                    ocn_scatter, which reverse every scalar where the two sides
+                                    differ; index arrays, offsets and masks are native data:
+                                    OCN_ERR_BYTEORDER otherwise.  The field
                                     takes the place of what used to be padding: zero it */
 } ocn_tensor;
 

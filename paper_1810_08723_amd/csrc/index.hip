@@ -21,6 +21,7 @@
 
 #include "../../include/ocn.h"
 #include "dtypes.hpp"
+#include "dev_types.hpp"
 #include "planner.hpp"
 
 namespace ocn {
@@ -311,7 +312,16 @@ struct GatherArgs {
                                       // 256 >> items_log2 rows per workgroup; -1: workgroups per row below
   FastDiv chunks_div;                 // workgroups per row
   int32_t nt_rows;                    // gather of single elements: stream the (large) result past the caches
+  int32_t swap_sc;                    // the two sides are stored in different byte orders: bytes of one scalar (0: same order)
 };
+
+// reverses every scalar of `sc` bytes in a piece that is moved between byte orders
+template <class P> __device__ __forceinline__ void reorder(P &v, int sc) {
+  if (sc == 0) return;
+  if constexpr (sizeof(P) >= 2) { if (sc == 2) reverse_scalars<2>(v); }
+  if constexpr (sizeof(P) >= 4) { if (sc == 4) reverse_scalars<4>(v); }
+  if constexpr (sizeof(P) >= 8) { if (sc == 8) reverse_scalars<8>(v); }
+}
 
 template <int ES> struct Bytes { unsigned char b[ES]; };
 template <> struct alignas(2) Bytes<2> { unsigned char b[2]; };
@@ -355,14 +365,21 @@ template <int ES, bool SCATTER> __global__ __launch_bounds__(kBlock) void gather
   else { os += off; od += j * p.row_stride; }
   if (V > 1 && p.vec > 1) {
     if ((off & 15) == 0) {
-      *reinterpret_cast<Bytes<16> *>(p.dst + od) = *reinterpret_cast<const Bytes<16> *>(p.src + os);
+      Bytes<16> v = *reinterpret_cast<const Bytes<16> *>(p.src + os);
+      reorder(v, p.swap_sc);
+      *reinterpret_cast<Bytes<16> *>(p.dst + od) = v;
     } else {
 #pragma unroll
-      for (int e = 0; e < V; ++e)
-        *reinterpret_cast<Bytes<ES> *>(p.dst + od + e * ES) = *reinterpret_cast<const Bytes<ES> *>(p.src + os + e * ES);
+      for (int e = 0; e < V; ++e) {
+        Bytes<ES> v = *reinterpret_cast<const Bytes<ES> *>(p.src + os + e * ES);
+        reorder(v, p.swap_sc);
+        *reinterpret_cast<Bytes<ES> *>(p.dst + od + e * ES) = v;
+      }
     }
   } else {
-    *reinterpret_cast<Bytes<ES> *>(p.dst + od) = *reinterpret_cast<const Bytes<ES> *>(p.src + os);
+    Bytes<ES> v = *reinterpret_cast<const Bytes<ES> *>(p.src + os);
+    reorder(v, p.swap_sc);
+    *reinterpret_cast<Bytes<ES> *>(p.dst + od) = v;
   }
 }
 
@@ -389,7 +406,8 @@ template <int ES, bool SCATTER> __global__ __launch_bounds__(kBlock) void gather
       all = all && ok[i];
     }
     if (SCATTER) {
-      const E4 v = *reinterpret_cast<const E4 *>(src + j0 * ES);
+      E4 v = *reinterpret_cast<const E4 *>(src + j0 * ES);
+      reorder(v, p.swap_sc);
 #pragma unroll
       for (int i = 0; i < 4; ++i)
         if (ok[i]) *reinterpret_cast<E *>(dst + off[i]) = v.e[i];
@@ -398,6 +416,7 @@ template <int ES, bool SCATTER> __global__ __launch_bounds__(kBlock) void gather
 #pragma unroll
       for (int i = 0; i < 4; ++i)
         if (ok[i]) v.e[i] = *reinterpret_cast<const E *>(src + off[i]);
+      reorder(v, p.swap_sc);
       if (all) {
         if (ES == 4 && p.nt_rows) {   // (16 bytes per lane: a wavefront's store covers whole lines)
           using Q = uint32_t __attribute__((ext_vector_type(4)));
@@ -419,8 +438,10 @@ template <int ES, bool SCATTER> __global__ __launch_bounds__(kBlock) void gather
     for (int64_t j = j0; j < p.n; ++j) {
       const int64_t off = p.offsets[j];
       if (off < p.lo || off > p.hi) continue;
-      if (SCATTER) *reinterpret_cast<E *>(dst + off) = *reinterpret_cast<const E *>(src + j * ES);
-      else *reinterpret_cast<E *>(dst + j * ES) = *reinterpret_cast<const E *>(src + off);
+      E v = SCATTER ? *reinterpret_cast<const E *>(src + j * ES) : *reinterpret_cast<const E *>(src + off);
+      reorder(v, p.swap_sc);
+      if (SCATTER) *reinterpret_cast<E *>(dst + off) = v;
+      else *reinterpret_cast<E *>(dst + j * ES) = v;
     }
   }
 }
@@ -565,8 +586,9 @@ static int run_gather(bool scatter, const ocn_tensor *inner, const void *offsets
                       const ocn_tensor *rows, void *stream) {
   if (bad_tensor(inner) || bad_tensor(rows)) return (!inner || !rows) ? OCN_ERR_NULLPTR : OCN_ERR_SHAPE;
   if (inner->dtype != rows->dtype) return OCN_ERR_DTYPE;
-  // a copy of elements between two tensors of the same byte order needs no reversal
-  if (other_byte_order(inner) != other_byte_order(rows)) return OCN_ERR_BYTEORDER;
+  // a copy of elements between two tensors of the same byte order needs no reversal; between
+  // different orders every scalar is reversed on the way (section 3.1.3)
+  const bool reorder_scalars = other_byte_order(inner) != other_byte_order(rows);
   if (inner->device != rows->device) return OCN_ERR_DEVICE;
   if (n < 0 || rows->ndim != inner->ndim + 1 || rows->size[0] != n) return OCN_ERR_SHAPE;
   for (int d = 0; d < inner->ndim; ++d)
@@ -614,6 +636,7 @@ static int run_gather(bool scatter, const ocn_tensor *inner, const void *offsets
   g.lo = lo;
   g.hi = hi;
   g.row_stride = rows->stride[0];
+  g.swap_sc = reorder_scalars ? sc : 0;
   g.inner = (uint32_t)inner_elems;
   // 16-byte items along the rows' fastest dim when it is contiguous and everything else keeps
   // such items aligned (the offsets themselves are checked row by row in the kernel)

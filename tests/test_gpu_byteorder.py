@@ -144,16 +144,69 @@ def test_reduction_of_an_elementwise_result_in_either_byte_order():
     assert np.all(np.abs(g - w) <= 1e-6 * mag + 1e-300)
 
 
+@pytest.mark.parametrize("dt", ("int16", "float", "double", "chalf", "cfloat", "cdouble"))
+def test_gather_and_scatter_between_byte_orders(dt):
+    """Indexed copies between tensors stored in different byte orders move values: single
+    elements (four offsets per lane, ragged counts, an unaligned rows side) and rows of 16-byte
+    pieces, in both directions."""
+    import torch
+    import paper_1810_08723_amd as ocn
+    from oracle import indexing as OI
+    from workloads.views import itemsize
+    es = itemsize(dt)
+    rng = rng_for(18005 + es)
+    dev64 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int64)).to("cuda:0")
+    for src_swapped, out_swapped in ((True, False), (False, True), (True, True)):
+        src = random_view(rng, dt, (3000,))
+        if src_swapped:
+            src = src.in_other_byte_order()
+        scalar = View(src.storage, dt, (), (), 0, src.byteswapped)
+        for n, skew in ((1, 0), (7, 0), (1024, 0), (1027, 1)):
+            offs = rng.integers(0, 3000, size=n).astype(np.int64) * es
+            base = View.empty(dt, (n + skew,))
+            out = View(base.storage, dt, (n,), (es,), skew * es, out_swapped)
+            dv = H.DeviceViews()
+            ocn.gather(dv.tensor(scalar), dev64(offs), 0, 2999 * es, dv.tensor(out))
+            torch.cuda.synchronize()
+            got = dv.download(out).copy()
+            OI.gather(scalar, offs, out, 0, 2999 * es)
+            assert np.array_equal(got, out.storage), (dt, n, skew, src_swapped, out_swapped)
+            perm = rng.permutation(3000)[:n].astype(np.int64) * es
+            vals_base = random_view(rng, dt, (n + skew,))
+            vals = View(vals_base.storage, dt, (n,), (es,), skew * es, out_swapped)
+            target = random_view(rng, dt, (3000,))
+            tscalar = View(target.storage, dt, (), (), 0, src_swapped)
+            dv = H.DeviceViews()
+            ocn.scatter(dv.tensor(vals), dev64(perm), 0, 2999 * es, dv.tensor(tscalar))
+            torch.cuda.synchronize()
+            got_t = dv.download(tscalar).copy()
+            OI.scatter(vals, perm, tscalar, 0, 2999 * es)
+            assert np.array_equal(got_t, target.storage), (dt, n, skew, src_swapped, out_swapped)
+        # rows of several elements (16-byte pieces where the offsets allow)
+        table = random_view(rng, dt, (200, 24))
+        if src_swapped:
+            table = table.in_other_byte_order()
+        inner = View(table.storage, dt, (24,), (es,), 0, table.byteswapped)
+        roffs = rng.integers(0, 200, size=77).astype(np.int64) * 24 * es
+        rows_base = View.empty(dt, (77, 24))
+        rows = View(rows_base.storage, dt, (77, 24), rows_base.strides, 0, out_swapped)
+        dv = H.DeviceViews()
+        ocn.gather(dv.tensor(inner), dev64(roffs), 0, 199 * 24 * es, dv.tensor(rows))
+        torch.cuda.synchronize()
+        got = dv.download(rows).copy()
+        OI.gather(inner, roffs, rows, 0, 199 * 24 * es)
+        assert np.array_equal(got, rows.storage), (dt, "rows", src_swapped, out_swapped)
+
+
 def test_calls_that_take_native_order_only_say_so():
     import paper_1810_08723_amd as ocn
     rng = rng_for(18003)
     import torch
-    a = random_view(rng, "float", (8, 8)).in_other_byte_order()
+    idx = View.from_numpy(rng.integers(0, 8, size=(8,)).astype(np.int64)).in_other_byte_order()
     dv = H.DeviceViews()
-    offs = torch.zeros(4, dtype=torch.int64, device="cuda:0")
-    with pytest.raises(ocn.OcnError) as e:
-        ocn.gather(dv.tensor(View(a.storage, "float", (), (), 0, byteswapped=True)), offs, 0, 0,
-                   dv.tensor(View.empty("float", (4,))))
+    bad = torch.zeros(1, dtype=torch.int64, device="cuda:0")
+    with pytest.raises(ocn.OcnError) as e:      # index arrays are the library's own native data
+        ocn.index_offsets(dv.tensor(idx), 8, 4, dv.tensor(View.empty("int64", (8,))), bad)
     assert e.value.code == ocn.binding.ERR["BYTEORDER"]
     # one-byte scalars have no byte order: the flag is ignored
     m = random_view(rng, "int8", (8, 8)).in_other_byte_order()
