@@ -432,6 +432,7 @@ template <class F> OCN_DEV F hypot_any(F x, F y) { if constexpr (sizeof(F) == 4)
 template <class F> OCN_DEV F atan2_any(F y, F x) { if constexpr (sizeof(F) == 4) return atan2f(y, x); else return atan2(y, x); }
 template <class F> OCN_DEV F sinh_any(F x) { if constexpr (sizeof(F) == 4) return sinhf(x); else return sinh(x); }
 template <class F> OCN_DEV F cosh_any(F x) { if constexpr (sizeof(F) == 4) return coshf(x); else return cosh(x); }
+template <class F> OCN_DEV F expm1_any(F x) { if constexpr (sizeof(F) == 4) return expm1f(x); else return expm1(x); }
 template <class F> OCN_DEV F abs_any(F x) { if constexpr (sizeof(F) == 4) return __builtin_fabsf(x); else return __builtin_fabs(x); }
 template <class F> OCN_DEV F copysign_any(F x, F y) { if constexpr (sizeof(F) == 4) return __builtin_copysignf(x, y); else return __builtin_copysign(x, y); }
 
@@ -468,6 +469,15 @@ template <> struct FloatLimits<double> {
 // both families share one set of conventions for infinite and NaN parts (C's Annex G: an
 // infinite part of the result keeps its direction where the other part of the argument fixes
 // one, and an exact zero times anything is that zero).
+// sinh x and cosh x from one exponential: with t = e^|x| - 1 (no cancellation for small x),
+// sinh |x| = (t + t / (t + 1)) / 2 and cosh x = ((t + 1) + 1 / (t + 1)) / 2, each a few roundings
+// from exact.  For |x| below the overflow threshold of e^x only.
+template <class F> OCN_DEV void sinh_cosh_any(F x, F &sh, F &ch) {
+  const F t = expm1_any(abs_any(x)), e = t + (F)1;
+  sh = copysign_any((t + t / e) * (F)0.5, x);
+  ch = (e + (F)1 / e) * (F)0.5;
+}
+
 template <class F> OCN_DEV void sinh_cosh_complex(F x, F y, bool want_sinh, F &re, F &im) {
   const F half_range = sizeof(F) == 4 ? (F)88 : (F)709;
   const F inf = (F)__builtin_inff();
@@ -485,7 +495,8 @@ template <class F> OCN_DEV void sinh_cosh_complex(F x, F y, bool want_sinh, F &r
     re = times_zero_wins(times_zero_wins(c, h), want_sinh ? sh : ch);
     im = times_zero_wins(times_zero_wins(s, h), want_sinh ? ch : sh);
   } else {
-    const F sh = sinh_any(x), ch = cosh_any(x);
+    F sh, ch;
+    sinh_cosh_any(x, sh, ch);
     re = times_zero_wins(want_sinh ? sh : ch, c);
     im = times_zero_wins(want_sinh ? ch : sh, s);
   }
@@ -521,7 +532,8 @@ template <class F> OCN_DEV void tanh_complex(F x, F y, F &re, F &im) {
     re = copysign_any((F)1, x);
     im = 4 * s * c * exp_any(-2 * abs_any(x));
   } else {                                       // (sinh x cosh x + i sin y cos y) / (cos^2 y + sinh^2 x)
-    const F sh = sinh_any(x), ch = cosh_any(x);
+    F sh, ch;
+    sinh_cosh_any(x, sh, ch);
     const F den = c * c + sh * sh;               // a sum of squares: no cancellation
     re = sh * ch / den;
     im = s * c / den;
