@@ -171,6 +171,29 @@ def test_rows_of_whole_aligned_vectors(dt):
     _check("mul", "sum", off, rag2.slice(1, 1, 1025, 1), (1,), dt, expect_fused=True)
 
 
+@pytest.mark.parametrize("dt", ("int32", "float", "double", "cfloat"))
+def test_tall_column_reductions(dt):
+    """Columns with thousands of rows: sixteen wavefronts per workgroup with a run of rows each,
+    rows split over workgroups, partial results folded by a second launch - sums of products
+    and counts / any / all of comparisons (sixteen columns per lane for a bool intermediate)."""
+    rng = rng_for(15380 + X.ALL.index(dt))
+    sp = X.kind(dt) not in "fc"
+    for shape in ((5000, 300), (20000, 64), (3000, 7), (2500, 1024 + 16)):
+        a = random_view(rng, dt, shape, specials=sp)
+        b = random_view(rng, dt, shape, specials=sp)
+        _check("mul", "sum", a, b, (0,), dt, expect_fused=True)
+        b.storage[: b.storage.size // 2] = a.storage[: a.storage.size // 2]
+        for red in ("sum", "any", "all"):
+            _check("eq", red, a, b, (0,), "bool", expect_fused=True)
+        if dt != "cfloat":
+            _check("gt", "sum", a, b, (0,), "bool", expect_fused=True)
+    # three dims, the middle one reduced, and a row operand broadcast over the reduced dim
+    a = random_view(rng, dt, (6, 2000, 40), specials=sp)
+    b = random_view(rng, dt, (6, 1, 40), specials=sp)
+    _check("mul", "sum", a, b, (1,), dt, expect_fused=True)
+    _check("sub", "sum", b, a, (1,), dt, expect_fused=True)
+
+
 def test_unaligned_reversed_and_stepped_views():
     rng = rng_for(15400)
     big = random_view(rng, "float", (50, 131), specials=False)
