@@ -57,6 +57,31 @@ def test_index_binding():
     assert int(bad.cpu()[0]) == 0
 
 
+@pytest.mark.parametrize("shape", ((1,), (2,), (7,), (4096,), (100003,), (37, 53), (5, 1, 9, 11)))
+def test_index_binding_contiguous_arrays(shape):
+    """Contiguous index and offset arrays take the kernel with two indices per lane: odd counts,
+    negative and invalid indices, and the capped grid (lanes loop)."""
+    import torch
+    import paper_1810_08723_amd as ocn
+    rng = rng_for(17010 + len(shape) + shape[0])
+    idx = rng.integers(-70, 70, size=shape).astype(np.int64)               # dim_size 64: some invalid
+    for cap in (None, 3):
+        iv, ov = View.from_numpy(idx), View.empty("int64", shape)
+        dv = H.DeviceViews()
+        bad = torch.full((1,), 123, dtype=torch.int64, device="cuda:0")
+        if cap:
+            ocn.binding.set_max_launch_blocks(cap)
+        try:
+            ocn.index_offsets(dv.tensor(iv), 64, 24, dv.tensor(ov), bad)
+            torch.cuda.synchronize()
+        finally:
+            if cap:
+                ocn.binding.set_max_launch_blocks(0)
+        want, nbad = OI.index_offsets(idx, 64, 24)
+        got = View(dv.download(ov), "int64", ov.sizes, ov.strides, 0).to_numpy()
+        assert np.array_equal(got, want) and int(bad.cpu()[0]) == nbad
+
+
 @pytest.mark.parametrize("density", (0.0, 0.03, 0.5, 1.0))
 def test_mask_offsets_contiguous(density):
     rng = rng_for(17100)
