@@ -52,3 +52,21 @@ def test_five_dimensional_permutation_with_paired_tiles():
         plan = ocn.plan_binary(c.op, dv.tensor(c.inputs[0]), dv.tensor(c.inputs[1]), dv.tensor(c.out))
         print(c.name, plan["kernel"], plan["unclipped"], plan["tile_group"], flush=True)
         H.check_binary(c.op, c.inputs[0], c.inputs[1], c.out)
+
+
+@pytest.mark.parametrize("dt", ("int8", "uint8", "bool"))
+def test_one_byte_transposes(dt):
+    """One-byte elements (sixteen per vector): transposes with extents that are and are not
+    multiples of the tile, with a second operand, and with a third tiled axis."""
+    rng = rng_for(19400 + len(dt))
+    a = random_view(rng, dt, (1024, 1536)).permute(1, 0)
+    H.check_unary("ident", a, View.empty(dt, (1536, 1024)))
+    if dt != "bool":
+        b = random_view(rng, dt, (1536, 1024))
+        H.check_binary("add", a, b, View.empty(dt, (1536, 1024)))
+        H.check_unary("neg", random_view(rng, dt, (640, 1000)).permute(1, 0), View.empty(dt, (1000, 640)))
+    else:
+        b = random_view(rng, dt, (1536, 1024))
+        H.check_binary("lxor", a, b, View.empty(dt, (1536, 1024)))
+    c = random_view(rng, dt, (256, 384, 128)).permute(2, 0, 1)
+    H.check_unary("ident", c, View.empty(dt, (128, 256, 384)))
